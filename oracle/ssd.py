@@ -1,0 +1,143 @@
+"""Greedy self-speculative decoding on top of the reference decoder (TEST INFRASTRUCTURE).
+
+Follows the generation step of Figure 2 / Section 3: the draft model (target model minus the
+skip set S) proposes k tokens one at a time, the full model scores the pending token plus the
+k proposals in one pass, and the longest prefix of proposals that equals the full model's own
+greedy choices is kept, followed by the full model's token at the first mismatch (greedy
+verification keeps the target model's output, Section 4.2.2).
+
+State convention: committed tokens t_0..t_{n-1}; the cache holds verified K/V for positions
+0..n-2; the last committed token is "pending" (not yet in the cache).
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Sequence
+
+import numpy as np
+
+from .decoder import OracleModel, argmax_lowest, DEFAULT_CLAMP, DEFAULT_EPS
+
+
+class OracleSSD:
+    def __init__(self, model: OracleModel):
+        self.m = model
+        self.tokens: List[int] = []
+        self.last_taps: Optional[np.ndarray] = None    # [rows][L][2][d] of the last verify / prefill
+        self.last_logits: Optional[np.ndarray] = None
+        self.drafted = 0
+        self.accepted = 0
+        self.cycles = 0
+
+    # number of committed tokens
+    @property
+    def n(self) -> int:
+        return len(self.tokens)
+
+    @property
+    def pending(self) -> int:
+        return self.tokens[-1]
+
+    def prefill(self, prompt: Sequence[int]) -> int:
+        prompt = [int(t) for t in prompt]
+        out = self.m.forward(prompt, 0, want_taps=True)
+        first = argmax_lowest(out["logits"][-1])
+        self.tokens = prompt + [first]
+        self.last_taps = out["taps"][-1:]
+        self.last_logits = out["logits"][-1:]
+        return first
+
+    def decode(self) -> int:
+        """One vanilla autoregressive step with the full model; commits its token."""
+        out = self.m.forward([self.pending], self.n - 1)
+        t = argmax_lowest(out["logits"][0])
+        self.last_logits = out["logits"]
+        self.tokens.append(t)
+        return t
+
+    def draft(self, skip_mask, k: int, want_maxprob=False):
+        """k greedy tokens from the draft model; its K/V rows land at positions n-1..n+k-2."""
+        d, mp = [], []
+        tok, pos = self.pending, self.n - 1
+        for _ in range(k):
+            out = self.m.forward([tok], pos, skip_mask=skip_mask)
+            z = out["logits"][0]
+            tok = argmax_lowest(z)
+            if want_maxprob:
+                e = np.exp(z - z.max())
+                mp.append(float(e.max() / e.sum()))
+            d.append(tok)
+            pos += 1
+        return (d, mp) if want_maxprob else d
+
+    def verify(self, draft: Sequence[int]):
+        """Full model over [pending, d_1..d_k]; returns its greedy token after each row."""
+        rows = [self.pending] + [int(t) for t in draft]
+        out = self.m.forward(rows, self.n - 1, want_taps=True)
+        self.last_taps = out["taps"]
+        self.last_logits = out["logits"]
+        return [argmax_lowest(z) for z in out["logits"]]
+
+    def accept(self, draft: Sequence[int], target: Sequence[int]):
+        """a = longest prefix with d_j == y_{j-1}; commit d_1..d_a and y_a. Returns (a, y_a)."""
+        k = len(draft)
+        assert len(target) == k + 1
+        a = 0
+        while a < k and int(draft[a]) == int(target[a]):
+            a += 1
+        self.tokens.extend(int(t) for t in draft[:a])
+        self.tokens.append(int(target[a]))
+        self.drafted += k
+        self.accepted += a
+        self.cycles += 1
+        return a, int(target[a])
+
+    def force_commit(self, toks: Sequence[int]):
+        self.tokens.extend(int(t) for t in toks)
+
+    def layer_confidence(self, row: int = 0, clamp=DEFAULT_CLAMP, eps=DEFAULT_EPS, taps: int = 2):
+        """Per-layer confidence of one row of the last verify/prefill.
+
+        taps=2: mean of the confidences of the post-attention and post-MLP hidden states
+        (the "FFNN and Attention" hidden states of Section 3.1); taps=1: post-MLP only.
+        Returns (conf[L], per_tap dict with conf/maxprob/argmax arrays shaped [L][2]).
+        """
+        t = self.last_taps[row]                      # [L][2][d]
+        L = t.shape[0]
+        r = self.m.confidence(t.reshape(L * 2, -1), clamp=clamp, eps=eps)
+        c = r["conf"].reshape(L, 2)
+        per = {k_: v.reshape(L, 2) for k_, v in r.items()}
+        conf = (c[:, 0] + c[:, 1]) / 2.0 if taps == 2 else c[:, 1].copy()
+        return conf, per
+
+
+def generate_vanilla(model: OracleModel, prompt: Sequence[int], n_new: int) -> List[int]:
+    s = OracleSSD(model)
+    s.prefill(prompt)
+    while s.n - len(prompt) < n_new:
+        s.decode()
+    return s.tokens[len(prompt):len(prompt) + n_new]
+
+
+def generate_ssd(model: OracleModel, prompt: Sequence[int], n_new: int, k: int, skip_mask,
+                 on_cycle: Optional[Callable] = None):
+    """Greedy SSD until n_new tokens exist (the surplus of the last cycle is dropped).
+
+    skip_mask: array[L] of 0/1, or a callable(state) -> mask evaluated before every cycle.
+    on_cycle(state, draft, target, a) is called after each accept (search drivers hook in here).
+    Returns (new tokens, dict(accepted per cycle, drafted, accepted, cycles)).
+    """
+    s = OracleSSD(model)
+    s.prefill(prompt)
+    per_cycle = []
+    P = len(prompt)
+    while s.n - P < n_new:
+        mask = skip_mask(s) if callable(skip_mask) else skip_mask
+        d = s.draft(mask, k)
+        y = s.verify(d)
+        a, _ = s.accept(d, y)
+        per_cycle.append(a)
+        if on_cycle is not None:
+            on_cycle(s, d, y, a)
+    stats = {"accepted_per_cycle": per_cycle, "drafted": s.drafted, "accepted": s.accepted,
+             "cycles": s.cycles}
+    return s.tokens[P:P + n_new], stats

@@ -1,0 +1,202 @@
+"""Pins of the reference decoder against library routines, closed forms and invariants.
+
+None of these tests touches the HIP library.  The independent reference below is built from
+PyTorch library ops in float64 (rms_norm, scaled_dot_product_attention, silu, linear,
+embedding) with the rotary embedding written as a complex multiplication, i.e. a different
+formulation from the oracle's pairwise rotation.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import OracleModel, OracleSSD, generate_ssd, generate_vanilla
+from synth import ModelShape, WORKLOADS, make_prompt, make_weights
+
+
+def torch_reference_logits(shape, w, tokens):
+    """Full-sequence recompute with library ops, float64. Returns logits [T][V]."""
+    dd = torch.float64
+    T = len(tokens)
+    H, Hkv, hd = shape.n_heads, shape.n_kv_heads, shape.head_dim
+    x = F.embedding(torch.tensor(tokens, dtype=torch.long), w["embed"].to(dd))
+    pos = torch.arange(T, dtype=dd)
+    inv = shape.rope_base ** (-torch.arange(0, hd, 2, dtype=dd) / hd)       # base^(-2i/hd)
+    rot = torch.polar(torch.ones(T, hd // 2, dtype=dd), pos[:, None] * inv[None, :])  # e^{i p theta_i}
+
+    def rope(t):                       # t: [T][heads][hd], pairs (i, i+hd/2)
+        z = torch.complex(t[..., : hd // 2], t[..., hd // 2:]) * rot[:, None, :]
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    for l in range(shape.n_layers):
+        h = F.rms_norm(x, (shape.d_model,), w["attn_norm"][l].to(dd), eps=shape.rms_eps)
+        q = rope(F.linear(h, w["wq"][l].to(dd)).view(T, H, hd))
+        k = rope(F.linear(h, w["wk"][l].to(dd)).view(T, Hkv, hd))
+        v = F.linear(h, w["wv"][l].to(dd)).view(T, Hkv, hd)
+        k = k.repeat_interleave(H // Hkv, dim=1)
+        v = v.repeat_interleave(H // Hkv, dim=1)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                           v.transpose(0, 1)[None], is_causal=True)[0]
+        x = x + F.linear(o.transpose(0, 1).reshape(T, H * hd), w["wo"][l].to(dd))
+        h = F.rms_norm(x, (shape.d_model,), w["mlp_norm"][l].to(dd), eps=shape.rms_eps)
+        x = x + F.linear(F.silu(F.linear(h, w["wg"][l].to(dd))) * F.linear(h, w["wu"][l].to(dd)),
+                         w["wd"][l].to(dd))
+    h = F.rms_norm(x, (shape.d_model,), w["final_norm"].to(dd), eps=shape.rms_eps)
+    return F.linear(h, w["lm_head"].to(dd)).numpy()
+
+
+SHAPES = [
+    ModelShape(3, 64, 4, 4, 96, 50, dtype="fp32"),
+    ModelShape(2, 96, 6, 2, 160, 77, dtype="fp32", rope_base=500.0, rms_eps=1e-3),   # GQA 3:1
+    ModelShape(2, 64, 2, 1, 88, 40, dtype="bf16"),                                    # MQA, bf16 storage
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_matches_library_op_reference(shape):
+    # init_std 0.3 and jittered gains make every term (gain, rope, softmax scale) visible
+    w = make_weights(shape, 11, norm_gain_std=0.2, init_std=0.3)
+    toks = make_prompt(shape.vocab, 13, 5).tolist()
+    ref = torch_reference_logits(shape, w, toks)
+    m = OracleModel(shape, w, 32)
+    got = m.forward(toks, 0)["logits"]
+    assert np.abs(got - ref).max() <= 1e-9 * max(1.0, np.abs(ref).max())
+    assert np.abs(ref).max() > 0.1        # the comparison is not vacuous
+
+
+def test_tiny_workload_matches_library_op_reference(tiny_workload):
+    wl = tiny_workload
+    w = make_weights(wl.shape, wl.seed)
+    toks = make_prompt(wl.shape.vocab, wl.prompt_len, wl.seed).tolist()
+    ref = torch_reference_logits(wl.shape, w, toks)
+    got = OracleModel(wl.shape, w, 64).forward(toks, 0)["logits"]
+    assert np.abs(got - ref).max() <= 1e-11
+
+
+def test_incremental_equals_full_recompute():
+    shape = SHAPES[1]
+    w = make_weights(shape, 3, norm_gain_std=0.1, init_std=0.2)
+    toks = make_prompt(shape.vocab, 12, 1).tolist()
+    full = OracleModel(shape, w, 16).forward(toks, 0)["logits"]
+    m = OracleModel(shape, w, 16)
+    for p, t in enumerate(toks):
+        z = m.forward([t], p)["logits"][0]
+        assert np.array_equal(z, full[p])          # same row routine, same order: bit-exact
+    # mixed chunking
+    m2 = OracleModel(shape, w, 16)
+    a = m2.forward(toks[:5], 0)["logits"]
+    b = m2.forward(toks[5:], 5)["logits"]
+    assert np.array_equal(np.concatenate([a, b]), full)
+
+
+def test_all_layers_skipped_is_embedding_through_head():
+    shape = SHAPES[0]
+    w = make_weights(shape, 5, norm_gain_std=0.3, init_std=0.5)
+    m = OracleModel(shape, w, 8)
+    t = 17
+    z = m.forward([t], 0, skip_mask=np.ones(shape.n_layers, np.uint8))["logits"][0]
+    e = w["embed"][t].double().numpy()
+    h = e / np.sqrt(np.mean(e * e) + shape.rms_eps) * w["final_norm"].double().numpy()
+    np.testing.assert_allclose(z, w["lm_head"].double().numpy() @ h, rtol=1e-12, atol=1e-12)
+    # a skipped layer writes nothing to the cache
+    assert not m.kcache().any() and not m.vcache().any()
+
+
+def test_rope_is_identity_at_position_zero_and_preserves_norm():
+    shape = ModelShape(1, 64, 2, 2, 96, 30, dtype="fp32")
+    w = make_weights(shape, 9, init_std=0.4)
+    m = OracleModel(shape, w, 8)
+    toks = [3, 3, 3, 3]
+    m.forward(toks, 0)
+    e = w["embed"][3].double()
+    h = F.rms_norm(e, (64,), w["attn_norm"][0].double(), eps=shape.rms_eps)
+    k_raw = F.linear(h, w["wk"][0].double()).view(2, 32).numpy()
+    K = m.kcache()[0]
+    np.testing.assert_allclose(K[0], k_raw, rtol=1e-12, atol=1e-14)          # angle 0
+    for p in range(1, 4):                                                   # same token => same raw k
+        np.testing.assert_allclose(np.linalg.norm(K[p], axis=-1), np.linalg.norm(k_raw, axis=-1), rtol=1e-12)
+        assert np.abs(K[p] - k_raw).max() > 1e-3
+    # V is never rotated
+    v_raw = F.linear(h, w["wv"][0].double()).view(2, 32).numpy()
+    for p in range(4):
+        np.testing.assert_allclose(m.vcache()[0][p], v_raw, rtol=1e-12, atol=1e-14)
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads():
+    g = ModelShape(2, 64, 4, 2, 96, 40, dtype="fp32")
+    w = make_weights(g, 21, init_std=0.3)
+    mha = dataclasses.replace(g, n_kv_heads=4)
+    w2 = dict(w)
+    hd = g.head_dim
+    for name in ("wk", "wv"):
+        w2[name] = [t.view(2, hd, -1).repeat_interleave(2, dim=0).reshape(4 * hd, -1).contiguous() for t in w[name]]
+    toks = make_prompt(40, 9, 2).tolist()
+    a = OracleModel(g, w, 16).forward(toks, 0)["logits"]
+    b = OracleModel(mha, w2, 16).forward(toks, 0)["logits"]
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-13)
+
+
+# ---- greedy self-speculative decoding -----------------------------------------------------
+
+def _tiny():
+    wl = WORKLOADS["tiny"]
+    w = make_weights(wl.shape, wl.seed)
+    return wl, w, make_prompt(wl.shape.vocab, wl.prompt_len, wl.seed).tolist()
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_ssd_is_lossless_for_any_mask(k):
+    wl, w, p = _tiny()
+    m = OracleModel(wl.shape, w, 128)
+    van = generate_vanilla(m, p, 24)
+    rng = np.random.default_rng(k)
+    masks = [np.zeros(4, np.uint8), np.array([0, 1, 1, 0], np.uint8), np.ones(4, np.uint8)]
+    masks += [rng.integers(0, 2, 4).astype(np.uint8) for _ in range(3)]
+    for mask in masks:
+        got, st = generate_ssd(OracleModel(wl.shape, w, 128), p, 24, k, mask)
+        assert got == van, mask
+        assert st["drafted"] == st["cycles"] * k
+
+
+@pytest.mark.parametrize("k", [1, 3, 4])
+def test_empty_skip_set_accepts_everything(k):
+    wl, w, p = _tiny()
+    m = OracleModel(wl.shape, w, 128)
+    _, st = generate_ssd(m, p, 20, k, np.zeros(4, np.uint8))
+    assert all(a == k for a in st["accepted_per_cycle"])
+    assert st["accepted"] == st["drafted"]
+
+
+def test_stale_cache_entries_are_never_read():
+    wl, w, p = _tiny()
+    mask = np.array([0, 1, 0, 1], np.uint8)
+    ref, _ = generate_ssd(OracleModel(wl.shape, w, 128), p, 20, 4, mask)
+    m = OracleModel(wl.shape, w, 128)
+
+    def poison(state, d, y, a):
+        state.m.kv_poison(state.n - 1)          # valid entries are 0..n-2
+
+    got, _ = generate_ssd(m, p, 20, 4, mask, on_cycle=poison)
+    assert got == ref
+
+
+def test_accept_rule_on_hand_cases():
+    s = OracleSSD.__new__(OracleSSD)
+    s.tokens, s.drafted, s.accepted, s.cycles = [9], 0, 0, 0
+    assert s.accept([5, 6, 7], [5, 6, 7, 8]) == (3, 8) and s.tokens == [9, 5, 6, 7, 8]
+    assert s.accept([1, 2, 3], [1, 9, 3, 4]) == (1, 9) and s.tokens[-2:] == [1, 9]
+    assert s.accept([1, 2], [0, 2, 3]) == (0, 0)
+    # a later match after a mismatch does not count
+    assert s.accept([4, 4, 4], [4, 5, 4, 4]) == (1, 5)
+    assert (s.drafted, s.accepted, s.cycles) == (11, 5, 4)
+
+
+def test_bad_arguments_are_rejected():
+    wl, w, p = _tiny()
+    m = OracleModel(wl.shape, w, 8)
+    with pytest.raises(ValueError):
+        m.forward([1] * 9, 0)
+    with pytest.raises(ValueError):
+        m.forward([wl.shape.vocab], 0)
