@@ -24,6 +24,7 @@ class OracleSSD:
         self.tokens: List[int] = []
         self.last_taps: Optional[np.ndarray] = None    # [rows][L][2][d] of the last verify / prefill
         self.last_logits: Optional[np.ndarray] = None
+        self.last_draft_logits: List[np.ndarray] = []   # logits of each step of the last draft
         self.drafted = 0
         self.accepted = 0
         self.cycles = 0
@@ -58,9 +59,11 @@ class OracleSSD:
         """k greedy tokens from the draft model; its K/V rows land at positions n-1..n+k-2."""
         d, mp = [], []
         tok, pos = self.pending, self.n - 1
+        self.last_draft_logits = []
         for _ in range(k):
             out = self.m.forward([tok], pos, skip_mask=skip_mask)
             z = out["logits"][0]
+            self.last_draft_logits.append(z)
             tok = argmax_lowest(z)
             if want_maxprob:
                 e = np.exp(z - z.max())

@@ -1,0 +1,46 @@
+"""Builds libssd.so (gfx950 kernels + C ABI) in-tree with hipcc."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libssd.so")
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def sources():
+    return [os.path.join(CSRC, f) for f in ("ssd_kernels.hip", "ssd_api.cpp", "ssd_policy.cpp")]
+
+
+def build(verbose: bool = False) -> str:
+    objs = []
+    for src in sources():
+        obj = os.path.splitext(src)[0] + ".o"
+        if src.endswith("ssd_policy.cpp"):
+            # pure host arithmetic: no contraction, so results do not depend on the build
+            cmd = [HIPCC, "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-c", src, "-o", obj]
+        elif src.endswith(".hip"):
+            cmd = [HIPCC] + DEVICE_FLAGS + ["-c", src, "-o", obj]
+        else:
+            cmd = [HIPCC, "-x", "hip"] + DEVICE_FLAGS + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd))
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed for %s:\n%s" % (src, err))
+        if verbose and err.strip():
+            print(err)
+        objs.append(obj)
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,630 @@
+// Host side of the C ABI declared in include/ssd.h: argument checks, the decoding state
+// machine, the workspace carve-up and the per-layer launch sequences.  All arithmetic of the
+// hot path lives in the kernels (ssd_kernels.hip); this file only orders them.
+#include "../../include/ssd.h"
+#include "ssd_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace ssdk;
+
+namespace {
+
+enum State { ST_CREATED = 0, ST_READY = 1, ST_IDLE = 2, ST_DRAFTED = 3, ST_VERIFIED = 4 };
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layout {
+    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, small, total;
+    int rows;       // activation rows: max(max_k + 1, SSD_PREFILL_ROWS)
+    int conf_rows;  // rows of one confidence pass: 2 * L
+    int logit_rows;
+    size_t kv_layer_elems;  // elements of K (or V) of one layer
+};
+
+bool valid_cfg(const ssd_config* c)
+{
+    if (!c) return false;
+    if (c->n_layers < 1 || c->d_model < 16 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 16 ||
+        c->vocab < 16 || c->max_seq < 2)
+        return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->n_heads % c->n_kv_heads) return false;
+    long dq = (long)c->n_heads * c->head_dim, dkv = (long)c->n_kv_heads * c->head_dim;
+    if (c->d_model % 16 || c->d_ffn % 16 || dq % 16 || dkv % 16 || c->vocab % 16) return false;
+    if (c->weight_dtype != 0 && c->weight_dtype != 1) return false;
+    if (c->conf_taps != 1 && c->conf_taps != 2) return false;
+    if (c->max_k < 1 || c->max_k > SSD_MAX_K) return false;
+    if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f) || !(c->conf_clamp > 0.f) || !(c->conf_eps >= 0.f)) return false;
+    return true;
+}
+
+Dims make_dims(const ssd_config& c)
+{
+    Dims D;
+    D.L = c.n_layers; D.d = c.d_model; D.H = c.n_heads; D.Hkv = c.n_kv_heads; D.hd = c.head_dim;
+    D.dq = c.n_heads * c.head_dim; D.dkv = c.n_kv_heads * c.head_dim; D.f = c.d_ffn; D.V = c.vocab;
+    D.max_seq = c.max_seq; D.eps = c.rms_eps; D.wt = c.weight_dtype;
+    return D;
+}
+
+Layout make_layout(const ssd_config& c)
+{
+    Dims D = make_dims(c);
+    Layout l;
+    size_t esz = c.weight_dtype == 1 ? 2 : 4;
+    l.rows = c.max_k + 1 > SSD_PREFILL_ROWS ? c.max_k + 1 : SSD_PREFILL_ROWS;
+    l.conf_rows = 2 * c.n_layers;
+    l.logit_rows = l.rows > l.conf_rows ? l.rows : l.conf_rows;
+    l.kv_layer_elems = (size_t)D.Hkv * D.max_seq * D.hd;
+    size_t kmax = (size_t)(D.d > D.dq ? D.d : D.dq);
+    size_t o = 0;
+    l.rope = o;   o += align_up((size_t)D.max_seq * (D.hd / 2) * 2 * sizeof(float));
+    l.kv = o;     o += align_up((size_t)D.L * 2 * l.kv_layer_elems * esz);
+    l.x = o;      o += align_up((size_t)l.rows * D.d * sizeof(float));
+    l.h = o;      o += align_up((size_t)l.rows * kmax * sizeof(float));
+    l.qkv = o;    o += align_up((size_t)l.rows * (D.dq + 2 * D.dkv) * sizeof(float));
+    l.att = o;    o += align_up((size_t)l.rows * D.dq * sizeof(float));
+    l.act = o;    o += align_up((size_t)l.rows * D.f * sizeof(float));
+    l.part = o;   o += align_up(attention_scratch_floats(D, l.rows) * sizeof(float));
+    l.logits = o; o += align_up((size_t)l.logit_rows * D.V * sizeof(float));
+    l.taps = o;   o += align_up((size_t)l.rows * D.L * 2 * D.d * sizeof(float));
+    l.tapn = o;   o += align_up((size_t)l.conf_rows * D.d * sizeof(float));
+    l.small = o;  o += align_up(4096);
+    l.total = o;
+    return l;
+}
+
+// offsets (in 4-byte words) inside the "small" region
+enum { SM_POS = 0, SM_TOK = 8 /* 17 ints: pending + drafts */, SM_TARGET = 32 /* 16 */, SM_RES = 56 /* 2 */,
+       SM_MAXPROB = 64 /* 16 floats */, SM_SINK = 96, SM_CONF = 128 /* conf_rows floats x3 follow */ };
+
+}  // namespace
+
+struct ssd_ctx {
+    ssd_config cfg;
+    Dims D;
+    Layout lay;
+    hipStream_t stream;
+    State state;
+    std::string err;
+    char* ws;
+    size_t ws_bytes;
+    bool have_w;
+    ssd_weights w;
+    std::vector<const float*> attn_norm, mlp_norm;
+    std::vector<const void*> wq, wk, wv, wo, wg, wu, wd;
+    int n;             // committed tokens
+    int k_pending;     // k of the draft awaiting verification / acceptance
+    int tap_rows;      // rows with valid taps (0 = none)
+    int tap_row0;      // index of the first valid tap row inside the tap buffer
+    int logit_rows;    // rows with valid logits
+    int32_t* pinned;   // host-pinned readback buffer
+    ssd_stats st;
+    int prof_kid;      // kernel id being timed, -1 = off
+    size_t prof_used;  // event pairs in use
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_ev;
+
+    float* f(size_t off) const { return reinterpret_cast<float*>(ws + off); }
+    int32_t* small_i() const { return reinterpret_cast<int32_t*>(ws + lay.small); }
+    float* small_f() const { return reinterpret_cast<float*>(ws + lay.small); }
+    int* pos_dev() const { return small_i() + SM_POS; }
+    void* kcache(int l) const
+    {
+        size_t esz = cfg.weight_dtype == 1 ? 2 : 4;
+        return ws + lay.kv + ((size_t)l * 2 + 0) * lay.kv_layer_elems * esz;
+    }
+    void* vcache(int l) const
+    {
+        size_t esz = cfg.weight_dtype == 1 ? 2 : 4;
+        return ws + lay.kv + ((size_t)l * 2 + 1) * lay.kv_layer_elems * esz;
+    }
+};
+
+namespace {
+
+int fail(ssd_ctx* c, int code, const char* msg)
+{
+    if (c) c->err = msg;
+    return code;
+}
+
+int hip_fail(ssd_ctx* c, hipError_t e, const char* where)
+{
+    if (c) c->err = std::string(where) + ": " + hipGetErrorString(e);
+    return SSD_EHIP;
+}
+
+#define HIPCHK(call, where)                                  \
+    do {                                                     \
+        hipError_t e__ = (call);                             \
+        if (e__ != hipSuccess) return hip_fail(c, e__, where); \
+    } while (0)
+
+// Launch `call`; when kernel `kid` is selected for timing, bracket it with a pair of events.
+#define TIMED(kid, call, where)                                                            \
+    do {                                                                                   \
+        if (c->prof_kid == (kid)) {                                                        \
+            if (c->prof_used == c->prof_ev.size()) {                                       \
+                hipEvent_t a__, b__;                                                       \
+                HIPCHK(hipEventCreate(&a__), "event create");                              \
+                HIPCHK(hipEventCreate(&b__), "event create");                              \
+                c->prof_ev.emplace_back(a__, b__);                                         \
+            }                                                                              \
+            HIPCHK(hipEventRecord(c->prof_ev[c->prof_used].first, c->stream), "event");    \
+            HIPCHK(call, where);                                                           \
+            HIPCHK(hipEventRecord(c->prof_ev[c->prof_used].second, c->stream), "event");   \
+            c->prof_used++;                                                                \
+        } else {                                                                           \
+            HIPCHK(call, where);                                                           \
+        }                                                                                  \
+    } while (0)
+
+// One decoder layer for a single row (draft / vanilla decode path).
+int layer_single(ssd_ctx* c, int l, int pos_off)
+{
+    const Dims& D = c->D;
+    float* x = c->f(c->lay.x);
+    TIMED(SSD_K_GEMV_QKV, gemv_qkv(D, c->wq[l], c->wk[l], c->wv[l], c->attn_norm[l], x, c->f(c->lay.rope), c->pos_dev(),
+                                   pos_off, c->f(c->lay.qkv), c->kcache(l), c->vcache(l), c->stream), "gemv_qkv");
+    TIMED(SSD_K_ATTENTION, attention(D, c->f(c->lay.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
+                                     c->n - 1, 1, c->f(c->lay.part), c->f(c->lay.att), c->stream), "attention");
+    TIMED(SSD_K_GEMV_O, gemv_resid(D, c->wo[l], D.d, D.dq, c->f(c->lay.att), x, nullptr, c->stream), "gemv_o");
+    TIMED(SSD_K_GEMV_GATEUP, gemv_swiglu(D, c->wg[l], c->wu[l], c->mlp_norm[l], x, c->f(c->lay.act), c->stream),
+          "gemv_swiglu");
+    TIMED(SSD_K_GEMV_DOWN, gemv_resid(D, c->wd[l], D.d, D.f, c->f(c->lay.act), x, nullptr, c->stream), "gemv_down");
+    return SSD_OK;
+}
+
+// Single-row forward of the token in tok slot `slot` at position *pos + pos_off; the greedy token goes to
+// tok slot `slot_out`, its logits to logits row `lrow`, its max-probability to SM_MAXPROB[lrow].
+int forward_single(ssd_ctx* c, const uint8_t* skip, int slot, int slot_out, int pos_off, int lrow)
+{
+    const Dims& D = c->D;
+    TokArg none = {};
+    HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_TOK + slot, none, 1, c->f(c->lay.x), c->stream), "embed");
+    for (int l = 0; l < D.L; l++) {
+        if (skip && skip[l]) continue;
+        int rc = layer_single(c, l, pos_off);
+        if (rc) return rc;
+    }
+    float* logits = c->f(c->lay.logits) + (size_t)lrow * D.V;
+    TIMED(SSD_K_GEMV_LMHEAD, gemv_lmhead(D, c->w.lm_head, c->w.final_norm, c->f(c->lay.x), logits, c->stream),
+          "gemv_lmhead");
+    TIMED(SSD_K_VOCAB, vocab_reduce(logits, 1, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, c->small_i() + SM_TOK + slot_out, 1, nullptr,
+                                    c->small_f() + SM_MAXPROB + lrow, nullptr, c->stream), "vocab_reduce");
+    return SSD_OK;
+}
+
+// Full-model forward of M rows (M <= 16) at positions *pos + pos_off + r; taps into tap rows 0..M-1;
+// logits (when want_logits) into logits rows 0..M-1 and greedy tokens into SM_TARGET.
+int forward_rows(ssd_ctx* c, const int32_t* tok0_dev, const TokArg& toks, int M, int pos_off, int pos_host,
+                 bool want_logits)
+{
+    const Dims& D = c->D;
+    const Layout& Y = c->lay;
+    float* x = c->f(Y.x);
+    float* h = c->f(Y.h);
+    HIPCHK(embed_rows(D, c->w.embed, tok0_dev, toks, M, x, c->stream), "embed");
+    const int tap_ld = D.L * 2 * D.d;
+    for (int l = 0; l < D.L; l++) {
+        HIPCHK(rmsnorm_rows(x, c->attn_norm[l], M, D.d, D.eps, h, c->stream), "rmsnorm");
+        RowsGemm g = {};
+        g.w[0] = c->wq[l]; g.w[1] = c->wk[l]; g.w[2] = c->wv[l];
+        g.n[0] = D.dq; g.n[1] = D.dkv; g.n[2] = D.dkv;
+        g.K = D.d; g.x = h; g.y = c->f(Y.qkv); g.ldy = D.dq + 2 * D.dkv; g.M = M; g.mode = 0;
+        TIMED(SSD_K_ROWS_QKV, gemm_rows(D, g, c->stream), "gemm_qkv");
+        HIPCHK(rope_kv_rows(D, c->f(Y.qkv), c->f(Y.rope), c->pos_dev(), pos_off, M, c->kcache(l), c->vcache(l),
+                            c->stream), "rope_kv");
+        TIMED(SSD_K_ATTENTION, attention(D, c->f(Y.qkv), D.dq + 2 * D.dkv, c->kcache(l), c->vcache(l), c->pos_dev(),
+                                         pos_off, pos_host, M, c->f(Y.part), c->f(Y.att), c->stream), "attention");
+        RowsGemm o = {};
+        o.w[0] = c->wo[l]; o.n[0] = D.d; o.K = D.dq; o.x = c->f(Y.att); o.y = x; o.ldy = D.d; o.M = M; o.mode = 1;
+        o.tap = c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d; o.tap_ld = tap_ld;
+        TIMED(SSD_K_ROWS_O, gemm_rows(D, o, c->stream), "gemm_o");
+        HIPCHK(rmsnorm_rows(x, c->mlp_norm[l], M, D.d, D.eps, h, c->stream), "rmsnorm");
+        RowsGemm gu = {};
+        gu.w[0] = c->wg[l]; gu.w[1] = c->wu[l]; gu.n[0] = D.f; gu.n[1] = D.f; gu.K = D.d; gu.x = h;
+        gu.y = c->f(Y.act); gu.ldy = D.f; gu.M = M; gu.mode = 2;
+        TIMED(SSD_K_ROWS_GATEUP, gemm_rows(D, gu, c->stream), "gemm_gateup");
+        RowsGemm dn = {};
+        dn.w[0] = c->wd[l]; dn.n[0] = D.d; dn.K = D.f; dn.x = c->f(Y.act); dn.y = x; dn.ldy = D.d; dn.M = M; dn.mode = 1;
+        dn.tap = c->f(Y.taps) + ((size_t)l * 2 + 1) * D.d; dn.tap_ld = tap_ld;
+        TIMED(SSD_K_ROWS_DOWN, gemm_rows(D, dn, c->stream), "gemm_down");
+    }
+    if (want_logits) {
+        HIPCHK(rmsnorm_rows(x, c->w.final_norm, M, D.d, D.eps, h, c->stream), "rmsnorm");
+        RowsGemm lm = {};
+        lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = h; lm.y = c->f(Y.logits); lm.ldy = D.V; lm.M = M;
+        lm.mode = 0;
+        TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm_lmhead");
+        HIPCHK(vocab_reduce(c->f(Y.logits), M, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, c->small_i() + SM_TARGET, 1,
+                            nullptr, nullptr, nullptr, c->stream), "vocab_reduce");
+    }
+    return SSD_OK;
+}
+
+int readback(ssd_ctx* c, const void* dev, size_t bytes, void* host)
+{
+    HIPCHK(hipMemcpyAsync(c->pinned, dev, bytes, hipMemcpyDeviceToHost, c->stream), "readback copy");
+    HIPCHK(hipStreamSynchronize(c->stream), "readback sync");
+    memcpy(host, c->pinned, bytes);
+    return SSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ssd_create(const ssd_config* cfg, void* hip_stream, ssd_ctx** out)
+{
+    if (!out) return SSD_EINVAL;
+    *out = nullptr;
+    if (!valid_cfg(cfg)) return SSD_EINVAL;
+    ssd_ctx* c = new ssd_ctx();
+    c->cfg = *cfg;
+    c->D = make_dims(*cfg);
+    c->lay = make_layout(*cfg);
+    c->stream = (hipStream_t)hip_stream;
+    c->state = ST_CREATED;
+    c->ws = nullptr; c->ws_bytes = 0; c->have_w = false;
+    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->tap_row0 = 0; c->logit_rows = 0; c->pinned = nullptr;
+    memset(&c->st, 0, sizeof(c->st));
+    memset(&c->w, 0, sizeof(c->w));
+    c->prof_kid = -1; c->prof_used = 0;
+    *out = c;
+    return SSD_OK;
+}
+
+size_t ssd_workspace_bytes(const ssd_config* cfg)
+{
+    if (!valid_cfg(cfg)) return 0;
+    return make_layout(*cfg).total;
+}
+
+int ssd_set_workspace(ssd_ctx* c, void* dev, size_t bytes)
+{
+    if (!c) return SSD_EINVAL;
+    if (!dev || bytes < c->lay.total) return fail(c, SSD_ENOMEM, "workspace missing or smaller than ssd_workspace_bytes");
+    if (reinterpret_cast<uintptr_t>(dev) % ALIGN) return fail(c, SSD_EINVAL, "workspace must be 256-byte aligned");
+    if (c->state != ST_CREATED && c->state != ST_READY) return fail(c, SSD_ESTATE, "workspace can only be set before prefill");
+    // rotary table in double precision on the host: cos/sin(p * base^(-2i/hd))
+    const int half = c->D.hd / 2;
+    std::vector<float> tab((size_t)c->D.max_seq * half * 2);
+    for (int p = 0; p < c->D.max_seq; p++)
+        for (int i = 0; i < half; i++) {
+            double ang = (double)p * std::pow((double)c->cfg.rope_base, -2.0 * (double)i / (double)c->D.hd);
+            tab[((size_t)p * half + i) * 2 + 0] = (float)std::cos(ang);
+            tab[((size_t)p * half + i) * 2 + 1] = (float)std::sin(ang);
+        }
+    if (!c->pinned) HIPCHK(hipHostMalloc((void**)&c->pinned, 64 * 1024, hipHostMallocDefault), "hipHostMalloc");
+    c->ws = static_cast<char*>(dev);
+    c->ws_bytes = bytes;
+    HIPCHK(hipMemcpyAsync(c->ws + c->lay.rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice, c->stream),
+           "rope upload");
+    HIPCHK(hipMemsetAsync(c->ws + c->lay.small, 0, 4096, c->stream), "state clear");
+    HIPCHK(hipStreamSynchronize(c->stream), "workspace sync");  // tab goes out of scope
+    if (c->have_w) c->state = ST_READY;
+    return SSD_OK;
+}
+
+int ssd_load_weights(ssd_ctx* c, const ssd_weights* w)
+{
+    if (!c || !w) return SSD_EINVAL;
+    if (c->state != ST_CREATED && c->state != ST_READY) return fail(c, SSD_ESTATE, "weights can only be loaded before prefill");
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+        !w->mlp_norm || !w->wg || !w->wu || !w->wd)
+        return fail(c, SSD_EINVAL, "null weight pointer");
+    const int L = c->D.L;
+    for (int l = 0; l < L; l++)
+        if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->mlp_norm[l] || !w->wg[l] ||
+            !w->wu[l] || !w->wd[l])
+            return fail(c, SSD_EINVAL, "null per-layer weight pointer");
+    auto chk = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+    bool ok = chk(w->embed) && chk(w->lm_head) && chk(w->final_norm);
+    for (int l = 0; l < L && ok; l++)
+        ok = chk(w->attn_norm[l]) && chk(w->wq[l]) && chk(w->wk[l]) && chk(w->wv[l]) && chk(w->wo[l]) &&
+             chk(w->mlp_norm[l]) && chk(w->wg[l]) && chk(w->wu[l]) && chk(w->wd[l]);
+    if (!ok) return fail(c, SSD_EINVAL, "weight pointers must be 16-byte aligned");
+    c->w = *w;
+    c->attn_norm.assign(w->attn_norm, w->attn_norm + L);
+    c->mlp_norm.assign(w->mlp_norm, w->mlp_norm + L);
+    c->wq.assign(w->wq, w->wq + L); c->wk.assign(w->wk, w->wk + L); c->wv.assign(w->wv, w->wv + L);
+    c->wo.assign(w->wo, w->wo + L); c->wg.assign(w->wg, w->wg + L); c->wu.assign(w->wu, w->wu + L);
+    c->wd.assign(w->wd, w->wd + L);
+    c->have_w = true;
+    if (c->ws) c->state = ST_READY;
+    return SSD_OK;
+}
+
+int ssd_reset(ssd_ctx* c)
+{
+    if (!c) return SSD_EINVAL;
+    if (c->state == ST_CREATED) return fail(c, SSD_ESTATE, "nothing to reset");
+    c->state = ST_READY;
+    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->logit_rows = 0;
+    memset(&c->st, 0, sizeof(c->st));
+    return SSD_OK;
+}
+
+void ssd_destroy(ssd_ctx* c)
+{
+    if (!c) return;
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    for (auto& e : c->prof_ev) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+    delete c;
+}
+
+const char* ssd_last_error(const ssd_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+int ssd_get_stats(const ssd_ctx* c, ssd_stats* out)
+{
+    if (!c || !out) return SSD_EINVAL;
+    *out = c->st;
+    out->n_tokens = c->n;
+    out->state = (int32_t)c->state;
+    return SSD_OK;
+}
+
+int ssd_prefill(ssd_ctx* c, const int32_t* tokens, int n, int32_t* first_token_out)
+{
+    if (!c || !tokens || !first_token_out || n < 1) return c ? fail(c, SSD_EINVAL, "prefill: bad argument") : SSD_EINVAL;
+    if (c->state != ST_READY) return fail(c, SSD_ESTATE, "prefill needs workspace + weights and an empty sequence");
+    if (n + 1 > c->D.max_seq) return fail(c, SSD_ECAPACITY, "prompt does not fit max_seq");
+    for (int i = 0; i < n; i++)
+        if (tokens[i] < 0 || tokens[i] >= c->D.V) return fail(c, SSD_EINVAL, "prompt token id out of range");
+    HIPCHK(set_state(c->small_i() + SM_TOK, 0, c->pos_dev(), 0, c->stream), "set_state");
+    int last_M = 0;
+    for (int p0 = 0; p0 < n; p0 += SSD_PREFILL_ROWS) {
+        int M = n - p0 < SSD_PREFILL_ROWS ? n - p0 : SSD_PREFILL_ROWS;
+        TokArg t = {};
+        for (int r = 0; r < M; r++) t.t[r] = tokens[p0 + r];
+        bool last = p0 + M == n;
+        int rc = forward_rows(c, nullptr, t, M, p0, 0, last);
+        if (rc) return rc;
+        last_M = M;
+    }
+    // pending token = greedy token after the last prompt row; n_cached positions = n
+    HIPCHK(advance_state(c->pos_dev(), n, c->small_i() + SM_TOK, c->small_i() + SM_TARGET + (last_M - 1), c->stream),
+           "advance_state");
+    int rc = readback(c, c->small_i() + SM_TARGET + (last_M - 1), sizeof(int32_t), first_token_out);
+    if (rc) return rc;
+    c->n = n + 1;
+    c->state = ST_IDLE;
+    c->tap_rows = 1; c->tap_row0 = last_M - 1;
+    c->logit_rows = 1;
+    // logits of the last row sit at row last_M-1; move them to row 0 so ssd_copy_logits sees one row
+    if (last_M > 1) {
+        HIPCHK(copy_f32(c->f(c->lay.logits) + (size_t)(last_M - 1) * c->D.V, c->f(c->lay.logits), c->D.V, c->stream),
+               "logits move");
+    }
+    c->st.committed = 1;
+    return SSD_OK;
+}
+
+int ssd_decode(ssd_ctx* c, int32_t* token_out)
+{
+    if (!c || !token_out) return c ? fail(c, SSD_EINVAL, "decode: bad argument") : SSD_EINVAL;
+    if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "decode needs a prefilled sequence with no draft in flight");
+    if (c->n + 1 > c->D.max_seq) return fail(c, SSD_ECAPACITY, "sequence would exceed max_seq");
+    // pending token sits in tok slot 0; its successor is written to slot 1, then promoted
+    int rc = forward_single(c, nullptr, 0, 1, 0, 0);
+    if (rc) return rc;
+    HIPCHK(advance_state(c->pos_dev(), 1, c->small_i() + SM_TOK, c->small_i() + SM_TOK + 1, c->stream), "advance_state");
+    rc = readback(c, c->small_i() + SM_TOK + 1, sizeof(int32_t), token_out);
+    if (rc) return rc;
+    c->n += 1;
+    c->logit_rows = 1;
+    c->tap_rows = 0;
+    c->st.decode_steps++; c->st.committed++;
+    return SSD_OK;
+}
+
+int ssd_draft_step(ssd_ctx* c, const uint8_t* skip_mask, int k, int32_t* draft_out, float* draft_maxprob_out)
+{
+    if (!c || !skip_mask || !draft_out) return c ? fail(c, SSD_EINVAL, "draft_step: bad argument") : SSD_EINVAL;
+    if (k < 1) return fail(c, SSD_EINVAL, "k must be at least 1");
+    if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "draft_step needs a prefilled sequence with no draft in flight");
+    if (k > c->cfg.max_k) return fail(c, SSD_ECAPACITY, "k exceeds max_k");
+    if (c->n + k > c->D.max_seq) return fail(c, SSD_ECAPACITY, "draft + verification would exceed max_seq");
+    for (int i = 0; i < k; i++) {
+        int rc = forward_single(c, skip_mask, i, i + 1, i, i);
+        if (rc) return rc;
+    }
+    int rc = readback(c, c->small_i() + SM_TOK + 1, sizeof(int32_t) * k, draft_out);
+    if (rc) return rc;
+    if (draft_maxprob_out) {
+        rc = readback(c, c->small_f() + SM_MAXPROB, sizeof(float) * k, draft_maxprob_out);
+        if (rc) return rc;
+    }
+    c->state = ST_DRAFTED;
+    c->k_pending = k;
+    c->logit_rows = k;
+    c->tap_rows = 0;
+    c->st.draft_steps += k;
+    return SSD_OK;
+}
+
+int ssd_verify(ssd_ctx* c, const int32_t* draft, int k, int32_t* target_out)
+{
+    if (!c || !draft || !target_out) return c ? fail(c, SSD_EINVAL, "verify: bad argument") : SSD_EINVAL;
+    if (c->state != ST_DRAFTED) return fail(c, SSD_ESTATE, "verify must follow draft_step");
+    if (k != c->k_pending) return fail(c, SSD_EINVAL, "verify: k differs from the draft's");
+    for (int i = 0; i < k; i++)
+        if (draft[i] < 0 || draft[i] >= c->D.V) return fail(c, SSD_EINVAL, "draft token id out of range");
+    TokArg t = {};
+    for (int i = 0; i < k; i++) t.t[i + 1] = draft[i];
+    int rc = forward_rows(c, c->small_i() + SM_TOK, t, k + 1, 0, c->n - 1, true);
+    if (rc) return rc;
+    rc = readback(c, c->small_i() + SM_TARGET, sizeof(int32_t) * (k + 1), target_out);
+    if (rc) return rc;
+    c->state = ST_VERIFIED;
+    c->tap_rows = k + 1; c->tap_row0 = 0;
+    c->logit_rows = k + 1;
+    c->st.verify_rows += k + 1;
+    return SSD_OK;
+}
+
+int ssd_accept(ssd_ctx* c, const int32_t* draft, const int32_t* target, int k, int32_t* n_accepted_out,
+               int32_t* next_token_out)
+{
+    if (!c || !draft || !target || !n_accepted_out || !next_token_out)
+        return c ? fail(c, SSD_EINVAL, "accept: bad argument") : SSD_EINVAL;
+    if (c->state != ST_VERIFIED) return fail(c, SSD_ESTATE, "accept must follow verify");
+    if (k != c->k_pending) return fail(c, SSD_EINVAL, "accept: k differs from the draft's");
+    for (int i = 0; i <= k; i++)
+        if (target[i] < 0 || target[i] >= c->D.V) return fail(c, SSD_EINVAL, "target token id out of range");
+    // the target tokens are taken from the host array: upload them next to the device copy
+    HIPCHK(hipMemcpyAsync(c->small_i() + SM_TARGET, target, sizeof(int32_t) * (k + 1), hipMemcpyHostToDevice, c->stream),
+           "target upload");
+    TokArg d = {};
+    for (int i = 0; i < k; i++) d.t[i] = draft[i];
+    HIPCHK(accept_commit(d, c->small_i() + SM_TARGET, k, c->small_i() + SM_RES, c->small_i() + SM_TOK, c->pos_dev(),
+                         c->stream), "accept");
+    int32_t res[2];
+    int rc = readback(c, c->small_i() + SM_RES, sizeof(res), res);
+    if (rc) return rc;
+    *n_accepted_out = res[0];
+    *next_token_out = res[1];
+    c->n += res[0] + 1;
+    c->state = ST_IDLE;
+    c->k_pending = 0;
+    c->st.cycles++; c->st.drafted += k; c->st.accepted += res[0]; c->st.committed += res[0] + 1;
+    return SSD_OK;
+}
+
+int ssd_force_commit(ssd_ctx* c, const int32_t* draft, int k, int n_accepted, int32_t next_token)
+{
+    if (!c || !draft) return c ? fail(c, SSD_EINVAL, "force_commit: bad argument") : SSD_EINVAL;
+    if (c->state != ST_VERIFIED) return fail(c, SSD_ESTATE, "force_commit must follow verify");
+    if (k != c->k_pending || n_accepted < 0 || n_accepted > k || next_token < 0 || next_token >= c->D.V)
+        return fail(c, SSD_EINVAL, "force_commit: bad argument");
+    HIPCHK(set_state(c->small_i() + SM_TOK, next_token, c->pos_dev(), c->n - 1 + n_accepted + 1, c->stream), "set_state");
+    HIPCHK(hipStreamSynchronize(c->stream), "sync");
+    c->n += n_accepted + 1;
+    c->state = ST_IDLE;
+    c->k_pending = 0;
+    c->st.cycles++; c->st.drafted += k; c->st.accepted += n_accepted; c->st.committed += n_accepted + 1;
+    return SSD_OK;
+}
+
+int ssd_copy_logits(ssd_ctx* c, int row_begin, int n_rows, float* logits_out)
+{
+    if (!c || !logits_out || row_begin < 0 || n_rows < 1) return c ? fail(c, SSD_EINVAL, "copy_logits: bad argument") : SSD_EINVAL;
+    if (c->state < ST_IDLE) return fail(c, SSD_ESTATE, "no logits yet");
+    if (row_begin + n_rows > c->logit_rows) return fail(c, SSD_EINVAL, "copy_logits: rows out of range");
+    HIPCHK(hipMemcpyAsync(logits_out, c->f(c->lay.logits) + (size_t)row_begin * c->D.V,
+                          (size_t)n_rows * c->D.V * sizeof(float), hipMemcpyDeviceToHost, c->stream), "logits copy");
+    HIPCHK(hipStreamSynchronize(c->stream), "sync");
+    return SSD_OK;
+}
+
+int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out, float* tap_conf_out,
+                         float* tap_maxprob_out, int32_t* tap_argmax_out)
+{
+    if (!c || !conf_out || row_begin < 0 || n_rows < 1) return c ? fail(c, SSD_EINVAL, "layer_confidence: bad argument") : SSD_EINVAL;
+    if (c->state < ST_IDLE || c->tap_rows == 0) return fail(c, SSD_ESTATE, "no hidden-state taps: call after prefill or verify");
+    if (row_begin + n_rows > c->tap_rows) return fail(c, SSD_EINVAL, "layer_confidence: rows out of range");
+    const Dims& D = c->D;
+    const Layout& Y = c->lay;
+    const int R = 2 * D.L;
+    float* confd = c->small_f() + SM_CONF;            // [R] conf, [R] maxprob, [R] argmax
+    if ((size_t)(SM_CONF + 3 * R) * 4 > 4096) return fail(c, SSD_ECAPACITY, "too many layers for the confidence scratch");
+    for (int r = 0; r < n_rows; r++) {
+        const float* taps = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
+        HIPCHK(rmsnorm_rows(taps, c->w.final_norm, R, D.d, D.eps, c->f(Y.tapn), c->stream), "rmsnorm taps");
+        for (int b = 0; b < R; b += 16) {
+            int M = R - b < 16 ? R - b : 16;
+            RowsGemm lm = {};
+            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = c->f(Y.tapn) + (size_t)b * D.d;
+            lm.y = c->f(Y.logits) + (size_t)b * D.V; lm.ldy = D.V; lm.M = M; lm.mode = 0;
+            TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm conf lmhead");
+        }
+        HIPCHK(vocab_reduce(c->f(Y.logits), R, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, nullptr, 1,
+                            reinterpret_cast<int32_t*>(confd + 2 * R), confd + R, confd, c->stream), "vocab_reduce conf");
+        std::vector<float> hb(3 * R);
+        int rc = readback(c, confd, sizeof(float) * 3 * R, hb.data());
+        if (rc) return rc;
+        for (int l = 0; l < D.L; l++) {
+            float ca = hb[l * 2], cb = hb[l * 2 + 1];
+            conf_out[(size_t)r * D.L + l] = c->cfg.conf_taps == 2 ? 0.5f * (ca + cb) : cb;
+            for (int t = 0; t < 2; t++) {
+                size_t o = ((size_t)r * D.L + l) * 2 + t;
+                if (tap_conf_out) tap_conf_out[o] = hb[l * 2 + t];
+                if (tap_maxprob_out) tap_maxprob_out[o] = hb[R + l * 2 + t];
+                if (tap_argmax_out) memcpy(&tap_argmax_out[o], &hb[2 * R + l * 2 + t], 4);
+            }
+        }
+    }
+    c->logit_rows = 0;  // the logits buffer was reused
+    c->st.confidence_rows += (int64_t)n_rows * R;
+    return SSD_OK;
+}
+
+int ssd_profile_select(ssd_ctx* c, int kernel_id)
+{
+    if (!c || kernel_id < -1 || kernel_id >= SSD_K_COUNT) return c ? fail(c, SSD_EINVAL, "profile_select: bad kernel id") : SSD_EINVAL;
+    c->prof_kid = kernel_id;
+    c->prof_used = 0;
+    return SSD_OK;
+}
+
+int ssd_profile_read(ssd_ctx* c, int64_t* launches_out, double* total_ms_out)
+{
+    if (!c || !launches_out || !total_ms_out) return SSD_EINVAL;
+    *launches_out = 0; *total_ms_out = 0.0;
+    if (c->prof_used == 0) return SSD_OK;
+    HIPCHK(hipStreamSynchronize(c->stream), "profile sync");
+    double tot = 0.0;
+    for (size_t i = 0; i < c->prof_used; i++) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, c->prof_ev[i].first, c->prof_ev[i].second), "event elapsed");
+        tot += ms;
+    }
+    *launches_out = (int64_t)c->prof_used;
+    *total_ms_out = tot;
+    return SSD_OK;
+}
+
+int ssd_kv_poison_stale(ssd_ctx* c)
+{
+    if (!c) return SSD_EINVAL;
+    if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "kv_poison_stale needs an idle prefilled sequence");
+    HIPCHK(kv_poison(c->D, c->ws + c->lay.kv, c->pos_dev(), c->stream), "kv_poison");
+    HIPCHK(hipStreamSynchronize(c->stream), "sync");
+    return SSD_OK;
+}
+
+int ssd_hbm_read_probe(const void* dev, size_t bytes, int iters, void* hip_stream, float* ms_out)
+{
+    if (!dev || bytes < 16 || iters < 1 || !ms_out || reinterpret_cast<uintptr_t>(dev) % 16) return SSD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    float* sink = nullptr;
+    hipEvent_t e0, e1;
+    if (hipMalloc((void**)&sink, 256) != hipSuccess) return SSD_EHIP;
+    int rc = SSD_OK;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) rc = SSD_EHIP;
+    if (!rc && read_probe(dev, bytes, sink, s) != hipSuccess) rc = SSD_EHIP;  // warm-up
+    if (!rc) {
+        (void)hipEventRecord(e0, s);
+        for (int i = 0; i < iters && !rc; i++)
+            if (read_probe(dev, bytes, sink, s) != hipSuccess) rc = SSD_EHIP;
+        (void)hipEventRecord(e1, s);
+        if (hipEventSynchronize(e1) != hipSuccess) rc = SSD_EHIP;
+        float ms = 0.f;
+        if (!rc && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = SSD_EHIP;
+        *ms_out = ms / (float)iters;
+    }
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    (void)hipFree(sink);
+    return rc;
+}
+
+}  // extern "C"

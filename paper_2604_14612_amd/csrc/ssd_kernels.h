@@ -1,0 +1,97 @@
+// Internal launch interface between the host state machine (ssd_api.cpp) and the gfx950
+// kernels (ssd_kernels.hip).  Plain pointers and sizes only; every launcher enqueues on the
+// given stream and returns the HIP status of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssdk {
+
+enum WeightType { WT_F32 = 0, WT_BF16 = 1 };
+
+// Shape constants shared by all launches of one context.
+struct Dims {
+    int L, d, H, Hkv, hd, dq, dkv, f, V, max_seq;
+    float eps;
+    int wt;  // WeightType; the KV cache uses the same element type
+};
+
+// x[r][:] = embed[tok[r]][:] widened to fp32.  Row 0 may come from device memory
+// (tok0_dev != nullptr), the others from the by-value array.
+struct TokArg { int32_t t[16]; };
+hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok0_dev, TokArg toks, int M,
+                      float* x, hipStream_t s);
+
+// ---- single-row (draft / vanilla decode) path: weight-streaming GEMV kernels ----------------
+// h = rmsnorm(x, gain); q,k,v = Wq h, Wk h, Wv h; rotary on q,k at position *pos_dev + pos_off;
+// q -> qbuf (fp32), k,v -> cache rows of this layer.
+hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* wv, const float* gain,
+                    const float* x, const float* rope, const int* pos_dev, int pos_off, float* qbuf,
+                    void* kcache_l, void* vcache_l, hipStream_t s);
+// x[n] += W[n][:] . in[:]   (N x K), optional tap copy of the updated x
+hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap,
+                      hipStream_t s);
+// act[n] = silu(Wg[n] . h) * (Wu[n] . h), h = rmsnorm(x, gain)
+hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const float* gain, const float* x,
+                       float* act, hipStream_t s);
+// logits[n] = Wlm[n] . rmsnorm(x, gain)
+hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits,
+                       hipStream_t s);
+
+// ---- multi-row (verify / prefill / confidence) path ------------------------------------------
+// out[r][:] = rmsnorm(in[r][:], gain) for r < M   (rows of length K)
+hipError_t rmsnorm_rows(const float* in, const float* gain, int M, int K, float eps, float* out, hipStream_t s);
+// Y[r][n] (op)= sum_k W[n][k] X[r][k], r < M <= 16.  bf16 weights use MFMA tiles, fp32 weights plain FMAs.
+//   mode 0: store to y (ld = N_total), up to three stacked matrices (QKV) written side by side
+//   mode 1: y += (residual add), optional tap copy (tap row stride tap_ld)
+//   mode 2: y = silu(W0 x) * (W1 x)  (two matrices of n0 rows each)
+struct RowsGemm {
+    const void* w[3];
+    int n[3];
+    int K;
+    const float* x;  // [M][K]
+    float* y;        // [M][ldy]
+    int ldy;
+    float* tap;      // mode 1 only, may be null
+    int tap_ld;
+    int M;
+    int mode;
+};
+hipError_t gemm_rows(const Dims& D, const RowsGemm& g, hipStream_t s);
+// rotary on q,k rows + cache write for the multi-row path. qkv: [M][dq + 2 dkv]; q is rotated in place.
+hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int* pos_dev, int pos_off, int M,
+                        void* kcache_l, void* vcache_l, hipStream_t s);
+
+// ---- attention over the KV cache ---------------------------------------------------------------
+// Row r (r < M) at position p_r = *pos_dev + pos_off + r attends cache positions 0..p_r.
+// q: [M][ldq] fp32 (head h at offset h*hd); out: [M][dq].  part: scratch for the split partials.
+hipError_t attention(const Dims& D, const float* q, int ldq, const void* kcache_l, const void* vcache_l,
+                     const int* pos_dev, int pos_off, int pos_host_hint, int M, float* part, float* out,
+                     hipStream_t s);
+size_t attention_scratch_floats(const Dims& D, int max_rows);
+
+// ---- vocabulary reduction ------------------------------------------------------------------------
+// Per row of logits [M][V]: arg-max (lowest index on ties), softmax max-probability and, when
+// conf != nullptr, the entropy confidence of Eq. 1-4 (clamp applied first).  tok_out[r*tok_stride]
+// receives the arg-max when tok_out != nullptr.
+hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float eps, int32_t* tok_out,
+                        int tok_stride, int32_t* argmax_out, float* maxprob_out, float* conf_out,
+                        hipStream_t s);
+
+// ---- small state kernels ---------------------------------------------------------------------------
+// Greedy acceptance on the device: a = longest prefix with draft[j] == target[j]; writes
+// res[0] = a, res[1] = target[a]; tok0 = target[a]; *pos_dev += a + 1.
+hipError_t accept_commit(TokArg draft, const int32_t* target_dev, int k, int32_t* res, int32_t* tok0,
+                         int* pos_dev, hipStream_t s);
+// tok0 = token, *pos_dev = pos
+hipError_t set_state(int32_t* tok0, int32_t token, int* pos_dev, int pos, hipStream_t s);
+// *pos_dev += delta;  tok0 = src[0] when src != nullptr
+hipError_t advance_state(int* pos_dev, int delta, int32_t* tok0, const int32_t* src, hipStream_t s);
+// NaN-fill cache positions >= *pos_dev of all layers
+hipError_t kv_poison(const Dims& D, void* kv_all, const int* pos_dev, hipStream_t s);
+// copy n floats
+hipError_t copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
+// read-only streaming probe; *sink_dev receives a checksum so the loads cannot be dropped
+hipError_t read_probe(const void* dev, size_t bytes, float* sink_dev, hipStream_t s);
+
+}  // namespace ssdk

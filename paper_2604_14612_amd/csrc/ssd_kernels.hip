@@ -1,0 +1,982 @@
+// gfx950 (CDNA4, wave64) kernels of the self-speculative decoding hot path.
+//
+// Single-row path (draft model of Section 3 and vanilla decoding): bf16/fp32 weight-streaming
+// GEMV kernels -- every lane issues 128-bit loads along K, fp32 FMAs against the activation
+// vector held in LDS, wave-shuffle reduction; RMSNorm is fused into the prologue, rotary
+// embedding + KV-cache write / residual add / SwiGLU into the epilogues.
+// Multi-row path (verification of k+1 rows, prompt rows, per-layer confidence rows): the same
+// weight stream feeds 16x16x32 bf16 MFMA tiles, activations entering as an exact bf16 hi+lo
+// split of their fp32 values.
+// Attention reads the cache through LDS-staged K/V tiles, split over the sequence.
+#include "ssd_kernels.h"
+
+#include <math.h>
+
+namespace ssdk {
+
+// ---------------------------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);                                            // round to nearest even
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int VEC = 4;  // elements per 128-bit load
+    __device__ static __forceinline__ void load(const float* p, float (&o)[4])
+    {
+        float4 v = *reinterpret_cast<const float4*>(p);
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+    __device__ static __forceinline__ float get(const float* p, size_t i) { return p[i]; }
+    __device__ static __forceinline__ void put(float* p, size_t i, float v) { p[i] = v; }
+};
+template <> struct Elem<uint16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ void load(const uint16_t* p, float (&o)[8])
+    {
+        uint4 v = *reinterpret_cast<const uint4*>(p);
+        o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+        o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+        o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
+        o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+    __device__ static __forceinline__ float get(const uint16_t* p, size_t i) { return bf16_bits_to_f32(p[i]); }
+    __device__ static __forceinline__ void put(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Block-wide sum for blocks of NW waves; red must hold NW floats. All threads get the result.
+template <int NW>
+__device__ __forceinline__ float block_sum(float v, float* red)
+{
+    v = wave_sum(v);
+    int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; i++) t += red[i];
+    return t;
+}
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---------------------------------------------------------------------------------------------
+// embedding gather
+// ---------------------------------------------------------------------------------------------
+template <typename WT>
+__global__ void embed_kernel(const WT* __restrict__ E, const int32_t* tok0_dev, TokArg toks, int d, int V,
+                             float* __restrict__ x)
+{
+    int r = blockIdx.y;
+    int t = (r == 0 && tok0_dev) ? tok0_dev[0] : toks.t[r];
+    t = min(max(t, 0), V - 1);
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < d; i += gridDim.x * blockDim.x)
+        x[(size_t)r * d + i] = Elem<WT>::get(E, (size_t)t * d + i);
+}
+
+hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok0_dev, TokArg toks, int M, float* x,
+                      hipStream_t s)
+{
+    dim3 grid(ceil_div(D.d, 256), M);
+    if (D.wt == WT_BF16)
+        hipLaunchKernelGGL(embed_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)embed, tok0_dev, toks, D.d,
+                           D.V, x);
+    else
+        hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, s, (const float*)embed, tok0_dev, toks, D.d, D.V, x);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// single-row weight-streaming GEMV
+// ---------------------------------------------------------------------------------------------
+constexpr int GEMV_WAVES = 4;
+constexpr int GEMV_THREADS = GEMV_WAVES * 64;
+constexpr int GEMV_ROWS = 4;  // weight rows in flight per wave iteration
+
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_STORE = 3 };
+
+struct GemvP {
+    const void* w0; const void* w1; const void* w2;
+    const float* in;    // [K]
+    const float* gain;  // rmsnorm gain or nullptr (input used as is)
+    float eps;
+    int K;
+    int n_units;        // groups of GEMV_ROWS rows (EPI_SWIGLU: 2 output rows = 4 weight rows)
+    float* y;           // QKV: qbuf; RESID: residual (+=); SWIGLU: act; STORE: logits
+    float* tap;
+    void* kc; void* vc;
+    const float* rope;  // [max_seq][hd/2][2] (cos, sin)
+    const int* pos_dev; int pos_off;
+    int hd, dq, dkv, max_seq;
+};
+
+// Loads the input vector into LDS (optionally RMS-normalised with gain applied).
+__device__ __forceinline__ void gemv_stage_input(const GemvP& p, float* xs, float* red)
+{
+    float ss = 0.f;
+    for (int i = threadIdx.x * 4; i < p.K; i += GEMV_THREADS * 4) {
+        float4 v = *reinterpret_cast<const float4*>(p.in + i);
+        *reinterpret_cast<float4*>(xs + i) = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    if (p.gain) {
+        float tot = block_sum<GEMV_WAVES>(ss, red);
+        float sc = 1.0f / sqrtf(tot / (float)p.K + p.eps);
+        for (int i = threadIdx.x * 4; i < p.K; i += GEMV_THREADS * 4) {
+            float4 v = *reinterpret_cast<float4*>(xs + i);
+            float4 g = *reinterpret_cast<const float4*>(p.gain + i);
+            v.x = v.x * sc * g.x; v.y = v.y * sc * g.y; v.z = v.z * sc * g.z; v.w = v.w * sc * g.w;
+            *reinterpret_cast<float4*>(xs + i) = v;
+        }
+    }
+    __syncthreads();
+}
+
+template <typename WT, int EPI>
+__global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(GemvP p)
+{
+    extern __shared__ __align__(16) float xs[];
+    __shared__ float red[GEMV_WAVES];
+    constexpr int VEC = Elem<WT>::VEC;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int K = p.K;
+
+    gemv_stage_input(p, xs, red);
+
+    for (int u = blockIdx.x * GEMV_WAVES + wave; u < p.n_units; u += gridDim.x * GEMV_WAVES) {
+        const WT* wr[GEMV_ROWS];
+        int kind = 0, head = 0, i0 = 0;  // QKV bookkeeping
+        if (EPI == EPI_QKV) {
+            const int half = p.hd >> 1, uph = p.hd >> 2;  // units per head
+            const int nq = p.dq >> 2, nk = p.dkv >> 2;
+            if (u < nq + nk) {
+                const WT* base; int uu;
+                if (u < nq) { kind = 0; base = (const WT*)p.w0; uu = u; }
+                else { kind = 1; base = (const WT*)p.w1; uu = u - nq; }
+                head = uu / uph; i0 = (uu % uph) * 2;
+                size_t r0 = (size_t)head * p.hd + i0;
+                wr[0] = base + r0 * K; wr[1] = base + (r0 + half) * K;
+                wr[2] = base + (r0 + 1) * K; wr[3] = base + (r0 + 1 + half) * K;
+            } else {
+                kind = 2; i0 = (u - nq - nk) * 4;
+                const WT* base = (const WT*)p.w2;
+#pragma unroll
+                for (int r = 0; r < 4; r++) wr[r] = base + (size_t)(i0 + r) * K;
+            }
+        } else if (EPI == EPI_SWIGLU) {
+            size_t n = (size_t)u * 2;
+            wr[0] = (const WT*)p.w0 + n * K; wr[1] = (const WT*)p.w1 + n * K;
+            wr[2] = (const WT*)p.w0 + (n + 1) * K; wr[3] = (const WT*)p.w1 + (n + 1) * K;
+        } else {
+            size_t n = (size_t)u * 4;
+#pragma unroll
+            for (int r = 0; r < 4; r++) wr[r] = (const WT*)p.w0 + (n + r) * K;
+        }
+
+        float acc[GEMV_ROWS] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+        for (int k = lane * VEC; k < K; k += 64 * VEC) {
+            float wv[GEMV_ROWS][VEC];
+#pragma unroll
+            for (int r = 0; r < GEMV_ROWS; r++) Elem<WT>::load(wr[r] + k, wv[r]);
+            float xv[VEC];
+#pragma unroll
+            for (int j = 0; j < VEC; j += 4) {
+                float4 t = *reinterpret_cast<const float4*>(xs + k + j);
+                xv[j] = t.x; xv[j + 1] = t.y; xv[j + 2] = t.z; xv[j + 3] = t.w;
+            }
+#pragma unroll
+            for (int r = 0; r < GEMV_ROWS; r++)
+#pragma unroll
+                for (int j = 0; j < VEC; j++) acc[r] = fmaf(wv[r][j], xv[j], acc[r]);
+        }
+#pragma unroll
+        for (int r = 0; r < GEMV_ROWS; r++) acc[r] = wave_sum(acc[r]);
+
+        if (lane == 0) {
+            if (EPI == EPI_QKV) {
+                const int half = p.hd >> 1;
+                if (kind == 2) {
+                    int kvh = i0 / p.hd, e = i0 % p.hd;
+                    int pos = p.pos_dev[0] + p.pos_off;
+                    size_t o = ((size_t)kvh * p.max_seq + pos) * p.hd + e;
+#pragma unroll
+                    for (int r = 0; r < 4; r++) Elem<WT>::put((WT*)p.vc, o + r, acc[r]);
+                } else {
+                    int pos = p.pos_dev[0] + p.pos_off;
+                    const float* cs = p.rope + ((size_t)pos * half + i0) * 2;
+                    float c0 = cs[0], s0 = cs[1], c1 = cs[2], s1 = cs[3];
+                    float a0 = acc[0] * c0 - acc[1] * s0, b0 = acc[1] * c0 + acc[0] * s0;
+                    float a1 = acc[2] * c1 - acc[3] * s1, b1 = acc[3] * c1 + acc[2] * s1;
+                    if (kind == 0) {
+                        float* q = p.y + (size_t)head * p.hd + i0;
+                        q[0] = a0; q[half] = b0; q[1] = a1; q[1 + half] = b1;
+                    } else {
+                        size_t o = ((size_t)head * p.max_seq + pos) * p.hd + i0;
+                        WT* kc = (WT*)p.kc;
+                        Elem<WT>::put(kc, o, a0); Elem<WT>::put(kc, o + half, b0);
+                        Elem<WT>::put(kc, o + 1, a1); Elem<WT>::put(kc, o + 1 + half, b1);
+                    }
+                }
+            } else if (EPI == EPI_RESID) {
+                size_t n = (size_t)u * 4;
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    float v = p.y[n + r] + acc[r];
+                    p.y[n + r] = v;
+                    if (p.tap) p.tap[n + r] = v;
+                }
+            } else if (EPI == EPI_SWIGLU) {
+                size_t n = (size_t)u * 2;
+                p.y[n] = acc[0] / (1.0f + __expf(-acc[0])) * acc[1];
+                p.y[n + 1] = acc[2] / (1.0f + __expf(-acc[2])) * acc[3];
+            } else {
+                size_t n = (size_t)u * 4;
+#pragma unroll
+                for (int r = 0; r < 4; r++) p.y[n + r] = acc[r];
+            }
+        }
+    }
+}
+
+template <typename WT, int EPI>
+static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s)
+{
+    size_t lds = (size_t)p.K * sizeof(float);
+    static size_t lds_limit = 0;  // per instantiation
+    if (lds > 64 * 1024 && lds > lds_limit) {
+        hipError_t e = hipFuncSetAttribute((const void*)gemv_kernel<WT, EPI>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        lds_limit = lds;
+    }
+    int blocks = ceil_div(p.n_units, GEMV_WAVES);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL((gemv_kernel<WT, EPI>), dim3(blocks), dim3(GEMV_THREADS), lds, s, p);
+    return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_gemv(int wt, const GemvP& p, hipStream_t s)
+{
+    return wt == WT_BF16 ? launch_gemv_t<uint16_t, EPI>(p, s) : launch_gemv_t<float, EPI>(p, s);
+}
+
+hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* wv, const float* gain, const float* x,
+                    const float* rope, const int* pos_dev, int pos_off, float* qbuf, void* kc, void* vc, hipStream_t s)
+{
+    GemvP p = {};
+    p.w0 = wq; p.w1 = wk; p.w2 = wv; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d;
+    p.n_units = (D.dq + 2 * D.dkv) / 4;
+    p.y = qbuf; p.kc = kc; p.vc = vc; p.rope = rope; p.pos_dev = pos_dev; p.pos_off = pos_off;
+    p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq;
+    return launch_gemv<EPI_QKV>(D.wt, p, s);
+}
+
+hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap, hipStream_t s)
+{
+    GemvP p = {};
+    p.w0 = w; p.in = in; p.gain = nullptr; p.eps = D.eps; p.K = K; p.n_units = N / 4; p.y = x; p.tap = tap;
+    return launch_gemv<EPI_RESID>(D.wt, p, s);
+}
+
+hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const float* gain, const float* x, float* act,
+                       hipStream_t s)
+{
+    GemvP p = {};
+    p.w0 = wg; p.w1 = wu; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_units = D.f / 2; p.y = act;
+    return launch_gemv<EPI_SWIGLU>(D.wt, p, s);
+}
+
+hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits, hipStream_t s)
+{
+    GemvP p = {};
+    p.w0 = wlm; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_units = D.V / 4; p.y = logits;
+    return launch_gemv<EPI_STORE>(D.wt, p, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// multi-row path
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rmsnorm_rows_kernel(const float* __restrict__ in, const float* __restrict__ gain,
+                                                           int K, float eps, float* __restrict__ out)
+{
+    __shared__ float red[4];
+    const float* x = in + (size_t)blockIdx.x * K;
+    float* o = out + (size_t)blockIdx.x * K;
+    float ss = 0.f;
+    for (int i = threadIdx.x * 4; i < K; i += 1024) {
+        float4 v = *reinterpret_cast<const float4*>(x + i);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    float tot = block_sum<4>(ss, red);
+    float sc = 1.0f / sqrtf(tot / (float)K + eps);
+    for (int i = threadIdx.x * 4; i < K; i += 1024) {
+        float4 v = *reinterpret_cast<const float4*>(x + i);
+        float4 g = *reinterpret_cast<const float4*>(gain + i);
+        v.x = v.x * sc * g.x; v.y = v.y * sc * g.y; v.z = v.z * sc * g.z; v.w = v.w * sc * g.w;
+        *reinterpret_cast<float4*>(o + i) = v;
+    }
+}
+
+hipError_t rmsnorm_rows(const float* in, const float* gain, int M, int K, float eps, float* out, hipStream_t s)
+{
+    hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3(M), dim3(256), 0, s, in, gain, K, eps, out);
+    return hipGetLastError();
+}
+
+struct RowsP {
+    const void* w[3];
+    int n[3];       // rows of each stacked matrix (multiples of 16)
+    int K;
+    const float* x; // [M][K]
+    float* y; int ldy;
+    float* tap; int tap_ld;
+    int M;
+};
+
+enum { RM_STORE = 0, RM_RESID = 1, RM_SWIGLU = 2 };
+
+__device__ __forceinline__ void rows_epilogue(const RowsP& p, int mode, int r, size_t col, float v, float v2)
+{
+    if (mode == RM_STORE) {
+        p.y[(size_t)r * p.ldy + col] = v;
+    } else if (mode == RM_RESID) {
+        float* dst = p.y + (size_t)r * p.ldy + col;
+        float t = *dst + v;
+        *dst = t;
+        if (p.tap) p.tap[(size_t)r * p.tap_ld + col] = t;
+    } else {
+        p.y[(size_t)r * p.ldy + col] = v / (1.0f + __expf(-v)) * v2;
+    }
+}
+
+// --- bf16 weights: MFMA tiles -------------------------------------------------------------------
+// One block owns 16 consecutive output rows (RM_SWIGLU: 16 gate rows and the matching 16 up rows).
+// Its 8 waves interleave over the K dimension in steps of 32: the weight tile is the MFMA A
+// operand loaded straight from global memory (lane (r, g): row r, 8 consecutive k at 8g), the
+// activations are the B operand (lane (c, g): token row c, same 8 k), split on the fly into
+// bf16 hi = rne(x) and lo = rne(x - hi), so that hi + lo carries 16 mantissa bits of x.
+constexpr int MF_WAVES = 8;
+constexpr int MF_THREADS = MF_WAVES * 64;
+
+__device__ __forceinline__ void split_hi_lo(const float (&x)[8], bf16x8_t& hi, bf16x8_t& lo)
+{
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        __bf16 h = (__bf16)x[j];
+        hi[j] = h;
+        lo[j] = (__bf16)(x[j] - (float)h);
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(MF_THREADS) void gemm_rows_mfma_kernel(RowsP p)
+{
+    __shared__ float red[MF_WAVES][2][256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int K = p.K;
+
+    // which matrix / row tile does this block own?
+    int tile = blockIdx.x;
+    const uint16_t* W0; const uint16_t* W1 = nullptr;
+    size_t col0;  // first output column of the tile
+    if (MODE == RM_SWIGLU) {
+        W0 = (const uint16_t*)p.w[0] + (size_t)tile * 16 * K;
+        W1 = (const uint16_t*)p.w[1] + (size_t)tile * 16 * K;
+        col0 = (size_t)tile * 16;
+    } else {
+        int t0 = p.n[0] >> 4, t1 = p.n[1] >> 4;
+        if (tile < t0) { W0 = (const uint16_t*)p.w[0] + (size_t)tile * 16 * K; col0 = (size_t)tile * 16; }
+        else if (tile < t0 + t1) { W0 = (const uint16_t*)p.w[1] + (size_t)(tile - t0) * 16 * K; col0 = (size_t)tile * 16; }
+        else { W0 = (const uint16_t*)p.w[2] + (size_t)(tile - t0 - t1) * 16 * K; col0 = (size_t)tile * 16; }
+    }
+    const uint16_t* a0p = W0 + (size_t)r16 * K + g * 8;
+    const uint16_t* a1p = MODE == RM_SWIGLU ? W1 + (size_t)r16 * K + g * 8 : nullptr;
+    const bool have_col = r16 < p.M;
+    const float* bp = p.x + (size_t)(have_col ? r16 : 0) * K + g * 8;
+
+    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    const int steps = (K + 31) >> 5;
+#pragma unroll 2
+    for (int st = wave; st < steps; st += MF_WAVES) {
+        const int k0 = st << 5;
+        const bool in_k = (k0 + g * 8) < K;  // K is a multiple of 8: a lane's 8 k are all in or all out
+        bf16x8_t a0 = {}, a1 = {};
+        float xb[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (in_k) {
+            a0 = *reinterpret_cast<const bf16x8_t*>(a0p + k0);
+            if (MODE == RM_SWIGLU) a1 = *reinterpret_cast<const bf16x8_t*>(a1p + k0);
+            if (have_col) {
+                float4 t0 = *reinterpret_cast<const float4*>(bp + k0);
+                float4 t1 = *reinterpret_cast<const float4*>(bp + k0 + 4);
+                xb[0] = t0.x; xb[1] = t0.y; xb[2] = t0.z; xb[3] = t0.w;
+                xb[4] = t1.x; xb[5] = t1.y; xb[6] = t1.z; xb[7] = t1.w;
+            }
+        }
+        bf16x8_t bh, bl;
+        split_hi_lo(xb, bh, bl);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh, acc0, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl, acc0, 0, 0, 0);
+        if (MODE == RM_SWIGLU) {
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh, acc1, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bl, acc1, 0, 0, 0);
+        }
+    }
+    // D layout: lane (c = lane % 16, g = lane / 16) holds rows 4g..4g+3 of column c
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        red[wave][0][(g * 4 + j) * 16 + r16] = acc0[j];
+        if (MODE == RM_SWIGLU) red[wave][1][(g * 4 + j) * 16 + r16] = acc1[j];
+    }
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        int row = threadIdx.x & 15;   // output feature within the tile (fastest: coalesced stores)
+        int c = threadIdx.x >> 4;     // token row
+        if (c < p.M) {
+            float v = 0.f, v2 = 0.f;
+#pragma unroll
+            for (int w = 0; w < MF_WAVES; w++) {
+                v += red[w][0][row * 16 + c];
+                if (MODE == RM_SWIGLU) v2 += red[w][1][row * 16 + c];
+            }
+            rows_epilogue(p, MODE, c, col0 + row, v, v2);
+        }
+    }
+}
+
+// --- fp32 weights (and any dtype as a plain cross-check): FMA rows --------------------------------
+// One wave owns 4 consecutive output rows (RM_SWIGLU: 2 gate + 2 up rows) and up to 4 token rows at a time.
+template <typename WT, int MODE>
+__global__ __launch_bounds__(256) void gemm_rows_fma_kernel(RowsP p)
+{
+    constexpr int VEC = Elem<WT>::VEC;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int K = p.K;
+    const int n_out = MODE == RM_SWIGLU ? p.n[0] : p.n[0] + p.n[1] + p.n[2];
+    const int n_units = MODE == RM_SWIGLU ? n_out / 2 : n_out / 4;
+    for (int u = blockIdx.x * 4 + wave; u < n_units; u += gridDim.x * 4) {
+        const WT* wr[4];
+        size_t col[4];
+        if (MODE == RM_SWIGLU) {
+            size_t n = (size_t)u * 2;
+            wr[0] = (const WT*)p.w[0] + n * K; wr[1] = (const WT*)p.w[1] + n * K;
+            wr[2] = (const WT*)p.w[0] + (n + 1) * K; wr[3] = (const WT*)p.w[1] + (n + 1) * K;
+            col[0] = n; col[1] = n; col[2] = n + 1; col[3] = n + 1;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                size_t n = (size_t)u * 4 + r;
+                col[r] = n;
+                if (n < (size_t)p.n[0]) wr[r] = (const WT*)p.w[0] + n * K;
+                else if (n < (size_t)(p.n[0] + p.n[1])) wr[r] = (const WT*)p.w[1] + (n - p.n[0]) * K;
+                else wr[r] = (const WT*)p.w[2] + (n - p.n[0] - p.n[1]) * K;
+            }
+        }
+        for (int m0 = 0; m0 < p.M; m0 += 4) {
+            float acc[4][4] = {};
+            for (int k = lane * VEC; k < K; k += 64 * VEC) {
+                float wv[4][VEC];
+#pragma unroll
+                for (int r = 0; r < 4; r++) Elem<WT>::load(wr[r] + k, wv[r]);
+#pragma unroll
+                for (int m = 0; m < 4; m++) {
+                    if (m0 + m < p.M) {
+                        const float* xr = p.x + (size_t)(m0 + m) * K + k;
+#pragma unroll
+                        for (int j = 0; j < VEC; j++) {
+                            float xv = xr[j];
+#pragma unroll
+                            for (int r = 0; r < 4; r++) acc[r][m] = fmaf(wv[r][j], xv, acc[r][m]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+#pragma unroll
+                for (int m = 0; m < 4; m++) acc[r][m] = wave_sum(acc[r][m]);
+            if (lane == 0) {
+                for (int m = 0; m < 4 && m0 + m < p.M; m++) {
+                    if (MODE == RM_SWIGLU) {
+                        rows_epilogue(p, MODE, m0 + m, col[0], acc[0][m], acc[1][m]);
+                        rows_epilogue(p, MODE, m0 + m, col[2], acc[2][m], acc[3][m]);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; r++) rows_epilogue(p, MODE, m0 + m, col[r], acc[r][m], 0.f);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int MODE>
+static hipError_t gemm_rows_mode(const Dims& D, const RowsP& p, hipStream_t s)
+{
+    if (D.wt == WT_BF16) {
+        int tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
+        hipLaunchKernelGGL((gemm_rows_mfma_kernel<MODE>), dim3(tiles), dim3(MF_THREADS), 0, s, p);
+    } else {
+        int n_out = MODE == RM_SWIGLU ? p.n[0] : p.n[0] + p.n[1] + p.n[2];
+        int units = MODE == RM_SWIGLU ? n_out / 2 : n_out / 4;
+        int blocks = ceil_div(units, 4);
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL((gemm_rows_fma_kernel<float, MODE>), dim3(blocks), dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t gemm_rows(const Dims& D, const RowsGemm& g, hipStream_t s)
+{
+    RowsP p = {};
+    for (int i = 0; i < 3; i++) { p.w[i] = g.w[i]; p.n[i] = g.n[i]; }
+    p.K = g.K; p.x = g.x; p.y = g.y; p.ldy = g.ldy; p.tap = g.tap; p.tap_ld = g.tap_ld; p.M = g.M;
+    if (g.M < 1 || g.M > 16) return hipErrorInvalidValue;
+    switch (g.mode) {
+        case RM_STORE: return gemm_rows_mode<RM_STORE>(D, p, s);
+        case RM_RESID: return gemm_rows_mode<RM_RESID>(D, p, s);
+        case RM_SWIGLU: return gemm_rows_mode<RM_SWIGLU>(D, p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// rotary + cache write for the multi-row path: one thread per (row, head slot, pair index)
+template <typename KT>
+__global__ void rope_kv_rows_kernel(float* __restrict__ qkv, const float* __restrict__ rope, const int* pos_dev,
+                                    int pos_off, int M, int H, int Hkv, int hd, int max_seq, KT* __restrict__ kc,
+                                    KT* __restrict__ vc)
+{
+    const int half = hd >> 1;
+    const int dq = H * hd, dkv = Hkv * hd, ld = dq + 2 * dkv;
+    const int per_row = (H + Hkv) * half + dkv;  // q pairs, k pairs, v elements
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= M * per_row) return;
+    int r = idx / per_row, e = idx % per_row;
+    int pos = pos_dev[0] + pos_off + r;
+    float* row = qkv + (size_t)r * ld;
+    if (e < (H + Hkv) * half) {
+        int hs = e / half, i = e % half;  // head slot over q heads then k heads
+        const float* cs = rope + ((size_t)pos * half + i) * 2;
+        float c = cs[0], s = cs[1];
+        if (hs < H) {
+            float* v = row + (size_t)hs * hd;
+            float a = v[i], b = v[i + half];
+            v[i] = a * c - b * s;
+            v[i + half] = b * c + a * s;
+        } else {
+            int kvh = hs - H;
+            const float* v = row + dq + (size_t)kvh * hd;
+            float a = v[i], b = v[i + half];
+            size_t o = ((size_t)kvh * max_seq + pos) * hd;
+            Elem<KT>::put(kc, o + i, a * c - b * s);
+            Elem<KT>::put(kc, o + i + half, b * c + a * s);
+        }
+    } else {
+        int j = e - (H + Hkv) * half;  // element of v
+        int kvh = j / hd, i = j % hd;
+        Elem<KT>::put(vc, ((size_t)kvh * max_seq + pos) * hd + i, row[dq + dkv + j]);
+    }
+}
+
+hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int* pos_dev, int pos_off, int M, void* kc,
+                        void* vc, hipStream_t s)
+{
+    int per_row = (D.H + D.Hkv) * (D.hd / 2) + D.dkv;
+    int blocks = ceil_div(M * per_row, 256);
+    if (D.wt == WT_BF16)
+        hipLaunchKernelGGL(rope_kv_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, qkv, rope, pos_dev, pos_off, M,
+                           D.H, D.Hkv, D.hd, D.max_seq, (uint16_t*)kc, (uint16_t*)vc);
+    else
+        hipLaunchKernelGGL(rope_kv_rows_kernel<float>, dim3(blocks), dim3(256), 0, s, qkv, rope, pos_dev, pos_off, M, D.H,
+                           D.Hkv, D.hd, D.max_seq, (float*)kc, (float*)vc);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// attention over the cache: split over the sequence, K/V tiles staged through LDS
+// ---------------------------------------------------------------------------------------------
+constexpr int AT_THREADS = 256;
+constexpr int AT_TILE = 64;        // cache positions per LDS tile
+constexpr int AT_MAX_CHUNK = 2048; // positions one block may own (LDS score buffer)
+
+// partial layout per (row, head, split): [hd] unnormalised output, then m (max score), l (sum of exp)
+template <typename KT, int HD>
+__global__ __launch_bounds__(AT_THREADS) void attn_partial_kernel(const float* __restrict__ q, int ldq,
+                                                                  const KT* __restrict__ kc, const KT* __restrict__ vc,
+                                                                  const int* pos_dev, int pos_off, int M, int H, int Hkv,
+                                                                  int max_seq, int n_splits, float* __restrict__ part)
+{
+    constexpr int ROWB = HD * (int)sizeof(KT) + 16;  // padded LDS row (bytes) to spread banks
+    constexpr int NG = AT_THREADS / HD;              // position groups in the P.V phase
+    __shared__ __align__(16) unsigned char tile[AT_TILE * ROWB];
+    __shared__ float sc[AT_MAX_CHUNK];
+    __shared__ float red[4];
+    __shared__ float accs[NG][HD];
+
+    const int split = blockIdx.x, head = blockIdx.y, r = blockIdx.z;
+    const int kvh = head / (H / Hkv);
+    const int p0 = pos_dev[0] + pos_off;
+    const int n_ctx = p0 + r + 1;                        // this row sees positions 0..p0+r
+    const int chunk = (p0 + M + n_splits - 1) / n_splits; // same chunking for all rows of the block
+    const int j0 = split * chunk;
+    const int j1 = min(min(j0 + chunk, n_ctx), j0 + AT_MAX_CHUNK);  // host sizes chunk <= AT_MAX_CHUNK
+    float* out = part + (((size_t)r * H + head) * n_splits + split) * (HD + 2);
+    const int tid = threadIdx.x;
+    if (j1 <= j0) {  // nothing for this row in this split
+        if (tid < HD) out[tid] = 0.f;
+        if (tid == 0) { out[HD] = -INFINITY; out[HD + 1] = 0.f; }
+        return;
+    }
+    const int n = j1 - j0;
+    const KT* kbase = kc + ((size_t)kvh * max_seq + j0) * HD;
+    const KT* vbase = vc + ((size_t)kvh * max_seq + j0) * HD;
+    constexpr int EPV = 16 / (int)sizeof(KT);  // elements per 16-byte vector
+    constexpr int VPR = HD / EPV;              // vectors per cache row
+
+    // phase A: scores. 4 threads per position, each owns HD/4 dims of q in registers.
+    const int spos = tid >> 2, part4 = tid & 3;
+    constexpr int DPT = HD / 4;
+    float qr[DPT];
+    const float scale = 1.0f / sqrtf((float)HD);
+    {
+        const float* qv = q + (size_t)r * ldq + (size_t)head * HD + part4 * DPT;
+#pragma unroll
+        for (int i = 0; i < DPT; i++) qr[i] = qv[i] * scale;
+    }
+    for (int t0 = 0; t0 < n; t0 += AT_TILE) {
+        const int nt = min(AT_TILE, n - t0);
+        __syncthreads();
+        for (int v = tid; v < nt * VPR; v += AT_THREADS) {
+            int pr = v / VPR, pv = v % VPR;
+            uint4 d = *reinterpret_cast<const uint4*>(kbase + (size_t)(t0 + pr) * HD + pv * EPV);
+            *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = d;
+        }
+        __syncthreads();
+        float dot = 0.f;
+        if (spos < nt) {
+            const KT* kr = reinterpret_cast<const KT*>(tile + spos * ROWB) + part4 * DPT;
+#pragma unroll
+            for (int i = 0; i < DPT; i += EPV) {
+                float kv[EPV];
+                Elem<KT>::load(kr + i, kv);
+#pragma unroll
+                for (int j = 0; j < EPV; j++) dot = fmaf(qr[i + j], kv[j], dot);
+            }
+        }
+        dot += __shfl_xor(dot, 1, 64);
+        dot += __shfl_xor(dot, 2, 64);
+        if (spos < nt && part4 == 0) sc[t0 + spos] = dot;
+    }
+    __syncthreads();
+    // phase B: max, exp, sum
+    float mx = -INFINITY;
+    for (int j = tid; j < n; j += AT_THREADS) mx = fmaxf(mx, sc[j]);
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float ls = 0.f;
+    for (int j = tid; j < n; j += AT_THREADS) {
+        float e = __expf(sc[j] - mx);
+        sc[j] = e;
+        ls += e;
+    }
+    float lsum = block_sum<4>(ls, red);  // contains the barriers that publish sc[]
+    // phase C: o[d] = sum_j e_j V[j][d]; thread = (group, d)
+    const int d = tid % HD, grp = tid / HD;
+    float acc = 0.f;
+    for (int t0 = 0; t0 < n; t0 += AT_TILE) {
+        const int nt = min(AT_TILE, n - t0);
+        __syncthreads();
+        for (int v = tid; v < nt * VPR; v += AT_THREADS) {
+            int pr = v / VPR, pv = v % VPR;
+            uint4 dd = *reinterpret_cast<const uint4*>(vbase + (size_t)(t0 + pr) * HD + pv * EPV);
+            *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = dd;
+        }
+        __syncthreads();
+        for (int j = grp; j < nt; j += NG) {
+            const KT* vr = reinterpret_cast<const KT*>(tile + j * ROWB);
+            acc = fmaf(sc[t0 + j], Elem<KT>::get(vr, d), acc);
+        }
+    }
+    accs[grp][d] = acc;
+    __syncthreads();
+    if (tid < HD) {
+        float o = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < NG; gg++) o += accs[gg][tid];
+        out[tid] = o;
+    }
+    if (tid == 0) { out[HD] = mx; out[HD + 1] = lsum; }
+}
+
+template <int HD>
+__global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n_splits, float* __restrict__ out, int dq)
+{
+    const int head = blockIdx.x, r = blockIdx.y, d = threadIdx.x;
+    const float* p = part + ((size_t)r * H + head) * n_splits * (HD + 2);
+    float mx = -INFINITY;
+    for (int s = 0; s < n_splits; s++) mx = fmaxf(mx, p[(size_t)s * (HD + 2) + HD]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < n_splits; s++) {
+        const float* ps = p + (size_t)s * (HD + 2);
+        float l = ps[HD + 1];
+        if (l > 0.f) {
+            float w = __expf(ps[HD] - mx);
+            num = fmaf(w, ps[d], num);
+            den = fmaf(w, l, den);
+        }
+    }
+    out[(size_t)r * dq + (size_t)head * HD + d] = num / den;
+}
+
+static int attn_splits(const Dims& D, int ctx, int M)
+{
+    // enough blocks to cover the chip, at least 64 positions per split, chunk within the LDS score buffer
+    int want = ceil_div(512, D.H * M);
+    int by_len = ceil_div(ctx, 64);
+    int s = want < by_len ? want : by_len;
+    int need = ceil_div(ctx, AT_MAX_CHUNK);
+    if (s < need) s = need;
+    if (s < 1) s = 1;
+    return s;
+}
+
+size_t attention_scratch_floats(const Dims& D, int max_rows)
+{
+    // splits never exceed ceil(max_seq / 64) nor max(ceil(512 / (H*M)), ceil(max_seq / AT_MAX_CHUNK))
+    size_t worst = 0;
+    for (int M = 1; M <= max_rows; M++) {
+        size_t s = (size_t)attn_splits(D, D.max_seq, M);
+        size_t v = (size_t)M * D.H * s * (D.hd + 2);
+        if (v > worst) worst = v;
+    }
+    return worst;
+}
+
+template <typename KT, int HD>
+static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
+                              int pos_off, int n_splits, int M, float* part, float* out, hipStream_t s)
+{
+    hipLaunchKernelGGL((attn_partial_kernel<KT, HD>), dim3(n_splits, D.H, M), dim3(AT_THREADS), 0, s, q, ldq,
+                       (const KT*)kc, (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(D.H, M), dim3(HD), 0, s, part, D.H, n_splits, out, D.dq);
+    return hipGetLastError();
+}
+
+hipError_t attention(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
+                     int pos_off, int pos_host_hint, int M, float* part, float* out, hipStream_t s)
+{
+    int ctx = pos_host_hint + pos_off + M;  // positions the last row sees
+    if (ctx < 1 || ctx > D.max_seq) return hipErrorInvalidValue;
+    int n_splits = attn_splits(D, ctx, M);
+    if (D.wt == WT_BF16) {
+        if (D.hd == 128) return attention_t<uint16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
+        if (D.hd == 64) return attention_t<uint16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
+    } else {
+        if (D.hd == 128) return attention_t<float, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
+        if (D.hd == 64) return attention_t<float, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------------
+// vocabulary reduction: arg-max, softmax max-probability, entropy confidence (Eq. 1-4)
+// ---------------------------------------------------------------------------------------------
+constexpr int VR_THREADS = 1024;
+
+__global__ __launch_bounds__(VR_THREADS) void vocab_reduce_kernel(const float* __restrict__ logits, int V, float clamp,
+                                                                  float eps, int32_t* tok_out, int tok_stride,
+                                                                  int32_t* argmax_out, float* maxprob_out, float* conf_out)
+{
+    __shared__ float rv[16];
+    __shared__ int ri[16];
+    const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* z = logits + (size_t)r * V;
+    // pass 1: max and its lowest index
+    float m = -INFINITY;
+    int mi = 0x7fffffff;
+    for (int i = tid; i < V; i += VR_THREADS) {
+        float v = fminf(fmaxf(z[i], -clamp), clamp);
+        if (v > m) { m = v; mi = i; }  // ascending i per thread: first occurrence kept
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float om = __shfl_xor(m, o, 64);
+        int oi = __shfl_xor(mi, o, 64);
+        if (om > m || (om == m && oi < mi)) { m = om; mi = oi; }
+    }
+    if (lane == 0) { rv[wave] = m; ri[wave] = mi; }
+    __syncthreads();
+    m = rv[0]; mi = ri[0];
+#pragma unroll
+    for (int w = 1; w < 16; w++) {
+        float om = rv[w]; int oi = ri[w];
+        if (om > m || (om == m && oi < mi)) { m = om; mi = oi; }
+    }
+    // pass 2: Z = sum exp(z - m)
+    float zs = 0.f;
+    for (int i = tid; i < V; i += VR_THREADS) zs += expf(fminf(fmaxf(z[i], -clamp), clamp) - m);
+    float Z = block_sum<16>(zs, rv);
+    if (tid == 0) {
+        if (tok_out) tok_out[(size_t)r * tok_stride] = mi;
+        if (argmax_out) argmax_out[r] = mi;
+        if (maxprob_out) maxprob_out[r] = 1.0f / Z;
+    }
+    if (conf_out) {
+        // pass 3: H = -sum p log(p + eps)
+        float hs = 0.f;
+        const float invZ = 1.0f / Z;
+        for (int i = tid; i < V; i += VR_THREADS) {
+            float pr = expf(fminf(fmaxf(z[i], -clamp), clamp) - m) * invZ;
+            hs -= pr * logf(pr + eps);
+        }
+        float Hs = block_sum<16>(hs, rv);
+        if (tid == 0) conf_out[r] = 1.0f - Hs / logf((float)V);
+    }
+}
+
+hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float eps, int32_t* tok_out, int tok_stride,
+                        int32_t* argmax_out, float* maxprob_out, float* conf_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(vocab_reduce_kernel, dim3(M), dim3(VR_THREADS), 0, s, logits, V, clamp, eps, tok_out, tok_stride,
+                       argmax_out, maxprob_out, conf_out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// state kernels
+// ---------------------------------------------------------------------------------------------
+__global__ void accept_kernel(TokArg draft, const int32_t* target, int k, int32_t* res, int32_t* tok0, int* pos_dev)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        int a = 0;
+        while (a < k && draft.t[a] == target[a]) a++;
+        res[0] = a;
+        res[1] = target[a];
+        tok0[0] = target[a];
+        pos_dev[0] += a + 1;
+    }
+}
+
+hipError_t accept_commit(TokArg draft, const int32_t* target_dev, int k, int32_t* res, int32_t* tok0, int* pos_dev,
+                         hipStream_t s)
+{
+    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, draft, target_dev, k, res, tok0, pos_dev);
+    return hipGetLastError();
+}
+
+__global__ void set_state_kernel(int32_t* tok0, int32_t token, int* pos_dev, int pos)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) { tok0[0] = token; pos_dev[0] = pos; }
+}
+hipError_t set_state(int32_t* tok0, int32_t token, int* pos_dev, int pos, hipStream_t s)
+{
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, s, tok0, token, pos_dev, pos);
+    return hipGetLastError();
+}
+
+__global__ void advance_state_kernel(int* pos_dev, int delta, int32_t* tok0, const int32_t* src)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        pos_dev[0] += delta;
+        if (src) tok0[0] = src[0];
+    }
+}
+hipError_t advance_state(int* pos_dev, int delta, int32_t* tok0, const int32_t* src, hipStream_t s)
+{
+    hipLaunchKernelGGL(advance_state_kernel, dim3(1), dim3(64), 0, s, pos_dev, delta, tok0, src);
+    return hipGetLastError();
+}
+
+template <typename KT>
+__global__ void kv_poison_kernel(KT* kv, int planes, int max_seq, int hd, const int* pos_dev)
+{
+    // kv: [planes][max_seq][hd] where planes = L * 2 * Hkv
+    const int from = pos_dev[0];
+    size_t per_plane = (size_t)(max_seq - from) * hd;
+    size_t total = per_plane * planes;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        size_t pl = i / per_plane, o = i % per_plane;
+        Elem<KT>::put(kv, (pl * max_seq + from) * hd + o, __int_as_float(0x7fc00000));
+    }
+}
+hipError_t kv_poison(const Dims& D, void* kv_all, const int* pos_dev, hipStream_t s)
+{
+    int planes = D.L * 2 * D.Hkv;
+    if (D.wt == WT_BF16)
+        hipLaunchKernelGGL(kv_poison_kernel<uint16_t>, dim3(1024), dim3(256), 0, s, (uint16_t*)kv_all, planes, D.max_seq,
+                           D.hd, pos_dev);
+    else
+        hipLaunchKernelGGL(kv_poison_kernel<float>, dim3(1024), dim3(256), 0, s, (float*)kv_all, planes, D.max_seq, D.hd,
+                           pos_dev);
+    return hipGetLastError();
+}
+
+__global__ void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+hipError_t copy_f32(const float* src, float* dst, size_t n, hipStream_t s)
+{
+    int blocks = (int)((n + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, s, src, dst, n);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void read_probe_kernel(const uint4* __restrict__ src, size_t n_vec, float* sink)
+{
+    uint32_t acc = 0;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n_vec; i += stride) {
+        uint4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = 1.0f;  // practically never true; keeps the loads alive
+}
+hipError_t read_probe(const void* dev, size_t bytes, float* sink_dev, hipStream_t s)
+{
+    hipLaunchKernelGGL(read_probe_kernel, dim3(256 * 8), dim3(256), 0, s, (const uint4*)dev, bytes / 16, sink_dev);
+    return hipGetLastError();
+}
+
+}  // namespace ssdk
