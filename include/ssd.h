@@ -248,6 +248,10 @@ enum {
     SSD_K_COUNT = 12
 };
 int ssd_profile_select(ssd_ctx *ctx, int kernel_id);
+/* Launch mode: 1 (default) replays decode / draft / verify launch sequences as HIP graphs once a
+ * sequence has been seen twice (needs a non-default stream); 0 launches kernel by kernel.  Both
+ * modes run the same kernels with the same arguments and give bit-identical results. */
+int ssd_set_graphs(ssd_ctx *ctx, int enable);
 int ssd_profile_read(ssd_ctx *ctx, int64_t *launches_out, double *total_ms_out);
 
 /* Test hook: overwrite every cache entry at positions >= the number of valid positions

@@ -94,6 +94,7 @@ SYMBOLS = {
     "ssd_kv_poison_stale": (C.c_int, [_P]),
     "ssd_profile_select": (C.c_int, [_P, C.c_int]),
     "ssd_profile_read": (C.c_int, [_P, _P, _P]),
+    "ssd_set_graphs": (C.c_int, [_P, C.c_int]),
 }
 
 _lib = None
@@ -227,11 +228,13 @@ class Context:
         self.shape = shape
         self.cfg = make_config(shape, max_seq, max_k, **cfg_kw)
         h = C.c_void_p()
-        stream = torch.cuda.current_stream().cuda_stream
-        self._check(self._l.ssd_create(C.byref(self.cfg), C.c_void_p(stream), C.byref(h)), None)
+        # a stream of its own (default priority): the legacy default stream cannot be graph-captured
+        self.stream = torch.cuda.Stream()
+        self._check(self._l.ssd_create(C.byref(self.cfg), C.c_void_p(self.stream.cuda_stream), C.byref(h)), None)
         self._h = h
         nbytes = self._l.ssd_workspace_bytes(C.byref(self.cfg))
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()      # weights / workspace were produced on other streams
         self._check(self._l.ssd_set_workspace(self._h, C.c_void_p(self.workspace.data_ptr()), nbytes))
         self._weights = weights   # keep tensors alive
         L = shape.n_layers
@@ -331,6 +334,9 @@ class Context:
 
     def ssd_kv_poison_stale(self):
         self._check(self._l.ssd_kv_poison_stale(self._h))
+
+    def ssd_set_graphs(self, enable: bool):
+        self._check(self._l.ssd_set_graphs(self._h, 1 if enable else 0))
 
     def ssd_profile_select(self, kernel_id: int):
         self._check(self._l.ssd_profile_select(self._h, int(kernel_id)))

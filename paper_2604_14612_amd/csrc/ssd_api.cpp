@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <string>
 #include <vector>
 
@@ -84,7 +85,7 @@ Layout make_layout(const ssd_config& c)
 
 // offsets (in 4-byte words) inside the "small" region
 enum { SM_POS = 0, SM_TOK = 8 /* 17 ints: pending + drafts */, SM_TARGET = 32 /* 16 */, SM_RES = 56 /* 2 */,
-       SM_MAXPROB = 64 /* 16 floats */, SM_SINK = 96, SM_CONF = 128 /* conf_rows floats x3 follow */ };
+       SM_MAXPROB = 64 /* 16 floats */, SM_VTOK = 80 /* 16: tokens of a row block */, SM_SINK = 96, SM_CONF = 128 /* conf_rows floats x3 follow */ };
 
 }  // namespace
 
@@ -108,6 +109,8 @@ struct ssd_ctx {
     int logit_rows;    // rows with valid logits
     int32_t* pinned;   // host-pinned readback buffer
     ssd_stats st;
+    bool use_graphs;   // replay captured launch sequences instead of launching kernel by kernel
+    std::map<std::string, hipGraphExec_t> graphs;  // nullptr = sequence seen once, not captured yet
     int prof_kid;      // kernel id being timed, -1 = off
     size_t prof_used;  // event pairs in use
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_ev;
@@ -188,8 +191,7 @@ int layer_single(ssd_ctx* c, int l, int pos_off)
 int forward_single(ssd_ctx* c, const uint8_t* skip, int slot, int slot_out, int pos_off, int lrow)
 {
     const Dims& D = c->D;
-    TokArg none = {};
-    HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_TOK + slot, none, 1, c->f(c->lay.x), c->stream), "embed");
+    HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_TOK + slot, 1, c->f(c->lay.x), c->stream), "embed");
     for (int l = 0; l < D.L; l++) {
         if (skip && skip[l]) continue;
         int rc = layer_single(c, l, pos_off);
@@ -203,16 +205,15 @@ int forward_single(ssd_ctx* c, const uint8_t* skip, int slot, int slot_out, int 
     return SSD_OK;
 }
 
-// Full-model forward of M rows (M <= 16) at positions *pos + pos_off + r; taps into tap rows 0..M-1;
+// Full-model forward of the M tokens in SM_VTOK (M <= 16) at positions *pos + pos_off + r; taps into tap rows 0..M-1;
 // logits (when want_logits) into logits rows 0..M-1 and greedy tokens into SM_TARGET.
-int forward_rows(ssd_ctx* c, const int32_t* tok0_dev, const TokArg& toks, int M, int pos_off, int pos_host,
-                 bool want_logits)
+int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
 {
     const Dims& D = c->D;
     const Layout& Y = c->lay;
     float* x = c->f(Y.x);
     float* h = c->f(Y.h);
-    HIPCHK(embed_rows(D, c->w.embed, tok0_dev, toks, M, x, c->stream), "embed");
+    HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_VTOK, M, x, c->stream), "embed");
     const int tap_ld = D.L * 2 * D.d;
     for (int l = 0; l < D.L; l++) {
         HIPCHK(rmsnorm_rows(x, c->attn_norm[l], M, D.d, D.eps, h, c->stream), "rmsnorm");
@@ -251,6 +252,45 @@ int forward_rows(ssd_ctx* c, const int32_t* tok0_dev, const TokArg& toks, int M,
     return SSD_OK;
 }
 
+// Runs a launch sequence.  The first time a key is seen the sequence runs kernel by kernel; the
+// second time it is captured into a HIP graph, and from then on the graph is replayed (one
+// submission instead of hundreds of launches).  Everything position-dependent is read from
+// device memory by the kernels, so a graph stays valid as the sequence grows; what is baked into
+// it (skip mask, k, attention split counts) is part of the key.
+template <typename F>
+int run_sequence(ssd_ctx* c, const std::string& key, F&& body)
+{
+    if (!c->use_graphs || c->prof_kid >= 0 || c->stream == nullptr) return body();
+    auto it = c->graphs.find(key);
+    if (it == c->graphs.end()) {
+        if (c->graphs.size() >= 256) {  // masks change during the search: keep the cache bounded
+            for (auto& e : c->graphs)
+                if (e.second) (void)hipGraphExecDestroy(e.second);
+            c->graphs.clear();
+        }
+        c->graphs[key] = nullptr;
+        return body();
+    }
+    if (!it->second) {
+        HIPCHK(hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed), "begin capture");
+        int rc = body();
+        hipGraph_t g = nullptr;
+        hipError_t e = hipStreamEndCapture(c->stream, &g);
+        if (rc != SSD_OK || e != hipSuccess || !g) {
+            if (g) (void)hipGraphDestroy(g);
+            c->graphs.erase(it);
+            return rc != SSD_OK ? rc : hip_fail(c, e, "end capture");
+        }
+        hipGraphExec_t exec = nullptr;
+        e = hipGraphInstantiate(&exec, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (e != hipSuccess) { c->graphs.erase(it); return hip_fail(c, e, "graph instantiate"); }
+        it->second = exec;
+    }
+    HIPCHK(hipGraphLaunch(it->second, c->stream), "graph launch");
+    return SSD_OK;
+}
+
 int readback(ssd_ctx* c, const void* dev, size_t bytes, void* host)
 {
     HIPCHK(hipMemcpyAsync(c->pinned, dev, bytes, hipMemcpyDeviceToHost, c->stream), "readback copy");
@@ -279,6 +319,7 @@ int ssd_create(const ssd_config* cfg, void* hip_stream, ssd_ctx** out)
     memset(&c->st, 0, sizeof(c->st));
     memset(&c->w, 0, sizeof(c->w));
     c->prof_kid = -1; c->prof_used = 0;
+    c->use_graphs = true;
     *out = c;
     return SSD_OK;
 }
@@ -359,6 +400,8 @@ void ssd_destroy(ssd_ctx* c)
     if (!c) return;
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto& e : c->prof_ev) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+    for (auto& e : c->graphs)
+        if (e.second) (void)hipGraphExecDestroy(e.second);
     delete c;
 }
 
@@ -387,7 +430,8 @@ int ssd_prefill(ssd_ctx* c, const int32_t* tokens, int n, int32_t* first_token_o
         TokArg t = {};
         for (int r = 0; r < M; r++) t.t[r] = tokens[p0 + r];
         bool last = p0 + M == n;
-        int rc = forward_rows(c, nullptr, t, M, p0, 0, last);
+        HIPCHK(set_tokens(t, M, nullptr, c->small_i() + SM_VTOK, c->stream), "set_tokens");
+        int rc = forward_rows(c, M, p0, 0, last);
         if (rc) return rc;
         last_M = M;
     }
@@ -415,9 +459,14 @@ int ssd_decode(ssd_ctx* c, int32_t* token_out)
     if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "decode needs a prefilled sequence with no draft in flight");
     if (c->n + 1 > c->D.max_seq) return fail(c, SSD_ECAPACITY, "sequence would exceed max_seq");
     // pending token sits in tok slot 0; its successor is written to slot 1, then promoted
-    int rc = forward_single(c, nullptr, 0, 1, 0, 0);
+    std::string key = "D|" + std::to_string(attention_splits(c->D, c->n, 1));
+    int rc = run_sequence(c, key, [&]() {
+        int r = forward_single(c, nullptr, 0, 1, 0, 0);
+        if (r) return r;
+        HIPCHK(advance_state(c->pos_dev(), 1, c->small_i() + SM_TOK, c->small_i() + SM_TOK + 1, c->stream), "advance_state");
+        return (int)SSD_OK;
+    });
     if (rc) return rc;
-    HIPCHK(advance_state(c->pos_dev(), 1, c->small_i() + SM_TOK, c->small_i() + SM_TOK + 1, c->stream), "advance_state");
     rc = readback(c, c->small_i() + SM_TOK + 1, sizeof(int32_t), token_out);
     if (rc) return rc;
     c->n += 1;
@@ -434,11 +483,17 @@ int ssd_draft_step(ssd_ctx* c, const uint8_t* skip_mask, int k, int32_t* draft_o
     if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "draft_step needs a prefilled sequence with no draft in flight");
     if (k > c->cfg.max_k) return fail(c, SSD_ECAPACITY, "k exceeds max_k");
     if (c->n + k > c->D.max_seq) return fail(c, SSD_ECAPACITY, "draft + verification would exceed max_seq");
-    for (int i = 0; i < k; i++) {
-        int rc = forward_single(c, skip_mask, i, i + 1, i, i);
-        if (rc) return rc;
-    }
-    int rc = readback(c, c->small_i() + SM_TOK + 1, sizeof(int32_t) * k, draft_out);
+    std::string key = "S|" + std::to_string(k) + "|" + std::string(skip_mask, skip_mask + c->D.L) + "|";
+    for (int i = 0; i < k; i++) key += std::to_string(attention_splits(c->D, c->n + i, 1)) + ",";
+    int rc = run_sequence(c, key, [&]() {
+        for (int i = 0; i < k; i++) {
+            int r = forward_single(c, skip_mask, i, i + 1, i, i);
+            if (r) return r;
+        }
+        return (int)SSD_OK;
+    });
+    if (rc) return rc;
+    rc = readback(c, c->small_i() + SM_TOK + 1, sizeof(int32_t) * k, draft_out);
     if (rc) return rc;
     if (draft_maxprob_out) {
         rc = readback(c, c->small_f() + SM_MAXPROB, sizeof(float) * k, draft_maxprob_out);
@@ -461,7 +516,9 @@ int ssd_verify(ssd_ctx* c, const int32_t* draft, int k, int32_t* target_out)
         if (draft[i] < 0 || draft[i] >= c->D.V) return fail(c, SSD_EINVAL, "draft token id out of range");
     TokArg t = {};
     for (int i = 0; i < k; i++) t.t[i + 1] = draft[i];
-    int rc = forward_rows(c, c->small_i() + SM_TOK, t, k + 1, 0, c->n - 1, true);
+    HIPCHK(set_tokens(t, k + 1, c->small_i() + SM_TOK, c->small_i() + SM_VTOK, c->stream), "set_tokens");
+    std::string key = "V|" + std::to_string(k) + "|" + std::to_string(attention_splits(c->D, c->n + k, k + 1));
+    int rc = run_sequence(c, key, [&]() { return forward_rows(c, k + 1, 0, c->n - 1, true); });
     if (rc) return rc;
     rc = readback(c, c->small_i() + SM_TARGET, sizeof(int32_t) * (k + 1), target_out);
     if (rc) return rc;
@@ -565,6 +622,13 @@ int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out,
     }
     c->logit_rows = 0;  // the logits buffer was reused
     c->st.confidence_rows += (int64_t)n_rows * R;
+    return SSD_OK;
+}
+
+int ssd_set_graphs(ssd_ctx* c, int enable)
+{
+    if (!c) return SSD_EINVAL;
+    c->use_graphs = enable != 0;
     return SSD_OK;
 }
 

@@ -16,11 +16,11 @@ struct Dims {
     int wt;  // WeightType; the KV cache uses the same element type
 };
 
-// x[r][:] = embed[tok[r]][:] widened to fp32.  Row 0 may come from device memory
-// (tok0_dev != nullptr), the others from the by-value array.
+// x[r][:] = embed[tok_dev[r]][:] widened to fp32 (token ids in device memory, clamped to the vocabulary).
 struct TokArg { int32_t t[16]; };
-hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok0_dev, TokArg toks, int M,
-                      float* x, hipStream_t s);
+hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok_dev, int M, float* x, hipStream_t s);
+// dst[i] = toks.t[i] for i < n, except dst[0] = first_dev[0] when first_dev != nullptr
+hipError_t set_tokens(TokArg toks, int n, const int32_t* first_dev, int32_t* dst, hipStream_t s);
 
 // ---- single-row (draft / vanilla decode) path: weight-streaming GEMV kernels ----------------
 // h = rmsnorm(x, gain); q,k,v = Wq h, Wk h, Wv h; rotary on q,k at position *pos_dev + pos_off;
@@ -69,6 +69,8 @@ hipError_t attention(const Dims& D, const float* q, int ldq, const void* kcache_
                      const int* pos_dev, int pos_off, int pos_host_hint, int M, float* part, float* out,
                      hipStream_t s);
 size_t attention_scratch_floats(const Dims& D, int max_rows);
+// number of sequence splits attention() uses when the last of M rows sees ctx positions
+int attention_splits(const Dims& D, int ctx, int M);
 
 // ---- vocabulary reduction ------------------------------------------------------------------------
 // Per row of logits [M][V]: arg-max (lowest index on ties), softmax max-probability and, when

@@ -91,34 +91,50 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // embedding gather
 // ---------------------------------------------------------------------------------------------
 template <typename WT>
-__global__ void embed_kernel(const WT* __restrict__ E, const int32_t* tok0_dev, TokArg toks, int d, int V,
+__global__ void embed_kernel(const WT* __restrict__ E, const int32_t* __restrict__ tok_dev, int d, int V,
                              float* __restrict__ x)
 {
     int r = blockIdx.y;
-    int t = (r == 0 && tok0_dev) ? tok0_dev[0] : toks.t[r];
+    int t = tok_dev[r];
     t = min(max(t, 0), V - 1);
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < d; i += gridDim.x * blockDim.x)
         x[(size_t)r * d + i] = Elem<WT>::get(E, (size_t)t * d + i);
 }
 
-hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok0_dev, TokArg toks, int M, float* x,
-                      hipStream_t s)
+hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok_dev, int M, float* x, hipStream_t s)
 {
     dim3 grid(ceil_div(D.d, 256), M);
     if (D.wt == WT_BF16)
-        hipLaunchKernelGGL(embed_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)embed, tok0_dev, toks, D.d,
-                           D.V, x);
+        hipLaunchKernelGGL(embed_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)embed, tok_dev, D.d, D.V, x);
     else
-        hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, s, (const float*)embed, tok0_dev, toks, D.d, D.V, x);
+        hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, s, (const float*)embed, tok_dev, D.d, D.V, x);
+    return hipGetLastError();
+}
+
+__global__ void set_tokens_kernel(TokArg toks, int n, const int32_t* first_dev, int32_t* dst)
+{
+    int i = threadIdx.x;
+    if (i < n) dst[i] = (i == 0 && first_dev) ? first_dev[0] : toks.t[i];
+}
+hipError_t set_tokens(TokArg toks, int n, const int32_t* first_dev, int32_t* dst, hipStream_t s)
+{
+    hipLaunchKernelGGL(set_tokens_kernel, dim3(1), dim3(64), 0, s, toks, n, first_dev, dst);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
 // single-row weight-streaming GEMV
 // ---------------------------------------------------------------------------------------------
-constexpr int GEMV_WAVES = 4;
-constexpr int GEMV_THREADS = GEMV_WAVES * 64;
-constexpr int GEMV_ROWS = 4;  // weight rows in flight per wave iteration
+// A block has 8 waves.  KS consecutive waves form a group that owns R "logical" weight rows;
+// the K dimension is cut into chunks of one 128-bit load per lane (512 bf16 / 256 fp32) and the
+// waves of a group take chunks kp, kp+KS, ...  Every wave keeps D chunk-steps of R non-temporal
+// loads in flight (weights are read exactly once, they should not displace activations in the
+// caches).  The input vector sits in LDS already multiplied by the norm gain; the RMS scale is a
+// per-vector scalar and is applied to the finished dot products.
+// Logical row order: QKV interleaves the two rows of a rotary pair (i, i + hd/2), gate/up
+// interleaves gate row n and up row n, so that one lane holds both operands of the epilogue.
+constexpr int GV_WAVES = 8;
+constexpr int GV_THREADS = GV_WAVES * 64;
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_STORE = 3 };
 
@@ -128,7 +144,7 @@ struct GemvP {
     const float* gain;  // rmsnorm gain or nullptr (input used as is)
     float eps;
     int K;
-    int n_units;        // groups of GEMV_ROWS rows (EPI_SWIGLU: 2 output rows = 4 weight rows)
+    int n_rows;         // logical rows (QKV: dq + 2 dkv; SWIGLU: 2 f; else N)
     float* y;           // QKV: qbuf; RESID: residual (+=); SWIGLU: act; STORE: logits
     float* tap;
     void* kc; void* vc;
@@ -137,150 +153,267 @@ struct GemvP {
     int hd, dq, dkv, max_seq;
 };
 
-// Loads the input vector into LDS (optionally RMS-normalised with gain applied).
-__device__ __forceinline__ void gemv_stage_input(const GemvP& p, float* xs, float* red)
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+template <typename WT> __device__ __forceinline__ u32x4_t gv_load(const WT* p)
 {
-    float ss = 0.f;
-    for (int i = threadIdx.x * 4; i < p.K; i += GEMV_THREADS * 4) {
-        float4 v = *reinterpret_cast<const float4*>(p.in + i);
-        *reinterpret_cast<float4*>(xs + i) = v;
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-    }
-    if (p.gain) {
-        float tot = block_sum<GEMV_WAVES>(ss, red);
-        float sc = 1.0f / sqrtf(tot / (float)p.K + p.eps);
-        for (int i = threadIdx.x * 4; i < p.K; i += GEMV_THREADS * 4) {
-            float4 v = *reinterpret_cast<float4*>(xs + i);
-            float4 g = *reinterpret_cast<const float4*>(p.gain + i);
-            v.x = v.x * sc * g.x; v.y = v.y * sc * g.y; v.z = v.z * sc * g.z; v.w = v.w * sc * g.w;
-            *reinterpret_cast<float4*>(xs + i) = v;
-        }
-    }
-    __syncthreads();
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+}
+
+// acc += w . x for one 128-bit weight vector; xs points at the matching activations in LDS
+template <typename WT> __device__ __forceinline__ float gv_dot(u32x4_t w, const float* xs, float acc);
+template <> __device__ __forceinline__ float gv_dot<uint16_t>(u32x4_t w, const float* xs, float acc)
+{
+    float4 a = *reinterpret_cast<const float4*>(xs), b = *reinterpret_cast<const float4*>(xs + 4);
+    acc = fmaf(__uint_as_float(w.x << 16), a.x, acc);
+    acc = fmaf(__uint_as_float(w.x & 0xffff0000u), a.y, acc);
+    acc = fmaf(__uint_as_float(w.y << 16), a.z, acc);
+    acc = fmaf(__uint_as_float(w.y & 0xffff0000u), a.w, acc);
+    acc = fmaf(__uint_as_float(w.z << 16), b.x, acc);
+    acc = fmaf(__uint_as_float(w.z & 0xffff0000u), b.y, acc);
+    acc = fmaf(__uint_as_float(w.w << 16), b.z, acc);
+    acc = fmaf(__uint_as_float(w.w & 0xffff0000u), b.w, acc);
+    return acc;
+}
+template <> __device__ __forceinline__ float gv_dot<float>(u32x4_t w, const float* xs, float acc)
+{
+    float4 a = *reinterpret_cast<const float4*>(xs);
+    acc = fmaf(__uint_as_float(w.x), a.x, acc);
+    acc = fmaf(__uint_as_float(w.y), a.y, acc);
+    acc = fmaf(__uint_as_float(w.z), a.z, acc);
+    acc = fmaf(__uint_as_float(w.w), a.w, acc);
+    return acc;
 }
 
 template <typename WT, int EPI>
-__global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(GemvP p)
+__device__ __forceinline__ const WT* gv_row_ptr(const GemvP& p, int j)
+{
+    if (EPI == EPI_QKV) {
+        if (j < p.dq + p.dkv) {
+            const WT* base = (const WT*)p.w0;
+            int jj = j;
+            if (j >= p.dq) { base = (const WT*)p.w1; jj = j - p.dq; }
+            const int head = jj / p.hd, e = jj % p.hd;
+            const int i = (e >> 1) + (e & 1) * (p.hd >> 1);
+            return base + (size_t)(head * p.hd + i) * p.K;
+        }
+        return (const WT*)p.w2 + (size_t)(j - p.dq - p.dkv) * p.K;
+    } else if (EPI == EPI_SWIGLU) {
+        return ((j & 1) ? (const WT*)p.w1 : (const WT*)p.w0) + (size_t)(j >> 1) * p.K;
+    } else {
+        return (const WT*)p.w0 + (size_t)j * p.K;
+    }
+}
+
+// finished sums s[0..R) of logical rows j0.. ; sc = RMS scale (1 when no norm)
+template <typename WT, int EPI, int R>
+__device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float (&s)[R], float sc)
+{
+    if (EPI == EPI_QKV) {
+        const int half = p.hd >> 1;
+        const int pos = p.pos_dev[0] + p.pos_off;
+#pragma unroll
+        for (int t = 0; t < R; t += 2) {
+            const int j = j0 + t;
+            const float a = s[t] * sc, b = s[t + 1] * sc;
+            if (j < p.dq + p.dkv) {
+                const bool is_q = j < p.dq;
+                const int jj = is_q ? j : j - p.dq;
+                const int head = jj / p.hd, i = (jj % p.hd) >> 1;
+                const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+                const float c = cs[0], sn = cs[1];
+                const float ra = a * c - b * sn, rb = b * c + a * sn;
+                if (is_q) {
+                    float* q = p.y + (size_t)head * p.hd + i;
+                    q[0] = ra; q[half] = rb;
+                } else {
+                    const size_t o = ((size_t)head * p.max_seq + pos) * p.hd + i;
+                    Elem<WT>::put((WT*)p.kc, o, ra);
+                    Elem<WT>::put((WT*)p.kc, o + half, rb);
+                }
+            } else {
+                const int e = j - p.dq - p.dkv;
+                const size_t o = ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd);
+                Elem<WT>::put((WT*)p.vc, o, a);
+                Elem<WT>::put((WT*)p.vc, o + 1, b);
+            }
+        }
+    } else if (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int t = 0; t < R; t += 2) {
+            const float g = s[t] * sc, u = s[t + 1] * sc;
+            p.y[(j0 + t) >> 1] = g / (1.0f + __expf(-g)) * u;
+        }
+    } else if (EPI == EPI_RESID) {
+#pragma unroll
+        for (int t = 0; t < R; t++) {
+            const float v = p.y[j0 + t] + s[t];
+            p.y[j0 + t] = v;
+            if (p.tap) p.tap[j0 + t] = v;
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < R; t++) p.y[j0 + t] = s[t] * sc;
+    }
+}
+
+template <typename WT, int EPI, int R, int D, int KS>
+__global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
 {
     extern __shared__ __align__(16) float xs[];
-    __shared__ float red[GEMV_WAVES];
-    constexpr int VEC = Elem<WT>::VEC;
+    __shared__ float red[GV_WAVES];
+    __shared__ float part[GV_WAVES][R];
+    constexpr int VEC = Elem<WT>::VEC, CH = 64 * VEC, GPB = GV_WAVES / KS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = wave / KS, kp = wave % KS;
     const int K = p.K;
+    const int n_groups = p.n_rows / R;
+    const int nfull = K / CH, tail = K - nfull * CH;   // tail is a multiple of VEC
+    // Every wave of the block walks the same (round, step) sequence so that block barriers stay
+    // uniform: S steps per group, wave kp owns chunk kp + step*KS when that chunk exists.
+    const int S = nfull > 0 ? (nfull + KS - 1) / KS : 1;
+    const bool my_tail = tail > 0 && (nfull % KS) == kp && lane * VEC < tail;
+    const int n_gblocks = (n_groups + GPB - 1) / GPB;
+    const int n_rounds = (n_gblocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const size_t lane_off = (size_t)kp * CH + lane * VEC;
 
-    gemv_stage_input(p, xs, red);
-
-    for (int u = blockIdx.x * GEMV_WAVES + wave; u < p.n_units; u += gridDim.x * GEMV_WAVES) {
-        const WT* wr[GEMV_ROWS];
-        int kind = 0, head = 0, i0 = 0;  // QKV bookkeeping
-        if (EPI == EPI_QKV) {
-            const int half = p.hd >> 1, uph = p.hd >> 2;  // units per head
-            const int nq = p.dq >> 2, nk = p.dkv >> 2;
-            if (u < nq + nk) {
-                const WT* base; int uu;
-                if (u < nq) { kind = 0; base = (const WT*)p.w0; uu = u; }
-                else { kind = 1; base = (const WT*)p.w1; uu = u - nq; }
-                head = uu / uph; i0 = (uu % uph) * 2;
-                size_t r0 = (size_t)head * p.hd + i0;
-                wr[0] = base + r0 * K; wr[1] = base + (r0 + half) * K;
-                wr[2] = base + (r0 + 1) * K; wr[3] = base + (r0 + 1 + half) * K;
-            } else {
-                kind = 2; i0 = (u - nq - nk) * 4;
-                const WT* base = (const WT*)p.w2;
+    // issue side of the software pipeline: runs D steps ahead of the consume side, across groups
+    int ri = 0, ci = 0;
+    bool ai = false;
+    const WT* wi[R];
+    auto set_issue_rows = [&]() {
+        const int g = ((int)blockIdx.x + ri * (int)gridDim.x) * GPB + grp;
+        ai = ri < n_rounds && g < n_groups;
+        if (ai) {
 #pragma unroll
-                for (int r = 0; r < 4; r++) wr[r] = base + (size_t)(i0 + r) * K;
-            }
-        } else if (EPI == EPI_SWIGLU) {
-            size_t n = (size_t)u * 2;
-            wr[0] = (const WT*)p.w0 + n * K; wr[1] = (const WT*)p.w1 + n * K;
-            wr[2] = (const WT*)p.w0 + (n + 1) * K; wr[3] = (const WT*)p.w1 + (n + 1) * K;
-        } else {
-            size_t n = (size_t)u * 4;
-#pragma unroll
-            for (int r = 0; r < 4; r++) wr[r] = (const WT*)p.w0 + (n + r) * K;
+            for (int r = 0; r < R; r++) wi[r] = gv_row_ptr<WT, EPI>(p, g * R + r) + lane_off;
         }
-
-        float acc[GEMV_ROWS] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-        for (int k = lane * VEC; k < K; k += 64 * VEC) {
-            float wv[GEMV_ROWS][VEC];
+    };
+    set_issue_rows();
+    u32x4_t buf[D][R];
+    auto issue = [&](int s) {
+        if (ri < n_rounds) {
+            if (ai && kp + ci * KS < nfull) {
 #pragma unroll
-            for (int r = 0; r < GEMV_ROWS; r++) Elem<WT>::load(wr[r] + k, wv[r]);
-            float xv[VEC];
-#pragma unroll
-            for (int j = 0; j < VEC; j += 4) {
-                float4 t = *reinterpret_cast<const float4*>(xs + k + j);
-                xv[j] = t.x; xv[j + 1] = t.y; xv[j + 2] = t.z; xv[j + 3] = t.w;
+                for (int r = 0; r < R; r++) buf[s][r] = gv_load(wi[r] + (size_t)ci * KS * CH);
             }
-#pragma unroll
-            for (int r = 0; r < GEMV_ROWS; r++)
-#pragma unroll
-                for (int j = 0; j < VEC; j++) acc[r] = fmaf(wv[r][j], xv[j], acc[r]);
+            if (++ci == S) { ci = 0; ++ri; set_issue_rows(); }
         }
+    };
+    // the first weight loads do not depend on the activations: start them before staging the input
 #pragma unroll
-        for (int r = 0; r < GEMV_ROWS; r++) acc[r] = wave_sum(acc[r]);
+    for (int s = 0; s < D; s++) issue(s);
 
-        if (lane == 0) {
-            if (EPI == EPI_QKV) {
-                const int half = p.hd >> 1;
-                if (kind == 2) {
-                    int kvh = i0 / p.hd, e = i0 % p.hd;
-                    int pos = p.pos_dev[0] + p.pos_off;
-                    size_t o = ((size_t)kvh * p.max_seq + pos) * p.hd + e;
+    // stage the input vector (times gain); the sum of squares gives the RMS scale
+    float ss = 0.f;
+    for (int i = threadIdx.x * 4; i < K; i += GV_THREADS * 4) {
+        float4 v = *reinterpret_cast<const float4*>(p.in + i);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        if (p.gain) {
+            const float4 g = *reinterpret_cast<const float4*>(p.gain + i);
+            v.x *= g.x; v.y *= g.y; v.z *= g.z; v.w *= g.w;
+        }
+        *reinterpret_cast<float4*>(xs + i) = v;
+    }
+    float sc = 1.0f;
+    if (p.gain) {
+        ss = wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+    }
+    __syncthreads();
+    if (p.gain) {
+        float t = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 4; r++) Elem<WT>::put((WT*)p.vc, o + r, acc[r]);
-                } else {
-                    int pos = p.pos_dev[0] + p.pos_off;
-                    const float* cs = p.rope + ((size_t)pos * half + i0) * 2;
-                    float c0 = cs[0], s0 = cs[1], c1 = cs[2], s1 = cs[3];
-                    float a0 = acc[0] * c0 - acc[1] * s0, b0 = acc[1] * c0 + acc[0] * s0;
-                    float a1 = acc[2] * c1 - acc[3] * s1, b1 = acc[3] * c1 + acc[2] * s1;
-                    if (kind == 0) {
-                        float* q = p.y + (size_t)head * p.hd + i0;
-                        q[0] = a0; q[half] = b0; q[1] = a1; q[1 + half] = b1;
-                    } else {
-                        size_t o = ((size_t)head * p.max_seq + pos) * p.hd + i0;
-                        WT* kc = (WT*)p.kc;
-                        Elem<WT>::put(kc, o, a0); Elem<WT>::put(kc, o + half, b0);
-                        Elem<WT>::put(kc, o + 1, a1); Elem<WT>::put(kc, o + 1 + half, b1);
+        for (int i = 0; i < GV_WAVES; i++) t += red[i];
+        sc = 1.0f / sqrtf(t / (float)K + p.eps);
+    }
+
+    const float* xp = xs + lane_off;
+    int rc = 0, cc = 0;
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; r++) acc[r] = 0.f;
+    while (rc < n_rounds) {
+#pragma unroll
+        for (int s = 0; s < D; s++) {
+            if (rc < n_rounds) {  // uniform over the block
+                const int g = ((int)blockIdx.x + rc * (int)gridDim.x) * GPB + grp;
+                const bool act = g < n_groups;
+                if (act && kp + cc * KS < nfull) {
+#pragma unroll
+                    for (int r = 0; r < R; r++) acc[r] = gv_dot<WT>(buf[s][r], xp + (size_t)cc * KS * CH, acc[r]);
+                }
+                issue(s);
+                if (++cc == S) {  // group finished
+                    if (act && my_tail) {  // the one partial chunk: only lanes still inside the row take part
+                        const size_t o = (size_t)(nfull - kp) * CH;
+#pragma unroll
+                        for (int r = 0; r < R; r++) {
+                            const WT* w = gv_row_ptr<WT, EPI>(p, g * R + r) + lane_off + o;
+                            acc[r] = gv_dot<WT>(gv_load(w), xp + o, acc[r]);
+                        }
                     }
-                }
-            } else if (EPI == EPI_RESID) {
-                size_t n = (size_t)u * 4;
 #pragma unroll
-                for (int r = 0; r < 4; r++) {
-                    float v = p.y[n + r] + acc[r];
-                    p.y[n + r] = v;
-                    if (p.tap) p.tap[n + r] = v;
-                }
-            } else if (EPI == EPI_SWIGLU) {
-                size_t n = (size_t)u * 2;
-                p.y[n] = acc[0] / (1.0f + __expf(-acc[0])) * acc[1];
-                p.y[n + 1] = acc[2] / (1.0f + __expf(-acc[2])) * acc[3];
-            } else {
-                size_t n = (size_t)u * 4;
+                    for (int r = 0; r < R; r++) acc[r] = wave_sum(acc[r]);
+                    if (KS == 1) {
+                        if (act && lane == 0) gv_epilogue<WT, EPI, R>(p, g * R, acc, sc);
+                    } else {
+                        if (lane == 0) {
 #pragma unroll
-                for (int r = 0; r < 4; r++) p.y[n + r] = acc[r];
+                            for (int r = 0; r < R; r++) part[wave][r] = acc[r];
+                        }
+                        __syncthreads();
+                        if (act && kp == 0 && lane == 0) {
+                            float sm[R];
+#pragma unroll
+                            for (int r = 0; r < R; r++) {
+                                float t = 0.f;
+#pragma unroll
+                                for (int j = 0; j < KS; j++) t += part[grp * KS + j][r];
+                                sm[r] = t;
+                            }
+                            gv_epilogue<WT, EPI, R>(p, g * R, sm, sc);
+                        }
+                        __syncthreads();
+                    }
+#pragma unroll
+                    for (int r = 0; r < R; r++) acc[r] = 0.f;
+                    cc = 0;
+                    ++rc;
+                }
             }
         }
     }
 }
 
-template <typename WT, int EPI>
-static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s)
+template <typename WT, int EPI, int R, int D, int KS>
+static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
 {
     size_t lds = (size_t)p.K * sizeof(float);
     static size_t lds_limit = 0;  // per instantiation
     if (lds > 64 * 1024 && lds > lds_limit) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemv_kernel<WT, EPI>,
+        hipError_t e = hipFuncSetAttribute((const void*)gemv_kernel<WT, EPI, R, D, KS>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         lds_limit = lds;
     }
-    int blocks = ceil_div(p.n_units, GEMV_WAVES);
-    if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL((gemv_kernel<WT, EPI>), dim3(blocks), dim3(GEMV_THREADS), lds, s, p);
+    constexpr int GPB = GV_WAVES / KS;
+    int blocks = ceil_div(p.n_rows / R, GPB);
+    if (blocks > 256 * 4) blocks = 256 * 4;
+    hipLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, p);
     return hipGetLastError();
+}
+
+// Work split: many rows -> one wave per row pair, deep pipeline; few rows -> split K over the waves
+// of a group so that every wave still has a handful of chunks and the chip has thousands of waves.
+template <typename WT, int EPI>
+static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s)
+{
+    const int ch = ceil_div(p.K, 64 * Elem<WT>::VEC);
+    if (p.n_rows >= 8192) return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s);
+    if (ch <= 12) return launch_gemv_cfg<WT, EPI, 2, 2, 2>(p, s);
+    if (ch <= 40) return launch_gemv_cfg<WT, EPI, 4, 2, 4>(p, s);
+    return launch_gemv_cfg<WT, EPI, 4, 2, 8>(p, s);
 }
 
 template <int EPI>
@@ -294,7 +427,7 @@ hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* w
 {
     GemvP p = {};
     p.w0 = wq; p.w1 = wk; p.w2 = wv; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d;
-    p.n_units = (D.dq + 2 * D.dkv) / 4;
+    p.n_rows = D.dq + 2 * D.dkv;
     p.y = qbuf; p.kc = kc; p.vc = vc; p.rope = rope; p.pos_dev = pos_dev; p.pos_off = pos_off;
     p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq;
     return launch_gemv<EPI_QKV>(D.wt, p, s);
@@ -303,7 +436,7 @@ hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* w
 hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap, hipStream_t s)
 {
     GemvP p = {};
-    p.w0 = w; p.in = in; p.gain = nullptr; p.eps = D.eps; p.K = K; p.n_units = N / 4; p.y = x; p.tap = tap;
+    p.w0 = w; p.in = in; p.gain = nullptr; p.eps = D.eps; p.K = K; p.n_rows = N; p.y = x; p.tap = tap;
     return launch_gemv<EPI_RESID>(D.wt, p, s);
 }
 
@@ -311,14 +444,14 @@ hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const floa
                        hipStream_t s)
 {
     GemvP p = {};
-    p.w0 = wg; p.w1 = wu; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_units = D.f / 2; p.y = act;
+    p.w0 = wg; p.w1 = wu; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = 2 * D.f; p.y = act;
     return launch_gemv<EPI_SWIGLU>(D.wt, p, s);
 }
 
 hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits, hipStream_t s)
 {
     GemvP p = {};
-    p.w0 = wlm; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_units = D.V / 4; p.y = logits;
+    p.w0 = wlm; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = D.V; p.y = logits;
     return launch_gemv<EPI_STORE>(D.wt, p, s);
 }
 
@@ -630,10 +763,11 @@ constexpr int AT_MAX_CHUNK = 2048; // positions one block may own (LDS score buf
 
 // partial layout per (row, head, split): [hd] unnormalised output, then m (max score), l (sum of exp)
 template <typename KT, int HD>
-__global__ __launch_bounds__(AT_THREADS) void attn_partial_kernel(const float* __restrict__ q, int ldq,
-                                                                  const KT* __restrict__ kc, const KT* __restrict__ vc,
-                                                                  const int* pos_dev, int pos_off, int M, int H, int Hkv,
-                                                                  int max_seq, int n_splits, float* __restrict__ part)
+__global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restrict__ q, int ldq,
+                                                          const KT* __restrict__ kc, const KT* __restrict__ vc,
+                                                          const int* pos_dev, int pos_off, int M, int H, int Hkv,
+                                                          int max_seq, int n_splits, float* __restrict__ part,
+                                                          float* __restrict__ outp, int dq)
 {
     constexpr int ROWB = HD * (int)sizeof(KT) + 16;  // padded LDS row (bytes) to spread banks
     constexpr int NG = AT_THREADS / HD;              // position groups in the P.V phase
@@ -645,113 +779,115 @@ __global__ __launch_bounds__(AT_THREADS) void attn_partial_kernel(const float* _
     const int split = blockIdx.x, head = blockIdx.y, r = blockIdx.z;
     const int kvh = head / (H / Hkv);
     const int p0 = pos_dev[0] + pos_off;
-    const int n_ctx = p0 + r + 1;                        // this row sees positions 0..p0+r
+    const int n_ctx = p0 + r + 1;                         // this row sees positions 0..p0+r
     const int chunk = (p0 + M + n_splits - 1) / n_splits; // same chunking for all rows of the block
     const int j0 = split * chunk;
     const int j1 = min(min(j0 + chunk, n_ctx), j0 + AT_MAX_CHUNK);  // host sizes chunk <= AT_MAX_CHUNK
-    float* out = part + (((size_t)r * H + head) * n_splits + split) * (HD + 2);
+    const int n = j1 - j0;                                // may be <= 0: nothing for this row in this split
     const int tid = threadIdx.x;
-    if (j1 <= j0) {  // nothing for this row in this split
-        if (tid < HD) out[tid] = 0.f;
-        if (tid == 0) { out[HD] = -INFINITY; out[HD + 1] = 0.f; }
-        return;
-    }
-    const int n = j1 - j0;
-    const KT* kbase = kc + ((size_t)kvh * max_seq + j0) * HD;
-    const KT* vbase = vc + ((size_t)kvh * max_seq + j0) * HD;
-    constexpr int EPV = 16 / (int)sizeof(KT);  // elements per 16-byte vector
-    constexpr int VPR = HD / EPV;              // vectors per cache row
-
-    // phase A: scores. 4 threads per position, each owns HD/4 dims of q in registers.
-    const int spos = tid >> 2, part4 = tid & 3;
-    constexpr int DPT = HD / 4;
-    float qr[DPT];
-    const float scale = 1.0f / sqrtf((float)HD);
-    {
-        const float* qv = q + (size_t)r * ldq + (size_t)head * HD + part4 * DPT;
+    float o_val = 0.f, mx = -INFINITY, lsum = 0.f;        // o_val: element tid of the unnormalised output
+    if (n > 0) {
+        const KT* kbase = kc + ((size_t)kvh * max_seq + j0) * HD;
+        const KT* vbase = vc + ((size_t)kvh * max_seq + j0) * HD;
+        constexpr int EPV = 16 / (int)sizeof(KT);  // elements per 16-byte vector
+        constexpr int VPR = HD / EPV;              // vectors per cache row
+        // phase A: scores. 4 threads per position, each owns HD/4 dims of q in registers.
+        const int spos = tid >> 2, part4 = tid & 3;
+        constexpr int DPT = HD / 4;
+        float qr[DPT];
+        const float scale = 1.0f / sqrtf((float)HD);
+        {
+            const float* qv = q + (size_t)r * ldq + (size_t)head * HD + part4 * DPT;
 #pragma unroll
-        for (int i = 0; i < DPT; i++) qr[i] = qv[i] * scale;
-    }
-    for (int t0 = 0; t0 < n; t0 += AT_TILE) {
-        const int nt = min(AT_TILE, n - t0);
-        __syncthreads();
-        for (int v = tid; v < nt * VPR; v += AT_THREADS) {
-            int pr = v / VPR, pv = v % VPR;
-            uint4 d = *reinterpret_cast<const uint4*>(kbase + (size_t)(t0 + pr) * HD + pv * EPV);
-            *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = d;
+            for (int i = 0; i < DPT; i++) qr[i] = qv[i] * scale;
+        }
+        for (int t0 = 0; t0 < n; t0 += AT_TILE) {
+            const int nt = min(AT_TILE, n - t0);
+            __syncthreads();
+            for (int v = tid; v < nt * VPR; v += AT_THREADS) {
+                int pr = v / VPR, pv = v % VPR;
+                uint4 d = *reinterpret_cast<const uint4*>(kbase + (size_t)(t0 + pr) * HD + pv * EPV);
+                *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = d;
+            }
+            __syncthreads();
+            float dot = 0.f;
+            if (spos < nt) {
+                const KT* kr = reinterpret_cast<const KT*>(tile + spos * ROWB) + part4 * DPT;
+#pragma unroll
+                for (int i = 0; i < DPT; i += EPV) {
+                    float kv[EPV];
+                    Elem<KT>::load(kr + i, kv);
+#pragma unroll
+                    for (int j = 0; j < EPV; j++) dot = fmaf(qr[i + j], kv[j], dot);
+                }
+            }
+            dot += __shfl_xor(dot, 1, 64);
+            dot += __shfl_xor(dot, 2, 64);
+            if (spos < nt && part4 == 0) sc[t0 + spos] = dot;
         }
         __syncthreads();
-        float dot = 0.f;
-        if (spos < nt) {
-            const KT* kr = reinterpret_cast<const KT*>(tile + spos * ROWB) + part4 * DPT;
-#pragma unroll
-            for (int i = 0; i < DPT; i += EPV) {
-                float kv[EPV];
-                Elem<KT>::load(kr + i, kv);
-#pragma unroll
-                for (int j = 0; j < EPV; j++) dot = fmaf(qr[i + j], kv[j], dot);
+        // phase B: max, exp, sum
+        for (int j = tid; j < n; j += AT_THREADS) mx = fmaxf(mx, sc[j]);
+        mx = wave_max(mx);
+        if ((tid & 63) == 0) red[tid >> 6] = mx;
+        __syncthreads();
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        float ls = 0.f;
+        for (int j = tid; j < n; j += AT_THREADS) {
+            float e = __expf(sc[j] - mx);
+            sc[j] = e;
+            ls += e;
+        }
+        lsum = block_sum<4>(ls, red);  // contains the barriers that publish sc[]
+        // phase C: o[d] = sum_j e_j V[j][d]; thread = (group, d)
+        const int d = tid % HD, grp = tid / HD;
+        float acc = 0.f;
+        for (int t0 = 0; t0 < n; t0 += AT_TILE) {
+            const int nt = min(AT_TILE, n - t0);
+            __syncthreads();
+            for (int v = tid; v < nt * VPR; v += AT_THREADS) {
+                int pr = v / VPR, pv = v % VPR;
+                uint4 dd = *reinterpret_cast<const uint4*>(vbase + (size_t)(t0 + pr) * HD + pv * EPV);
+                *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = dd;
+            }
+            __syncthreads();
+            for (int j = grp; j < nt; j += NG) {
+                const KT* vr = reinterpret_cast<const KT*>(tile + j * ROWB);
+                acc = fmaf(sc[t0 + j], Elem<KT>::get(vr, d), acc);
             }
         }
-        dot += __shfl_xor(dot, 1, 64);
-        dot += __shfl_xor(dot, 2, 64);
-        if (spos < nt && part4 == 0) sc[t0 + spos] = dot;
-    }
-    __syncthreads();
-    // phase B: max, exp, sum
-    float mx = -INFINITY;
-    for (int j = tid; j < n; j += AT_THREADS) mx = fmaxf(mx, sc[j]);
-    mx = wave_max(mx);
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    float ls = 0.f;
-    for (int j = tid; j < n; j += AT_THREADS) {
-        float e = __expf(sc[j] - mx);
-        sc[j] = e;
-        ls += e;
-    }
-    float lsum = block_sum<4>(ls, red);  // contains the barriers that publish sc[]
-    // phase C: o[d] = sum_j e_j V[j][d]; thread = (group, d)
-    const int d = tid % HD, grp = tid / HD;
-    float acc = 0.f;
-    for (int t0 = 0; t0 < n; t0 += AT_TILE) {
-        const int nt = min(AT_TILE, n - t0);
+        accs[grp][d] = acc;
         __syncthreads();
-        for (int v = tid; v < nt * VPR; v += AT_THREADS) {
-            int pr = v / VPR, pv = v % VPR;
-            uint4 dd = *reinterpret_cast<const uint4*>(vbase + (size_t)(t0 + pr) * HD + pv * EPV);
-            *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = dd;
-        }
-        __syncthreads();
-        for (int j = grp; j < nt; j += NG) {
-            const KT* vr = reinterpret_cast<const KT*>(tile + j * ROWB);
-            acc = fmaf(sc[t0 + j], Elem<KT>::get(vr, d), acc);
-        }
-    }
-    accs[grp][d] = acc;
-    __syncthreads();
-    if (tid < HD) {
-        float o = 0.f;
+        if (tid < HD) {
 #pragma unroll
-        for (int gg = 0; gg < NG; gg++) o += accs[gg][tid];
-        out[tid] = o;
+            for (int gg = 0; gg < NG; gg++) o_val += accs[gg][tid];
+        }
     }
-    if (tid == 0) { out[HD] = mx; out[HD + 1] = lsum; }
+    if (n_splits == 1) {  // the whole row in one block: finish here
+        if (tid < HD) outp[(size_t)r * dq + (size_t)head * HD + tid] = o_val / lsum;
+        return;
+    }
+    float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 2);
+    if (tid < HD) mine[tid] = o_val;
+    if (tid == 0) { mine[HD] = mx; mine[HD + 1] = lsum; }
 }
 
+// Folds the split partials of one (row, head) into the attention output.  (Folding inside the
+// attention kernel by the last-arriving block needs device-scope fences, which on this
+// multi-XCD part cost far more than this extra launch.)
 template <int HD>
 __global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n_splits, float* __restrict__ out, int dq)
 {
     const int head = blockIdx.x, r = blockIdx.y, d = threadIdx.x;
     const float* p = part + ((size_t)r * H + head) * n_splits * (HD + 2);
-    float mx = -INFINITY;
-    for (int s = 0; s < n_splits; s++) mx = fmaxf(mx, p[(size_t)s * (HD + 2) + HD]);
+    float gm = -INFINITY;
+    for (int s = 0; s < n_splits; s++) gm = fmaxf(gm, p[(size_t)s * (HD + 2) + HD]);
     float num = 0.f, den = 0.f;
     for (int s = 0; s < n_splits; s++) {
         const float* ps = p + (size_t)s * (HD + 2);
-        float l = ps[HD + 1];
+        const float l = ps[HD + 1];
         if (l > 0.f) {
-            float w = __expf(ps[HD] - mx);
+            const float w = __expf(ps[HD] - gm);
             num = fmaf(w, ps[d], num);
             den = fmaf(w, l, den);
         }
@@ -771,6 +907,8 @@ static int attn_splits(const Dims& D, int ctx, int M)
     return s;
 }
 
+int attention_splits(const Dims& D, int ctx, int M) { return attn_splits(D, ctx, M); }
+
 size_t attention_scratch_floats(const Dims& D, int max_rows)
 {
     // splits never exceed ceil(max_seq / 64) nor max(ceil(512 / (H*M)), ceil(max_seq / AT_MAX_CHUNK))
@@ -787,10 +925,10 @@ template <typename KT, int HD>
 static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
                               int pos_off, int n_splits, int M, float* part, float* out, hipStream_t s)
 {
-    hipLaunchKernelGGL((attn_partial_kernel<KT, HD>), dim3(n_splits, D.H, M), dim3(AT_THREADS), 0, s, q, ldq,
-                       (const KT*)kc, (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part);
+    hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.H, M), dim3(AT_THREADS), 0, s, q, ldq, (const KT*)kc,
+                       (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || n_splits == 1) return e;
     hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(D.H, M), dim3(HD), 0, s, part, D.H, n_splits, out, D.dq);
     return hipGetLastError();
 }

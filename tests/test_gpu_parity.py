@@ -264,3 +264,35 @@ def test_ssd_equals_vanilla_on_the_library_itself(ssd):
         assert first_diff >= 24
         if not any(mask):
             assert sum(acc) >= 0.9 * k * len(acc)
+
+
+def test_graph_replay_is_bit_identical_to_kernel_by_kernel_launches(ssd):
+    """Decode, draft and verify sequences replayed as HIP graphs (several replays, with eager work and
+    synchronisations in between) give exactly the logits and tokens of plain launches."""
+    shape = MINI
+    w = to_gpu(make_weights(shape, 5))
+    prompt = make_prompt(shape.vocab, 70, 3).tolist()      # long enough that attention split counts change
+    mask = np.array([0, 1, 0, 0], np.uint8)
+
+    def run(graphs):
+        ctx = ssd.Context(shape, w, 200, 4)
+        ctx.ssd_set_graphs(graphs)
+        out = [ctx.ssd_prefill(prompt)]
+        logs = []
+        for cyc in range(12):
+            out.append(ctx.ssd_decode())
+            logs.append(ctx.ssd_copy_logits(0, 1).copy())
+            d = ctx.ssd_draft_step(mask, 4)
+            logs.append(ctx.ssd_copy_logits(0, 4).copy())
+            y = ctx.ssd_verify(d)
+            logs.append(ctx.ssd_copy_logits(0, 5).copy())
+            a, nx = ctx.ssd_accept(d, y)
+            if cyc % 3 == 0:
+                logs.append(ctx.ssd_layer_confidence(0, 1).copy())
+            out += d + y + [a, nx]
+        return out, logs
+
+    o1, l1 = run(False)
+    o2, l2 = run(True)
+    assert o1 == o2
+    assert all(np.array_equal(a, b) for a, b in zip(l1, l2))
