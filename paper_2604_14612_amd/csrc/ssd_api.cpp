@@ -23,7 +23,7 @@ constexpr size_t ALIGN = 256;
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
-    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, small, total;
+    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, small, total;
     int rows;       // activation rows: max(max_k + 1, SSD_PREFILL_ROWS)
     int conf_rows;  // rows of one confidence pass: 2 * L
     int logit_rows;
@@ -78,6 +78,13 @@ Layout make_layout(const ssd_config& c)
     l.logits = o; o += align_up((size_t)l.logit_rows * D.V * sizeof(float));
     l.taps = o;   o += align_up((size_t)l.rows * D.L * 2 * D.d * sizeof(float));
     l.tapn = o;   o += align_up((size_t)l.conf_rows * D.d * sizeof(float));
+    {   // bf16 hi/lo staging of activation rows for the MFMA path: rows x max(d, dq, f), or the confidence rows x d
+        size_t kbig = (size_t)(D.f > (int)kmax ? D.f : (int)kmax);
+        size_t a = (size_t)l.rows * kbig, b = (size_t)l.conf_rows * D.d;
+        size_t n = a > b ? a : b;
+        l.hi = o; o += align_up(n * 2);
+        l.lo = o; o += align_up(n * 2);
+    }
     l.small = o;  o += align_up(4096);
     l.total = o;
     return l;
@@ -116,6 +123,7 @@ struct ssd_ctx {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_ev;
 
     float* f(size_t off) const { return reinterpret_cast<float*>(ws + off); }
+    uint16_t* h16(size_t off) const { return reinterpret_cast<uint16_t*>(ws + off); }
     int32_t* small_i() const { return reinterpret_cast<int32_t*>(ws + lay.small); }
     float* small_f() const { return reinterpret_cast<float*>(ws + lay.small); }
     int* pos_dev() const { return small_i() + SM_POS; }
@@ -178,7 +186,7 @@ int layer_single(ssd_ctx* c, int l, int pos_off)
     TIMED(SSD_K_GEMV_QKV, gemv_qkv(D, c->wq[l], c->wk[l], c->wv[l], c->attn_norm[l], x, c->f(c->lay.rope), c->pos_dev(),
                                    pos_off, c->f(c->lay.qkv), c->kcache(l), c->vcache(l), c->stream), "gemv_qkv");
     TIMED(SSD_K_ATTENTION, attention(D, c->f(c->lay.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
-                                     c->n - 1, 1, c->f(c->lay.part), c->f(c->lay.att), c->stream), "attention");
+                                     c->n - 1, 1, c->f(c->lay.part), c->f(c->lay.att), nullptr, nullptr, c->stream), "attention");
     TIMED(SSD_K_GEMV_O, gemv_resid(D, c->wo[l], D.d, D.dq, c->f(c->lay.att), x, nullptr, c->stream), "gemv_o");
     TIMED(SSD_K_GEMV_GATEUP, gemv_swiglu(D, c->wg[l], c->wu[l], c->mlp_norm[l], x, c->f(c->lay.act), c->stream),
           "gemv_swiglu");
@@ -215,6 +223,45 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
     float* h = c->f(Y.h);
     HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_VTOK, M, x, c->stream), "embed");
     const int tap_ld = D.L * 2 * D.d;
+    if (rows_fused_supported(D)) {
+        // bf16 fast path: activations travel between the GEMMs as bf16 hi/lo pairs
+        uint16_t* hi = c->h16(Y.hi);
+        uint16_t* lo = c->h16(Y.lo);
+        for (int l = 0; l < D.L; l++) {
+            HIPCHK(rows_prep(x, D.d, c->attn_norm[l], M, D.d, D.eps, hi, lo, c->stream), "rows_prep");
+            RowsFused q = {};
+            q.w[0] = c->wq[l]; q.w[1] = c->wk[l]; q.w[2] = c->wv[l]; q.n[0] = D.dq; q.n[1] = D.dkv; q.n[2] = D.dkv;
+            q.K = D.d; q.bh = hi; q.bl = lo; q.ldb = D.d; q.y = c->f(Y.qkv); q.ldy = D.dq; q.M = M; q.mode = 3;
+            q.rope = c->f(Y.rope); q.pos_dev = c->pos_dev(); q.pos_off = pos_off; q.kc = c->kcache(l); q.vc = c->vcache(l);
+            TIMED(SSD_K_ROWS_QKV, rows_fused(D, q, c->stream), "rows_qkv");
+            TIMED(SSD_K_ATTENTION, attention(D, c->f(Y.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
+                                             pos_host, M, c->f(Y.part), nullptr, hi, lo, c->stream), "attention");
+            RowsFused o = {};
+            o.w[0] = c->wo[l]; o.n[0] = D.d; o.K = D.dq; o.bh = hi; o.bl = lo; o.ldb = D.dq; o.y = x; o.ldy = D.d; o.M = M;
+            o.mode = 1; o.tap = c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d; o.tap_ld = tap_ld;
+            TIMED(SSD_K_ROWS_O, rows_fused(D, o, c->stream), "rows_o");
+            HIPCHK(rows_prep(x, D.d, c->mlp_norm[l], M, D.d, D.eps, hi, lo, c->stream), "rows_prep");
+            RowsFused gu = {};
+            gu.w[0] = c->wg[l]; gu.w[1] = c->wu[l]; gu.n[0] = D.f; gu.n[1] = D.f; gu.K = D.d; gu.bh = hi; gu.bl = lo;
+            gu.ldb = D.d; gu.oh = c->h16(Y.act); gu.ol = c->h16(Y.act) + (size_t)Y.rows * D.f; gu.ldo = D.f; gu.M = M;
+            gu.mode = 2;
+            TIMED(SSD_K_ROWS_GATEUP, rows_fused(D, gu, c->stream), "rows_gateup");
+            RowsFused dn = {};
+            dn.w[0] = c->wd[l]; dn.n[0] = D.d; dn.K = D.f; dn.bh = gu.oh; dn.bl = gu.ol; dn.ldb = D.f; dn.y = x; dn.ldy = D.d;
+            dn.M = M; dn.mode = 1; dn.tap = c->f(Y.taps) + ((size_t)l * 2 + 1) * D.d; dn.tap_ld = tap_ld;
+            TIMED(SSD_K_ROWS_DOWN, rows_fused(D, dn, c->stream), "rows_down");
+        }
+        if (want_logits) {
+            HIPCHK(rows_prep(x, D.d, c->w.final_norm, M, D.d, D.eps, hi, lo, c->stream), "rows_prep");
+            RowsFused lm = {};
+            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = hi; lm.bl = lo; lm.ldb = D.d;
+            lm.y = c->f(Y.logits); lm.ldy = D.V; lm.M = M; lm.mode = 0;
+            TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows_lmhead");
+            HIPCHK(vocab_reduce(c->f(Y.logits), M, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, c->small_i() + SM_TARGET, 1,
+                                nullptr, nullptr, nullptr, c->stream), "vocab_reduce");
+        }
+        return SSD_OK;
+    }
     for (int l = 0; l < D.L; l++) {
         HIPCHK(rmsnorm_rows(x, c->attn_norm[l], M, D.d, D.eps, h, c->stream), "rmsnorm");
         RowsGemm g = {};
@@ -225,7 +272,7 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
         HIPCHK(rope_kv_rows(D, c->f(Y.qkv), c->f(Y.rope), c->pos_dev(), pos_off, M, c->kcache(l), c->vcache(l),
                             c->stream), "rope_kv");
         TIMED(SSD_K_ATTENTION, attention(D, c->f(Y.qkv), D.dq + 2 * D.dkv, c->kcache(l), c->vcache(l), c->pos_dev(),
-                                         pos_off, pos_host, M, c->f(Y.part), c->f(Y.att), c->stream), "attention");
+                                         pos_off, pos_host, M, c->f(Y.part), c->f(Y.att), nullptr, nullptr, c->stream), "attention");
         RowsGemm o = {};
         o.w[0] = c->wo[l]; o.n[0] = D.d; o.K = D.dq; o.x = c->f(Y.att); o.y = x; o.ldy = D.d; o.M = M; o.mode = 1;
         o.tap = c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d; o.tap_ld = tap_ld;
@@ -596,13 +643,24 @@ int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out,
     if ((size_t)(SM_CONF + 3 * R) * 4 > 4096) return fail(c, SSD_ECAPACITY, "too many layers for the confidence scratch");
     for (int r = 0; r < n_rows; r++) {
         const float* taps = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
-        HIPCHK(rmsnorm_rows(taps, c->w.final_norm, R, D.d, D.eps, c->f(Y.tapn), c->stream), "rmsnorm taps");
-        for (int b = 0; b < R; b += 16) {
-            int M = R - b < 16 ? R - b : 16;
-            RowsGemm lm = {};
-            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = c->f(Y.tapn) + (size_t)b * D.d;
-            lm.y = c->f(Y.logits) + (size_t)b * D.V; lm.ldy = D.V; lm.M = M; lm.mode = 0;
-            TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm conf lmhead");
+        if (rows_fused_supported(D)) {
+            HIPCHK(rows_prep(taps, D.d, c->w.final_norm, R, D.d, D.eps, c->h16(Y.hi), c->h16(Y.lo), c->stream), "rows_prep taps");
+            for (int b = 0; b < R; b += 16) {
+                RowsFused lm = {};
+                lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = c->h16(Y.hi) + (size_t)b * D.d;
+                lm.bl = c->h16(Y.lo) + (size_t)b * D.d; lm.ldb = D.d; lm.y = c->f(Y.logits) + (size_t)b * D.V; lm.ldy = D.V;
+                lm.M = R - b < 16 ? R - b : 16; lm.mode = 0;
+                TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows conf lmhead");
+            }
+        } else {
+            HIPCHK(rmsnorm_rows(taps, c->w.final_norm, R, D.d, D.eps, c->f(Y.tapn), c->stream), "rmsnorm taps");
+            for (int b = 0; b < R; b += 16) {
+                int M = R - b < 16 ? R - b : 16;
+                RowsGemm lm = {};
+                lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = c->f(Y.tapn) + (size_t)b * D.d;
+                lm.y = c->f(Y.logits) + (size_t)b * D.V; lm.ldy = D.V; lm.M = M; lm.mode = 0;
+                TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm conf lmhead");
+            }
         }
         HIPCHK(vocab_reduce(c->f(Y.logits), R, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, nullptr, 1,
                             reinterpret_cast<int32_t*>(confd + 2 * R), confd + R, confd, c->stream), "vocab_reduce conf");

@@ -58,16 +58,41 @@ struct RowsGemm {
     int mode;
 };
 hipError_t gemm_rows(const Dims& D, const RowsGemm& g, hipStream_t s);
+// Multi-row MFMA GEMM for bf16 weights with K a multiple of 64.  Activations come pre-split into
+// bf16 hi/lo arrays [M][ldb] (rows_prep, attention with out_hi/out_lo, or the SwiGLU mode below).
+//   mode 0 store fp32, 1 residual add into y (+ tap), 2 SwiGLU of two matrices written as hi/lo to
+//   oh/ol, 3 QKV: rotary on q and k at positions *pos_dev + pos_off + r, q -> y [M][dq] fp32,
+//   k and v -> cache rows.
+struct RowsFused {
+    const void* w[3];
+    int n[3];
+    int K;
+    const uint16_t* bh; const uint16_t* bl; int ldb;
+    float* y; int ldy;
+    uint16_t* oh; uint16_t* ol; int ldo;
+    float* tap; int tap_ld;
+    int M;
+    int mode;
+    const float* rope; const int* pos_dev; int pos_off;
+    void* kc; void* vc;
+};
+bool rows_fused_supported(const Dims& D);
+hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s);
+// hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
+// gain first when gain != nullptr
+hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi, uint16_t* lo,
+                     hipStream_t s);
 // rotary on q,k rows + cache write for the multi-row path. qkv: [M][dq + 2 dkv]; q is rotated in place.
 hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int* pos_dev, int pos_off, int M,
                         void* kcache_l, void* vcache_l, hipStream_t s);
 
 // ---- attention over the KV cache ---------------------------------------------------------------
 // Row r (r < M) at position p_r = *pos_dev + pos_off + r attends cache positions 0..p_r.
-// q: [M][ldq] fp32 (head h at offset h*hd); out: [M][dq].  part: scratch for the split partials.
+// q: [M][ldq] fp32 (head h at offset h*hd); out: [M][dq] fp32, or, when out_hi != nullptr, the bf16
+// hi/lo pair [M][dq] instead.  part: scratch for the split partials.
 hipError_t attention(const Dims& D, const float* q, int ldq, const void* kcache_l, const void* vcache_l,
                      const int* pos_dev, int pos_off, int pos_host_hint, int M, float* part, float* out,
-                     hipStream_t s);
+                     uint16_t* out_hi, uint16_t* out_lo, hipStream_t s);
 size_t attention_scratch_floats(const Dims& D, int max_rows);
 // number of sequence splits attention() uses when the last of M rows sees ctx positions
 int attention_splits(const Dims& D, int ctx, int M);

@@ -702,6 +702,271 @@ hipError_t gemm_rows(const Dims& D, const RowsGemm& g, hipStream_t s)
     return hipErrorInvalidValue;
 }
 
+// --- bf16 weights, multi-row MFMA GEMM at streaming speed (K a multiple of 64) -----------------------
+// The verify / prompt path.  Activations arrive already split into two bf16 arrays hi = rne(x),
+// lo = rne(x - hi) (hi + lo carries 16 mantissa bits of x), written once by whoever produced x,
+// so the GEMM itself is nothing but loads and MFMAs:
+//   * a block has 8 waves; KS waves share one 16-row tile and take K-steps of 64 in turn;
+//   * per step a lane loads 2 x 128 bits of weights (non-temporal), each instruction covering 64
+//     contiguous bytes of 16 rows, feeding two 16x16x32 MFMAs each for hi and lo;
+//   * weight loads run DA steps ahead, the cache-resident activations one step ahead;
+//   * QKV mode orders the 16 rows of a tile as 8 rotary pairs (i, i + hd/2), so the epilogue can
+//     rotate q and k and write k, v straight into the cache; SwiGLU mode writes its result
+//     directly as the hi/lo pair the down projection consumes.
+constexpr int RM_QKV = 3;
+constexpr int M2_DA = 4;
+
+struct RowsP2 {
+    const void* w[3];
+    int n[3];  // rows of each stacked matrix (multiples of 16); SWIGLU: n[0] = n[1] = f
+    int K;
+    const uint16_t* bh; const uint16_t* bl; int ldb;  // activations [M][ldb], bf16 hi and lo
+    float* y; int ldy;                                // fp32 output (STORE / RESID / QKV: q)
+    uint16_t* oh; uint16_t* ol; int ldo;              // SWIGLU: hi/lo output
+    float* tap; int tap_ld;
+    int M;
+    const float* rope; const int* pos_dev; int pos_off;
+    int hd, dq, dkv, max_seq;
+    void* kc; void* vc;
+};
+
+__device__ __forceinline__ void split_store(float v, uint16_t* hi, uint16_t* lo, size_t i)
+{
+    const uint16_t h = f32_to_bf16_bits(v);
+    hi[i] = h;
+    lo[i] = f32_to_bf16_bits(v - bf16_bits_to_f32(h));
+}
+
+// weight row of logical row r16 of tile `tile`
+template <int MODE>
+__device__ __forceinline__ const uint16_t* m2_row(const RowsP2& p, int tile, int r16, int which /*SWIGLU: 0 gate, 1 up*/)
+{
+    if (MODE == RM_SWIGLU) return (const uint16_t*)p.w[which] + (size_t)(tile * 16 + r16) * p.K;
+    if (MODE == RM_QKV) {
+        const int tq = p.dq >> 4, tk = p.dkv >> 4;
+        if (tile < tq + tk) {
+            const uint16_t* base = (const uint16_t*)p.w[0];
+            int tt = tile;
+            if (tile >= tq) { base = (const uint16_t*)p.w[1]; tt = tile - tq; }
+            const int tph = p.hd >> 4, head = tt / tph, th = tt % tph;
+            const int row = head * p.hd + th * 8 + (r16 & 7) + (r16 >> 3) * (p.hd >> 1);
+            return base + (size_t)row * p.K;
+        }
+        return (const uint16_t*)p.w[2] + (size_t)((tile - tq - tk) * 16 + r16) * p.K;
+    }
+    int row = tile * 16 + r16;
+    if (row < p.n[0]) return (const uint16_t*)p.w[0] + (size_t)row * p.K;
+    row -= p.n[0];
+    if (row < p.n[1]) return (const uint16_t*)p.w[1] + (size_t)row * p.K;
+    return (const uint16_t*)p.w[2] + (size_t)(row - p.n[1]) * p.K;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(512) void rows_mfma2_kernel(RowsP2 p, int KS)
+{
+    __shared__ float red[8][MODE == RM_SWIGLU ? 2 : 1][256];
+    __shared__ float fin[256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int TPB = 8 / KS, slot = wave / KS, kp = wave % KS;
+    const int n_tiles = MODE == RM_SWIGLU ? (p.n[0] >> 4) : ((p.n[0] + p.n[1] + p.n[2]) >> 4);
+    const int tile = blockIdx.x * TPB + slot;
+    const bool act = tile < n_tiles;
+    const int steps = p.K >> 6;
+    const int my_n = act && steps > kp ? (steps - kp + KS - 1) / KS : 0;
+    const bool col = r16 < p.M;
+
+    const uint16_t* a0p = nullptr;
+    const uint16_t* a1p = nullptr;
+    if (act) {
+        a0p = m2_row<MODE>(p, tile, r16, 0) + (size_t)kp * 64 + g * 8;
+        if (MODE == RM_SWIGLU) a1p = m2_row<MODE>(p, tile, r16, 1) + (size_t)kp * 64 + g * 8;
+    }
+    const size_t boff = (size_t)(col ? r16 : 0) * p.ldb + (size_t)kp * 64 + g * 8;
+    const uint16_t* bhp = p.bh + boff;
+    const uint16_t* blp = p.bl + boff;
+    const size_t kstride = (size_t)KS * 64;
+
+    u32x4_t a[M2_DA][2], a2[M2_DA][2];
+    u32x4_t bh[2][2], bl[2][2];
+    auto load_a = [&](int s, int i) {
+        const uint16_t* q0 = a0p + (size_t)i * kstride;
+        a[s][0] = gv_load(q0);
+        a[s][1] = gv_load(q0 + 32);
+        if (MODE == RM_SWIGLU) {
+            const uint16_t* q1 = a1p + (size_t)i * kstride;
+            a2[s][0] = gv_load(q1);
+            a2[s][1] = gv_load(q1 + 32);
+        }
+    };
+    auto load_b = [&](int b, int i) {
+        if (col) {
+            const uint16_t* qh = bhp + (size_t)i * kstride;
+            const uint16_t* ql = blp + (size_t)i * kstride;
+            bh[b][0] = *reinterpret_cast<const u32x4_t*>(qh);
+            bh[b][1] = *reinterpret_cast<const u32x4_t*>(qh + 32);
+            bl[b][0] = *reinterpret_cast<const u32x4_t*>(ql);
+            bl[b][1] = *reinterpret_cast<const u32x4_t*>(ql + 32);
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < M2_DA; s++)
+        if (s < my_n) load_a(s, s);
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+    bh[0][0] = zero4; bh[0][1] = zero4; bh[1][0] = zero4; bh[1][1] = zero4;
+    bl[0][0] = zero4; bl[0][1] = zero4; bl[1][0] = zero4; bl[1][1] = zero4;
+    if (my_n > 0) load_b(0, 0);
+
+    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    for (int i0 = 0; i0 < my_n; i0 += M2_DA) {
+#pragma unroll
+        for (int s = 0; s < M2_DA; s++) {
+            const int i = i0 + s;
+            if (i < my_n) {  // uniform per wave
+                const int par = s & 1;
+                if (i + 1 < my_n) load_b(par ^ 1, i + 1);
+                const bf16x8_t h0 = __builtin_bit_cast(bf16x8_t, bh[par][0]), h1 = __builtin_bit_cast(bf16x8_t, bh[par][1]);
+                const bf16x8_t l0 = __builtin_bit_cast(bf16x8_t, bl[par][0]), l1 = __builtin_bit_cast(bf16x8_t, bl[par][1]);
+                const bf16x8_t w0 = __builtin_bit_cast(bf16x8_t, a[s][0]), w1 = __builtin_bit_cast(bf16x8_t, a[s][1]);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, h0, acc0, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, l0, acc0, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, h1, acc0, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, l1, acc0, 0, 0, 0);
+                if (MODE == RM_SWIGLU) {
+                    const bf16x8_t u0 = __builtin_bit_cast(bf16x8_t, a2[s][0]), u1 = __builtin_bit_cast(bf16x8_t, a2[s][1]);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u0, h0, acc1, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u0, l0, acc1, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u1, h1, acc1, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u1, l1, acc1, 0, 0, 0);
+                }
+                if (i + M2_DA < my_n) load_a(s, i + M2_DA);
+            }
+        }
+    }
+    // D layout: lane (c = lane % 16, g = lane / 16) holds rows 4g..4g+3 of column c
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        red[wave][0][(g * 4 + j) * 16 + r16] = acc0[j];
+        if (MODE == RM_SWIGLU) red[wave][1][(g * 4 + j) * 16 + r16] = acc1[j];
+    }
+    __syncthreads();
+    for (int ts = 0; ts < TPB; ts++) {
+        const int t = blockIdx.x * TPB + ts;
+        if (t >= n_tiles) break;  // uniform
+        const int rr = tid & 15, c = (tid >> 4) & 15;
+        float v = 0.f, v2 = 0.f;
+        if (tid < 256) {
+            for (int j = 0; j < KS; j++) {
+                v += red[ts * KS + j][0][rr * 16 + c];
+                if (MODE == RM_SWIGLU) v2 += red[ts * KS + j][1][rr * 16 + c];
+            }
+            if (MODE == RM_QKV) fin[rr * 16 + c] = v;
+        }
+        if (MODE == RM_QKV) __syncthreads();
+        if (tid < 256 && c < p.M) {
+            if (MODE == RM_QKV) {
+                const int tq = p.dq >> 4, tk = p.dkv >> 4;
+                const int pos = p.pos_dev[0] + p.pos_off + c;
+                if (t < tq + tk) {
+                    const bool is_q = t < tq;
+                    const int tt = is_q ? t : t - tq;
+                    const int tph = p.hd >> 4, head = tt / tph, th = tt % tph, half = p.hd >> 1;
+                    const int i = th * 8 + (rr & 7);
+                    const float av = fin[(rr & 7) * 16 + c], bv = fin[((rr & 7) + 8) * 16 + c];
+                    const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+                    const float o = rr < 8 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
+                    const int e = rr < 8 ? i : i + half;
+                    if (is_q) p.y[(size_t)c * p.ldy + (size_t)head * p.hd + e] = o;
+                    else Elem<uint16_t>::put((uint16_t*)p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, o);
+                } else {
+                    const int e = (t - tq - tk) * 16 + rr;
+                    Elem<uint16_t>::put((uint16_t*)p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v);
+                }
+            } else {
+                const size_t colx = (size_t)t * 16 + rr;
+                if (MODE == RM_STORE) p.y[(size_t)c * p.ldy + colx] = v;
+                else if (MODE == RM_RESID) {
+                    float* dst = p.y + (size_t)c * p.ldy + colx;
+                    const float tv = *dst + v;
+                    *dst = tv;
+                    if (p.tap) p.tap[(size_t)c * p.tap_ld + colx] = tv;
+                } else split_store(v / (1.0f + __expf(-v)) * v2, p.oh, p.ol, (size_t)c * p.ldo + colx);
+            }
+        }
+        if (MODE == RM_QKV) __syncthreads();
+    }
+}
+
+template <int MODE>
+static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
+{
+    const int n_tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
+    const int steps = p.K / 64;
+    // One tile per block, its 8 waves side by side along K: the block then reads 1 KB-wide stripes of
+    // 16 consecutive rows, the widest footprint a 16-row tile allows (narrower stripes stream slower).
+    int KS = 8;
+    while (KS > 1 && steps < KS) KS >>= 1;
+    const int TPB = 8 / KS;
+    hipLaunchKernelGGL((rows_mfma2_kernel<MODE>), dim3(ceil_div(n_tiles, TPB)), dim3(512), 0, s, p, KS);
+    return hipGetLastError();
+}
+
+bool rows_fused_supported(const Dims& D)
+{
+    return D.wt == WT_BF16 && D.d % 64 == 0 && D.dq % 64 == 0 && D.f % 64 == 0;
+}
+
+hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s)
+{
+    if (!rows_fused_supported(D) || f.M < 1 || f.M > 16 || f.K % 64) return hipErrorInvalidValue;
+    RowsP2 p = {};
+    for (int i = 0; i < 3; i++) { p.w[i] = f.w[i]; p.n[i] = f.n[i]; }
+    p.K = f.K; p.bh = f.bh; p.bl = f.bl; p.ldb = f.ldb; p.y = f.y; p.ldy = f.ldy; p.oh = f.oh; p.ol = f.ol; p.ldo = f.ldo;
+    p.tap = f.tap; p.tap_ld = f.tap_ld; p.M = f.M; p.rope = f.rope; p.pos_dev = f.pos_dev; p.pos_off = f.pos_off;
+    p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq; p.kc = f.kc; p.vc = f.vc;
+    switch (f.mode) {
+        case RM_STORE: return rows_fused_mode<RM_STORE>(p, s);
+        case RM_RESID: return rows_fused_mode<RM_RESID>(p, s);
+        case RM_SWIGLU: return rows_fused_mode<RM_SWIGLU>(p, s);
+        case RM_QKV: return rows_fused_mode<RM_QKV>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// hi/lo bf16 split of M rows of length K, optionally RMS-normalised first (gain != nullptr)
+__global__ __launch_bounds__(256) void rows_prep_kernel(const float* __restrict__ in, int ldx, const float* __restrict__ gain,
+                                                        int K, float eps, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo)
+{
+    __shared__ float red[4];
+    const float* x = in + (size_t)blockIdx.x * ldx;
+    float sc = 1.0f;
+    if (gain) {
+        float ss = 0.f;
+        for (int i = threadIdx.x * 4; i < K; i += 1024) {
+            const float4 v = *reinterpret_cast<const float4*>(x + i);
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+        sc = 1.0f / sqrtf(block_sum<4>(ss, red) / (float)K + eps);
+    }
+    for (int i = threadIdx.x * 4; i < K; i += 1024) {
+        float4 v = *reinterpret_cast<const float4*>(x + i);
+        if (gain) {
+            const float4 g = *reinterpret_cast<const float4*>(gain + i);
+            v.x = v.x * sc * g.x; v.y = v.y * sc * g.y; v.z = v.z * sc * g.z; v.w = v.w * sc * g.w;
+        }
+        const size_t o = (size_t)blockIdx.x * K + i;
+        split_store(v.x, hi, lo, o); split_store(v.y, hi, lo, o + 1);
+        split_store(v.z, hi, lo, o + 2); split_store(v.w, hi, lo, o + 3);
+    }
+}
+
+hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi, uint16_t* lo,
+                     hipStream_t s)
+{
+    hipLaunchKernelGGL(rows_prep_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, eps, hi, lo);
+    return hipGetLastError();
+}
+
 // rotary + cache write for the multi-row path: one thread per (row, head slot, pair index)
 template <typename KT>
 __global__ void rope_kv_rows_kernel(float* __restrict__ qkv, const float* __restrict__ rope, const int* pos_dev,
@@ -767,7 +1032,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
                                                           const KT* __restrict__ kc, const KT* __restrict__ vc,
                                                           const int* pos_dev, int pos_off, int M, int H, int Hkv,
                                                           int max_seq, int n_splits, float* __restrict__ part,
-                                                          float* __restrict__ outp, int dq)
+                                                          float* __restrict__ outp, int dq,
+                                                          uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
 {
     constexpr int ROWB = HD * (int)sizeof(KT) + 16;  // padded LDS row (bytes) to spread banks
     constexpr int NG = AT_THREADS / HD;              // position groups in the P.V phase
@@ -864,7 +1130,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
         }
     }
     if (n_splits == 1) {  // the whole row in one block: finish here
-        if (tid < HD) outp[(size_t)r * dq + (size_t)head * HD + tid] = o_val / lsum;
+        if (tid < HD) {
+            const size_t o = (size_t)r * dq + (size_t)head * HD + tid;
+            if (out_hi) split_store(o_val / lsum, out_hi, out_lo, o);
+            else outp[o] = o_val / lsum;
+        }
         return;
     }
     float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 2);
@@ -876,7 +1146,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
 // attention kernel by the last-arriving block needs device-scope fences, which on this
 // multi-XCD part cost far more than this extra launch.)
 template <int HD>
-__global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n_splits, float* __restrict__ out, int dq)
+__global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n_splits, float* __restrict__ out, int dq,
+                                    uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
 {
     const int head = blockIdx.x, r = blockIdx.y, d = threadIdx.x;
     const float* p = part + ((size_t)r * H + head) * n_splits * (HD + 2);
@@ -892,7 +1163,9 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n
             den = fmaf(w, l, den);
         }
     }
-    out[(size_t)r * dq + (size_t)head * HD + d] = num / den;
+    const size_t o = (size_t)r * dq + (size_t)head * HD + d;
+    if (out_hi) split_store(num / den, out_hi, out_lo, o);
+    else out[o] = num / den;
 }
 
 static int attn_splits(const Dims& D, int ctx, int M)
@@ -923,28 +1196,31 @@ size_t attention_scratch_floats(const Dims& D, int max_rows)
 
 template <typename KT, int HD>
 static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
-                              int pos_off, int n_splits, int M, float* part, float* out, hipStream_t s)
+                              int pos_off, int n_splits, int M, float* part, float* out, uint16_t* out_hi, uint16_t* out_lo,
+                              hipStream_t s)
 {
     hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.H, M), dim3(AT_THREADS), 0, s, q, ldq, (const KT*)kc,
-                       (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq);
+                       (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_splits == 1) return e;
-    hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(D.H, M), dim3(HD), 0, s, part, D.H, n_splits, out, D.dq);
+    hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(D.H, M), dim3(HD), 0, s, part, D.H, n_splits, out, D.dq, out_hi,
+                       out_lo);
     return hipGetLastError();
 }
 
 hipError_t attention(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
-                     int pos_off, int pos_host_hint, int M, float* part, float* out, hipStream_t s)
+                     int pos_off, int pos_host_hint, int M, float* part, float* out, uint16_t* out_hi, uint16_t* out_lo,
+                     hipStream_t s)
 {
     int ctx = pos_host_hint + pos_off + M;  // positions the last row sees
     if (ctx < 1 || ctx > D.max_seq) return hipErrorInvalidValue;
     int n_splits = attn_splits(D, ctx, M);
     if (D.wt == WT_BF16) {
-        if (D.hd == 128) return attention_t<uint16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
-        if (D.hd == 64) return attention_t<uint16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
+        if (D.hd == 128) return attention_t<uint16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
+        if (D.hd == 64) return attention_t<uint16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
     } else {
-        if (D.hd == 128) return attention_t<float, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
-        if (D.hd == 64) return attention_t<float, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, s);
+        if (D.hd == 128) return attention_t<float, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
+        if (D.hd == 64) return attention_t<float, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
     }
     return hipErrorInvalidValue;
 }
