@@ -17,6 +17,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the draft gate/up GEMV at Llama-2-7B shape: rocprofv3 FETCH_SIZE + WRITE_SIZE per
+# dispatch, scaled by the factors a known-size read / copy kernel gives (FETCH_SIZE x2.000, WRITE_SIZE x1.000);
+# the run and the arithmetic are in profiles/kernel_bench_llama7b_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"llama7b": 180.76e6}
 
 
 def layer_bytes(s):
@@ -43,7 +47,7 @@ def gateup_kernel_bytes(s):
     return 2 * s.d_ffn * s.d_model * s.bytes_per_weight() + 2 * s.d_model * 4 + s.d_ffn * 4
 
 
-def cpu_baseline(shape, weights_gpu, prompt, k, mask, n_prompt=8, n_cycles=3):
+def cpu_baseline(shape, weights_gpu, prompt, k, mask, n_prompt=8, n_cycles=8):
     """Times the CPU oracle (as it stands) on a bounded sample of the same workload."""
     import numpy as np
     from oracle import OracleModel, OracleSSD
@@ -200,7 +204,7 @@ def main():
         "hbm_read_probe_GBps": probe_gbps,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel<bf16, SWIGLU> (draft gate/up GEMV)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None, "avg_launch_us": kern_ms * 1e3, "launches_timed": n_launch,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if args.layers is None else None, "avg_launch_us": kern_ms * 1e3, "launches_timed": n_launch,
                      "algorithmic_bytes_per_launch": kern_bytes},
     }
     if not args.no_cpu_baseline:

@@ -257,6 +257,8 @@ class Context:
                         arr("wo", exp_dt), arr("mlp_norm", torch.float32), arr("wg", exp_dt), arr("wu", exp_dt),
                         arr("wd", exp_dt))
         self._check(self._l.ssd_load_weights(self._h, C.byref(w)))
+        if os.environ.get("SSD_NO_GRAPHS"):       # e.g. under counter-collecting profilers
+            self.ssd_set_graphs(False)
 
     def _check(self, rc, h="self"):
         if rc != 0:

@@ -5,6 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssd.so")
+KERNEL_BENCH = os.path.join(HERE, "kernel_bench")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -39,6 +40,14 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    # stand-alone kernel micro-benchmark (tuning, rocprofv3 counter runs)
+    kb_src = os.path.join(CSRC, "kernel_bench.cpp")
+    kb_obj = os.path.join(CSRC, "kernel_bench.o")
+    for cmd in ([HIPCC, "-x", "hip"] + DEVICE_FLAGS + ["-c", kb_src, "-o", kb_obj],
+                [HIPCC, "--offload-arch=gfx950", "-o", KERNEL_BENCH, kb_obj, os.path.join(CSRC, "ssd_kernels.o")]):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("kernel_bench build failed:\n" + r.stderr)
     return LIB
 
 

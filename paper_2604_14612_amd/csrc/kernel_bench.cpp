@@ -1,0 +1,121 @@
+// kernel_bench: runs the library's hot kernels in isolation at Llama-2-7B shapes (distinct weights for
+// every launch, so nothing is served from the caches) and prints the time per launch.  Used for tuning
+// and, under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`, for the HBM traffic of each kernel; the
+// read probe and the fp32 copy move a known number of bytes and calibrate those counters.
+#include "ssd_kernels.h"
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#define CK(x)                                                                         \
+    do {                                                                              \
+        hipError_t e__ = (x);                                                         \
+        if (e__ != hipSuccess) {                                                      \
+            std::printf("HIP error %s at line %d\n", hipGetErrorString(e__), __LINE__); \
+            std::exit(1);                                                             \
+        }                                                                             \
+    } while (0)
+
+using namespace ssdk;
+
+template <typename F>
+static void timeit(const char* name, double bytes, int n, F&& launch)
+{
+    hipEvent_t a, b;
+    CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
+    float best = 1e30f;
+    for (int rep = 0; rep < 3; rep++) {
+        CK(hipDeviceSynchronize());
+        CK(hipEventRecord(a, 0));
+        for (int i = 0; i < n; i++) launch(i);
+        CK(hipEventRecord(b, 0));
+        CK(hipEventSynchronize(b));
+        float ms;
+        CK(hipEventElapsedTime(&ms, a, b));
+        if (ms < best) best = ms;
+    }
+    const double us = best * 1e3 / n;
+    std::printf("%-28s %9.2f us per launch  %8.1f MB  %7.0f GB/s\n", name, us, bytes / 1e6, bytes / us / 1e3);
+    std::fflush(stdout);
+    CK(hipEventDestroy(a)); CK(hipEventDestroy(b));
+}
+
+int main(int argc, char** argv)
+{
+    const int M = argc > 1 ? std::atoi(argv[1]) : 5;  // rows of the multi-row kernels (k + 1)
+    if (M < 1 || M > 16) { std::printf("rows must be 1..16\n"); return 1; }
+    Dims D;
+    D.L = 32; D.d = 4096; D.H = 32; D.Hkv = 32; D.hd = 128; D.dq = 4096; D.dkv = 4096; D.f = 11008; D.V = 32000;
+    D.max_seq = 1024; D.eps = 1e-5f; D.wt = WT_BF16;
+    const size_t wbig = (size_t)3 << 30;  // 6 GB of bf16 weights to walk through
+    uint16_t* W;
+    CK(hipMalloc(&W, wbig * 2));
+    {
+        std::vector<uint16_t> h(1 << 24);
+        unsigned st = 12345;
+        for (auto& v : h) { st = st * 1664525u + 1013904223u; v = (uint16_t)(0x3c00 | ((st >> 16) & 0x83ff)); }
+        for (size_t o = 0; o < wbig; o += h.size()) CK(hipMemcpy(W + o, h.data(), h.size() * 2, hipMemcpyHostToDevice));
+    }
+    float *x, *gain, *act, *q, *rope, *logits, *part, *sink, *big_a, *big_b;
+    int* pos;
+    uint16_t *kc, *vc, *hi, *lo;
+    const size_t act_floats = (size_t)16 * 32000;
+    CK(hipMalloc(&x, act_floats * 4)); CK(hipMalloc(&gain, 1 << 20)); CK(hipMalloc(&act, act_floats * 4));
+    CK(hipMalloc(&q, act_floats * 4)); CK(hipMalloc(&logits, act_floats * 4)); CK(hipMalloc(&part, 64 << 20));
+    CK(hipMalloc(&rope, (size_t)1024 * 64 * 2 * 4)); CK(hipMalloc(&pos, 64)); CK(hipMalloc(&sink, 256));
+    CK(hipMalloc(&kc, (size_t)32 * 1024 * 128 * 2)); CK(hipMalloc(&vc, (size_t)32 * 1024 * 128 * 2));
+    CK(hipMalloc(&hi, act_floats * 2)); CK(hipMalloc(&lo, act_floats * 2));
+    CK(hipMalloc(&big_a, (size_t)256 << 20)); CK(hipMalloc(&big_b, (size_t)256 << 20));
+    CK(hipMemset(x, 0, act_floats * 4)); CK(hipMemset(gain, 0, 1 << 20)); CK(hipMemset(act, 0, act_floats * 4));
+    CK(hipMemset(q, 0, act_floats * 4)); CK(hipMemset(rope, 0, (size_t)1024 * 64 * 2 * 4));
+    CK(hipMemset(kc, 0, (size_t)32 * 1024 * 128 * 2)); CK(hipMemset(vc, 0, (size_t)32 * 1024 * 128 * 2));
+    CK(hipMemset(hi, 0, act_floats * 2)); CK(hipMemset(lo, 0, act_floats * 2));
+    const int ctx = 640;
+    CK(hipMemcpy(pos, &ctx, 4, hipMemcpyHostToDevice));
+    const size_t gu = (size_t)11008 * 4096, qk = (size_t)4096 * 4096, lm = (size_t)32000 * 4096;
+    const int n = 12;
+
+    // calibration kernels: known traffic
+    timeit("read_probe 256 MiB", 268435456.0, 4, [&](int i) { CK(read_probe(W + (size_t)i * (134217728), (size_t)256 << 20, sink, 0)); });
+    timeit("copy_f32 256 MiB", 2 * 268435456.0, 4, [&](int) { CK(copy_f32(big_a, big_b, (size_t)64 << 20, 0)); });
+
+    // single-row (draft / vanilla decode) kernels
+    timeit("gemv_qkv", 3 * qk * 2.0, n, [&](int i) {
+        const uint16_t* w = W + (size_t)i * 3 * qk;
+        CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc, vc, 0)); });
+    timeit("gemv_o (resid)", qk * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, q, x, nullptr, 0)); });
+    timeit("gemv_gateup (swiglu)", 2 * gu * 2.0, n, [&](int i) {
+        const uint16_t* w = W + (size_t)i * 2 * gu;
+        CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0)); });
+    timeit("gemv_down (resid)", gu * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * gu, 4096, 11008, act, x, nullptr, 0)); });
+    timeit("gemv_lmhead", lm * 2.0, n, [&](int i) { CK(gemv_lmhead(D, W + (size_t)i * lm, gain, x, logits, 0)); });
+    timeit("attention 1 row ctx 641", 2.0 * 641 * 4096 * 2, n, [&](int) {
+        CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0)); });
+    timeit("vocab_reduce 1 row", 32000 * 4.0, n, [&](int) {
+        CK(vocab_reduce(logits, 1, 32000, 1e4f, 1e-10f, pos + 8, 1, nullptr, sink, nullptr, 0)); });
+
+    // multi-row (verify) kernels, M rows
+    auto fused = [&](int mode, const uint16_t* w0, const uint16_t* w1, const uint16_t* w2, int n0, int n1, int n2, int K,
+                     float* y, int ldy) {
+        RowsFused f = {};
+        f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
+        f.bh = hi; f.bl = lo; f.ldb = K; f.y = y; f.ldy = ldy; f.oh = hi; f.ol = lo; f.ldo = 11008; f.M = M; f.mode = mode;
+        f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
+        CK(rows_fused(D, f, 0));
+    };
+    timeit("rows_prep (norm+split)", M * 4096 * 8.0, n, [&](int) { CK(rows_prep(x, 4096, gain, M, 4096, 1e-5f, hi, lo, 0)); });
+    timeit("rows_qkv", 3 * qk * 2.0, n, [&](int i) {
+        const uint16_t* w = W + (size_t)i * 3 * qk;
+        fused(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, q, 4096); });
+    timeit("rows_o (resid)", qk * 2.0, n, [&](int i) { fused(1, W + (size_t)i * qk, nullptr, nullptr, 4096, 0, 0, 4096, x, 4096); });
+    timeit("rows_gateup (swiglu)", 2 * gu * 2.0, n, [&](int i) {
+        const uint16_t* w = W + (size_t)i * 2 * gu;
+        fused(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
+    timeit("rows_down (resid)", gu * 2.0, n, [&](int i) { fused(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, x, 4096); });
+    timeit("rows_lmhead", lm * 2.0, n, [&](int i) { fused(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, logits, 32000); });
+    timeit("attention M rows ctx 640+M", 2.0 * (640 + M) * 4096 * 2, n, [&](int) {
+        CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, M, part, nullptr, hi, lo, 0)); });
+    return 0;
+}
