@@ -93,6 +93,14 @@ int main(int argc, char** argv)
     timeit("gemv_lmhead", lm * 2.0, n, [&](int i) { CK(gemv_lmhead(D, W + (size_t)i * lm, gain, x, logits, 0)); });
     timeit("attention 1 row ctx 641", 2.0 * 641 * 4096 * 2, n, [&](int) {
         CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0)); });
+    for (int sp : {1, 2, 4, 8, 16, 32}) {
+        attention_force_splits(sp);
+        char nm[64];
+        std::snprintf(nm, sizeof nm, "attention 1 row, %d splits", sp);
+        timeit(nm, 2.0 * 641 * 4096 * 2, n, [&](int) {
+            CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0)); });
+    }
+    attention_force_splits(0);
     timeit("vocab_reduce 1 row", 32000 * 4.0, n, [&](int) {
         CK(vocab_reduce(logits, 1, 32000, 1e4f, 1e-10f, pos + 8, 1, nullptr, sink, nullptr, 0)); });
 

@@ -96,6 +96,8 @@ hipError_t attention(const Dims& D, const float* q, int ldq, const void* kcache_
 size_t attention_scratch_floats(const Dims& D, int max_rows);
 // number of sequence splits attention() uses when the last of M rows sees ctx positions
 int attention_splits(const Dims& D, int ctx, int M);
+// tuning hook: n > 0 forces the split count (scratch must have been sized for it), 0 restores the heuristic
+void attention_force_splits(int n);
 
 // ---- vocabulary reduction ------------------------------------------------------------------------
 // Per row of logits [M][V]: arg-max (lowest index on ties), softmax max-probability and, when

@@ -1023,9 +1023,25 @@ hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int*
 // attention over the cache: split over the sequence, K/V tiles staged through LDS
 // ---------------------------------------------------------------------------------------------
 constexpr int AT_THREADS = 256;
-constexpr int AT_TILE = 64;        // cache positions per LDS tile
-constexpr int AT_MAX_CHUNK = 2048; // positions one block may own (LDS score buffer)
+constexpr int AT_CHUNK = 96;   // cache positions one block owns (K and V of the chunk live in LDS together)
+constexpr int AT_QPASS = 16;   // query vectors handled per pass over the staged chunk
 
+// P.V for up to NQ query vectors at once: acc[qi] += e[qi][j] * V[j][d] over this thread's positions
+template <typename KT, int NQ>
+__device__ __forceinline__ void attn_pv(const KT* vtile, int rowb, const float* sc, int d, int grp, int ng, int n,
+                                        float (&acc)[AT_QPASS])
+{
+    for (int j = grp; j < n; j += ng) {
+        const float v = Elem<KT>::get(reinterpret_cast<const KT*>(reinterpret_cast<const unsigned char*>(vtile) + (size_t)j * rowb), d);
+#pragma unroll
+        for (int qi = 0; qi < NQ; qi++) acc[qi] = fmaf(sc[qi * AT_CHUNK + j], v, acc[qi]);
+    }
+}
+
+// One block = one KV head x one chunk of positions x ALL query vectors that read this head (the G
+// query heads of the group times the M rows), so K and V are fetched once however many rows verify.
+// All global loads of the chunk are issued up front, land in LDS (rows padded by 16 bytes to spread
+// banks), and the three phases -- scores, softmax statistics, P.V -- then run out of LDS only.
 // partial layout per (row, head, split): [hd] unnormalised output, then m (max score), l (sum of exp)
 template <typename KT, int HD>
 __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restrict__ q, int ldq,
@@ -1035,111 +1051,147 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
                                                           float* __restrict__ outp, int dq,
                                                           uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
 {
-    constexpr int ROWB = HD * (int)sizeof(KT) + 16;  // padded LDS row (bytes) to spread banks
-    constexpr int NG = AT_THREADS / HD;              // position groups in the P.V phase
-    __shared__ __align__(16) unsigned char tile[AT_TILE * ROWB];
-    __shared__ float sc[AT_MAX_CHUNK];
-    __shared__ float red[4];
-    __shared__ float accs[NG][HD];
+    constexpr int ROWB = HD * (int)sizeof(KT) + 16;
+    constexpr int EPV = 16 / (int)sizeof(KT);  // elements per 16-byte vector
+    constexpr int VPR = HD / EPV;              // vectors per cache row
+    constexpr int NG = AT_THREADS / HD;        // position groups in the P.V phase
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* ktile = smem;
+    unsigned char* vtile = smem + AT_CHUNK * ROWB;
+    float* qs = reinterpret_cast<float*>(smem + 2 * AT_CHUNK * ROWB);  // [AT_QPASS][HD], pre-scaled
+    float* sc = qs + AT_QPASS * HD;                                    // [AT_QPASS][AT_CHUNK]
+    float* ml = sc + AT_QPASS * AT_CHUNK;                              // [AT_QPASS][2]
+    float* fold = ml + AT_QPASS * 2;                                   // [NG][AT_QPASS][HD]
 
-    const int split = blockIdx.x, head = blockIdx.y, r = blockIdx.z;
-    const int kvh = head / (H / Hkv);
+    const int split = blockIdx.x, kvh = blockIdx.y;
+    const int G = H / Hkv, Q = G * M;
     const int p0 = pos_dev[0] + pos_off;
-    const int n_ctx = p0 + r + 1;                         // this row sees positions 0..p0+r
-    const int chunk = (p0 + M + n_splits - 1) / n_splits; // same chunking for all rows of the block
+    const int total = p0 + M;                                  // positions the last row sees
+    const int chunk = min((total + n_splits - 1) / n_splits, AT_CHUNK);  // host sizes n_splits so this is <= AT_CHUNK
     const int j0 = split * chunk;
-    const int j1 = min(min(j0 + chunk, n_ctx), j0 + AT_MAX_CHUNK);  // host sizes chunk <= AT_MAX_CHUNK
-    const int n = j1 - j0;                                // may be <= 0: nothing for this row in this split
-    const int tid = threadIdx.x;
-    float o_val = 0.f, mx = -INFINITY, lsum = 0.f;        // o_val: element tid of the unnormalised output
-    if (n > 0) {
+    const int n = min(chunk, total - j0);                      // may be <= 0
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    if (n > 0) {  // stage K and V of the chunk: every load is issued before the first is used
         const KT* kbase = kc + ((size_t)kvh * max_seq + j0) * HD;
         const KT* vbase = vc + ((size_t)kvh * max_seq + j0) * HD;
-        constexpr int EPV = 16 / (int)sizeof(KT);  // elements per 16-byte vector
-        constexpr int VPR = HD / EPV;              // vectors per cache row
-        // phase A: scores. 4 threads per position, each owns HD/4 dims of q in registers.
-        const int spos = tid >> 2, part4 = tid & 3;
-        constexpr int DPT = HD / 4;
-        float qr[DPT];
-        const float scale = 1.0f / sqrtf((float)HD);
-        {
-            const float* qv = q + (size_t)r * ldq + (size_t)head * HD + part4 * DPT;
+        constexpr int NV = (AT_CHUNK * VPR + AT_THREADS - 1) / AT_THREADS;
+        uint4 kr[NV], vr[NV];
+        const int vmax = n * VPR - 1;
 #pragma unroll
-            for (int i = 0; i < DPT; i++) qr[i] = qv[i] * scale;
+        for (int t = 0; t < NV; t++) {  // clamped, not predicated: the loads stay in registers and in flight together
+            const int v = min(tid + t * AT_THREADS, vmax);
+            kr[t] = *reinterpret_cast<const uint4*>(kbase + (size_t)(v / VPR) * HD + (v % VPR) * EPV);
+            vr[t] = *reinterpret_cast<const uint4*>(vbase + (size_t)(v / VPR) * HD + (v % VPR) * EPV);
         }
-        for (int t0 = 0; t0 < n; t0 += AT_TILE) {
-            const int nt = min(AT_TILE, n - t0);
-            __syncthreads();
-            for (int v = tid; v < nt * VPR; v += AT_THREADS) {
-                int pr = v / VPR, pv = v % VPR;
-                uint4 d = *reinterpret_cast<const uint4*>(kbase + (size_t)(t0 + pr) * HD + pv * EPV);
-                *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = d;
+#pragma unroll
+        for (int t = 0; t < NV; t++) {
+            const int v = tid + t * AT_THREADS;
+            if (v <= vmax) {
+                *reinterpret_cast<uint4*>(ktile + (v / VPR) * ROWB + (v % VPR) * 16) = kr[t];
+                *reinterpret_cast<uint4*>(vtile + (v / VPR) * ROWB + (v % VPR) * 16) = vr[t];
             }
-            __syncthreads();
-            float dot = 0.f;
-            if (spos < nt) {
-                const KT* kr = reinterpret_cast<const KT*>(tile + spos * ROWB) + part4 * DPT;
+        }
+    }
+    const float scale = 1.0f / sqrtf((float)HD);
+    for (int q0 = 0; q0 < Q; q0 += AT_QPASS) {   // uniform over the block
+        const int nq = min(AT_QPASS, Q - q0);
+        __syncthreads();                         // staged tiles visible / previous pass done with qs, sc
+        for (int e = tid; e < nq * HD; e += AT_THREADS) {
+            const int qi = q0 + e / HD, r = qi / G, g = qi % G;
+            qs[e] = q[(size_t)r * ldq + (size_t)(kvh * G + g) * HD + (e % HD)] * scale;
+        }
+        __syncthreads();
+        if (n > 0) {
+            // phase A: scores. 2 lanes per position, each holding half a key row in registers
+            constexpr int DPT = HD / 2;
+            for (int jb = 0; jb < n; jb += AT_THREADS / 2) {
+                const int j = jb + (tid >> 1), half = tid & 1;
+                float kf[DPT];
+                if (j < n) {
+                    const KT* krow = reinterpret_cast<const KT*>(ktile + j * ROWB) + half * DPT;
 #pragma unroll
-                for (int i = 0; i < DPT; i += EPV) {
-                    float kv[EPV];
-                    Elem<KT>::load(kr + i, kv);
+                    for (int i = 0; i < DPT; i += EPV) {
+                        float t8[EPV];
+                        Elem<KT>::load(krow + i, t8);
 #pragma unroll
-                    for (int j = 0; j < EPV; j++) dot = fmaf(qr[i + j], kv[j], dot);
+                        for (int u = 0; u < EPV; u++) kf[i + u] = t8[u];
+                    }
+                }
+                for (int qi = 0; qi < nq; qi++) {
+                    float dot = 0.f;
+                    if (j < n) {
+                        const float* qv = qs + qi * HD + half * DPT;
+#pragma unroll
+                        for (int i = 0; i < DPT; i += 4) {
+                            const float4 t4 = *reinterpret_cast<const float4*>(qv + i);
+                            dot = fmaf(kf[i], t4.x, dot); dot = fmaf(kf[i + 1], t4.y, dot);
+                            dot = fmaf(kf[i + 2], t4.z, dot); dot = fmaf(kf[i + 3], t4.w, dot);
+                        }
+                    }
+                    dot += __shfl_xor(dot, 1, 64);
+                    if (j < n && half == 0) sc[qi * AT_CHUNK + j] = dot;
                 }
             }
-            dot += __shfl_xor(dot, 1, 64);
-            dot += __shfl_xor(dot, 2, 64);
-            if (spos < nt && part4 == 0) sc[t0 + spos] = dot;
         }
         __syncthreads();
-        // phase B: max, exp, sum
-        for (int j = tid; j < n; j += AT_THREADS) mx = fmaxf(mx, sc[j]);
-        mx = wave_max(mx);
-        if ((tid & 63) == 0) red[tid >> 6] = mx;
-        __syncthreads();
-        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        float ls = 0.f;
-        for (int j = tid; j < n; j += AT_THREADS) {
-            float e = __expf(sc[j] - mx);
-            sc[j] = e;
-            ls += e;
+        // phase B: per query vector (one wave each): causal mask, max, exp, sum
+        for (int qi = wave; qi < nq; qi += AT_THREADS / 64) {
+            const int r = (q0 + qi) / G;
+            const int vis = min(n, p0 + r + 1 - j0);   // positions of this chunk the row may see
+            float mx = -INFINITY;
+            for (int j = lane; j < vis; j += 64) mx = fmaxf(mx, sc[qi * AT_CHUNK + j]);
+            mx = wave_max(mx);
+            float ls = 0.f;
+            for (int j = lane; j < n; j += 64) {
+                const float e = j < vis ? __expf(sc[qi * AT_CHUNK + j] - mx) : 0.f;
+                sc[qi * AT_CHUNK + j] = e;
+                ls += e;
+            }
+            ls = wave_sum(ls);
+            if (lane == 0) { ml[qi * 2] = mx; ml[qi * 2 + 1] = ls; }
         }
-        lsum = block_sum<4>(ls, red);  // contains the barriers that publish sc[]
-        // phase C: o[d] = sum_j e_j V[j][d]; thread = (group, d)
+        __syncthreads();
+        // phase C: o[qi][d] = sum_j e[qi][j] V[j][d]; thread = (position group, d), all nq accumulators in registers
         const int d = tid % HD, grp = tid / HD;
-        float acc = 0.f;
-        for (int t0 = 0; t0 < n; t0 += AT_TILE) {
-            const int nt = min(AT_TILE, n - t0);
-            __syncthreads();
-            for (int v = tid; v < nt * VPR; v += AT_THREADS) {
-                int pr = v / VPR, pv = v % VPR;
-                uint4 dd = *reinterpret_cast<const uint4*>(vbase + (size_t)(t0 + pr) * HD + pv * EPV);
-                *reinterpret_cast<uint4*>(tile + pr * ROWB + pv * 16) = dd;
-            }
-            __syncthreads();
-            for (int j = grp; j < nt; j += NG) {
-                const KT* vr = reinterpret_cast<const KT*>(tile + j * ROWB);
-                acc = fmaf(sc[t0 + j], Elem<KT>::get(vr, d), acc);
-            }
-        }
-        accs[grp][d] = acc;
-        __syncthreads();
-        if (tid < HD) {
+        float acc[AT_QPASS];
 #pragma unroll
-            for (int gg = 0; gg < NG; gg++) o_val += accs[gg][tid];
+        for (int qi = 0; qi < AT_QPASS; qi++) acc[qi] = 0.f;
+        const KT* vcol = reinterpret_cast<const KT*>(vtile);
+        if (nq == 1) attn_pv<KT, 1>(vcol, ROWB, sc, d, grp, NG, n, acc);
+        else if (nq <= 4) attn_pv<KT, 4>(vcol, ROWB, sc, d, grp, NG, n, acc);
+        else if (nq <= 8) attn_pv<KT, 8>(vcol, ROWB, sc, d, grp, NG, n, acc);
+        else attn_pv<KT, AT_QPASS>(vcol, ROWB, sc, d, grp, NG, n, acc);
+        // fold the NG position groups and write this split's result
+#pragma unroll
+        for (int qi = 0; qi < AT_QPASS; qi++)
+            if (qi < nq) fold[(grp * AT_QPASS + qi) * HD + d] = acc[qi];
+        __syncthreads();
+        for (int e = tid; e < nq * HD; e += AT_THREADS) {
+            const int qi = e / HD, dd = e % HD;
+            float o = 0.f;
+#pragma unroll
+            for (int gg = 0; gg < NG; gg++) o += fold[(gg * AT_QPASS + qi) * HD + dd];
+            const int qg = q0 + qi, r = qg / G, head = kvh * G + qg % G;
+            const float mx = ml[qi * 2], ls = ml[qi * 2 + 1];
+            if (n_splits == 1) {
+                const size_t oo = (size_t)r * dq + (size_t)head * HD + dd;
+                if (out_hi) split_store(o / ls, out_hi, out_lo, oo);
+                else outp[oo] = o / ls;
+            } else {
+                float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 2);
+                mine[dd] = o;
+                if (dd == 0) { mine[HD] = n > 0 ? mx : -INFINITY; mine[HD + 1] = ls; }
+            }
         }
     }
-    if (n_splits == 1) {  // the whole row in one block: finish here
-        if (tid < HD) {
-            const size_t o = (size_t)r * dq + (size_t)head * HD + tid;
-            if (out_hi) split_store(o_val / lsum, out_hi, out_lo, o);
-            else outp[o] = o_val / lsum;
-        }
-        return;
-    }
-    float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 2);
-    if (tid < HD) mine[tid] = o_val;
-    if (tid == 0) { mine[HD] = mx; mine[HD + 1] = lsum; }
+}
+
+template <typename KT, int HD>
+static size_t attn_lds_bytes()
+{
+    return (size_t)2 * AT_CHUNK * (HD * sizeof(KT) + 16) + (size_t)AT_QPASS * HD * 4 + (size_t)AT_QPASS * AT_CHUNK * 4 +
+           (size_t)AT_QPASS * 2 * 4 + (size_t)AT_THREADS * AT_QPASS * 4;
 }
 
 // Folds the split partials of one (row, head) into the attention output.  (Folding inside the
@@ -1168,30 +1220,23 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n
     else out[o] = num / den;
 }
 
+static int g_force_splits = 0;  // tuning hook (kernel_bench): > 0 overrides the heuristic
+void attention_force_splits(int n) { g_force_splits = n; }
+
 static int attn_splits(const Dims& D, int ctx, int M)
 {
-    // enough blocks to cover the chip, at least 64 positions per split, chunk within the LDS score buffer
-    int want = ceil_div(512, D.H * M);
-    int by_len = ceil_div(ctx, 64);
-    int s = want < by_len ? want : by_len;
-    int need = ceil_div(ctx, AT_MAX_CHUNK);
-    if (s < need) s = need;
-    if (s < 1) s = 1;
-    return s;
+    (void)D; (void)M;
+    const int need = ceil_div(ctx, AT_CHUNK);  // a block owns at most AT_CHUNK positions
+    return g_force_splits > need ? g_force_splits : need;
 }
 
 int attention_splits(const Dims& D, int ctx, int M) { return attn_splits(D, ctx, M); }
 
 size_t attention_scratch_floats(const Dims& D, int max_rows)
 {
-    // splits never exceed ceil(max_seq / 64) nor max(ceil(512 / (H*M)), ceil(max_seq / AT_MAX_CHUNK))
-    size_t worst = 0;
-    for (int M = 1; M <= max_rows; M++) {
-        size_t s = (size_t)attn_splits(D, D.max_seq, M);
-        size_t v = (size_t)M * D.H * s * (D.hd + 2);
-        if (v > worst) worst = v;
-    }
-    return worst;
+    size_t splits = (size_t)ceil_div(D.max_seq, AT_CHUNK);
+    if (splits < 64) splits = 64;  // room for the tuning hook
+    return (size_t)max_rows * D.H * splits * (D.hd + 2);
 }
 
 template <typename KT, int HD>
@@ -1199,7 +1244,16 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
                               int pos_off, int n_splits, int M, float* part, float* out, uint16_t* out_hi, uint16_t* out_lo,
                               hipStream_t s)
 {
-    hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.H, M), dim3(AT_THREADS), 0, s, q, ldq, (const KT*)kc,
+    const size_t lds = attn_lds_bytes<KT, HD>();
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set && lds > 64 * 1024) {
+        hipError_t ea = hipFuncSetAttribute((const void*)attn_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)lds);
+        if (ea != hipSuccess) return ea;
+        attr_set = true;
+    }
+    if (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.Hkv, 1), dim3(AT_THREADS), lds, s, q, ldq, (const KT*)kc,
                        (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_splits == 1) return e;
