@@ -113,6 +113,9 @@ int main(int argc, char** argv)
         f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
         CK(rows_fused(D, f, 0));
     };
+    for (int variant : {2, 3}) {
+    rows_fused_variant(variant);
+    std::printf("-- multi-row GEMM variant %d\n", variant);
     timeit("rows_prep (norm+split)", M * 4096 * 8.0, n, [&](int) { CK(rows_prep(x, 4096, gain, M, 4096, 1e-5f, hi, lo, 0)); });
     timeit("rows_qkv", 3 * qk * 2.0, n, [&](int i) {
         const uint16_t* w = W + (size_t)i * 3 * qk;
@@ -123,6 +126,7 @@ int main(int argc, char** argv)
         fused(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
     timeit("rows_down (resid)", gu * 2.0, n, [&](int i) { fused(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, x, 4096); });
     timeit("rows_lmhead", lm * 2.0, n, [&](int i) { fused(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, logits, 32000); });
+    }
     timeit("attention M rows ctx 640+M", 2.0 * (640 + M) * 4096 * 2, n, [&](int) {
         CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, M, part, nullptr, hi, lo, 0)); });
     return 0;

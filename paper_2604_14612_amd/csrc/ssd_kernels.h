@@ -77,6 +77,8 @@ struct RowsFused {
     void* kc; void* vc;
 };
 bool rows_fused_supported(const Dims& D);
+// tuning hook: 2 = weights read in place as 16-row tiles, 3 (default) = LDS-staged 16x512 stripes
+void rows_fused_variant(int v);
 hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s);
 // hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
 // gain first when gain != nullptr

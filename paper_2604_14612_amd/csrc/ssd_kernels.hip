@@ -761,6 +761,56 @@ __device__ __forceinline__ const uint16_t* m2_row(const RowsP2& p, int tile, int
     return (const uint16_t*)p.w[2] + (size_t)(row - p.n[1]) * p.K;
 }
 
+// Final step of a tile: sum the KS per-wave partial tiles held in LDS (layout [wave][NT][256], element
+// row*16 + column) and apply the mode's epilogue.  Executed by the whole block (it contains barriers in QKV mode).
+template <int MODE>
+__device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float* red, int KS, int ts, float* fin)
+{
+    constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
+    const int tid = threadIdx.x;
+    const int rr = tid & 15, c = (tid >> 4) & 15;
+    float v = 0.f, v2 = 0.f;
+    if (tid < 256) {
+        for (int j = 0; j < KS; j++) {
+            v += red[((ts * KS + j) * NT + 0) * 256 + rr * 16 + c];
+            if (MODE == RM_SWIGLU) v2 += red[((ts * KS + j) * NT + 1) * 256 + rr * 16 + c];
+        }
+        if (MODE == RM_QKV) fin[rr * 16 + c] = v;
+    }
+    if (MODE == RM_QKV) __syncthreads();
+    if (tid < 256 && c < p.M) {
+        if (MODE == RM_QKV) {
+            const int tq = p.dq >> 4, tk = p.dkv >> 4;
+            const int pos = p.pos_dev[0] + p.pos_off + c;
+            if (t < tq + tk) {
+                const bool is_q = t < tq;
+                const int tt = is_q ? t : t - tq;
+                const int tph = p.hd >> 4, head = tt / tph, th = tt % tph, half = p.hd >> 1;
+                const int i = th * 8 + (rr & 7);
+                const float av = fin[(rr & 7) * 16 + c], bv = fin[((rr & 7) + 8) * 16 + c];
+                const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+                const float o = rr < 8 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
+                const int e = rr < 8 ? i : i + half;
+                if (is_q) p.y[(size_t)c * p.ldy + (size_t)head * p.hd + e] = o;
+                else Elem<uint16_t>::put((uint16_t*)p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, o);
+            } else {
+                const int e = (t - tq - tk) * 16 + rr;
+                Elem<uint16_t>::put((uint16_t*)p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v);
+            }
+        } else {
+            const size_t colx = (size_t)t * 16 + rr;
+            if (MODE == RM_STORE) p.y[(size_t)c * p.ldy + colx] = v;
+            else if (MODE == RM_RESID) {
+                float* dst = p.y + (size_t)c * p.ldy + colx;
+                const float tv = *dst + v;
+                *dst = tv;
+                if (p.tap) p.tap[(size_t)c * p.tap_ld + colx] = tv;
+            } else split_store(v / (1.0f + __expf(-v)) * v2, p.oh, p.ol, (size_t)c * p.ldo + colx);
+        }
+    }
+    if (MODE == RM_QKV) __syncthreads();
+}
+
 template <int MODE>
 __global__ __launch_bounds__(512) void rows_mfma2_kernel(RowsP2 p, int KS)
 {
@@ -853,55 +903,163 @@ __global__ __launch_bounds__(512) void rows_mfma2_kernel(RowsP2 p, int KS)
     for (int ts = 0; ts < TPB; ts++) {
         const int t = blockIdx.x * TPB + ts;
         if (t >= n_tiles) break;  // uniform
-        const int rr = tid & 15, c = (tid >> 4) & 15;
-        float v = 0.f, v2 = 0.f;
-        if (tid < 256) {
-            for (int j = 0; j < KS; j++) {
-                v += red[ts * KS + j][0][rr * 16 + c];
-                if (MODE == RM_SWIGLU) v2 += red[ts * KS + j][1][rr * 16 + c];
-            }
-            if (MODE == RM_QKV) fin[rr * 16 + c] = v;
-        }
-        if (MODE == RM_QKV) __syncthreads();
-        if (tid < 256 && c < p.M) {
-            if (MODE == RM_QKV) {
-                const int tq = p.dq >> 4, tk = p.dkv >> 4;
-                const int pos = p.pos_dev[0] + p.pos_off + c;
-                if (t < tq + tk) {
-                    const bool is_q = t < tq;
-                    const int tt = is_q ? t : t - tq;
-                    const int tph = p.hd >> 4, head = tt / tph, th = tt % tph, half = p.hd >> 1;
-                    const int i = th * 8 + (rr & 7);
-                    const float av = fin[(rr & 7) * 16 + c], bv = fin[((rr & 7) + 8) * 16 + c];
-                    const float* cs = p.rope + ((size_t)pos * half + i) * 2;
-                    const float o = rr < 8 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
-                    const int e = rr < 8 ? i : i + half;
-                    if (is_q) p.y[(size_t)c * p.ldy + (size_t)head * p.hd + e] = o;
-                    else Elem<uint16_t>::put((uint16_t*)p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, o);
-                } else {
-                    const int e = (t - tq - tk) * 16 + rr;
-                    Elem<uint16_t>::put((uint16_t*)p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v);
-                }
-            } else {
-                const size_t colx = (size_t)t * 16 + rr;
-                if (MODE == RM_STORE) p.y[(size_t)c * p.ldy + colx] = v;
-                else if (MODE == RM_RESID) {
-                    float* dst = p.y + (size_t)c * p.ldy + colx;
-                    const float tv = *dst + v;
-                    *dst = tv;
-                    if (p.tap) p.tap[(size_t)c * p.tap_ld + colx] = tv;
-                } else split_store(v / (1.0f + __expf(-v)) * v2, p.oh, p.ol, (size_t)c * p.ldo + colx);
-            }
-        }
-        if (MODE == RM_QKV) __syncthreads();
+        m2_epilogue<MODE>(p, t, &red[0][0][0], KS, ts, fin);
     }
 }
+
+// LDS-staged variant: the block fetches a 16-row x 512-k stripe of the weights the way the single-row
+// GEMV does -- every wave two whole rows, 1 KB contiguous per load instruction, which is the access
+// shape that streams fastest from HBM -- plus the matching slice of the hi/lo activations, parks both
+// in LDS, and the MFMA operands are then read from LDS in fragment order.  Activations never enter
+// the in-order global-load queue between weight loads, so the next stripe's loads stay in flight
+// during the whole MFMA phase.
+constexpr int M3_CK = 512;
+constexpr int M3_PITCH = M3_CK * 2 + 16;  // bytes per LDS row (16-byte pad spreads the banks)
+
+template <int MODE, int M3_D>  // M3_D = stripes in flight per block
+__global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
+{
+    constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
+    extern __shared__ __align__(16) unsigned char sm3[];
+    __shared__ float fin[256];
+    unsigned char* As = sm3;                          // [NT][16][PITCH]
+    unsigned char* Bh = sm3 + NT * 16 * M3_PITCH;     // [M][PITCH]
+    unsigned char* Bl = Bh + p.M * M3_PITCH;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int tile = blockIdx.x;
+    const int K = p.K, M = p.M;
+    const int NC = (K + M3_CK - 1) / M3_CK;
+
+    const uint16_t* ap[NT][2];
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) ap[t][j] = m2_row<MODE>(p, tile, 2 * wave + j, t) + lane * 8;
+    // activation vectors (16 bytes each) of one stripe: [hi|lo][M][64]; thread takes v = tid, tid+512, ...
+    const int nbv = M * 128;
+    const uint16_t* bsrc[4];
+    int bdst[4];
+    int bk[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+        const int v = min(tid + u * 512, nbv - 1);
+        const int which = v / (M * 64), rem = v % (M * 64), c = rem >> 6, kk = (rem & 63) * 8;
+        bsrc[u] = (which ? p.bl : p.bh) + (size_t)c * p.ldb + kk;
+        bdst[u] = (which ? M : 0) * M3_PITCH + c * M3_PITCH + kk * 2;
+        bk[u] = kk;
+    }
+    // register ring: the loads of the next M3_D stripes are in flight while one stripe is multiplied
+    u32x4_t ra[M3_D][NT][2], rb[M3_D][4];
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+    auto gload = [&](int slot, int ck) {
+        const int k0 = ck * M3_CK;
+        const bool ok = k0 + lane * 8 < K;
+#pragma unroll
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) ra[slot][t][j] = ok ? gv_load(ap[t][j] + k0) : zero4;
+#pragma unroll
+        for (int u = 0; u < 4; u++)
+            if (tid + u * 512 < nbv)
+                rb[slot][u] = k0 + bk[u] < K ? *reinterpret_cast<const u32x4_t*>(bsrc[u] + k0) : zero4;
+    };
+    f32x4_t acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; t++) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const int bc = min(r16, M - 1);  // columns >= M read a valid row; their results are never stored
+    auto stage = [&](int slot) {
+        __syncthreads();  // previous stripe fully consumed
+#pragma unroll
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+                *reinterpret_cast<u32x4_t*>(As + (t * 16 + 2 * wave + j) * M3_PITCH + lane * 16) = ra[slot][t][j];
+#pragma unroll
+        for (int u = 0; u < 4; u++)
+            if (tid + u * 512 < nbv) *reinterpret_cast<u32x4_t*>(Bh + bdst[u]) = rb[slot][u];
+        __syncthreads();
+    };
+    auto multiply = [&](int ck) {
+        const int nks = min(M3_CK / 32, (K - ck * M3_CK) / 32);
+        for (int s = wave; s < nks; s += 8) {
+            const int off = s * 64 + g * 16;
+            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bh + bc * M3_PITCH + off));
+            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bl + bc * M3_PITCH + off));
+#pragma unroll
+            for (int t = 0; t < NT; t++) {
+                const bf16x8_t w = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(As + (t * 16 + r16) * M3_PITCH + off));
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, bh, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, bl, acc[t], 0, 0, 0);
+            }
+        }
+    };
+#pragma unroll
+    for (int sl = 0; sl < M3_D; sl++)
+        if (sl < NC) gload(sl, sl);
+    int ck0 = 0;
+    for (; ck0 + 2 * M3_D <= NC; ck0 += M3_D) {  // steady state: every step refills its slot, no conditions
+#pragma unroll
+        for (int sl = 0; sl < M3_D; sl++) {
+            stage(sl);
+            gload(sl, ck0 + sl + M3_D);
+            multiply(ck0 + sl);
+        }
+    }
+    for (; ck0 < NC; ck0 += M3_D) {  // drain
+#pragma unroll
+        for (int sl = 0; sl < M3_D; sl++) {
+            if (ck0 + sl < NC) {
+                stage(sl);
+                if (ck0 + sl + M3_D < NC) gload(sl, ck0 + sl + M3_D);
+                multiply(ck0 + sl);
+            }
+        }
+    }
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(sm3);  // [8][NT][256] floats fit inside the weight stripe area
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) red[(wave * NT + t) * 256 + (g * 4 + j) * 16 + r16] = acc[t][j];
+    __syncthreads();
+    m2_epilogue<MODE>(p, tile, red, 8, 0, fin);
+}
+
+template <int MODE, int DEPTH>
+static hipError_t launch_mfma3(const RowsP2& p, int n_tiles, hipStream_t s)
+{
+    constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
+    const size_t lds = (size_t)(NT * 16 + 2 * p.M) * M3_PITCH;
+    static size_t lds_limit = 0;  // per instantiation
+    if (lds > 64 * 1024 && lds > lds_limit) {
+        hipError_t e = hipFuncSetAttribute((const void*)rows_mfma3_kernel<MODE, DEPTH>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        lds_limit = lds;
+    }
+    hipLaunchKernelGGL((rows_mfma3_kernel<MODE, DEPTH>), dim3(n_tiles), dim3(512), lds, s, p);
+    return hipGetLastError();
+}
+
+static int g_rows_variant = 3;  // tuning hook (kernel_bench): 2 = in-place tiles, 3 = LDS-staged stripes, 30+d = depth d
+void rows_fused_variant(int v) { g_rows_variant = v; }
 
 template <int MODE>
 static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
 {
     const int n_tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
     const int steps = p.K / 64;
+    if (g_rows_variant >= 3) {
+        // few tiles -> few blocks per CU -> each block keeps more stripes in flight
+        int depth = g_rows_variant > 30 ? g_rows_variant - 30 : (n_tiles <= 512 ? 3 : (MODE == RM_SWIGLU ? 2 : 1));
+        switch (depth) {
+            case 1: return launch_mfma3<MODE, 1>(p, n_tiles, s);
+            case 2: return launch_mfma3<MODE, 2>(p, n_tiles, s);
+            case 3: return launch_mfma3<MODE, 3>(p, n_tiles, s);
+            default: return launch_mfma3<MODE, 4>(p, n_tiles, s);
+        }
+    }
     // One tile per block, its 8 waves side by side along K: the block then reads 1 KB-wide stripes of
     // 16 consecutive rows, the widest footprint a 16-row tile allows (narrower stripes stream slower).
     int KS = 8;
