@@ -39,6 +39,8 @@ def _load():
         lib.orc_forward.restype = C.c_int
         lib.orc_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.orc_round_bf16.restype = C.c_double
+        lib.orc_round_bf16.argtypes = [C.c_double]
         lib.orc_argmax.restype = C.c_int32
         lib.orc_argmax.argtypes = [C.c_void_p, C.c_int]
         lib.orc_confidence_from_logits.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_double,
@@ -164,6 +166,11 @@ class OracleModel:
         if want_logits:
             out["logits"] = lg
         return out
+
+
+def round_bf16(x: float) -> float:
+    """The value a bf16 K/V cache entry holds for x: fp32 then bf16, round-to-nearest-even."""
+    return float(_load().orc_round_bf16(float(x)))
 
 
 def argmax_lowest(z: np.ndarray) -> int:

@@ -20,6 +20,13 @@
  * compiled with -ffp-contract=off so no fused multiply-add changes a rounding.
  * Matrices are row-major [out][in]; weights arrive as fp32 or as raw bf16 bit patterns
  * (uint16) and are widened exactly.
+ *
+ * Storage precision: the evaluated models are held in half precision (Section 4.1.1), so the
+ * K/V cache of such a model holds half-precision numbers.  The cache therefore stores each K
+ * (after the rotary embedding) and V element rounded to the weight storage type -- bf16 or
+ * fp32, round-to-nearest-even, via an fp32 intermediate as a half-precision tensor is produced
+ * from fp32 compute -- and attention reads those stored values, for the rows of the current
+ * block too.  Everything else stays in double.
  */
 #include <math.h>
 #include <stdint.h>
@@ -48,6 +55,21 @@ static double widen_bf16(uint16_t h)
     memcpy(&f, &u, 4);
     return (double)f;
 }
+
+/* x rounded to fp32 and then to bf16 (round-to-nearest-even both times), returned as a double */
+double orc_round_bf16(double x)
+{
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (double)f; /* inf / nan unchanged */
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+static double round_storage(double x, int dtype) { return dtype == 0 ? (double)(float)x : orc_round_bf16(x); }
 
 /* Y[r][n] = sum_k W[n][k] * X[r][k]   (W: N x K row-major, X: R x K, Y: R x N) */
 static void matmul_wt(const void *W, int dtype, int N, int K, const double *X, int R, double *Y)
@@ -197,8 +219,10 @@ int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint
             int p = pos0 + r;
             for (int hh = 0; hh < H; hh++) rope_head(q + (size_t)r * dq + hh * hd, hd, p, c->rope_base);
             for (int hh = 0; hh < Hkv; hh++) rope_head(kk + (size_t)r * dkv + hh * hd, hd, p, c->rope_base);
-            memcpy(Kc + (size_t)p * dkv, kk + (size_t)r * dkv, sizeof(double) * dkv);
-            memcpy(Vc + (size_t)p * dkv, vv + (size_t)r * dkv, sizeof(double) * dkv);
+            for (int i = 0; i < dkv; i++) {
+                Kc[(size_t)p * dkv + i] = round_storage(kk[(size_t)r * dkv + i], wt);
+                Vc[(size_t)p * dkv + i] = round_storage(vv[(size_t)r * dkv + i], wt);
+            }
         }
 #pragma omp parallel for schedule(static) collapse(2)
         for (int r = 0; r < R; r++)

@@ -27,6 +27,7 @@ class ModelShape:
     dtype: str = "bf16"          # weight storage: "bf16" or "fp32"
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    init_depth: int = 0          # depth the residual-projection init is scaled for (0 = n_layers)
 
     @property
     def head_dim(self) -> int:
@@ -90,8 +91,10 @@ def weight_tensor_names() -> List[str]:
 
 
 def reduced_depth(shape: ModelShape, n_layers: int) -> ModelShape:
-    """Same widths, fewer layers (used where the full depth is too slow for the CPU oracle)."""
-    return dataclasses.replace(shape, n_layers=n_layers)
+    """The first n_layers layers of the same model (used where the full depth is too slow for the CPU
+    oracle): widths, seeds and the init scale of the full-depth model are kept, so every tensor equals
+    the full model's."""
+    return dataclasses.replace(shape, n_layers=n_layers, init_depth=shape.init_depth or shape.n_layers)
 
 
 def _tensor_seed(seed: int, layer: int, tensor_id: int) -> int:
@@ -112,7 +115,7 @@ def make_weights(shape: ModelShape, seed: int, device: str = "cpu",
     """Random-init decoder weights.
 
     All matrices are row-major [out_features][in_features] and ~N(0, init_std); the two
-    projections that write into the residual stream (wo, wd) are scaled by 1/sqrt(2*n_layers).
+    projections that write into the residual stream (wo, wd) are scaled by 1/sqrt(2*depth), depth = init_depth or n_layers.
     Norm gains are 1 (+ norm_gain_std * N(0,1) when a test wants them non-trivial).
     bf16 models are rounded to bf16 once (round-to-nearest-even) and that rounded tensor is
     what every consumer sees.  The stream differs between CPU and GPU generators: move the
@@ -121,7 +124,7 @@ def make_weights(shape: ModelShape, seed: int, device: str = "cpu",
     dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
     L, d, f, V = shape.n_layers, shape.d_model, shape.d_ffn, shape.vocab
     dq, dkv = shape.n_heads * shape.head_dim, shape.d_kv
-    res_std = init_std / math.sqrt(2.0 * L)
+    res_std = init_std / math.sqrt(2.0 * (shape.init_depth or L))
 
     def gain(layer, tid):
         if norm_gain_std == 0.0:

@@ -24,6 +24,17 @@ def make_pair(shape, seed, max_seq, max_k=8, norm_gain_std=0.0, init_std=0.02, *
     return orc, ctx
 
 
+def make_pair_gpu_generated(shape, seed, max_seq, max_k=8, **ctx_kw):
+    """Large shapes: weights are drawn on the GPU (fast) and the very same tensors are copied to the host
+    for the oracle -- moved, never regenerated."""
+    import paper_2604_14612_amd as ssd
+    w = make_weights(shape, seed, device="cuda")
+    w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w.items()}
+    orc = OracleModel(shape, w_cpu, max_seq)
+    ctx = ssd.Context(shape, w, max_seq, max_k, **ctx_kw)
+    return orc, ctx
+
+
 def margin(z):
     """Top-2 gap of one oracle logit vector."""
     top = np.partition(z, -2)[-2:]
@@ -47,7 +58,7 @@ def decisive(z, dtype):
     return margin(z) > 2.0 * (a + r * float(np.abs(z).max()))
 
 
-def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype):
+def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None):
     """Runs greedy SSD on both sides cycle by cycle from the oracle's committed prefix.
 
     Every logit row is compared within tolerance; tokens, accepted counts and next tokens are
@@ -99,6 +110,10 @@ def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype):
         else:
             ctx.ssd_force_commit(d_o, a_o, nx_o)
         assert ctx.ssd_get_stats()["n_tokens"] == o.n
+        if next_mask is not None:
+            m2 = next_mask(o, ctx, stats["cycles"], a_o)
+            if m2 is not None:
+                mask = m2
         stats["cycles"] += 1
         stats["unpinned_cycles"] += 0 if pinned else 1
         stats["accepted"].append(a_o)

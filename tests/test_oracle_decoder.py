@@ -17,8 +17,10 @@ from synth import ModelShape, WORKLOADS, make_prompt, make_weights
 
 
 def torch_reference_logits(shape, w, tokens):
-    """Full-sequence recompute with library ops, float64. Returns logits [T][V]."""
+    """Full-sequence recompute with library ops, float64; K and V pass through the model's storage type
+    (the half-precision cache of Section 4.1.1) by the library's own casts. Returns logits [T][V]."""
     dd = torch.float64
+    st = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
     T = len(tokens)
     H, Hkv, hd = shape.n_heads, shape.n_kv_heads, shape.head_dim
     x = F.embedding(torch.tensor(tokens, dtype=torch.long), w["embed"].to(dd))
@@ -33,8 +35,8 @@ def torch_reference_logits(shape, w, tokens):
     for l in range(shape.n_layers):
         h = F.rms_norm(x, (shape.d_model,), w["attn_norm"][l].to(dd), eps=shape.rms_eps)
         q = rope(F.linear(h, w["wq"][l].to(dd)).view(T, H, hd))
-        k = rope(F.linear(h, w["wk"][l].to(dd)).view(T, Hkv, hd))
-        v = F.linear(h, w["wv"][l].to(dd)).view(T, Hkv, hd)
+        k = rope(F.linear(h, w["wk"][l].to(dd)).view(T, Hkv, hd)).to(torch.float32).to(st).to(dd)
+        v = F.linear(h, w["wv"][l].to(dd)).view(T, Hkv, hd).to(torch.float32).to(st).to(dd)
         k = k.repeat_interleave(H // Hkv, dim=1)
         v = v.repeat_interleave(H // Hkv, dim=1)
         o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
@@ -73,6 +75,36 @@ def test_tiny_workload_matches_library_op_reference(tiny_workload):
     ref = torch_reference_logits(wl.shape, w, toks)
     got = OracleModel(wl.shape, w, 64).forward(toks, 0)["logits"]
     assert np.abs(got - ref).max() <= 1e-11
+
+
+def test_cache_rounding_is_the_library_cast_and_is_applied():
+    """orc_round_bf16 against torch's fp32 -> bf16 cast (random values, exact ties, both parities), and the
+    cache of a bf16 model holds only bf16-representable numbers that differ from the unrounded K/V."""
+    from oracle import round_bf16
+    g = torch.Generator().manual_seed(7)
+    x = torch.randn(4000, generator=g, dtype=torch.float64) * torch.logspace(-6, 6, 4000, dtype=torch.float64)
+    ties = torch.tensor([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 2.0 ** -20 * (1 + 5 * 2.0 ** -8),
+                         1.0 + 2.0 ** -8 + 2.0 ** -30, 1.0 + 2.0 ** -8 - 2.0 ** -30, 0.0, 255.5, 3.3895e38],
+                        dtype=torch.float64)
+    x = torch.cat([x, ties])
+    ref = x.to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([round_bf16(v) for v in x.tolist()])
+    assert np.array_equal(got, ref)
+    assert round_bf16(1.0 + 2.0 ** -8) == 1.0 and round_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6   # ties to even
+    shape = SHAPES[2]
+    w = make_weights(shape, 11, norm_gain_std=0.2, init_std=0.3)
+    toks = make_prompt(shape.vocab, 9, 5).tolist()
+    m = OracleModel(shape, w, 16)
+    m.forward(toks, 0)
+    for c in (m.kcache(), m.vcache()):
+        c = np.asarray(c).reshape(shape.n_layers, 16, -1)[:, :9]
+        assert np.array_equal(c, torch.from_numpy(c.copy()).to(torch.bfloat16).to(torch.float64).numpy())
+        assert np.abs(c).max() > 0.1
+    # an fp32 model's cache holds fp32-representable numbers
+    m32 = OracleModel(SHAPES[0], make_weights(SHAPES[0], 1, init_std=0.3), 16)
+    m32.forward(toks[:5], 0)
+    c = np.asarray(m32.kcache()).reshape(SHAPES[0].n_layers, 16, -1)[:, :5]
+    assert np.array_equal(c, c.astype(np.float32).astype(np.float64)) and np.abs(c).max() > 0.1
 
 
 def test_incremental_equals_full_recompute():
@@ -114,14 +146,15 @@ def test_rope_is_identity_at_position_zero_and_preserves_norm():
     h = F.rms_norm(e, (64,), w["attn_norm"][0].double(), eps=shape.rms_eps)
     k_raw = F.linear(h, w["wk"][0].double()).view(2, 32).numpy()
     K = m.kcache()[0]
-    np.testing.assert_allclose(K[0], k_raw, rtol=1e-12, atol=1e-14)          # angle 0
+    # the cache of an fp32 model stores fp32 numbers: agreement to one fp32 rounding (2^-24 relative)
+    np.testing.assert_allclose(K[0], k_raw, rtol=6e-8, atol=1e-14)           # angle 0
     for p in range(1, 4):                                                   # same token => same raw k
-        np.testing.assert_allclose(np.linalg.norm(K[p], axis=-1), np.linalg.norm(k_raw, axis=-1), rtol=1e-12)
+        np.testing.assert_allclose(np.linalg.norm(K[p], axis=-1), np.linalg.norm(k_raw, axis=-1), rtol=6e-8)
         assert np.abs(K[p] - k_raw).max() > 1e-3
     # V is never rotated
     v_raw = F.linear(h, w["wv"][0].double()).view(2, 32).numpy()
     for p in range(4):
-        np.testing.assert_allclose(m.vcache()[0][p], v_raw, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(m.vcache()[0][p], v_raw, rtol=6e-8, atol=1e-14)
 
 
 def test_gqa_equals_mha_with_replicated_kv_heads():
