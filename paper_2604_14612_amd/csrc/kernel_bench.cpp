@@ -65,12 +65,13 @@ int main(int argc, char** argv)
     CK(hipMalloc(&x, act_floats * 4)); CK(hipMalloc(&gain, 1 << 20)); CK(hipMalloc(&act, act_floats * 4));
     CK(hipMalloc(&q, act_floats * 4)); CK(hipMalloc(&logits, act_floats * 4)); CK(hipMalloc(&part, 64 << 20));
     CK(hipMalloc(&rope, (size_t)1024 * 64 * 2 * 4)); CK(hipMalloc(&pos, 64)); CK(hipMalloc(&sink, 256));
-    CK(hipMalloc(&kc, (size_t)32 * 1024 * 128 * 2)); CK(hipMalloc(&vc, (size_t)32 * 1024 * 128 * 2));
+    const size_t kv_layer = (size_t)32 * 1024 * 128;  // elements of K (or V) of one layer; one copy per timed launch so the cache is cold
+    CK(hipMalloc(&kc, 12 * kv_layer * 2)); CK(hipMalloc(&vc, 12 * kv_layer * 2));
     CK(hipMalloc(&hi, act_floats * 2)); CK(hipMalloc(&lo, act_floats * 2));
     CK(hipMalloc(&big_a, (size_t)256 << 20)); CK(hipMalloc(&big_b, (size_t)256 << 20));
     CK(hipMemset(x, 0, act_floats * 4)); CK(hipMemset(gain, 0, 1 << 20)); CK(hipMemset(act, 0, act_floats * 4));
     CK(hipMemset(q, 0, act_floats * 4)); CK(hipMemset(rope, 0, (size_t)1024 * 64 * 2 * 4));
-    CK(hipMemset(kc, 0, (size_t)32 * 1024 * 128 * 2)); CK(hipMemset(vc, 0, (size_t)32 * 1024 * 128 * 2));
+    CK(hipMemset(kc, 0, 12 * kv_layer * 2)); CK(hipMemset(vc, 0, 12 * kv_layer * 2));
     CK(hipMemset(hi, 0, act_floats * 2)); CK(hipMemset(lo, 0, act_floats * 2));
     const int ctx = 640;
     CK(hipMemcpy(pos, &ctx, 4, hipMemcpyHostToDevice));
@@ -81,7 +82,29 @@ int main(int argc, char** argv)
     timeit("read_probe 256 MiB", 268435456.0, 4, [&](int i) { CK(read_probe(W + (size_t)i * (134217728), (size_t)256 << 20, sink, 0)); });
     timeit("copy_f32 256 MiB", 2 * 268435456.0, 4, [&](int) { CK(copy_f32(big_a, big_b, (size_t)64 << 20, 0)); });
 
+    if (std::getenv("KB_SWEEP")) {   // launch time against size: fixed cost and streaming rate of probe and GEMV
+        for (int mb : {16, 32, 64, 128, 256}) {
+            char nm[64];
+            std::snprintf(nm, sizeof nm, "read_probe %d MiB", mb);
+            timeit(nm, (double)mb * 1048576.0, 8, [&](int i) { CK(read_probe(W + (size_t)i * (134217728), (size_t)mb << 20, sink, 0)); });
+        }
+        for (int rows : {2048, 4096, 8192, 16384, 32768}) {
+            char nm[64];
+            std::snprintf(nm, sizeof nm, "gemv_resid %d x 4096", rows);
+            timeit(nm, rows * 8192.0, 8, [&](int i) { CK(gemv_resid(D, W + (size_t)i * lm, rows, 4096, q, logits, nullptr, 0)); });
+        }
+        for (int rows : {2048, 4096, 8192, 16384, 32000}) {
+            char nm[64];
+            Dims D2 = D; D2.V = rows;
+            std::snprintf(nm, sizeof nm, "gemv_lmhead %d x 4096", rows);
+            timeit(nm, rows * 8192.0, 8, [&](int i) { CK(gemv_lmhead(D2, W + (size_t)i * lm, gain, x, logits, 0)); });
+        }
+        return 0;
+    }
     // single-row (draft / vanilla decode) kernels
+    for (int cap : {0, 1024, 512}) {
+    gemv_block_cap(cap);
+    std::printf("-- gemv block cap %d\n", cap);
     timeit("gemv_qkv", 3 * qk * 2.0, n, [&](int i) {
         const uint16_t* w = W + (size_t)i * 3 * qk;
         CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc, vc, 0)); });
@@ -91,16 +114,40 @@ int main(int argc, char** argv)
         CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0)); });
     timeit("gemv_down (resid)", gu * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * gu, 4096, 11008, act, x, nullptr, 0)); });
     timeit("gemv_lmhead", lm * 2.0, n, [&](int i) { CK(gemv_lmhead(D, W + (size_t)i * lm, gain, x, logits, 0)); });
-    timeit("attention 1 row ctx 641", 2.0 * 641 * 4096 * 2, n, [&](int) {
-        CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0)); });
-    for (int sp : {1, 2, 4, 8, 16, 32}) {
-        attention_force_splits(sp);
-        char nm[64];
-        std::snprintf(nm, sizeof nm, "attention 1 row, %d splits", sp);
-        timeit(nm, 2.0 * 641 * 4096 * 2, n, [&](int) {
-            CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0)); });
+    }
+    gemv_block_cap(0);
+    for (int kind : {1, 0}) {   // 1 = LDS-staged kernel forced, 0 = launch plan (register-resident kernel for few queries)
+        attention_force_kernel(kind);
+        for (int sp : {0, 1, 2, 4, 8}) {
+            if (kind == 1 && sp != 0 && sp < 8) continue;   // the LDS-staged kernel needs ctx / 96 ranges at least
+            attention_force_splits(sp);
+            char nm[96];
+            std::snprintf(nm, sizeof nm, "attention 1 row ctx 641, %s, splits %s%d", kind ? "lds-staged" : "planned",
+                          sp ? "" : "auto=", sp ? sp : std::abs(attention_splits(D, ctx + 1, 1)));
+            timeit(nm, 2.0 * 641 * 4096 * 2, n, [&](int i) {
+                CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr,
+                             nullptr, 0)); });
+        }
     }
     attention_force_splits(0);
+    attention_force_kernel(0);
+    timeit("attention + gemv_o, fold kernel", 2.0 * 641 * 4096 * 2 + qk * 2.0, n, [&](int i) {
+        CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0));
+        CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
+    for (int cap : {0, 512}) for (int sp : {0, 4, 8}) {
+        attention_force_splits(sp);
+        gemv_block_cap(cap);
+        char nm[96];
+        std::snprintf(nm, sizeof nm, "attention + gemv_o, fold in gemv, splits %d cap %d", sp, cap);
+        timeit(nm, 2.0 * 641 * 4096 * 2 + qk * 2.0, n, [&](int i) {
+            int fold = 0;
+            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr, nullptr,
+                         0, &fold));
+            if (fold > 0) CK(gemv_resid_attn(D, W + (size_t)i * qk, part, fold, x, nullptr, 0));
+            else CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
+    }
+    attention_force_splits(0);
+    gemv_block_cap(0);
     timeit("vocab_reduce 1 row", 32000 * 4.0, n, [&](int) {
         CK(vocab_reduce(logits, 1, 32000, 1e4f, 1e-10f, pos + 8, 1, nullptr, sink, nullptr, 0)); });
 
@@ -127,7 +174,20 @@ int main(int argc, char** argv)
     timeit("rows_down (resid)", gu * 2.0, n, [&](int i) { fused(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, x, 4096); });
     timeit("rows_lmhead", lm * 2.0, n, [&](int i) { fused(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, logits, 32000); });
     }
-    timeit("attention M rows ctx 640+M", 2.0 * (640 + M) * 4096 * 2, n, [&](int) {
-        CK(attention(D, q, 4096, kc, vc, pos, 0, ctx, M, part, nullptr, hi, lo, 0)); });
+    for (int kind : {1, 0}) {
+        attention_force_kernel(kind);
+        for (int sp : {0, 2, 4, 8, 16}) {
+            if (kind == 1 && sp != 0) continue;
+            attention_force_splits(sp);
+            char nm[96];
+            std::snprintf(nm, sizeof nm, "attention M rows ctx 640+M, %s, splits %s%d", kind ? "lds-staged" : "planned",
+                          sp ? "" : "auto=", sp ? sp : std::abs(attention_splits(D, ctx + M, M)));
+            timeit(nm, 2.0 * (640 + M) * 4096 * 2, n, [&](int i) {
+                CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, M, part, nullptr, hi,
+                             lo, 0)); });
+        }
+    }
+    attention_force_splits(0);
+    attention_force_kernel(0);
     return 0;
 }

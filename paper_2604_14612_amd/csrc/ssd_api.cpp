@@ -185,9 +185,15 @@ int layer_single(ssd_ctx* c, int l, int pos_off)
     float* x = c->f(c->lay.x);
     TIMED(SSD_K_GEMV_QKV, gemv_qkv(D, c->wq[l], c->wk[l], c->wv[l], c->attn_norm[l], x, c->f(c->lay.rope), c->pos_dev(),
                                    pos_off, c->f(c->lay.qkv), c->kcache(l), c->vcache(l), c->stream), "gemv_qkv");
+    int fold = 0;  // > 0: attention left that many partials per head for the output projection to fold
     TIMED(SSD_K_ATTENTION, attention(D, c->f(c->lay.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
-                                     c->n - 1, 1, c->f(c->lay.part), c->f(c->lay.att), nullptr, nullptr, c->stream), "attention");
-    TIMED(SSD_K_GEMV_O, gemv_resid(D, c->wo[l], D.d, D.dq, c->f(c->lay.att), x, nullptr, c->stream), "gemv_o");
+                                     c->n - 1, 1, c->f(c->lay.part), c->f(c->lay.att), nullptr, nullptr, c->stream, &fold),
+          "attention");
+    if (fold > 0) {
+        TIMED(SSD_K_GEMV_O, gemv_resid_attn(D, c->wo[l], c->f(c->lay.part), fold, x, nullptr, c->stream), "gemv_o");
+    } else {
+        TIMED(SSD_K_GEMV_O, gemv_resid(D, c->wo[l], D.d, D.dq, c->f(c->lay.att), x, nullptr, c->stream), "gemv_o");
+    }
     TIMED(SSD_K_GEMV_GATEUP, gemv_swiglu(D, c->wg[l], c->wu[l], c->mlp_norm[l], x, c->f(c->lay.act), c->stream),
           "gemv_swiglu");
     TIMED(SSD_K_GEMV_DOWN, gemv_resid(D, c->wd[l], D.d, D.f, c->f(c->lay.act), x, nullptr, c->stream), "gemv_down");

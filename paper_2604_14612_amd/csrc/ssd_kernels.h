@@ -31,12 +31,18 @@ hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* w
 // x[n] += W[n][:] . in[:]   (N x K), optional tap copy of the updated x
 hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap,
                       hipStream_t s);
+// x += Wo . att (d x dq), att being the fold of the n_splits attention partials of a single row that
+// attention() left in part when asked to defer the fold
+hipError_t gemv_resid_attn(const Dims& D, const void* w, const float* part, int n_splits, float* x, float* tap,
+                           hipStream_t s);
 // act[n] = silu(Wg[n] . h) * (Wu[n] . h), h = rmsnorm(x, gain)
 hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const float* gain, const float* x,
                        float* act, hipStream_t s);
 // logits[n] = Wlm[n] . rmsnorm(x, gain)
 hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits,
                        hipStream_t s);
+
+void gemv_block_cap(int n);  // tuning hook: > 0 overrides the block cap of the GEMV launches
 
 // ---- multi-row (verify / prefill / confidence) path ------------------------------------------
 // out[r][:] = rmsnorm(in[r][:], gain) for r < M   (rows of length K)
@@ -94,12 +100,18 @@ hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int*
 // hi/lo pair [M][dq] instead.  part: scratch for the split partials.
 hipError_t attention(const Dims& D, const float* q, int ldq, const void* kcache_l, const void* vcache_l,
                      const int* pos_dev, int pos_off, int pos_host_hint, int M, float* part, float* out,
-                     uint16_t* out_hi, uint16_t* out_lo, hipStream_t s);
+                     uint16_t* out_hi, uint16_t* out_lo, hipStream_t s, int* deferred_splits = nullptr);
+// deferred_splits (single row only): when the positions are split over several blocks the fold is left to
+// the consumer; *deferred_splits = the number of partials per head to pass to gemv_resid_attn, or 0 when
+// out already holds the result.
 size_t attention_scratch_floats(const Dims& D, int max_rows);
-// number of sequence splits attention() uses when the last of M rows sees ctx positions
+// launch shape attention() uses when the last of M rows sees ctx positions: the number of position ranges,
+// negated for the register-resident kernel (two calls with equal values enqueue identical launches)
 int attention_splits(const Dims& D, int ctx, int M);
 // tuning hook: n > 0 forces the split count (scratch must have been sized for it), 0 restores the heuristic
 void attention_force_splits(int n);
+// tuning hook: 0 heuristic, 1 LDS-staged kernel always
+void attention_force_kernel(int v);
 
 // ---- vocabulary reduction ------------------------------------------------------------------------
 // Per row of logits [M][V]: arg-max (lowest index on ties), softmax max-probability and, when

@@ -135,12 +135,15 @@ hipError_t set_tokens(TokArg toks, int n, const int32_t* first_dev, int32_t* dst
 // interleaves gate row n and up row n, so that one lane holds both operands of the epilogue.
 constexpr int GV_WAVES = 8;
 constexpr int GV_THREADS = GV_WAVES * 64;
+constexpr int GV_FOLD_MAX = 8;  // attention partials per head the output projection can fold itself
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_STORE = 3 };
 
 struct GemvP {
     const void* w0; const void* w1; const void* w2;
     const float* in;    // [K]
+    const float* part;  // when set (RESID only): the input is the fold of n_splits attention partials of row 0
+    int n_splits;       //   laid out [K / hd heads][n_splits][hd + 4] as the attention kernels write them
     const float* gain;  // rmsnorm gain or nullptr (input used as is)
     float eps;
     int K;
@@ -306,6 +309,38 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
 
     // stage the input vector (times gain); the sum of squares gives the RMS scale
     float ss = 0.f;
+    if (EPI == EPI_RESID && p.part) {
+        // attention output folded on the fly: out = sum_s e^(m_s - m) o_s / sum_s e^(m_s - m) l_s per head.
+        // All partials of an element are fetched by independent, unconditional loads (index clamped, weight
+        // zeroed past n_splits) so that the fold costs one cache round trip, not one per partial.
+        const int hs = p.hd + 4, ns = p.n_splits;
+        for (int i = threadIdx.x * 4; i < K; i += GV_THREADS * 4) {
+            const float* base = p.part + (size_t)(i / p.hd) * ns * hs;
+            const int d = i % p.hd;
+            float mm[GV_FOLD_MAX], ll[GV_FOLD_MAX];
+            float4 oo[GV_FOLD_MAX];
+#pragma unroll
+            for (int sp = 0; sp < GV_FOLD_MAX; sp++) {
+                const float* ps = base + min(sp, ns - 1) * hs;
+                mm[sp] = ps[p.hd];
+                ll[sp] = ps[p.hd + 1];
+                oo[sp] = *reinterpret_cast<const float4*>(ps + d);
+            }
+            float gm = -INFINITY;
+#pragma unroll
+            for (int sp = 0; sp < GV_FOLD_MAX; sp++) gm = fmaxf(gm, mm[sp]);   // clamped duplicates do not change the max
+            float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+            float den = 0.f;
+#pragma unroll
+            for (int sp = 0; sp < GV_FOLD_MAX; sp++) {
+                const float w = (sp < ns && ll[sp] > 0.f) ? __expf(mm[sp] - gm) : 0.f;
+                num.x = fmaf(w, oo[sp].x, num.x); num.y = fmaf(w, oo[sp].y, num.y);
+                num.z = fmaf(w, oo[sp].z, num.z); num.w = fmaf(w, oo[sp].w, num.w);
+                den = fmaf(w, ll[sp], den);
+            }
+            *reinterpret_cast<float4*>(xs + i) = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
+        }
+    } else
     for (int i = threadIdx.x * 4; i < K; i += GV_THREADS * 4) {
         float4 v = *reinterpret_cast<const float4*>(p.in + i);
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
@@ -386,6 +421,9 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
     }
 }
 
+static int g_block_cap = 0;  // tuning hook (kernel_bench): > 0 overrides the block cap
+void gemv_block_cap(int n) { g_block_cap = n; }
+
 template <typename WT, int EPI, int R, int D, int KS>
 static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
 {
@@ -399,7 +437,12 @@ static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
     }
     constexpr int GPB = GV_WAVES / KS;
     int blocks = ceil_div(p.n_rows / R, GPB);
-    if (blocks > 256 * 4) blocks = 256 * 4;
+    // three blocks fit a CU at this kernel's register use: 768 persistent blocks are all resident at once
+    // and leave no second, partial round of blocks.  The variant that folds attention partials in its
+    // prologue re-reads them per block, so it runs one block per CU.
+    int cap = p.part ? 256 : 768;
+    if (g_block_cap > 0) cap = g_block_cap;
+    if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, p);
     return hipGetLastError();
 }
@@ -437,6 +480,16 @@ hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* i
 {
     GemvP p = {};
     p.w0 = w; p.in = in; p.gain = nullptr; p.eps = D.eps; p.K = K; p.n_rows = N; p.y = x; p.tap = tap;
+    return launch_gemv<EPI_RESID>(D.wt, p, s);
+}
+
+hipError_t gemv_resid_attn(const Dims& D, const void* w, const float* part, int n_splits, float* x, float* tap,
+                           hipStream_t s)
+{
+    if (n_splits < 1 || n_splits > GV_FOLD_MAX || D.hd % 4) return hipErrorInvalidValue;
+    GemvP p = {};
+    p.w0 = w; p.in = nullptr; p.part = part; p.n_splits = n_splits; p.hd = D.hd; p.gain = nullptr; p.eps = D.eps;
+    p.K = D.dq; p.n_rows = D.d; p.y = x; p.tap = tap;
     return launch_gemv<EPI_RESID>(D.wt, p, s);
 }
 
@@ -1200,7 +1253,8 @@ __device__ __forceinline__ void attn_pv(const KT* vtile, int rowb, const float* 
 // query heads of the group times the M rows), so K and V are fetched once however many rows verify.
 // All global loads of the chunk are issued up front, land in LDS (rows padded by 16 bytes to spread
 // banks), and the three phases -- scores, softmax statistics, P.V -- then run out of LDS only.
-// partial layout per (row, head, split): [hd] unnormalised output, then m (max score), l (sum of exp)
+// partial layout per (row, head, split): [hd] unnormalised output, then m (max score), l (sum of exp), 2 pad
+// (stride hd + 4 floats keeps every partial 16-byte aligned)
 template <typename KT, int HD>
 __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restrict__ q, int ldq,
                                                           const KT* __restrict__ kc, const KT* __restrict__ vc,
@@ -1337,7 +1391,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
                 if (out_hi) split_store(o / ls, out_hi, out_lo, oo);
                 else outp[oo] = o / ls;
             } else {
-                float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 2);
+                float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
                 mine[dd] = o;
                 if (dd == 0) { mine[HD] = n > 0 ? mx : -INFINITY; mine[HD + 1] = ls; }
             }
@@ -1360,12 +1414,12 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n
                                     uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
 {
     const int head = blockIdx.x, r = blockIdx.y, d = threadIdx.x;
-    const float* p = part + ((size_t)r * H + head) * n_splits * (HD + 2);
+    const float* p = part + ((size_t)r * H + head) * n_splits * (HD + 4);
     float gm = -INFINITY;
-    for (int s = 0; s < n_splits; s++) gm = fmaxf(gm, p[(size_t)s * (HD + 2) + HD]);
+    for (int s = 0; s < n_splits; s++) gm = fmaxf(gm, p[(size_t)s * (HD + 4) + HD]);
     float num = 0.f, den = 0.f;
     for (int s = 0; s < n_splits; s++) {
-        const float* ps = p + (size_t)s * (HD + 2);
+        const float* ps = p + (size_t)s * (HD + 4);
         const float l = ps[HD + 1];
         if (l > 0.f) {
             const float w = __expf(ps[HD] - gm);
@@ -1378,43 +1432,311 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n
     else out[o] = num / den;
 }
 
-static int g_force_splits = 0;  // tuning hook (kernel_bench): > 0 overrides the heuristic
-void attention_force_splits(int n) { g_force_splits = n; }
-
-static int attn_splits(const Dims& D, int ctx, int M)
+// ---- register-resident variant for few query vectors (decoding, short verification blocks) ----------
+// One block = one KV head x one range of positions x up to NQ query vectors.  No LDS staging: a lane
+// owns 16 bytes of a cache row (LPP lanes per position, PPL = 64 / LPP positions per wave-wide load)
+// and every wave keeps NL such K loads and NL V loads in flight, consecutive waves reading
+// consecutive 1 KB pieces.  Scores are reduced over the LPP lanes of a position by shuffles, each wave
+// runs an online softmax over its positions, and the NW waves are folded through LDS at the end.  With
+// one range per head the block writes the finished output and no second kernel is needed.
+template <typename KT> __device__ __forceinline__ void aw_unpack(u32x4_t w, float (&o)[16 / sizeof(KT)]);
+template <> __device__ __forceinline__ void aw_unpack<uint16_t>(u32x4_t w, float (&o)[8])
 {
-    (void)D; (void)M;
-    const int need = ceil_div(ctx, AT_CHUNK);  // a block owns at most AT_CHUNK positions
-    return g_force_splits > need ? g_force_splits : need;
+    o[0] = __uint_as_float(w.x << 16); o[1] = __uint_as_float(w.x & 0xffff0000u);
+    o[2] = __uint_as_float(w.y << 16); o[3] = __uint_as_float(w.y & 0xffff0000u);
+    o[4] = __uint_as_float(w.z << 16); o[5] = __uint_as_float(w.z & 0xffff0000u);
+    o[6] = __uint_as_float(w.w << 16); o[7] = __uint_as_float(w.w & 0xffff0000u);
+}
+template <> __device__ __forceinline__ void aw_unpack<float>(u32x4_t w, float (&o)[4])
+{
+    o[0] = __uint_as_float(w.x); o[1] = __uint_as_float(w.y); o[2] = __uint_as_float(w.z); o[3] = __uint_as_float(w.w);
+}
+// sum over the LPP lanes of one position (every lane of the segment gets it).  Segments of 8 and 16
+// lanes lie inside one DPP row: rotations by 8, 4, 2, 1 (or a half-row mirror and two quad swaps) add all
+// of them without going through the LDS crossbar.
+template <int CTRL> __device__ __forceinline__ float aw_dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int LPP> __device__ __forceinline__ float aw_seg_sum(float v)
+{
+    if (LPP == 16 || LPP == 32) {
+        v = aw_dpp_add<0x128>(v);  // row_ror:8
+        v = aw_dpp_add<0x124>(v);  // row_ror:4
+        v = aw_dpp_add<0x122>(v);  // row_ror:2
+        v = aw_dpp_add<0x121>(v);  // row_ror:1
+        if (LPP == 32) v += __shfl_xor(v, 16, 64);
+    } else if (LPP == 8) {
+        v = aw_dpp_add<0x141>(v);  // row_half_mirror: lane i <- lane 7 - i of its half row
+        v = aw_dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+        v = aw_dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    } else {
+#pragma unroll
+        for (int o = LPP / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    }
+    return v;
+}
+// sum / max across the segments of a wave, for values already uniform inside each segment
+template <int LPP> __device__ __forceinline__ float aw_xseg_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= LPP; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <int LPP> __device__ __forceinline__ float aw_xseg_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= LPP; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
 }
 
-int attention_splits(const Dims& D, int ctx, int M) { return attn_splits(D, ctx, M); }
+template <typename KT, int HD, int NQ, int NW, int NL>
+__global__ __launch_bounds__(NW * 64) void attn_wide_kernel(const float* __restrict__ q, int ldq,
+                                                            const KT* __restrict__ kc, const KT* __restrict__ vc,
+                                                            const int* pos_dev, int pos_off, int M, int H, int Hkv,
+                                                            int max_seq, int n_splits, float* __restrict__ part,
+                                                            float* __restrict__ outp, int dq,
+                                                            uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
+{
+    constexpr int EPV = 16 / (int)sizeof(KT), LPP = HD / EPV, PPL = 64 / LPP, NT = NW * 64;
+    constexpr int PASS = NL * NW * PPL;  // positions one pass of the block covers
+    __shared__ __align__(16) float qs[NQ * HD];     // query vectors, pre-scaled
+    __shared__ float wacc[NW * NQ * HD];            // per-wave unnormalised outputs
+    __shared__ float wml[NW * NQ * 2];              // per-wave (max, sum)
+    const int split = blockIdx.x, kvh = blockIdx.y, q0 = blockIdx.z * NQ;
+    const int G = H / Hkv, Q = G * M, nq = min(NQ, Q - q0);
+    const int p0 = pos_dev[0] + pos_off, total = p0 + M;
+    const int chunk = (total + n_splits - 1) / n_splits;
+    const int j0 = split * chunk, n = min(chunk, total - j0);  // may be <= 0
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seg = lane / LPP, sl = (lane % LPP) * EPV;
+    const int jlast = j0 + n - 1;
+    const int n_pass = n > 0 ? (n + PASS - 1) / PASS : 0;
+    const KT* kbase = kc + (size_t)kvh * max_seq * HD + sl;
+    const KT* vbase = vc + (size_t)kvh * max_seq * HD + sl;
+
+    u32x4_t kr[NL], vr[NL];
+    // addresses are clamped to the last position of the range, never predicated: all loads of a pass stay in
+    // flight together, and the positions past the range are masked out of the scores instead
+    auto issue_k = [&](int pass) {
+#pragma unroll
+        for (int t = 0; t < NL; t++) {
+            const int j = min(j0 + ((pass * NL + t) * NW + wave) * PPL + seg, jlast);
+            kr[t] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)j * HD);
+        }
+    };
+    auto issue_v = [&](int pass) {
+#pragma unroll
+        for (int t = 0; t < NL; t++) {
+            const int j = min(j0 + ((pass * NL + t) * NW + wave) * PPL + seg, jlast);
+            vr[t] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)j * HD);
+        }
+    };
+    if (n_pass > 0) { issue_k(0); issue_v(0); }
+
+    const float scale = 1.0f / sqrtf((float)HD);
+    for (int e = tid; e < NQ * HD; e += NT) {
+        const int qi = e / HD;
+        float v = 0.f;
+        if (qi < nq) {
+            const int qg = q0 + qi;
+            v = q[(size_t)(qg / G) * ldq + (size_t)(kvh * G + qg % G) * HD + (e % HD)] * scale;
+        }
+        qs[e] = v;
+    }
+    int vis[NQ];  // first position a query may NOT see
+#pragma unroll
+    for (int qi = 0; qi < NQ; qi++) vis[qi] = qi < nq ? min(p0 + (q0 + qi) / G + 1, j0 + n) : j0;
+    __syncthreads();
+
+    float m[NQ], l[NQ], acc[NQ][EPV];
+#pragma unroll
+    for (int qi = 0; qi < NQ; qi++) {
+        m[qi] = -INFINITY; l[qi] = 0.f;
+#pragma unroll
+        for (int u = 0; u < EPV; u++) acc[qi][u] = 0.f;
+    }
+    for (int pass = 0; pass < n_pass; pass++) {
+        float sc[NQ][NL];
+#pragma unroll
+        for (int t = 0; t < NL; t++) {
+            float kf[EPV];
+            aw_unpack<KT>(kr[t], kf);
+            const int j = j0 + ((pass * NL + t) * NW + wave) * PPL + seg;
+#pragma unroll
+            for (int qi = 0; qi < NQ; qi++) {
+                const float* qv = qs + qi * HD + sl;
+                float dot = 0.f;
+#pragma unroll
+                for (int u = 0; u < EPV; u += 4) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(qv + u);
+                    dot = fmaf(kf[u], t4.x, dot); dot = fmaf(kf[u + 1], t4.y, dot);
+                    dot = fmaf(kf[u + 2], t4.z, dot); dot = fmaf(kf[u + 3], t4.w, dot);
+                }
+                dot = aw_seg_sum<LPP>(dot);
+                sc[qi][t] = j < vis[qi] ? dot : -INFINITY;
+            }
+        }
+        if (pass + 1 < n_pass) issue_k(pass + 1);
+#pragma unroll
+        for (int qi = 0; qi < NQ; qi++) {
+            float mx = sc[qi][0];
+#pragma unroll
+            for (int t = 1; t < NL; t++) mx = fmaxf(mx, sc[qi][t]);
+            mx = aw_xseg_max<LPP>(mx);
+            const float mn = fmaxf(m[qi], mx);          // uniform over the wave
+            const bool live = mn > -INFINITY;
+            const float c = live ? __expf(m[qi] - mn) : 1.0f;   // exp(-inf) = 0 on the first live pass
+            l[qi] *= c;
+#pragma unroll
+            for (int u = 0; u < EPV; u++) acc[qi][u] *= c;
+            m[qi] = mn;
+#pragma unroll
+            for (int t = 0; t < NL; t++) {
+                const float e = live ? __expf(sc[qi][t] - mn) : 0.f;  // masked scores give 0
+                sc[qi][t] = e;
+                l[qi] += e;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NL; t++) {
+            float vf[EPV];
+            aw_unpack<KT>(vr[t], vf);
+#pragma unroll
+            for (int qi = 0; qi < NQ; qi++)
+#pragma unroll
+                for (int u = 0; u < EPV; u++) acc[qi][u] = fmaf(sc[qi][t], vf[u], acc[qi][u]);
+        }
+        if (pass + 1 < n_pass) issue_v(pass + 1);
+    }
+    // fold the position segments of the wave, then the waves of the block
+#pragma unroll
+    for (int qi = 0; qi < NQ; qi++) {
+        l[qi] = aw_xseg_sum<LPP>(l[qi]);
+#pragma unroll
+        for (int u = 0; u < EPV; u++) acc[qi][u] = aw_xseg_sum<LPP>(acc[qi][u]);
+        if (seg == 0) {
+#pragma unroll
+            for (int u = 0; u < EPV; u++) wacc[(wave * NQ + qi) * HD + sl + u] = acc[qi][u];
+        }
+        if (lane == 0) { wml[(wave * NQ + qi) * 2] = m[qi]; wml[(wave * NQ + qi) * 2 + 1] = l[qi]; }
+    }
+    __syncthreads();
+    for (int e = tid; e < nq * HD; e += NT) {
+        const int qi = e / HD, d = e % HD;
+        float gm = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; w++) gm = fmaxf(gm, wml[(w * NQ + qi) * 2]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; w++) {
+            const float mw = wml[(w * NQ + qi) * 2];
+            if (mw > -INFINITY) {
+                const float c = __expf(mw - gm);
+                num = fmaf(c, wacc[(w * NQ + qi) * HD + d], num);
+                den = fmaf(c, wml[(w * NQ + qi) * 2 + 1], den);
+            }
+        }
+        const int qg = q0 + qi, r = qg / G, head = kvh * G + qg % G;
+        if (n_splits == 1) {
+            const size_t oo = (size_t)r * dq + (size_t)head * HD + d;
+            if (out_hi) split_store(num / den, out_hi, out_lo, oo);
+            else outp[oo] = num / den;
+        } else {
+            float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
+            mine[d] = num;
+            if (d == 0) { mine[HD] = gm; mine[HD + 1] = den; }
+        }
+    }
+}
+
+// Launch plan.  Few query vectors per KV head (Q = M x group size <= AW_MAXQ_TOTAL): the register-resident
+// kernel over ranges of about AW_RANGE positions -- a single CU pulls only a few tens of GB/s, so a head's
+// cache is spread over many blocks even though that costs the fold of the partial results.  Many query
+// vectors (prompt blocks, wide GQA groups): the LDS-staged kernel, which fetches K/V once for all of them.
+constexpr int AW_MAXQ_TOTAL = 4;
+constexpr int AW_RANGE = 128;
+constexpr int AW_MAX_RANGES = 16;
+static int g_force_splits = 0;  // tuning hook (kernel_bench): > 0 overrides the heuristic
+static int g_force_attn = 0;    // tuning hook: 1 = LDS-staged kernel always
+void attention_force_splits(int n) { g_force_splits = n; }
+void attention_force_kernel(int v) { g_force_attn = v; }
+
+struct AttnPlan { bool wide; int n_splits; bool defer_fold; };
+
+static AttnPlan attn_plan(const Dims& D, int ctx, int M)
+{
+    AttnPlan pl;
+    pl.defer_fold = false;
+    const int Q = (D.H / D.Hkv) * M;
+    pl.wide = Q <= AW_MAXQ_TOTAL;
+    if (g_force_attn == 1) pl.wide = false;
+    if (pl.wide) {
+        // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
+        int ns = ceil_div(ctx, AW_RANGE);
+        if (ns > AW_MAX_RANGES) ns = AW_MAX_RANGES;
+        if (g_force_splits > 0) ns = g_force_splits;
+        if (ns > ctx) ns = ctx;
+        pl.n_splits = ns;
+    } else {
+        const int need = ceil_div(ctx, AT_CHUNK);  // a block owns at most AT_CHUNK positions
+        pl.n_splits = g_force_splits > need ? g_force_splits : need;
+    }
+    return pl;
+}
+
+int attention_splits(const Dims& D, int ctx, int M)
+{
+    const AttnPlan pl = attn_plan(D, ctx, M);
+    return pl.wide ? -pl.n_splits : pl.n_splits;  // distinct values for distinct launch shapes
+}
 
 size_t attention_scratch_floats(const Dims& D, int max_rows)
 {
     size_t splits = (size_t)ceil_div(D.max_seq, AT_CHUNK);
     if (splits < 64) splits = 64;  // room for the tuning hook
-    return (size_t)max_rows * D.H * splits * (D.hd + 2);
+    return (size_t)max_rows * D.H * splits * (D.hd + 4);
+}
+
+template <typename KT, int HD, int NQ, int NW, int NL>
+static void launch_attn_wide(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
+                             int pos_off, int n_splits, int zq, int M, float* part, float* out, uint16_t* out_hi,
+                             uint16_t* out_lo, hipStream_t s)
+{
+    hipLaunchKernelGGL((attn_wide_kernel<KT, HD, NQ, NW, NL>), dim3(n_splits, D.Hkv, zq), dim3(NW * 64), 0, s, q, ldq,
+                       (const KT*)kc, (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq,
+                       out_hi, out_lo);
 }
 
 template <typename KT, int HD>
 static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
-                              int pos_off, int n_splits, int M, float* part, float* out, uint16_t* out_hi, uint16_t* out_lo,
-                              hipStream_t s)
+                              int pos_off, AttnPlan pl, int ctx, int M, float* part, float* out, uint16_t* out_hi,
+                              uint16_t* out_lo, hipStream_t s)
 {
-    const size_t lds = attn_lds_bytes<KT, HD>();
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set && lds > 64 * 1024) {
-        hipError_t ea = hipFuncSetAttribute((const void*)attn_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)lds);
-        if (ea != hipSuccess) return ea;
-        attr_set = true;
+    const int n_splits = pl.n_splits;
+    if (n_splits < 1 || (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK))) return hipErrorInvalidValue;
+    if (pl.wide) {
+        const int Q = (D.H / D.Hkv) * M;
+        const int span = ceil_div(ctx, n_splits) * (HD / (16 / (int)sizeof(KT)));  // lanes' worth of 16-byte vectors per range
+        if (Q == 1 && span <= 8 * 64 * 4) launch_attn_wide<KT, HD, 1, 8, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
+        else if (Q == 1 && span <= 16 * 64 * 4) launch_attn_wide<KT, HD, 1, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
+        else if (Q == 1) launch_attn_wide<KT, HD, 1, 8, 16>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
+        else if (Q == 2) launch_attn_wide<KT, HD, 2, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
+        else launch_attn_wide<KT, HD, 4, 8, 8>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
+    } else {
+        const size_t lds = attn_lds_bytes<KT, HD>();
+        static bool attr_set = false;  // per instantiation
+        if (!attr_set && lds > 64 * 1024) {
+            hipError_t ea = hipFuncSetAttribute((const void*)attn_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                (int)lds);
+            if (ea != hipSuccess) return ea;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.Hkv, 1), dim3(AT_THREADS), lds, s, q, ldq, (const KT*)kc,
+                           (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo);
     }
-    if (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.Hkv, 1), dim3(AT_THREADS), lds, s, q, ldq, (const KT*)kc,
-                       (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || n_splits == 1) return e;
+    if (e != hipSuccess || n_splits == 1 || pl.defer_fold) return e;
     hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(D.H, M), dim3(HD), 0, s, part, D.H, n_splits, out, D.dq, out_hi,
                        out_lo);
     return hipGetLastError();
@@ -1422,17 +1744,22 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
 
 hipError_t attention(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
                      int pos_off, int pos_host_hint, int M, float* part, float* out, uint16_t* out_hi, uint16_t* out_lo,
-                     hipStream_t s)
+                     hipStream_t s, int* deferred_splits)
 {
     int ctx = pos_host_hint + pos_off + M;  // positions the last row sees
-    if (ctx < 1 || ctx > D.max_seq) return hipErrorInvalidValue;
-    int n_splits = attn_splits(D, ctx, M);
+    if (ctx < 1 || ctx > D.max_seq || M < 1) return hipErrorInvalidValue;
+    AttnPlan pl = attn_plan(D, ctx, M);
+    if (deferred_splits) {  // single row: the consumer (gemv_resid_attn) folds the partials itself
+        if (M != 1) return hipErrorInvalidValue;
+        pl.defer_fold = pl.n_splits > 1 && pl.n_splits <= GV_FOLD_MAX;
+        *deferred_splits = pl.defer_fold ? pl.n_splits : 0;
+    }
     if (D.wt == WT_BF16) {
-        if (D.hd == 128) return attention_t<uint16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
-        if (D.hd == 64) return attention_t<uint16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
+        if (D.hd == 128) return attention_t<uint16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
+        if (D.hd == 64) return attention_t<uint16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
     } else {
-        if (D.hd == 128) return attention_t<float, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
-        if (D.hd == 64) return attention_t<float, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
+        if (D.hd == 128) return attention_t<float, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
+        if (D.hd == 64) return attention_t<float, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
     }
     return hipErrorInvalidValue;
 }
