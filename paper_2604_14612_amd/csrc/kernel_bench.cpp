@@ -160,9 +160,7 @@ int main(int argc, char** argv)
         f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
         CK(rows_fused(D, f, 0));
     };
-    for (int variant : {2, 3}) {
-    rows_fused_variant(variant);
-    std::printf("-- multi-row GEMM variant %d\n", variant);
+    {
     timeit("rows_prep (norm+split)", M * 4096 * 8.0, n, [&](int) { CK(rows_prep(x, 4096, gain, M, 4096, 1e-5f, hi, lo, 0)); });
     timeit("rows_qkv", 3 * qk * 2.0, n, [&](int i) {
         const uint16_t* w = W + (size_t)i * 3 * qk;

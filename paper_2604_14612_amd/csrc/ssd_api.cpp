@@ -23,7 +23,7 @@ constexpr size_t ALIGN = 256;
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
-    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, small, total;
+    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, ssq, small, total;
     int rows;       // activation rows: max(max_k + 1, SSD_PREFILL_ROWS)
     int conf_rows;  // rows of one confidence pass: 2 * L
     int logit_rows;
@@ -85,6 +85,7 @@ Layout make_layout(const ssd_config& c)
         l.hi = o; o += align_up(n * 2);
         l.lo = o; o += align_up(n * 2);
     }
+    l.ssq = o;    o += align_up((size_t)l.rows * (D.d / 16 + 1) * sizeof(float));  // per-tile sums of squares of the residual rows
     l.small = o;  o += align_up(4096);
     l.total = o;
     return l;
@@ -230,14 +231,21 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
     HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_VTOK, M, x, c->stream), "embed");
     const int tap_ld = D.L * 2 * D.d;
     if (rows_fused_supported(D)) {
-        // bf16 fast path: activations travel between the GEMMs as bf16 hi/lo pairs
+        // bf16 fast path: activations travel between the GEMMs as bf16 hi/lo pairs.  The residual rows exist
+        // twice: x (fp32) and xh/xl = split(x * gain of the norm that reads them next) with their per-tile
+        // sums of squares in ssq, both left behind by the projection that last updated x.
         uint16_t* hi = c->h16(Y.hi);
         uint16_t* lo = c->h16(Y.lo);
+        uint16_t* xh = c->h16(Y.h);
+        uint16_t* xl = xh + (size_t)Y.rows * D.d;
+        float* ssq = c->f(Y.ssq);
+        const int n_ssq = D.d / 16;
+        HIPCHK(rows_gain_split(x, D.d, c->attn_norm[0], M, D.d, xh, xl, ssq, c->stream), "rows_gain_split");
         for (int l = 0; l < D.L; l++) {
-            HIPCHK(rows_prep(x, D.d, c->attn_norm[l], M, D.d, D.eps, hi, lo, c->stream), "rows_prep");
             RowsFused q = {};
             q.w[0] = c->wq[l]; q.w[1] = c->wk[l]; q.w[2] = c->wv[l]; q.n[0] = D.dq; q.n[1] = D.dkv; q.n[2] = D.dkv;
-            q.K = D.d; q.bh = hi; q.bl = lo; q.ldb = D.d; q.y = c->f(Y.qkv); q.ldy = D.dq; q.M = M; q.mode = 3;
+            q.K = D.d; q.bh = xh; q.bl = xl; q.ldb = D.d; q.ssq = ssq; q.n_ssq = n_ssq; q.y = c->f(Y.qkv); q.ldy = D.dq;
+            q.M = M; q.mode = 3;
             q.rope = c->f(Y.rope); q.pos_dev = c->pos_dev(); q.pos_off = pos_off; q.kc = c->kcache(l); q.vc = c->vcache(l);
             TIMED(SSD_K_ROWS_QKV, rows_fused(D, q, c->stream), "rows_qkv");
             TIMED(SSD_K_ATTENTION, attention(D, c->f(Y.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
@@ -245,23 +253,27 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
             RowsFused o = {};
             o.w[0] = c->wo[l]; o.n[0] = D.d; o.K = D.dq; o.bh = hi; o.bl = lo; o.ldb = D.dq; o.y = x; o.ldy = D.d; o.M = M;
             o.mode = 1; o.tap = c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d; o.tap_ld = tap_ld;
+            o.gain_out = c->mlp_norm[l]; o.oh = xh; o.ol = xl; o.ldo = D.d; o.ssq_out = ssq;
             TIMED(SSD_K_ROWS_O, rows_fused(D, o, c->stream), "rows_o");
-            HIPCHK(rows_prep(x, D.d, c->mlp_norm[l], M, D.d, D.eps, hi, lo, c->stream), "rows_prep");
             RowsFused gu = {};
-            gu.w[0] = c->wg[l]; gu.w[1] = c->wu[l]; gu.n[0] = D.f; gu.n[1] = D.f; gu.K = D.d; gu.bh = hi; gu.bl = lo;
-            gu.ldb = D.d; gu.oh = c->h16(Y.act); gu.ol = c->h16(Y.act) + (size_t)Y.rows * D.f; gu.ldo = D.f; gu.M = M;
+            gu.w[0] = c->wg[l]; gu.w[1] = c->wu[l]; gu.n[0] = D.f; gu.n[1] = D.f; gu.K = D.d; gu.bh = xh; gu.bl = xl;
+            gu.ldb = D.d; gu.ssq = ssq; gu.n_ssq = n_ssq;
+            gu.oh = c->h16(Y.act); gu.ol = c->h16(Y.act) + (size_t)Y.rows * D.f; gu.ldo = D.f; gu.M = M;
             gu.mode = 2;
             TIMED(SSD_K_ROWS_GATEUP, rows_fused(D, gu, c->stream), "rows_gateup");
             RowsFused dn = {};
             dn.w[0] = c->wd[l]; dn.n[0] = D.d; dn.K = D.f; dn.bh = gu.oh; dn.bl = gu.ol; dn.ldb = D.f; dn.y = x; dn.ldy = D.d;
             dn.M = M; dn.mode = 1; dn.tap = c->f(Y.taps) + ((size_t)l * 2 + 1) * D.d; dn.tap_ld = tap_ld;
+            if (l + 1 < D.L || want_logits) {
+                dn.gain_out = l + 1 < D.L ? c->attn_norm[l + 1] : c->w.final_norm;
+                dn.oh = xh; dn.ol = xl; dn.ldo = D.d; dn.ssq_out = ssq;
+            }
             TIMED(SSD_K_ROWS_DOWN, rows_fused(D, dn, c->stream), "rows_down");
         }
         if (want_logits) {
-            HIPCHK(rows_prep(x, D.d, c->w.final_norm, M, D.d, D.eps, hi, lo, c->stream), "rows_prep");
             RowsFused lm = {};
-            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = hi; lm.bl = lo; lm.ldb = D.d;
-            lm.y = c->f(Y.logits); lm.ldy = D.V; lm.M = M; lm.mode = 0;
+            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = xh; lm.bl = xl; lm.ldb = D.d; lm.ssq = ssq;
+            lm.n_ssq = n_ssq; lm.y = c->f(Y.logits); lm.ldy = D.V; lm.M = M; lm.mode = 0;
             TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows_lmhead");
             HIPCHK(vocab_reduce(c->f(Y.logits), M, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, c->small_i() + SM_TARGET, 1,
                                 nullptr, nullptr, nullptr, c->stream), "vocab_reduce");

@@ -65,10 +65,15 @@ struct RowsGemm {
 };
 hipError_t gemm_rows(const Dims& D, const RowsGemm& g, hipStream_t s);
 // Multi-row MFMA GEMM for bf16 weights with K a multiple of 64.  Activations come pre-split into
-// bf16 hi/lo arrays [M][ldb] (rows_prep, attention with out_hi/out_lo, or the SwiGLU mode below).
+// bf16 hi/lo arrays [M][ldb] (rows_prep, rows_gain_split, attention with out_hi/out_lo, the SwiGLU mode
+// or a RESID projection with gain_out).
 //   mode 0 store fp32, 1 residual add into y (+ tap), 2 SwiGLU of two matrices written as hi/lo to
 //   oh/ol, 3 QKV: rotary on q and k at positions *pos_dev + pos_off + r, q -> y [M][dq] fp32,
 //   k and v -> cache rows.
+// RMSNorm without a kernel: a mode-1 call with gain_out set also writes split(y * gain_out) to oh/ol
+// [M][ldo] and the sums of y^2 over each 16-column tile to ssq_out [M][n/16]; a mode-0/2/3 call with
+// ssq set treats bh/bl as such un-normalised rows and scales its results by
+// rsqrt(sum(ssq[r][0..n_ssq)) / K + eps).
 struct RowsFused {
     const void* w[3];
     int n[3];
@@ -81,15 +86,21 @@ struct RowsFused {
     int mode;
     const float* rope; const int* pos_dev; int pos_off;
     void* kc; void* vc;
+    const float* ssq; int n_ssq;
+    const float* gain_out; float* ssq_out;
 };
 bool rows_fused_supported(const Dims& D);
-// tuning hook: 2 = weights read in place as 16-row tiles, 3 (default) = LDS-staged 16x512 stripes
-void rows_fused_variant(int v);
+// tuning hook: > 0 forces the number of weight stripes a block keeps in flight
+void rows_fused_depth(int d);
 hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s);
 // hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
 // gain first when gain != nullptr
 hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi, uint16_t* lo,
                      hipStream_t s);
+// hi/lo = split(in * gain) (no norm scale) and ssq[r][t] = sum of in[r][16t..16t+16)^2: the form in which a
+// RESID projection with gain_out hands rows to its consumer
+hipError_t rows_gain_split(const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo, float* ssq,
+                           hipStream_t s);
 // rotary on q,k rows + cache write for the multi-row path. qkv: [M][dq + 2 dkv]; q is rotated in place.
 hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int* pos_dev, int pos_off, int M,
                         void* kcache_l, void* vcache_l, hipStream_t s);

@@ -758,16 +758,15 @@ hipError_t gemm_rows(const Dims& D, const RowsGemm& g, hipStream_t s)
 // --- bf16 weights, multi-row MFMA GEMM at streaming speed (K a multiple of 64) -----------------------
 // The verify / prompt path.  Activations arrive already split into two bf16 arrays hi = rne(x),
 // lo = rne(x - hi) (hi + lo carries 16 mantissa bits of x), written once by whoever produced x,
-// so the GEMM itself is nothing but loads and MFMAs:
-//   * a block has 8 waves; KS waves share one 16-row tile and take K-steps of 64 in turn;
-//   * per step a lane loads 2 x 128 bits of weights (non-temporal), each instruction covering 64
-//     contiguous bytes of 16 rows, feeding two 16x16x32 MFMAs each for hi and lo;
-//   * weight loads run DA steps ahead, the cache-resident activations one step ahead;
+// so the GEMM itself is nothing but loads and MFMAs.  RMSNorm costs no kernel of its own: the
+// projection that finishes a residual row block (RESID mode) also writes x * gain of the NEXT norm as
+// hi/lo plus, per 16-column tile, the partial sums of x^2; the consumer adds the partials of a row,
+// and scales its finished dot products by rsqrt(mean + eps) -- the scale is a per-row scalar and
+// commutes with the contraction.
 //   * QKV mode orders the 16 rows of a tile as 8 rotary pairs (i, i + hd/2), so the epilogue can
 //     rotate q and k and write k, v straight into the cache; SwiGLU mode writes its result
 //     directly as the hi/lo pair the down projection consumes.
 constexpr int RM_QKV = 3;
-constexpr int M2_DA = 4;
 
 struct RowsP2 {
     const void* w[3];
@@ -781,6 +780,8 @@ struct RowsP2 {
     const float* rope; const int* pos_dev; int pos_off;
     int hd, dq, dkv, max_seq;
     void* kc; void* vc;
+    const float* ssq; int n_ssq; float eps;     // consumer: partial sums of squares [M][n_ssq] of the input rows (or null)
+    const float* gain_out; float* ssq_out;      // RESID producer: gain of the next norm -> oh/ol = split(x * gain), ssq_out [M][n/16]
 };
 
 __device__ __forceinline__ void split_store(float v, uint16_t* hi, uint16_t* lo, size_t i)
@@ -814,10 +815,25 @@ __device__ __forceinline__ const uint16_t* m2_row(const RowsP2& p, int tile, int
     return (const uint16_t*)p.w[2] + (size_t)(row - p.n[1]) * p.K;
 }
 
+// v summed over the 16 lanes of a DPP row (rotations by 8, 4, 2, 1); every lane of the row gets the sum
+template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v = dpp_add<0x128>(v);  // row_ror:8
+    v = dpp_add<0x124>(v);  // row_ror:4
+    v = dpp_add<0x122>(v);  // row_ror:2
+    return dpp_add<0x121>(v);  // row_ror:1
+}
+
 // Final step of a tile: sum the KS per-wave partial tiles held in LDS (layout [wave][NT][256], element
 // row*16 + column) and apply the mode's epilogue.  Executed by the whole block (it contains barriers in QKV mode).
+// rs: per-column (= activation row) RMS scale in LDS, 1 where no norm applies.
 template <int MODE>
-__device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float* red, int KS, int ts, float* fin)
+__device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float* red, int KS, int ts, float* fin,
+                                            const float* rs)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     const int tid = threadIdx.x;
@@ -828,6 +844,7 @@ __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float*
             v += red[((ts * KS + j) * NT + 0) * 256 + rr * 16 + c];
             if (MODE == RM_SWIGLU) v2 += red[((ts * KS + j) * NT + 1) * 256 + rr * 16 + c];
         }
+        if (MODE != RM_RESID) { v *= rs[c]; v2 *= rs[c]; }
         if (MODE == RM_QKV) fin[rr * 16 + c] = v;
     }
     if (MODE == RM_QKV) __syncthreads();
@@ -858,106 +875,16 @@ __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float*
                 const float tv = *dst + v;
                 *dst = tv;
                 if (p.tap) p.tap[(size_t)c * p.tap_ld + colx] = tv;
+                if (p.gain_out) {
+                    split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)c * p.ldo + colx);
+                    // the 16 threads of one column are the 16 lanes of a DPP row, all active together
+                    const float sq = row16_sum(tv * tv);
+                    if (rr == 0) p.ssq_out[(size_t)c * (p.n[0] >> 4) + t] = sq;
+                }
             } else split_store(v / (1.0f + __expf(-v)) * v2, p.oh, p.ol, (size_t)c * p.ldo + colx);
         }
     }
     if (MODE == RM_QKV) __syncthreads();
-}
-
-template <int MODE>
-__global__ __launch_bounds__(512) void rows_mfma2_kernel(RowsP2 p, int KS)
-{
-    __shared__ float red[8][MODE == RM_SWIGLU ? 2 : 1][256];
-    __shared__ float fin[256];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r16 = lane & 15, g = lane >> 4;
-    const int TPB = 8 / KS, slot = wave / KS, kp = wave % KS;
-    const int n_tiles = MODE == RM_SWIGLU ? (p.n[0] >> 4) : ((p.n[0] + p.n[1] + p.n[2]) >> 4);
-    const int tile = blockIdx.x * TPB + slot;
-    const bool act = tile < n_tiles;
-    const int steps = p.K >> 6;
-    const int my_n = act && steps > kp ? (steps - kp + KS - 1) / KS : 0;
-    const bool col = r16 < p.M;
-
-    const uint16_t* a0p = nullptr;
-    const uint16_t* a1p = nullptr;
-    if (act) {
-        a0p = m2_row<MODE>(p, tile, r16, 0) + (size_t)kp * 64 + g * 8;
-        if (MODE == RM_SWIGLU) a1p = m2_row<MODE>(p, tile, r16, 1) + (size_t)kp * 64 + g * 8;
-    }
-    const size_t boff = (size_t)(col ? r16 : 0) * p.ldb + (size_t)kp * 64 + g * 8;
-    const uint16_t* bhp = p.bh + boff;
-    const uint16_t* blp = p.bl + boff;
-    const size_t kstride = (size_t)KS * 64;
-
-    u32x4_t a[M2_DA][2], a2[M2_DA][2];
-    u32x4_t bh[2][2], bl[2][2];
-    auto load_a = [&](int s, int i) {
-        const uint16_t* q0 = a0p + (size_t)i * kstride;
-        a[s][0] = gv_load(q0);
-        a[s][1] = gv_load(q0 + 32);
-        if (MODE == RM_SWIGLU) {
-            const uint16_t* q1 = a1p + (size_t)i * kstride;
-            a2[s][0] = gv_load(q1);
-            a2[s][1] = gv_load(q1 + 32);
-        }
-    };
-    auto load_b = [&](int b, int i) {
-        if (col) {
-            const uint16_t* qh = bhp + (size_t)i * kstride;
-            const uint16_t* ql = blp + (size_t)i * kstride;
-            bh[b][0] = *reinterpret_cast<const u32x4_t*>(qh);
-            bh[b][1] = *reinterpret_cast<const u32x4_t*>(qh + 32);
-            bl[b][0] = *reinterpret_cast<const u32x4_t*>(ql);
-            bl[b][1] = *reinterpret_cast<const u32x4_t*>(ql + 32);
-        }
-    };
-#pragma unroll
-    for (int s = 0; s < M2_DA; s++)
-        if (s < my_n) load_a(s, s);
-    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-    bh[0][0] = zero4; bh[0][1] = zero4; bh[1][0] = zero4; bh[1][1] = zero4;
-    bl[0][0] = zero4; bl[0][1] = zero4; bl[1][0] = zero4; bl[1][1] = zero4;
-    if (my_n > 0) load_b(0, 0);
-
-    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-    for (int i0 = 0; i0 < my_n; i0 += M2_DA) {
-#pragma unroll
-        for (int s = 0; s < M2_DA; s++) {
-            const int i = i0 + s;
-            if (i < my_n) {  // uniform per wave
-                const int par = s & 1;
-                if (i + 1 < my_n) load_b(par ^ 1, i + 1);
-                const bf16x8_t h0 = __builtin_bit_cast(bf16x8_t, bh[par][0]), h1 = __builtin_bit_cast(bf16x8_t, bh[par][1]);
-                const bf16x8_t l0 = __builtin_bit_cast(bf16x8_t, bl[par][0]), l1 = __builtin_bit_cast(bf16x8_t, bl[par][1]);
-                const bf16x8_t w0 = __builtin_bit_cast(bf16x8_t, a[s][0]), w1 = __builtin_bit_cast(bf16x8_t, a[s][1]);
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, h0, acc0, 0, 0, 0);
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, l0, acc0, 0, 0, 0);
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, h1, acc0, 0, 0, 0);
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, l1, acc0, 0, 0, 0);
-                if (MODE == RM_SWIGLU) {
-                    const bf16x8_t u0 = __builtin_bit_cast(bf16x8_t, a2[s][0]), u1 = __builtin_bit_cast(bf16x8_t, a2[s][1]);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u0, h0, acc1, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u0, l0, acc1, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u1, h1, acc1, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u1, l1, acc1, 0, 0, 0);
-                }
-                if (i + M2_DA < my_n) load_a(s, i + M2_DA);
-            }
-        }
-    }
-    // D layout: lane (c = lane % 16, g = lane / 16) holds rows 4g..4g+3 of column c
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-        red[wave][0][(g * 4 + j) * 16 + r16] = acc0[j];
-        if (MODE == RM_SWIGLU) red[wave][1][(g * 4 + j) * 16 + r16] = acc1[j];
-    }
-    __syncthreads();
-    for (int ts = 0; ts < TPB; ts++) {
-        const int t = blockIdx.x * TPB + ts;
-        if (t >= n_tiles) break;  // uniform
-        m2_epilogue<MODE>(p, t, &red[0][0][0], KS, ts, fin);
-    }
 }
 
 // LDS-staged variant: the block fetches a 16-row x 512-k stripe of the weights the way the single-row
@@ -975,6 +902,7 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     extern __shared__ __align__(16) unsigned char sm3[];
     __shared__ float fin[256];
+    __shared__ float rs[16];
     unsigned char* As = sm3;                          // [NT][16][PITCH]
     unsigned char* Bh = sm3 + NT * 16 * M3_PITCH;     // [M][PITCH]
     unsigned char* Bl = Bh + p.M * M3_PITCH;
@@ -1050,6 +978,17 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 #pragma unroll
     for (int sl = 0; sl < M3_D; sl++)
         if (sl < NC) gload(sl, sl);
+    // RMS scale of every activation row from the producer's per-tile sums of squares (read by the epilogue,
+    // many barriers from here)
+    if (tid < 16) rs[tid] = 1.0f;
+    if (MODE != RM_RESID && p.ssq) {
+        for (int c = wave; c < M; c += 8) {
+            float sq = 0.f;
+            for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)c * p.n_ssq + i];
+            sq = wave_sum(sq);
+            if (lane == 0) rs[c] = 1.0f / sqrtf(sq / (float)K + p.eps);
+        }
+    }
     int ck0 = 0;
     for (; ck0 + 2 * M3_D <= NC; ck0 += M3_D) {  // steady state: every step refills its slot, no conditions
 #pragma unroll
@@ -1076,7 +1015,7 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 #pragma unroll
         for (int j = 0; j < 4; j++) red[(wave * NT + t) * 256 + (g * 4 + j) * 16 + r16] = acc[t][j];
     __syncthreads();
-    m2_epilogue<MODE>(p, tile, red, 8, 0, fin);
+    m2_epilogue<MODE>(p, tile, red, 8, 0, fin, rs);
 }
 
 template <int MODE, int DEPTH>
@@ -1095,31 +1034,21 @@ static hipError_t launch_mfma3(const RowsP2& p, int n_tiles, hipStream_t s)
     return hipGetLastError();
 }
 
-static int g_rows_variant = 3;  // tuning hook (kernel_bench): 2 = in-place tiles, 3 = LDS-staged stripes, 30+d = depth d
-void rows_fused_variant(int v) { g_rows_variant = v; }
+static int g_rows_depth = 0;  // tuning hook (kernel_bench): > 0 forces the number of stripes in flight
+void rows_fused_depth(int d) { g_rows_depth = d; }
 
 template <int MODE>
 static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
 {
     const int n_tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
-    const int steps = p.K / 64;
-    if (g_rows_variant >= 3) {
-        // few tiles -> few blocks per CU -> each block keeps more stripes in flight
-        int depth = g_rows_variant > 30 ? g_rows_variant - 30 : (n_tiles <= 512 ? 3 : (MODE == RM_SWIGLU ? 2 : 1));
-        switch (depth) {
-            case 1: return launch_mfma3<MODE, 1>(p, n_tiles, s);
-            case 2: return launch_mfma3<MODE, 2>(p, n_tiles, s);
-            case 3: return launch_mfma3<MODE, 3>(p, n_tiles, s);
-            default: return launch_mfma3<MODE, 4>(p, n_tiles, s);
-        }
+    // few tiles -> few blocks per CU -> each block keeps more stripes in flight
+    const int depth = g_rows_depth > 0 ? g_rows_depth : (n_tiles <= 512 ? 3 : (MODE == RM_SWIGLU ? 2 : 1));
+    switch (depth) {
+        case 1: return launch_mfma3<MODE, 1>(p, n_tiles, s);
+        case 2: return launch_mfma3<MODE, 2>(p, n_tiles, s);
+        case 3: return launch_mfma3<MODE, 3>(p, n_tiles, s);
+        default: return launch_mfma3<MODE, 4>(p, n_tiles, s);
     }
-    // One tile per block, its 8 waves side by side along K: the block then reads 1 KB-wide stripes of
-    // 16 consecutive rows, the widest footprint a 16-row tile allows (narrower stripes stream slower).
-    int KS = 8;
-    while (KS > 1 && steps < KS) KS >>= 1;
-    const int TPB = 8 / KS;
-    hipLaunchKernelGGL((rows_mfma2_kernel<MODE>), dim3(ceil_div(n_tiles, TPB)), dim3(512), 0, s, p, KS);
-    return hipGetLastError();
 }
 
 bool rows_fused_supported(const Dims& D)
@@ -1135,6 +1064,9 @@ hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s)
     p.K = f.K; p.bh = f.bh; p.bl = f.bl; p.ldb = f.ldb; p.y = f.y; p.ldy = f.ldy; p.oh = f.oh; p.ol = f.ol; p.ldo = f.ldo;
     p.tap = f.tap; p.tap_ld = f.tap_ld; p.M = f.M; p.rope = f.rope; p.pos_dev = f.pos_dev; p.pos_off = f.pos_off;
     p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq; p.kc = f.kc; p.vc = f.vc;
+    p.ssq = f.ssq; p.n_ssq = f.n_ssq; p.eps = D.eps; p.gain_out = f.gain_out; p.ssq_out = f.ssq_out;
+    if (f.ssq && (f.mode == RM_RESID || f.n_ssq < 1)) return hipErrorInvalidValue;
+    if (f.gain_out && (f.mode != RM_RESID || !f.oh || !f.ol || !f.ssq_out)) return hipErrorInvalidValue;
     switch (f.mode) {
         case RM_STORE: return rows_fused_mode<RM_STORE>(p, s);
         case RM_RESID: return rows_fused_mode<RM_RESID>(p, s);
@@ -1175,6 +1107,40 @@ hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, 
                      hipStream_t s)
 {
     hipLaunchKernelGGL(rows_prep_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, eps, hi, lo);
+    return hipGetLastError();
+}
+
+// Entry of the fused path (rows straight from the embedding): hi/lo = split(x * gain) without the
+// norm scale, and the sums of squares of every 16 consecutive elements, i.e. exactly what a RESID
+// projection leaves behind for its consumer.
+__global__ __launch_bounds__(256) void rows_gain_split_kernel(const float* __restrict__ in, int ldx,
+                                                              const float* __restrict__ gain, int K,
+                                                              uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
+                                                              float* __restrict__ ssq)
+{
+    const float* x = in + (size_t)blockIdx.x * ldx;
+    const int n_t = K >> 4;
+    for (int t = threadIdx.x; t < n_t; t += 256) {
+        float sq = 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; u += 4) {
+            const int i = t * 16 + u;
+            const float4 v = *reinterpret_cast<const float4*>(x + i);
+            const float4 g = *reinterpret_cast<const float4*>(gain + i);
+            sq += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            const size_t o = (size_t)blockIdx.x * K + i;
+            split_store(v.x * g.x, hi, lo, o); split_store(v.y * g.y, hi, lo, o + 1);
+            split_store(v.z * g.z, hi, lo, o + 2); split_store(v.w * g.w, hi, lo, o + 3);
+        }
+        ssq[(size_t)blockIdx.x * n_t + t] = sq;
+    }
+}
+
+hipError_t rows_gain_split(const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo, float* ssq,
+                           hipStream_t s)
+{
+    if (K % 16 || !gain) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rows_gain_split_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, hi, lo, ssq);
     return hipGetLastError();
 }
 
@@ -1454,22 +1420,18 @@ template <> __device__ __forceinline__ void aw_unpack<float>(u32x4_t w, float (&
 // sum over the LPP lanes of one position (every lane of the segment gets it).  Segments of 8 and 16
 // lanes lie inside one DPP row: rotations by 8, 4, 2, 1 (or a half-row mirror and two quad swaps) add all
 // of them without going through the LDS crossbar.
-template <int CTRL> __device__ __forceinline__ float aw_dpp_add(float v)
-{
-    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
 template <int LPP> __device__ __forceinline__ float aw_seg_sum(float v)
 {
     if (LPP == 16 || LPP == 32) {
-        v = aw_dpp_add<0x128>(v);  // row_ror:8
-        v = aw_dpp_add<0x124>(v);  // row_ror:4
-        v = aw_dpp_add<0x122>(v);  // row_ror:2
-        v = aw_dpp_add<0x121>(v);  // row_ror:1
+        v = dpp_add<0x128>(v);  // row_ror:8
+        v = dpp_add<0x124>(v);  // row_ror:4
+        v = dpp_add<0x122>(v);  // row_ror:2
+        v = dpp_add<0x121>(v);  // row_ror:1
         if (LPP == 32) v += __shfl_xor(v, 16, 64);
     } else if (LPP == 8) {
-        v = aw_dpp_add<0x141>(v);  // row_half_mirror: lane i <- lane 7 - i of its half row
-        v = aw_dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
-        v = aw_dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+        v = dpp_add<0x141>(v);  // row_half_mirror: lane i <- lane 7 - i of its half row
+        v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+        v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
     } else {
 #pragma unroll
         for (int o = LPP / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
