@@ -296,3 +296,48 @@ def test_graph_replay_is_bit_identical_to_kernel_by_kernel_launches(ssd):
     o2, l2 = run(True)
     assert o1 == o2
     assert all(np.array_equal(a, b) for a, b in zip(l1, l2))
+
+
+# Attention launch shapes that the short prompts above never reach: several position ranges per head (partials
+# folded by the output projection), more than eight ranges (separate fold kernel), ranges longer than one pass,
+# two and four query heads per KV head, both element types and head sizes.
+LONG_SHAPES = {
+    "mha64_f32": ModelShape(2, 256, 4, 4, 512, 1024, dtype="fp32"),
+    "mha64_bf16": ModelShape(2, 256, 4, 4, 512, 1024),
+    "gqa2_128_bf16": ModelShape(2, 512, 4, 2, 1024, 1024),
+    "gqa4_128_bf16": ModelShape(2, 512, 4, 1, 1024, 1024),
+    "gqa2_128_f32": ModelShape(1, 512, 4, 2, 768, 1024, dtype="fp32"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(LONG_SHAPES))
+@pytest.mark.parametrize("plen", [130, 700, 1100, 2500])
+def test_long_context_decode_and_verify(ssd, name, plen):
+    shape = LONG_SHAPES[name]
+    orc, ctx = make_pair(shape, 21, plen + 24, max_k=4, norm_gain_std=0.1)
+    prompt = make_prompt(shape.vocab, plen, 8).tolist()
+    o = OracleSSD(orc)
+    o.prefill(prompt)
+    ctx.ssd_prefill(prompt)
+    worst = assert_logits_close(ctx.ssd_copy_logits(0, 1)[0], o.last_logits[0], shape.dtype, "prefill")
+    for step in range(3):
+        t_o, t_g = o.decode(), ctx.ssd_decode()
+        worst = max(worst, assert_logits_close(ctx.ssd_copy_logits(0, 1)[0], o.last_logits[0], shape.dtype,
+                                               "decode %d" % step))
+        if t_g != t_o:
+            assert not decisive(o.last_logits[0], shape.dtype)
+            pytest.skip("sub-tolerance arg-max tie: choose another seed")
+    zero = np.zeros(shape.n_layers, np.uint8)
+    d = o.draft(zero, 3)
+    d_g = ctx.ssd_draft_step(zero, 3)
+    y = o.verify(d)
+    if d_g == d:
+        y_g = ctx.ssd_verify(d)
+        lg = ctx.ssd_copy_logits(0, 4)
+        for r in range(4):
+            worst = max(worst, assert_logits_close(lg[r], o.last_logits[r], shape.dtype, "verify row %d" % r))
+        if all(decisive(o.last_logits[r], shape.dtype) for r in range(4)):
+            assert y_g == y
+    else:
+        assert not all(decisive(z, shape.dtype) for z in o.last_draft_logits)
+    print("long", name, plen, "max err %.2e" % worst)
