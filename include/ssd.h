@@ -128,11 +128,23 @@ int ssd_decode(ssd_ctx *ctx, int32_t *token_out);
 int ssd_draft_step(ssd_ctx *ctx, const uint8_t *skip_mask, int k, int32_t *draft_out,
                    float *draft_maxprob_out);
 
+/* Confidence-aware drafting (Section 3: once a skip set is found the candidate tokens are
+ * generated with the confidence-aware draft exit of the layer-skipping baseline the paper builds
+ * on; the paper gives no threshold, gamma is the caller's).  Same draft model and cache effects as
+ * ssd_draft_step, but tokens are drafted one at a time and drafting stops after the first token
+ * whose draft softmax max-probability is below gamma (that token is kept), or after k_max tokens.
+ * draft_out: host [k_max]; draft_maxprob_out: host [k_max] or NULL; *k_out (host) receives the
+ * number of tokens drafted (1..k_max), which is the k to pass to ssd_verify / ssd_accept.
+ * The comparison p < gamma is taken in fp32 on the max-probability the device computed.
+ * SSD_ECAPACITY if n + k_max > max_seq or k_max > max_k; SSD_EINVAL if gamma is NaN. */
+int ssd_draft_adaptive(ssd_ctx *ctx, const uint8_t *skip_mask, int k_max, float gamma,
+                       int32_t *draft_out, float *draft_maxprob_out, int32_t *k_out);
+
 /* Verification (Section 1: drafted tokens "verified by the target model in a single forward
  * pass"): the full model over the rows [pending, draft_1..draft_k] at positions n-1..n-1+k,
  * causal inside the block; overwrites the K/V of every layer at those positions and captures
  * the hidden-state taps of all k+1 rows.  target_out: host [k+1], the greedy token after
- * each row.  Must follow ssd_draft_step with the same k; the draft tokens passed here are
+ * each row.  Must follow ssd_draft_step / ssd_draft_adaptive with the same k; the draft tokens passed here are
  * the ones verified. */
 int ssd_verify(ssd_ctx *ctx, const int32_t *draft, int k, int32_t *target_out);
 

@@ -72,6 +72,27 @@ class OracleSSD:
             pos += 1
         return (d, mp) if want_maxprob else d
 
+    def draft_adaptive(self, skip_mask, k_max: int, gamma: float):
+        """Confidence-aware drafting (Section 3: candidates are generated "following the confidence-aware approach"
+        of the draft-exit baseline): tokens are drafted one at a time and drafting stops after the first token whose
+        draft soft-max probability is below gamma, or after k_max tokens.  The low-confidence token itself is kept
+        (it has been generated; verification decides).  Returns (tokens, their max-probabilities)."""
+        d, mp = [], []
+        tok, pos = self.pending, self.n - 1
+        self.last_draft_logits = []
+        while len(d) < k_max:
+            z = self.m.forward([tok], pos, skip_mask=skip_mask)["logits"][0]
+            self.last_draft_logits.append(z)
+            tok = argmax_lowest(z)
+            e = np.exp(z - z.max())
+            p = float(e.max() / e.sum())
+            d.append(tok)
+            mp.append(p)
+            pos += 1
+            if p < gamma:
+                break
+        return d, mp
+
     def verify(self, draft: Sequence[int]):
         """Full model over [pending, d_1..d_k]; returns its greedy token after each row."""
         rows = [self.pending] + [int(t) for t in draft]

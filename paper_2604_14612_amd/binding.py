@@ -76,6 +76,7 @@ SYMBOLS = {
     "ssd_prefill": (C.c_int, [_P, _P, C.c_int, _P]),
     "ssd_decode": (C.c_int, [_P, _P]),
     "ssd_draft_step": (C.c_int, [_P, _P, C.c_int, _P, _P]),
+    "ssd_draft_adaptive": (C.c_int, [_P, _P, C.c_int, C.c_float, _P, _P, _P]),
     "ssd_verify": (C.c_int, [_P, _P, C.c_int, _P]),
     "ssd_accept": (C.c_int, [_P, _P, _P, C.c_int, _P, _P]),
     "ssd_force_commit": (C.c_int, [_P, _P, C.c_int, C.c_int, C.c_int32]),
@@ -298,6 +299,18 @@ class Context:
         mp = np.zeros(max(k, 1), np.float32) if want_maxprob else None
         self._check(self._l.ssd_draft_step(self._h, _np_ptr(m), int(k), _np_ptr(d), _np_ptr(mp)))
         return (d[:k].tolist(), mp[:k].tolist()) if want_maxprob else d[:k].tolist()
+
+    def ssd_draft_adaptive(self, skip_mask, k_max: int, gamma: float):
+        """-> (tokens, their draft max-probabilities); len(tokens) is the k to verify."""
+        m = np.ascontiguousarray(np.asarray(skip_mask, dtype=np.uint8))
+        if m.shape != (self.shape.n_layers,):
+            raise SsdError(SSD_EINVAL, "skip_mask must have n_layers entries")
+        d = np.zeros(max(k_max, 1), np.int32)
+        mp = np.zeros(max(k_max, 1), np.float32)
+        k = C.c_int32()
+        self._check(self._l.ssd_draft_adaptive(self._h, _np_ptr(m), int(k_max), float(gamma), _np_ptr(d), _np_ptr(mp),
+                                               C.addressof(k)))
+        return d[:k.value].tolist(), mp[:k.value].tolist()
 
     def ssd_verify(self, draft: Sequence[int]):
         d = np.ascontiguousarray(np.asarray(draft, dtype=np.int32))

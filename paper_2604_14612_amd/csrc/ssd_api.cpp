@@ -572,6 +572,41 @@ int ssd_draft_step(ssd_ctx* c, const uint8_t* skip_mask, int k, int32_t* draft_o
     return SSD_OK;
 }
 
+int ssd_draft_adaptive(ssd_ctx* c, const uint8_t* skip_mask, int k_max, float gamma, int32_t* draft_out,
+                       float* draft_maxprob_out, int32_t* k_out)
+{
+    if (!c || !skip_mask || !draft_out || !k_out) return c ? fail(c, SSD_EINVAL, "draft_adaptive: bad argument") : SSD_EINVAL;
+    if (k_max < 1) return fail(c, SSD_EINVAL, "k_max must be at least 1");
+    if (gamma != gamma) return fail(c, SSD_EINVAL, "gamma is NaN");
+    if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "draft_adaptive needs a prefilled sequence with no draft in flight");
+    if (k_max > c->cfg.max_k) return fail(c, SSD_ECAPACITY, "k_max exceeds max_k");
+    if (c->n + k_max > c->D.max_seq) return fail(c, SSD_ECAPACITY, "draft + verification would exceed max_seq");
+    const std::string mask_key(skip_mask, skip_mask + c->D.L);
+    int k = 0;
+    while (k < k_max) {
+        // one draft step per submission: the host reads the step's max-probability before deciding on the next
+        const int i = k;
+        std::string key = "A|" + std::to_string(i) + "|" + mask_key + "|" + std::to_string(attention_splits(c->D, c->n + i, 1));
+        int rc = run_sequence(c, key, [&]() { return forward_single(c, skip_mask, i, i + 1, i, i); });
+        if (rc) return rc;
+        float p = 0.f;
+        rc = readback(c, c->small_f() + SM_MAXPROB + i, sizeof(float), &p);
+        if (rc) return rc;
+        k++;
+        if (draft_maxprob_out) draft_maxprob_out[i] = p;
+        if (p < gamma) break;
+    }
+    int rc = readback(c, c->small_i() + SM_TOK + 1, sizeof(int32_t) * k, draft_out);
+    if (rc) return rc;
+    *k_out = k;
+    c->state = ST_DRAFTED;
+    c->k_pending = k;
+    c->logit_rows = k;
+    c->tap_rows = 0;
+    c->st.draft_steps += k;
+    return SSD_OK;
+}
+
 int ssd_verify(ssd_ctx* c, const int32_t* draft, int k, int32_t* target_out)
 {
     if (!c || !draft || !target_out) return c ? fail(c, SSD_EINVAL, "verify: bad argument") : SSD_EINVAL;

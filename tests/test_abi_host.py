@@ -74,6 +74,11 @@ def test_call_order_and_argument_errors_without_a_gpu():
     assert l.ssd_reset(h) == ssd.SSD_ESTATE
     assert l.ssd_prefill(h, None, 4, p(out)) == ssd.SSD_EINVAL
     assert l.ssd_draft_step(h, p(mask), 0, p(out), None) == ssd.SSD_EINVAL
+    kout = np.zeros(1, np.int32)
+    assert l.ssd_draft_adaptive(h, p(mask), 4, C.c_float(0.5), p(out), None, p(kout)) == ssd.SSD_ESTATE
+    assert l.ssd_draft_adaptive(h, p(mask), 0, C.c_float(0.5), p(out), None, p(kout)) == ssd.SSD_EINVAL
+    assert l.ssd_draft_adaptive(h, p(mask), 4, C.c_float(float("nan")), p(out), None, p(kout)) == ssd.SSD_EINVAL
+    assert l.ssd_draft_adaptive(h, p(mask), 4, C.c_float(0.5), p(out), None, None) == ssd.SSD_EINVAL
     assert l.ssd_load_weights(h, None) == ssd.SSD_EINVAL
     st = ssd.binding.ssd_stats()
     assert l.ssd_get_stats(h, C.byref(st)) == 0 and st.state == 0 and st.n_tokens == 0

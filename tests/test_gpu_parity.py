@@ -341,3 +341,46 @@ def test_long_context_decode_and_verify(ssd, name, plen):
     else:
         assert not all(decisive(z, shape.dtype) for z in o.last_draft_logits)
     print("long", name, plen, "max err %.2e" % worst)
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa"])
+def test_confidence_aware_drafting_lockstep(ssd, name):
+    """ssd_draft_adaptive against the oracle's draft rule: same tokens, same max-probabilities, and the same draft
+    length whenever no max-probability of the cycle lies within the tolerance of gamma (p < gamma decides an
+    integer; a probability inside the band may legitimately fall on either side)."""
+    shape = SHAPES[name]
+    orc, ctx = make_pair(shape, 17, 160, max_k=8, norm_gain_std=0.1)
+    prompt = make_prompt(shape.vocab, 15, 11).tolist()
+    mask = np.array(MASKS[name][-1], np.uint8)
+    o = OracleSSD(orc)
+    o.prefill(prompt)
+    ctx.ssd_prefill(prompt)
+    # calibrate gamma on the oracle so that the rule stops some drafts early and lets others run
+    _, probe = o.draft(mask, 8, want_maxprob=True)
+    gamma = float(np.median(probe))
+    rel = 4e-2 if shape.dtype == "bf16" else 1e-3          # |dp| <= p * 2 * (logit tolerance)
+    lens, compared = [], 0
+    for cycle in range(10):
+        d_o, p_o = o.draft_adaptive(mask, 8, gamma)
+        d_g, p_g = ctx.ssd_draft_adaptive(mask, 8, gamma)
+        n = min(len(d_o), len(d_g))
+        np.testing.assert_allclose(p_g[:n], p_o[:n], rtol=rel)
+        if d_g != d_o:                                         # excusable only inside the tolerance bands
+            tokens_pinned = all(decisive(z, shape.dtype) for z in o.last_draft_logits[:n])
+            length_pinned = all(abs(p - gamma) > rel * gamma for p in p_o)
+            assert not (tokens_pinned and length_pinned), "draft %s vs oracle %s at gamma %.4g, p %s" % (
+                d_g, d_o, gamma, p_o)
+            break                                              # a sub-tolerance case: stop comparing here
+        y_o, y_g = o.verify(d_o), ctx.ssd_verify(d_g)
+        if y_g != y_o:
+            assert not all(decisive(z, shape.dtype) for z in o.last_logits)
+            break
+        a_o, _ = o.accept(d_o, y_o)
+        a_g, _ = ctx.ssd_accept(d_g, y_g)
+        assert a_g == a_o
+        lens.append(len(d_o))
+        compared += 1
+    print("adaptive", name, "gamma %.4g" % gamma, "draft lengths", lens)
+    assert compared >= 4
+    st = ctx.ssd_get_stats()
+    assert st["drafted"] == sum(lens) or compared < 10

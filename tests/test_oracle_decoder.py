@@ -202,6 +202,41 @@ def test_empty_skip_set_accepts_everything(k):
     assert st["accepted"] == st["drafted"]
 
 
+def test_adaptive_drafting_truncates_the_fixed_length_draft_and_stays_lossless():
+    """Confidence-aware drafting: gamma = 0 is the fixed-k draft, gamma > 1 drafts one token, any gamma gives a
+    prefix of the fixed-k draft whose length is set by the first max-probability below gamma (max-probabilities
+    recomputed here with scipy's softmax), and generation with it still equals vanilla decoding."""
+    from scipy.special import softmax
+    wl, w, _ = _tiny()
+    shape = wl.shape
+    prompt = make_prompt(shape.vocab, 9, 3).tolist()
+    mask = np.array([0, 1, 0, 0], np.uint8)
+    s = OracleSSD(OracleModel(shape, w, 64))
+    s.prefill(prompt)
+    fixed = s.draft(mask, 8)
+    probs = [float(softmax(z).max()) for z in s.last_draft_logits]
+    assert s.draft_adaptive(mask, 8, 0.0)[0] == fixed
+    d1, p1 = s.draft_adaptive(mask, 8, 1.5)
+    assert d1 == fixed[:1] and abs(p1[0] - probs[0]) < 1e-12
+    for gamma in sorted(probs)[1::2]:
+        d, mp = s.draft_adaptive(mask, 8, gamma + 1e-12)
+        stop = next(i for i, p in enumerate(probs) if p < gamma + 1e-12)
+        assert d == fixed[:stop + 1] and np.allclose(mp, probs[:stop + 1], rtol=1e-12)
+        assert all(p >= gamma for p in mp[:-1]) and mp[-1] < gamma + 1e-12
+    # lossless with a varying draft length
+    van = generate_vanilla(OracleModel(shape, w, 96), prompt, 24)
+    s = OracleSSD(OracleModel(shape, w, 96))
+    s.prefill(prompt)
+    gamma = float(np.median(probs))
+    lens = []
+    while s.n - len(prompt) < 24:
+        d, _ = s.draft_adaptive(mask, 6, gamma)
+        lens.append(len(d))
+        s.accept(d, s.verify(d))
+    assert s.tokens[len(prompt):len(prompt) + 24] == van
+    assert len(set(lens)) > 1          # the rule actually varied the length
+
+
 def test_stale_cache_entries_are_never_read():
     wl, w, p = _tiny()
     mask = np.array([0, 1, 0, 1], np.uint8)
