@@ -384,3 +384,19 @@ def test_confidence_aware_drafting_lockstep(ssd, name):
     assert compared >= 4
     st = ctx.ssd_get_stats()
     assert st["drafted"] == sum(lens) or compared < 10
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa"])
+def test_longest_draft_fills_the_row_block(ssd, name):
+    """k = 15 (the library's maximum): verification runs all 16 rows of a row block."""
+    shape = SHAPES[name]
+    orc, ctx = make_pair(shape, 29, 160, max_k=15, norm_gain_std=0.1)
+    prompt = make_prompt(shape.vocab, 23, 12).tolist()
+    for mask in (MASKS[name][0], MASKS[name][-1]):
+        st = lockstep_ssd(ctx, orc, prompt, 34, 15, np.array(mask, np.uint8), shape.dtype)
+        print("k15", name, mask, "cycles", st["cycles"], "unpinned", st["unpinned_cycles"], "max err %.2e" % st["max_err"],
+              "accepted", st["accepted"])
+        assert st["unpinned_cycles"] <= max(1, st["cycles"] // 3)
+        if not any(mask) and st["unpinned_cycles"] == 0:
+            assert all(a == 15 for a in st["accepted"])
+        ctx.ssd_reset()
