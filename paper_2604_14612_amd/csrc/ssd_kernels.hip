@@ -1617,6 +1617,7 @@ __global__ __launch_bounds__(NW * 64) void attn_wide_kernel(const float* __restr
 // cache is spread over many blocks even though that costs the fold of the partial results.  Many query
 // vectors (prompt blocks, wide GQA groups): the LDS-staged kernel, which fetches K/V once for all of them.
 constexpr int AW_MAXQ_TOTAL = 4;
+constexpr int AW_MAX_ROWS = 8;
 constexpr int AW_RANGE = 128;
 constexpr int AW_MAX_RANGES = 16;
 static int g_force_splits = 0;  // tuning hook (kernel_bench): > 0 overrides the heuristic
@@ -1631,7 +1632,9 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     AttnPlan pl;
     pl.defer_fold = false;
     const int Q = (D.H / D.Hkv) * M;
-    pl.wide = Q <= AW_MAXQ_TOTAL;
+    // a few rows of a model without grouped heads: still the register-resident kernel, one block per row (the
+    // rows re-read a range's K/V from the cache, which at up to AW_MAX_ROWS rows is cheaper than the LDS-staged kernel)
+    pl.wide = Q <= AW_MAXQ_TOTAL || (D.H == D.Hkv && M <= AW_MAX_ROWS);
     if (g_force_attn == 1) pl.wide = false;
     if (pl.wide) {
         // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
@@ -1678,11 +1681,12 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
     const int n_splits = pl.n_splits;
     if (n_splits < 1 || (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK))) return hipErrorInvalidValue;
     if (pl.wide) {
-        const int Q = (D.H / D.Hkv) * M;
+        int Q = (D.H / D.Hkv) * M, zq = 1;
+        if (Q > AW_MAXQ_TOTAL) { zq = Q; Q = 1; }  // one block per query vector: K/V of a range re-read from cache per row
         const int span = ceil_div(ctx, n_splits) * (HD / (16 / (int)sizeof(KT)));  // lanes' worth of 16-byte vectors per range
-        if (Q == 1 && span <= 8 * 64 * 4) launch_attn_wide<KT, HD, 1, 8, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
-        else if (Q == 1 && span <= 16 * 64 * 4) launch_attn_wide<KT, HD, 1, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
-        else if (Q == 1) launch_attn_wide<KT, HD, 1, 8, 16>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
+        if (Q == 1 && span <= 8 * 64 * 4) launch_attn_wide<KT, HD, 1, 8, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
+        else if (Q == 1 && span <= 16 * 64 * 4) launch_attn_wide<KT, HD, 1, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
+        else if (Q == 1) launch_attn_wide<KT, HD, 1, 8, 16>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
         else if (Q == 2) launch_attn_wide<KT, HD, 2, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
         else launch_attn_wide<KT, HD, 4, 8, 8>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
     } else {
