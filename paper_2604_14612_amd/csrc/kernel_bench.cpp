@@ -172,6 +172,14 @@ int main(int argc, char** argv)
     timeit("rows_down (resid)", gu * 2.0, n, [&](int i) { fused(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, x, 4096); });
     timeit("rows_lmhead", lm * 2.0, n, [&](int i) { fused(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, logits, 32000); });
     }
+    for (int depth : {1, 2, 3}) for (int rows : {16, 64}) {
+        rows_many_depth(depth);
+        char nm[96];
+        std::snprintf(nm, sizeof nm, "rows_many lmhead %d rows, depth %d", rows, depth);
+        timeit(nm, lm * 2.0, n, [&](int i) {
+            CK(rows_many(D, W + (size_t)i * lm, 32000, 4096, hi, lo, 4096, rows, big_a, 32000, 0)); });
+    }
+    rows_many_depth(1);
     for (int kind : {1, 0}) {
         attention_force_kernel(kind);
         for (int sp : {0, 2, 4, 8, 16}) {

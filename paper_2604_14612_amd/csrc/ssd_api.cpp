@@ -698,7 +698,13 @@ int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out,
         const float* taps = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
         if (rows_fused_supported(D)) {
             HIPCHK(rows_prep(taps, D.d, c->w.final_norm, R, D.d, D.eps, c->h16(Y.hi), c->h16(Y.lo), c->stream), "rows_prep taps");
-            for (int b = 0; b < R; b += 16) {
+            const bool many = rows_many_supported(D, D.V, D.d);
+            for (int b = 0; many && b < R; b += 64) {   // the LM head is streamed once per 64 tap rows
+                TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, c->h16(Y.hi) + (size_t)b * D.d,
+                                                   c->h16(Y.lo) + (size_t)b * D.d, D.d, R - b < 64 ? R - b : 64,
+                                                   c->f(Y.logits) + (size_t)b * D.V, D.V, c->stream), "rows conf lmhead");
+            }
+            for (int b = 0; !many && b < R; b += 16) {
                 RowsFused lm = {};
                 lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = c->h16(Y.hi) + (size_t)b * D.d;
                 lm.bl = c->h16(Y.lo) + (size_t)b * D.d; lm.ldb = D.d; lm.y = c->f(Y.logits) + (size_t)b * D.V; lm.ldy = D.V;

@@ -93,6 +93,12 @@ bool rows_fused_supported(const Dims& D);
 // tuning hook: > 0 forces the number of weight stripes a block keeps in flight
 void rows_fused_depth(int d);
 hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s);
+// y[r][n] = sum_k W[n][k] (bh + bl)[r][k] for up to 64 pre-split rows at once (the per-layer confidence rows
+// against the LM head): W is streamed once for all of them.  bf16, N a multiple of 64, K a multiple of 128.
+bool rows_many_supported(const Dims& D, int N, int K);
+hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t* bh, const uint16_t* bl, int ldb, int M,
+                     float* y, int ldy, hipStream_t s);
+void rows_many_depth(int d);  // tuning hook: stripes in flight (1..3)
 // hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
 // gain first when gain != nullptr
 hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi, uint16_t* lo,

@@ -1051,6 +1051,177 @@ static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
     }
 }
 
+// --- many-row variant for the per-layer confidence contraction (2L tap rows against the LM head) --------
+// With up to 64 activation rows a 16-row weight tile would pull eight times more activation bytes out
+// of the cache than weight bytes out of HBM.  Here a block owns 64 weight rows and all (<= 64) rows.
+// 64 x 128-k stripes of the weights (non-temporal) and of the hi/lo rows go through LDS; a stripe has four
+// 32-wide k-steps: wave w takes k-step w & 3 for the weight rows 32 (w >> 2) .. +31 and all rows, so
+// every staged byte is read twice only, and the four k-step partials are summed through LDS at the end.
+// 52 KB of LDS per block: three blocks share a CU and cover each other's load / stage / multiply phases.
+// M6_D stripes are in flight in registers while one is multiplied.
+constexpr int M6_CK = 128;
+constexpr int M6_PITCH = M6_CK * 2 + 16;
+
+template <int M6_D>
+__global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __restrict__ w, int K,
+                                                          const uint16_t* __restrict__ bh, const uint16_t* __restrict__ bl,
+                                                          int ldb, int M, float* __restrict__ y, int ldy)
+{
+    extern __shared__ __align__(16) unsigned char sm6[];
+    unsigned char* As = sm6;                       // [64][PITCH]
+    unsigned char* Bh = sm6 + 64 * M6_PITCH;       // [64][PITCH]
+    unsigned char* Bl = Bh + 64 * M6_PITCH;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int n0 = blockIdx.x * 64;
+    const int NC = K / M6_CK;
+    // weights: wave w loads rows 8w .. 8w+7; instruction j covers rows 8w+4j .. 8w+4j+3 (16 lanes = 256 B per row)
+    const int arow = 8 * wave + (lane >> 4), acol = (lane & 15) * 8;
+    const uint16_t* ap = w + (size_t)(n0 + arow) * K + acol;
+    // activations: 64 rows x 16 vectors per array; thread takes vectors tid and tid + 512 (row clamped to M - 1)
+    const uint16_t* bhp[2];
+    const uint16_t* blp[2];
+    int bdst[2];
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+        const int v = tid + u * 512, row = v >> 4, kk = (v & 15) * 8;
+        const size_t off = (size_t)min(row, M - 1) * ldb + kk;
+        bhp[u] = bh + off; blp[u] = bl + off;
+        bdst[u] = row * M6_PITCH + kk * 2;
+    }
+    u32x4_t ra[M6_D][2], rh[M6_D][2], rl[M6_D][2];
+    auto gload = [&](int slot, int ck) {
+        const int k0 = ck * M6_CK;
+#pragma unroll
+        for (int j = 0; j < 2; j++) ra[slot][j] = gv_load(ap + (size_t)(4 * j) * K + k0);
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            rh[slot][u] = *reinterpret_cast<const u32x4_t*>(bhp[u] + k0);
+            rl[slot][u] = *reinterpret_cast<const u32x4_t*>(blp[u] + k0);
+        }
+    };
+    auto stage = [&](int slot) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+            *reinterpret_cast<u32x4_t*>(As + (arow + 4 * j) * M6_PITCH + acol * 2) = ra[slot][j];
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            *reinterpret_cast<u32x4_t*>(Bh + bdst[u]) = rh[slot][u];
+            *reinterpret_cast<u32x4_t*>(Bl + bdst[u]) = rl[slot][u];
+        }
+        __syncthreads();
+    };
+    const int kq = wave & 3, nh = wave >> 2;             // k-step of the stripe, half of the weight rows
+    const int MT = (M + 15) >> 4;                        // live 16-row groups of activation rows
+    f32x4_t acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&]() {
+        const int off = kq * 64 + g * 16;
+        bf16x8_t a[2];
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+            a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(As + ((nh * 2 + i) * 16 + r16) * M6_PITCH + off));
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if (j < MT) {   // uniform
+                const bf16x8_t h = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bh + (j * 16 + r16) * M6_PITCH + off));
+                const bf16x8_t l = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bl + (j * 16 + r16) * M6_PITCH + off));
+#pragma unroll
+                for (int i = 0; i < 2; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], h, acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 2; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], l, acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+#pragma unroll
+    for (int sl = 0; sl < M6_D; sl++)
+        if (sl < NC) gload(sl, sl);
+    int ck0 = 0;
+    for (; ck0 + 2 * M6_D <= NC; ck0 += M6_D) {   // steady state: every step refills its slot
+#pragma unroll
+        for (int sl = 0; sl < M6_D; sl++) {
+            stage(sl);
+            gload(sl, ck0 + sl + M6_D);
+            multiply();
+        }
+    }
+    for (; ck0 < NC; ck0 += M6_D) {               // drain
+#pragma unroll
+        for (int sl = 0; sl < M6_D; sl++) {
+            if (ck0 + sl < NC) {
+                stage(sl);
+                if (ck0 + sl + M6_D < NC) gload(sl, ck0 + sl + M6_D);
+                multiply();
+            }
+        }
+    }
+    // Sum the four k-step partials of every output, one band of 16 activation rows at a time, through LDS:
+    // red[wave][i][256], element row * 16 + column of the D layout (lane (c = lane % 16, g) holds weight rows
+    // 4g .. 4g+3 of activation row c).
+    float* red = reinterpret_cast<float*>(sm6);   // 8 x 2 x 256 floats = 16 KB
+    for (int j = 0; j < MT; j++) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                float v;
+                switch (j) {  // acc is indexed by compile-time constants only
+                    case 0: v = acc[i][0][e]; break;
+                    case 1: v = acc[i][1][e]; break;
+                    case 2: v = acc[i][2][e]; break;
+                    default: v = acc[i][3][e]; break;
+                }
+                red[(wave * 2 + i) * 256 + (g * 4 + e) * 16 + r16] = v;
+            }
+        __syncthreads();
+        // 64 weight rows x 16 activation rows = 1024 outputs, two per thread; consecutive threads -> consecutive n
+        for (int o = tid; o < 1024; o += 512) {
+            const int nn = o & 63, c = o >> 6;     // weight row inside the tile, activation row inside the band
+            const int st = nn >> 4, hh = st >> 1, ii = st & 1;
+            float t = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; q++) t += red[((hh * 4 + q) * 2 + ii) * 256 + (nn & 15) * 16 + c];
+            const int m = j * 16 + c;
+            if (m < M) y[(size_t)m * ldy + n0 + nn] = t;
+        }
+    }
+}
+
+bool rows_many_supported(const Dims& D, int N, int K)
+{
+    return D.wt == WT_BF16 && N % 64 == 0 && K % M6_CK == 0 && K >= M6_CK;
+}
+
+static int g_many_depth = 1;  // tuning hook (1 measured best: three blocks per CU already overlap)
+void rows_many_depth(int d) { g_many_depth = d; }
+
+hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t* bh, const uint16_t* bl, int ldb, int M,
+                     float* y, int ldy, hipStream_t s)
+{
+    if (!rows_many_supported(D, N, K) || M < 1 || M > 64 || ldy % 4) return hipErrorInvalidValue;
+    const size_t lds = (size_t)3 * 64 * M6_PITCH;
+    static bool attr[4] = {false, false, false, false};
+    const int d = g_many_depth < 1 ? 1 : (g_many_depth > 3 ? 3 : g_many_depth);
+    const void* fn = d == 1 ? (const void*)rows_mfma64_kernel<1> : d == 2 ? (const void*)rows_mfma64_kernel<2>
+                                                                          : (const void*)rows_mfma64_kernel<3>;
+    if (!attr[d]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr[d] = true;
+    }
+    const dim3 grid(N / 64), block(512);
+    const uint16_t* wp = (const uint16_t*)w;
+    if (d == 1) hipLaunchKernelGGL((rows_mfma64_kernel<1>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy);
+    else if (d == 2) hipLaunchKernelGGL((rows_mfma64_kernel<2>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy);
+    else hipLaunchKernelGGL((rows_mfma64_kernel<3>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy);
+    return hipGetLastError();
+}
+
 bool rows_fused_supported(const Dims& D)
 {
     return D.wt == WT_BF16 && D.d % 64 == 0 && D.dq % 64 == 0 && D.f % 64 == 0;

@@ -80,6 +80,12 @@ WORKLOADS: Dict[str, Workload] = {
         "llama70b", ModelShape(80, 8192, 64, 8, 28672, 32000),
         seed=4, prompt_len=2048, new_tokens=128, k=4,
         note="grouped-query attention, ~138 GB of bf16 weights"),
+    # beyond the five benchmark configurations: the second model family of Section 4.1.1 (grouped heads,
+    # 128 256-entry vocabulary: a 1 GB LM head, so the confidence pass is four times dearer per row)
+    "llama3_8b": Workload(
+        "llama3_8b", ModelShape(32, 4096, 32, 8, 14336, 128256, rope_base=500000.0),
+        seed=5, prompt_len=512, new_tokens=128, k=4,
+        note="Llama-3-8B shape in bf16"),
 }
 
 _PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "wg", "wu", "wd")
