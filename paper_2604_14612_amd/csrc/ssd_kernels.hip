@@ -442,7 +442,12 @@ static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
     // prologue re-reads them per block, so it runs one block per CU.
     int cap = p.part ? 256 : 768;
     if (g_block_cap > 0) cap = g_block_cap;
-    if (blocks > cap) blocks = cap;
+    if (blocks > cap) {
+        // equal work per block: with r rounds needed, use just enough blocks for r full rounds (gate/up at 7B:
+        // 1376 block-rounds -> 688 blocks x 2 rather than 768 blocks of which 160 would do one round only)
+        const int rounds = ceil_div(blocks, cap);
+        blocks = ceil_div(blocks, rounds);
+    }
     hipLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, p);
     return hipGetLastError();
 }
