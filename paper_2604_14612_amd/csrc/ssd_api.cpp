@@ -160,6 +160,12 @@ int hip_fail(ssd_ctx* c, hipError_t e, const char* where)
         if (e__ != hipSuccess) return hip_fail(c, e__, where); \
     } while (0)
 
+// the single-launch GEMV kernels can time themselves (events bound to the kernel's own timestamps)
+static inline bool is_gemv_kid(int kid)
+{
+    return kid == SSD_K_GEMV_QKV || kid == SSD_K_GEMV_GATEUP || kid == SSD_K_GEMV_DOWN || kid == SSD_K_GEMV_LMHEAD;
+}
+
 // Launch `call`; when kernel `kid` is selected for timing, bracket it with a pair of events.
 #define TIMED(kid, call, where)                                                            \
     do {                                                                                   \
@@ -170,9 +176,14 @@ int hip_fail(ssd_ctx* c, hipError_t e, const char* where)
                 HIPCHK(hipEventCreate(&b__), "event create");                              \
                 c->prof_ev.emplace_back(a__, b__);                                         \
             }                                                                              \
-            HIPCHK(hipEventRecord(c->prof_ev[c->prof_used].first, c->stream), "event");    \
-            HIPCHK(call, where);                                                           \
-            HIPCHK(hipEventRecord(c->prof_ev[c->prof_used].second, c->stream), "event");   \
+            if (is_gemv_kid(kid)) {                                                        \
+                gemv_time_next_launch(c->prof_ev[c->prof_used].first, c->prof_ev[c->prof_used].second); \
+                HIPCHK(call, where);                                                       \
+            } else {                                                                       \
+                HIPCHK(hipEventRecord(c->prof_ev[c->prof_used].first, c->stream), "event"); \
+                HIPCHK(call, where);                                                       \
+                HIPCHK(hipEventRecord(c->prof_ev[c->prof_used].second, c->stream), "event"); \
+            }                                                                              \
             c->prof_used++;                                                                \
         } else {                                                                           \
             HIPCHK(call, where);                                                           \

@@ -42,6 +42,10 @@ hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const floa
 hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits,
                        hipStream_t s);
 
+// The next GEMV launch (any of the four below) records its own begin / end timestamps into the two events
+// (kernel time as a profiler reports it, without the dispatch latency a pair of stream events around the
+// launch would include).  One-shot.
+void gemv_time_next_launch(hipEvent_t start, hipEvent_t stop);
 void gemv_block_cap(int n);  // tuning hook: > 0 overrides the block cap of the GEMV launches
 
 // ---- multi-row (verify / prefill / confidence) path ------------------------------------------

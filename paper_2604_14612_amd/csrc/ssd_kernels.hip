@@ -10,6 +10,8 @@
 // Attention reads the cache through LDS-staged K/V tiles, split over the sequence.
 #include "ssd_kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include <math.h>
 
 namespace ssdk {
@@ -421,6 +423,9 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
     }
 }
 
+static hipEvent_t g_gemv_ev_start = nullptr, g_gemv_ev_stop = nullptr;
+void gemv_time_next_launch(hipEvent_t start, hipEvent_t stop) { g_gemv_ev_start = start; g_gemv_ev_stop = stop; }
+
 static int g_block_cap = 0;  // tuning hook (kernel_bench): > 0 overrides the block cap
 void gemv_block_cap(int n) { g_block_cap = n; }
 
@@ -448,7 +453,15 @@ static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
         const int rounds = ceil_div(blocks, cap);
         blocks = ceil_div(blocks, rounds);
     }
-    hipLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, p);
+    if (g_gemv_ev_start) {
+        // timing request for this one launch: the events take the kernel's own begin and end timestamps
+        hipExtLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, g_gemv_ev_start,
+                              g_gemv_ev_stop, 0, p);
+        g_gemv_ev_start = nullptr;
+        g_gemv_ev_stop = nullptr;
+    } else {
+        hipLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, p);
+    }
     return hipGetLastError();
 }
 
