@@ -41,6 +41,8 @@ def _load():
                                     C.c_void_p, C.c_void_p, C.c_void_p]
         lib.orc_round_bf16.restype = C.c_double
         lib.orc_round_bf16.argtypes = [C.c_double]
+        lib.orc_round_fp16.restype = C.c_double
+        lib.orc_round_fp16.argtypes = [C.c_double]
         lib.orc_argmax.restype = C.c_int32
         lib.orc_argmax.argtypes = [C.c_void_p, C.c_int]
         lib.orc_confidence_from_logits.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_double,
@@ -52,12 +54,12 @@ def _load():
 
 
 def _as_numpy(t):
-    """torch tensor (fp32 or bf16, CPU) or ndarray -> contiguous ndarray; bf16 becomes raw uint16."""
+    """torch tensor (fp32, bf16 or fp16, CPU) or ndarray -> contiguous ndarray; half types become raw uint16."""
     if isinstance(t, np.ndarray):
         return np.ascontiguousarray(t)
     import torch
     t = t.detach().cpu().contiguous()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16)
     return t.numpy()
 
@@ -77,7 +79,7 @@ class OracleModel:
         lib = _load()
         self.shape = shape
         self.max_seq = int(max_seq)
-        wt = 1 if shape.dtype == "bf16" else 0
+        wt = {"fp32": 0, "bf16": 1, "fp16": 2}[shape.dtype]
         self._keep = []
 
         def mat(t):
@@ -171,6 +173,11 @@ class OracleModel:
 def round_bf16(x: float) -> float:
     """The value a bf16 K/V cache entry holds for x: fp32 then bf16, round-to-nearest-even."""
     return float(_load().orc_round_bf16(float(x)))
+
+
+def round_fp16(x: float) -> float:
+    """The value an fp16 K/V cache entry holds for x: fp32 then fp16, round-to-nearest-even."""
+    return float(_load().orc_round_fp16(float(x)))
 
 
 def argmax_lowest(z: np.ndarray) -> int:

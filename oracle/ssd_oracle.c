@@ -18,12 +18,12 @@
  *
  * All arithmetic is IEEE double, sums run left to right over the reduction index,
  * compiled with -ffp-contract=off so no fused multiply-add changes a rounding.
- * Matrices are row-major [out][in]; weights arrive as fp32 or as raw bf16 bit patterns
+ * Matrices are row-major [out][in]; weights arrive as fp32 or as raw bf16 / fp16 bit patterns
  * (uint16) and are widened exactly.
  *
  * Storage precision: the evaluated models are held in half precision (Section 4.1.1), so the
  * K/V cache of such a model holds half-precision numbers.  The cache therefore stores each K
- * (after the rotary embedding) and V element rounded to the weight storage type -- bf16 or
+ * (after the rotary embedding) and V element rounded to the weight storage type -- bf16, fp16 or
  * fp32, round-to-nearest-even, via an fp32 intermediate as a half-precision tensor is produced
  * from fp32 compute -- and attention reads those stored values, for the rows of the current
  * block too.  Everything else stays in double.
@@ -36,7 +36,7 @@
 typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, max_seq;
     double rms_eps, rope_base;
-    int32_t weight_dtype; /* 0 = float32, 1 = bf16 stored as uint16 */
+    int32_t weight_dtype; /* 0 = float32, 1 = bf16 stored as uint16, 2 = IEEE fp16 stored as uint16 */
 } orc_config;
 
 typedef struct {
@@ -56,6 +56,36 @@ static double widen_bf16(uint16_t h)
     return (double)f;
 }
 
+/* IEEE binary16 bit pattern -> double (exact): 1 sign, 5 exponent (bias 15), 10 fraction bits */
+static double widen_fp16(uint16_t h)
+{
+    int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 0) v = ldexp((double)f, -24);                     /* zero and subnormals: f * 2^-24 */
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexp((double)(1024 + f), e - 25);               /* (1 + f/1024) * 2^(e-15) */
+    return sign ? -v : v;
+}
+
+/* x rounded to fp32 and then to fp16 (round-to-nearest-even both times), returned as a double.
+ * The fp16 step rounds the fp32 value on the fp16 grid: spacing 2^(e-10) for |x| in [2^e, 2^(e+1)),
+ * e >= -14, and 2^-24 below 2^-14; values that round to 65520 or more become infinity. */
+double orc_round_fp16(double x)
+{
+    float f = (float)x;
+    if (!(f == f) || f == INFINITY || f == -INFINITY) return (double)f;
+    double a = fabs((double)f);
+    if (a == 0.0) return (double)f;
+    int e;
+    (void)frexp(a, &e);              /* a = m * 2^e, m in [0.5, 1): a in [2^(e-1), 2^e) */
+    int ex = e - 1;
+    if (ex < -14) ex = -14;
+    double q = ldexp(1.0, ex - 10);  /* grid spacing */
+    double r = nearbyint(a / q) * q; /* a / q is exact (power of two), nearbyint rounds half to even */
+    if (r >= 65520.0) r = INFINITY;
+    return f < 0 ? -r : r;
+}
+
 /* x rounded to fp32 and then to bf16 (round-to-nearest-even both times), returned as a double */
 double orc_round_bf16(double x)
 {
@@ -69,7 +99,10 @@ double orc_round_bf16(double x)
     return (double)f;
 }
 
-static double round_storage(double x, int dtype) { return dtype == 0 ? (double)(float)x : orc_round_bf16(x); }
+static double round_storage(double x, int dtype)
+{
+    return dtype == 0 ? (double)(float)x : dtype == 1 ? orc_round_bf16(x) : orc_round_fp16(x);
+}
 
 /* Y[r][n] = sum_k W[n][k] * X[r][k]   (W: N x K row-major, X: R x K, Y: R x N) */
 static void matmul_wt(const void *W, int dtype, int N, int K, const double *X, int R, double *Y)
@@ -82,9 +115,12 @@ static void matmul_wt(const void *W, int dtype, int N, int K, const double *X, i
             if (dtype == 0) {
                 const float *w = (const float *)W + (size_t)n * K;
                 for (int k = 0; k < K; k++) acc += (double)w[k] * x[k];
-            } else {
+            } else if (dtype == 1) {
                 const uint16_t *w = (const uint16_t *)W + (size_t)n * K;
                 for (int k = 0; k < K; k++) acc += widen_bf16(w[k]) * x[k];
+            } else {
+                const uint16_t *w = (const uint16_t *)W + (size_t)n * K;
+                for (int k = 0; k < K; k++) acc += widen_fp16(w[k]) * x[k];
             }
             Y[(size_t)r * N + n] = acc;
         }
@@ -195,8 +231,9 @@ int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint
     for (int r = 0; r < R; r++)
         for (int i = 0; i < d; i++) {
             size_t o = (size_t)tokens[r] * d + i;
-            x[(size_t)r * d + i] = wt == 0 ? (double)((const float *)m->embed)[o]
-                                           : widen_bf16(((const uint16_t *)m->embed)[o]);
+            x[(size_t)r * d + i] = wt == 0   ? (double)((const float *)m->embed)[o]
+                                   : wt == 1 ? widen_bf16(((const uint16_t *)m->embed)[o])
+                                             : widen_fp16(((const uint16_t *)m->embed)[o]);
         }
 
     for (int l = 0; l < L; l++) {

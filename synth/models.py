@@ -24,7 +24,7 @@ class ModelShape:
     n_kv_heads: int
     d_ffn: int
     vocab: int
-    dtype: str = "bf16"          # weight storage: "bf16" or "fp32"
+    dtype: str = "bf16"          # weight storage: "bf16", "fp16" or "fp32"
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     init_depth: int = 0          # depth the residual-projection init is scaled for (0 = n_layers)
@@ -42,7 +42,7 @@ class ModelShape:
         return 2 * d * d + 2 * d * self.d_kv + 3 * d * f + 2 * d
 
     def bytes_per_weight(self) -> int:
-        return 2 if self.dtype == "bf16" else 4
+        return 4 if self.dtype == "fp32" else 2
 
 
 @dataclass(frozen=True)
@@ -123,11 +123,11 @@ def make_weights(shape: ModelShape, seed: int, device: str = "cpu",
     All matrices are row-major [out_features][in_features] and ~N(0, init_std); the two
     projections that write into the residual stream (wo, wd) are scaled by 1/sqrt(2*depth), depth = init_depth or n_layers.
     Norm gains are 1 (+ norm_gain_std * N(0,1) when a test wants them non-trivial).
-    bf16 models are rounded to bf16 once (round-to-nearest-even) and that rounded tensor is
+    bf16 / fp16 models are rounded to their type once (round-to-nearest-even) and that rounded tensor is
     what every consumer sees.  The stream differs between CPU and GPU generators: move the
     returned tensors, do not regenerate them on the other device.
     """
-    dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    dt = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[shape.dtype]
     L, d, f, V = shape.n_layers, shape.d_model, shape.d_ffn, shape.vocab
     dq, dkv = shape.n_heads * shape.head_dim, shape.d_kv
     res_std = init_std / math.sqrt(2.0 * (shape.init_depth or L))

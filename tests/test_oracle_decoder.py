@@ -20,7 +20,7 @@ def torch_reference_logits(shape, w, tokens):
     """Full-sequence recompute with library ops, float64; K and V pass through the model's storage type
     (the half-precision cache of Section 4.1.1) by the library's own casts. Returns logits [T][V]."""
     dd = torch.float64
-    st = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    st = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[shape.dtype]
     T = len(tokens)
     H, Hkv, hd = shape.n_heads, shape.n_kv_heads, shape.head_dim
     x = F.embedding(torch.tensor(tokens, dtype=torch.long), w["embed"].to(dd))
@@ -53,6 +53,7 @@ SHAPES = [
     ModelShape(3, 64, 4, 4, 96, 50, dtype="fp32"),
     ModelShape(2, 96, 6, 2, 160, 77, dtype="fp32", rope_base=500.0, rms_eps=1e-3),   # GQA 3:1
     ModelShape(2, 64, 2, 1, 88, 40, dtype="bf16"),                                    # MQA, bf16 storage
+    ModelShape(2, 64, 4, 2, 72, 48, dtype="fp16"),                                    # GQA, fp16 storage
 ]
 
 
@@ -91,15 +92,25 @@ def test_cache_rounding_is_the_library_cast_and_is_applied():
     got = np.array([round_bf16(v) for v in x.tolist()])
     assert np.array_equal(got, ref)
     assert round_bf16(1.0 + 2.0 ** -8) == 1.0 and round_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6   # ties to even
-    shape = SHAPES[2]
-    w = make_weights(shape, 11, norm_gain_std=0.2, init_std=0.3)
-    toks = make_prompt(shape.vocab, 9, 5).tolist()
-    m = OracleModel(shape, w, 16)
-    m.forward(toks, 0)
-    for c in (m.kcache(), m.vcache()):
-        c = np.asarray(c).reshape(shape.n_layers, 16, -1)[:, :9]
-        assert np.array_equal(c, torch.from_numpy(c.copy()).to(torch.bfloat16).to(torch.float64).numpy())
-        assert np.abs(c).max() > 0.1
+    # fp16: random values across the normal and subnormal range, ties, overflow to infinity
+    from oracle import round_fp16
+    xh = torch.cat([torch.randn(4000, generator=g, dtype=torch.float64) * torch.logspace(-9, 5, 4000, dtype=torch.float64),
+                    torch.tensor([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -(1.0 + 2.0 ** -11), 2.0 ** -24, 2.0 ** -25,
+                                  3 * 2.0 ** -25, 65504.0, 65519.9, 65520.0, 1e6, 0.0, 2.0 ** -14 - 2.0 ** -26],
+                                 dtype=torch.float64)])
+    refh = xh.to(torch.float32).to(torch.float16).to(torch.float64).numpy()
+    goth = np.array([round_fp16(v) for v in xh.tolist()])
+    assert np.array_equal(goth, refh)
+    assert round_fp16(1.0 + 2.0 ** -11) == 1.0 and round_fp16(65520.0) == np.inf and round_fp16(2.0 ** -25) == 0.0
+    for shape, st in ((SHAPES[2], torch.bfloat16), (SHAPES[3], torch.float16)):
+        w = make_weights(shape, 11, norm_gain_std=0.2, init_std=0.3)
+        toks = make_prompt(shape.vocab, 9, 5).tolist()
+        m = OracleModel(shape, w, 16)
+        m.forward(toks, 0)
+        for c in (m.kcache(), m.vcache()):
+            c = np.asarray(c).reshape(shape.n_layers, 16, -1)[:, :9]
+            assert np.array_equal(c, torch.from_numpy(c.copy()).to(st).to(torch.float64).numpy())
+            assert np.abs(c).max() > 0.1
     # an fp32 model's cache holds fp32-representable numbers
     m32 = OracleModel(SHAPES[0], make_weights(SHAPES[0], 1, init_std=0.3), 16)
     m32.forward(toks[:5], 0)
