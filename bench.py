@@ -183,7 +183,7 @@ def main():
         "metric": "decode tokens/s batch 1, SSD vs vanilla, 7B-shape bf16; achieved HBM GB/s",
         "value": ssd_tps, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": t_ssd / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": {"bf16": "bf16", "fp16": "f16", "fp32": "f32"}[shape.dtype], "data": "synthetic",
         "config": {"workload": "%s: %d layers, d_model %d, %d/%d heads, FFN %d, vocab %d, prompt %d, k=%d, "
                                "ConfLayers search active (interval 30), random-init weights"
                                % (wl.name, L, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_ffn,
@@ -202,7 +202,7 @@ def main():
                    "frac_of_hbm_peak": verify_gbps / HBM_PEAK_GBPS},
         "confidence_and_search_ms_per_cycle": timing["other_s"] / K * 1e3,
         "hbm_read_probe_GBps": probe_gbps,
-        "roofline": {"bound": "hbm", "kernel": "gemv_kernel<bf16, SWIGLU> (draft gate/up GEMV)",
+        "roofline": {"bound": "hbm", "kernel": "gemv_kernel<%s, SWIGLU> (draft gate/up GEMV)" % shape.dtype,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if args.layers is None else None, "avg_launch_us": kern_ms * 1e3, "launches_timed": n_launch,
                      "algorithmic_bytes_per_launch": kern_bytes},

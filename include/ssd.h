@@ -52,7 +52,8 @@ typedef struct ssd_ctx ssd_ctx;
 typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, max_seq;
     float rms_eps, rope_base;
-    int32_t weight_dtype; /* 0 = fp32 weights and fp32 KV cache, 1 = bf16 weights and bf16 KV cache */
+    int32_t weight_dtype; /* 0 = fp32, 1 = bf16, 2 = fp16 (the precision of Section 4.1.1): element type of the
+                             weight matrices and of the KV cache */
     int32_t conf_taps;    /* 2: confidence of a layer = mean over its post-attention and post-MLP hidden
                              states (Section 3.1: "FFNN and Attention" hidden states); 1: post-MLP only */
     float conf_clamp;     /* logits are clamped to [-conf_clamp, conf_clamp] before Eq. 1 */

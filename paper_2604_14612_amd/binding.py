@@ -213,7 +213,7 @@ def make_config(shape, max_seq: int, max_k: int = 8, conf_taps: int = 2, conf_cl
                 conf_eps: float = 1e-10) -> ssd_config:
     return ssd_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                       shape.d_ffn, shape.vocab, int(max_seq), shape.rms_eps, shape.rope_base,
-                      1 if shape.dtype == "bf16" else 0, conf_taps, conf_clamp, conf_eps, max_k)
+                      {"fp32": 0, "bf16": 1, "fp16": 2}[shape.dtype], conf_taps, conf_clamp, conf_eps, max_k)
 
 
 class Context:
@@ -239,7 +239,7 @@ class Context:
         self._check(self._l.ssd_set_workspace(self._h, C.c_void_p(self.workspace.data_ptr()), nbytes))
         self._weights = weights   # keep tensors alive
         L = shape.n_layers
-        exp_dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        exp_dt = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[shape.dtype]
 
         def dp(t, dt):
             assert t.is_cuda and t.is_contiguous() and t.dtype == dt, (t.device, t.dtype)

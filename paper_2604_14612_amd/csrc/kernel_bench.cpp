@@ -161,7 +161,7 @@ int main(int argc, char** argv)
         CK(rows_fused(D, f, 0));
     };
     {
-    timeit("rows_prep (norm+split)", M * 4096 * 8.0, n, [&](int) { CK(rows_prep(x, 4096, gain, M, 4096, 1e-5f, hi, lo, 0)); });
+    timeit("rows_prep (norm+split)", M * 4096 * 8.0, n, [&](int) { CK(rows_prep(D, x, 4096, gain, M, 4096, 1e-5f, hi, lo, 0)); });
     timeit("rows_qkv", 3 * qk * 2.0, n, [&](int i) {
         const uint16_t* w = W + (size_t)i * 3 * qk;
         fused(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, q, 4096); });

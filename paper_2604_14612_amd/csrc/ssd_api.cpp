@@ -40,7 +40,7 @@ bool valid_cfg(const ssd_config* c)
     if (c->n_heads % c->n_kv_heads) return false;
     long dq = (long)c->n_heads * c->head_dim, dkv = (long)c->n_kv_heads * c->head_dim;
     if (c->d_model % 16 || c->d_ffn % 16 || dq % 16 || dkv % 16 || c->vocab % 16) return false;
-    if (c->weight_dtype != 0 && c->weight_dtype != 1) return false;
+    if (c->weight_dtype < 0 || c->weight_dtype > 2) return false;
     if (c->conf_taps != 1 && c->conf_taps != 2) return false;
     if (c->max_k < 1 || c->max_k > SSD_MAX_K) return false;
     if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f) || !(c->conf_clamp > 0.f) || !(c->conf_eps >= 0.f)) return false;
@@ -60,7 +60,7 @@ Layout make_layout(const ssd_config& c)
 {
     Dims D = make_dims(c);
     Layout l;
-    size_t esz = c.weight_dtype == 1 ? 2 : 4;
+    size_t esz = c.weight_dtype == 0 ? 4 : 2;
     l.rows = c.max_k + 1 > SSD_PREFILL_ROWS ? c.max_k + 1 : SSD_PREFILL_ROWS;
     l.conf_rows = 2 * c.n_layers;
     l.logit_rows = l.rows > l.conf_rows ? l.rows : l.conf_rows;
@@ -130,12 +130,12 @@ struct ssd_ctx {
     int* pos_dev() const { return small_i() + SM_POS; }
     void* kcache(int l) const
     {
-        size_t esz = cfg.weight_dtype == 1 ? 2 : 4;
+        size_t esz = cfg.weight_dtype == 0 ? 4 : 2;
         return ws + lay.kv + ((size_t)l * 2 + 0) * lay.kv_layer_elems * esz;
     }
     void* vcache(int l) const
     {
-        size_t esz = cfg.weight_dtype == 1 ? 2 : 4;
+        size_t esz = cfg.weight_dtype == 0 ? 4 : 2;
         return ws + lay.kv + ((size_t)l * 2 + 1) * lay.kv_layer_elems * esz;
     }
 };
@@ -251,7 +251,7 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
         uint16_t* xl = xh + (size_t)Y.rows * D.d;
         float* ssq = c->f(Y.ssq);
         const int n_ssq = D.d / 16;
-        HIPCHK(rows_gain_split(x, D.d, c->attn_norm[0], M, D.d, xh, xl, ssq, c->stream), "rows_gain_split");
+        HIPCHK(rows_gain_split(D, x, D.d, c->attn_norm[0], M, D.d, xh, xl, ssq, c->stream), "rows_gain_split");
         for (int l = 0; l < D.L; l++) {
             RowsFused q = {};
             q.w[0] = c->wq[l]; q.w[1] = c->wk[l]; q.w[2] = c->wv[l]; q.n[0] = D.dq; q.n[1] = D.dkv; q.n[2] = D.dkv;
@@ -708,7 +708,7 @@ int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out,
     for (int r = 0; r < n_rows; r++) {
         const float* taps = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
         if (rows_fused_supported(D)) {
-            HIPCHK(rows_prep(taps, D.d, c->w.final_norm, R, D.d, D.eps, c->h16(Y.hi), c->h16(Y.lo), c->stream), "rows_prep taps");
+            HIPCHK(rows_prep(D, taps, D.d, c->w.final_norm, R, D.d, D.eps, c->h16(Y.hi), c->h16(Y.lo), c->stream), "rows_prep taps");
             const bool many = rows_many_supported(D, D.V, D.d);
             for (int b = 0; many && b < R; b += 64) {   // the LM head is streamed once per 64 tap rows
                 TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, c->h16(Y.hi) + (size_t)b * D.d,

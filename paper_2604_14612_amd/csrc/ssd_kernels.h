@@ -7,13 +7,13 @@
 
 namespace ssdk {
 
-enum WeightType { WT_F32 = 0, WT_BF16 = 1 };
+enum WeightType { WT_F32 = 0, WT_BF16 = 1, WT_F16 = 2 };
 
 // Shape constants shared by all launches of one context.
 struct Dims {
     int L, d, H, Hkv, hd, dq, dkv, f, V, max_seq;
     float eps;
-    int wt;  // WeightType; the KV cache uses the same element type
+    int wt;  // WeightType; the KV cache and the hi/lo activation pairs use the same element type
 };
 
 // x[r][:] = embed[tok_dev[r]][:] widened to fp32 (token ids in device memory, clamped to the vocabulary).
@@ -68,8 +68,8 @@ struct RowsGemm {
     int mode;
 };
 hipError_t gemm_rows(const Dims& D, const RowsGemm& g, hipStream_t s);
-// Multi-row MFMA GEMM for bf16 weights with K a multiple of 64.  Activations come pre-split into
-// bf16 hi/lo arrays [M][ldb] (rows_prep, rows_gain_split, attention with out_hi/out_lo, the SwiGLU mode
+// Multi-row MFMA GEMM for bf16 / fp16 weights with K a multiple of 64.  Activations come pre-split into
+// hi/lo arrays of the same 16-bit type [M][ldb] (rows_prep, rows_gain_split, attention with out_hi/out_lo, the SwiGLU mode
 // or a RESID projection with gain_out).
 //   mode 0 store fp32, 1 residual add into y (+ tap), 2 SwiGLU of two matrices written as hi/lo to
 //   oh/ol, 3 QKV: rotary on q and k at positions *pos_dev + pos_off + r, q -> y [M][dq] fp32,
@@ -105,12 +105,12 @@ hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t*
 void rows_many_depth(int d);  // tuning hook: stripes in flight (1..3)
 // hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
 // gain first when gain != nullptr
-hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi, uint16_t* lo,
-                     hipStream_t s);
+hipError_t rows_prep(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi,
+                     uint16_t* lo, hipStream_t s);
 // hi/lo = split(in * gain) (no norm scale) and ssq[r][t] = sum of in[r][16t..16t+16)^2: the form in which a
 // RESID projection with gain_out hands rows to its consumer
-hipError_t rows_gain_split(const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo, float* ssq,
-                           hipStream_t s);
+hipError_t rows_gain_split(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo,
+                           float* ssq, hipStream_t s);
 // rotary on q,k rows + cache write for the multi-row path. qkv: [M][dq + 2 dkv]; q is rotated in place.
 hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int* pos_dev, int pos_off, int M,
                         void* kcache_l, void* vcache_l, hipStream_t s);

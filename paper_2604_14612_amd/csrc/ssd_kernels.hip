@@ -59,6 +59,34 @@ template <> struct Elem<uint16_t> {
     __device__ static __forceinline__ void put(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
 };
 
+typedef _Float16 f16_t;   // IEEE binary16 storage (weights and cache of fp16 models)
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+template <> struct Elem<f16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ void load(const f16_t* p, float (&o)[8])
+    {
+        const f16x8_t v = *reinterpret_cast<const f16x8_t*>(p);
+#pragma unroll
+        for (int i = 0; i < 8; i++) o[i] = (float)v[i];
+    }
+    __device__ static __forceinline__ float get(const f16_t* p, size_t i) { return (float)p[i]; }
+    __device__ static __forceinline__ void put(f16_t* p, size_t i, float v) { p[i] = (f16_t)v; }  // round to nearest even
+};
+template <typename T> struct IsF16 { static constexpr bool value = false; };
+template <> struct IsF16<f16_t> { static constexpr bool value = true; };
+
+// one 16-bit storage element (bf16 or fp16 bit pattern) from an fp32 value
+__device__ __forceinline__ uint16_t f32_to_h16_bits(float v, bool f16)
+{
+    if (f16) return __builtin_bit_cast(uint16_t, (f16_t)v);
+    return f32_to_bf16_bits(v);
+}
+__device__ __forceinline__ float h16_bits_to_f32(uint16_t h, bool f16)
+{
+    if (f16) return (float)__builtin_bit_cast(f16_t, h);
+    return bf16_bits_to_f32(h);
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -108,6 +136,8 @@ hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok_dev, 
     dim3 grid(ceil_div(D.d, 256), M);
     if (D.wt == WT_BF16)
         hipLaunchKernelGGL(embed_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)embed, tok_dev, D.d, D.V, x);
+    else if (D.wt == WT_F16)
+        hipLaunchKernelGGL(embed_kernel<f16_t>, grid, dim3(256), 0, s, (const f16_t*)embed, tok_dev, D.d, D.V, x);
     else
         hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, s, (const float*)embed, tok_dev, D.d, D.V, x);
     return hipGetLastError();
@@ -178,6 +208,16 @@ template <> __device__ __forceinline__ float gv_dot<uint16_t>(u32x4_t w, const f
     acc = fmaf(__uint_as_float(w.z & 0xffff0000u), b.y, acc);
     acc = fmaf(__uint_as_float(w.w << 16), b.z, acc);
     acc = fmaf(__uint_as_float(w.w & 0xffff0000u), b.w, acc);
+    return acc;
+}
+template <> __device__ __forceinline__ float gv_dot<f16_t>(u32x4_t w, const float* xs, float acc)
+{
+    const f16x8_t h = __builtin_bit_cast(f16x8_t, w);
+    float4 a = *reinterpret_cast<const float4*>(xs), b = *reinterpret_cast<const float4*>(xs + 4);
+    acc = fmaf((float)h[0], a.x, acc); acc = fmaf((float)h[1], a.y, acc);
+    acc = fmaf((float)h[2], a.z, acc); acc = fmaf((float)h[3], a.w, acc);
+    acc = fmaf((float)h[4], b.x, acc); acc = fmaf((float)h[5], b.y, acc);
+    acc = fmaf((float)h[6], b.z, acc); acc = fmaf((float)h[7], b.w, acc);
     return acc;
 }
 template <> __device__ __forceinline__ float gv_dot<float>(u32x4_t w, const float* xs, float acc)
@@ -480,7 +520,9 @@ static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s)
 template <int EPI>
 static hipError_t launch_gemv(int wt, const GemvP& p, hipStream_t s)
 {
-    return wt == WT_BF16 ? launch_gemv_t<uint16_t, EPI>(p, s) : launch_gemv_t<float, EPI>(p, s);
+    if (wt == WT_BF16) return launch_gemv_t<uint16_t, EPI>(p, s);
+    if (wt == WT_F16) return launch_gemv_t<f16_t, EPI>(p, s);
+    return launch_gemv_t<float, EPI>(p, s);
 }
 
 hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* wv, const float* gain, const float* x,
@@ -754,7 +796,8 @@ static hipError_t gemm_rows_mode(const Dims& D, const RowsP& p, hipStream_t s)
         int units = MODE == RM_SWIGLU ? n_out / 2 : n_out / 4;
         int blocks = ceil_div(units, 4);
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL((gemm_rows_fma_kernel<float, MODE>), dim3(blocks), dim3(256), 0, s, p);
+        if (D.wt == WT_F16) hipLaunchKernelGGL((gemm_rows_fma_kernel<f16_t, MODE>), dim3(blocks), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((gemm_rows_fma_kernel<float, MODE>), dim3(blocks), dim3(256), 0, s, p);
     }
     return hipGetLastError();
 }
@@ -802,11 +845,18 @@ struct RowsP2 {
     const float* gain_out; float* ssq_out;      // RESID producer: gain of the next norm -> oh/ol = split(x * gain), ssq_out [M][n/16]
 };
 
-__device__ __forceinline__ void split_store(float v, uint16_t* hi, uint16_t* lo, size_t i)
+// hi = rne(v), lo = rne(v - hi) in the 16-bit storage type (bf16, or fp16 when f16 is set)
+__device__ __forceinline__ void split_store(float v, uint16_t* hi, uint16_t* lo, size_t i, bool f16)
 {
-    const uint16_t h = f32_to_bf16_bits(v);
+    const uint16_t h = f32_to_h16_bits(v, f16);
     hi[i] = h;
-    lo[i] = f32_to_bf16_bits(v - bf16_bits_to_f32(h));
+    lo[i] = f32_to_h16_bits(v - h16_bits_to_f32(h, f16), f16);
+}
+// 16x16x32 MFMA on two 128-bit operands holding 8 bf16 (or fp16) each
+template <bool F16> __device__ __forceinline__ f32x4_t mfma_h16(u32x4_t a, u32x4_t b, f32x4_t c)
+{
+    if (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
 // weight row of logical row r16 of tile `tile`
@@ -849,7 +899,7 @@ __device__ __forceinline__ float row16_sum(float v)
 // Final step of a tile: sum the KS per-wave partial tiles held in LDS (layout [wave][NT][256], element
 // row*16 + column) and apply the mode's epilogue.  Executed by the whole block (it contains barriers in QKV mode).
 // rs: per-column (= activation row) RMS scale in LDS, 1 where no norm applies.
-template <int MODE>
+template <int MODE, bool F16>
 __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float* red, int KS, int ts, float* fin,
                                             const float* rs)
 {
@@ -880,10 +930,10 @@ __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float*
                 const float o = rr < 8 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
                 const int e = rr < 8 ? i : i + half;
                 if (is_q) p.y[(size_t)c * p.ldy + (size_t)head * p.hd + e] = o;
-                else Elem<uint16_t>::put((uint16_t*)p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, o);
+                else ((uint16_t*)p.kc)[((size_t)head * p.max_seq + pos) * p.hd + e] = f32_to_h16_bits(o, F16);
             } else {
                 const int e = (t - tq - tk) * 16 + rr;
-                Elem<uint16_t>::put((uint16_t*)p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v);
+                ((uint16_t*)p.vc)[((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd)] = f32_to_h16_bits(v, F16);
             }
         } else {
             const size_t colx = (size_t)t * 16 + rr;
@@ -894,12 +944,12 @@ __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float*
                 *dst = tv;
                 if (p.tap) p.tap[(size_t)c * p.tap_ld + colx] = tv;
                 if (p.gain_out) {
-                    split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)c * p.ldo + colx);
+                    split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)c * p.ldo + colx, F16);
                     // the 16 threads of one column are the 16 lanes of a DPP row, all active together
                     const float sq = row16_sum(tv * tv);
                     if (rr == 0) p.ssq_out[(size_t)c * (p.n[0] >> 4) + t] = sq;
                 }
-            } else split_store(v / (1.0f + __expf(-v)) * v2, p.oh, p.ol, (size_t)c * p.ldo + colx);
+            } else split_store(v / (1.0f + __expf(-v)) * v2, p.oh, p.ol, (size_t)c * p.ldo + colx, F16);
         }
     }
     if (MODE == RM_QKV) __syncthreads();
@@ -914,7 +964,7 @@ __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float*
 constexpr int M3_CK = 512;
 constexpr int M3_PITCH = M3_CK * 2 + 16;  // bytes per LDS row (16-byte pad spreads the banks)
 
-template <int MODE, int M3_D>  // M3_D = stripes in flight per block
+template <int MODE, int M3_D, bool F16>  // M3_D = stripes in flight per block; F16: fp16 storage, else bf16
 __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
@@ -983,13 +1033,13 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
         const int nks = min(M3_CK / 32, (K - ck * M3_CK) / 32);
         for (int s = wave; s < nks; s += 8) {
             const int off = s * 64 + g * 16;
-            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bh + bc * M3_PITCH + off));
-            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bl + bc * M3_PITCH + off));
+            const u32x4_t bh = *reinterpret_cast<const u32x4_t*>(Bh + bc * M3_PITCH + off);
+            const u32x4_t bl = *reinterpret_cast<const u32x4_t*>(Bl + bc * M3_PITCH + off);
 #pragma unroll
             for (int t = 0; t < NT; t++) {
-                const bf16x8_t w = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(As + (t * 16 + r16) * M3_PITCH + off));
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, bh, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, bl, acc[t], 0, 0, 0);
+                const u32x4_t w = *reinterpret_cast<const u32x4_t*>(As + (t * 16 + r16) * M3_PITCH + off);
+                acc[t] = mfma_h16<F16>(w, bh, acc[t]);
+                acc[t] = mfma_h16<F16>(w, bl, acc[t]);
             }
         }
     };
@@ -1033,39 +1083,39 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 #pragma unroll
         for (int j = 0; j < 4; j++) red[(wave * NT + t) * 256 + (g * 4 + j) * 16 + r16] = acc[t][j];
     __syncthreads();
-    m2_epilogue<MODE>(p, tile, red, 8, 0, fin, rs);
+    m2_epilogue<MODE, F16>(p, tile, red, 8, 0, fin, rs);
 }
 
-template <int MODE, int DEPTH>
+template <int MODE, int DEPTH, bool F16>
 static hipError_t launch_mfma3(const RowsP2& p, int n_tiles, hipStream_t s)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     const size_t lds = (size_t)(NT * 16 + 2 * p.M) * M3_PITCH;
     static size_t lds_limit = 0;  // per instantiation
     if (lds > 64 * 1024 && lds > lds_limit) {
-        hipError_t e = hipFuncSetAttribute((const void*)rows_mfma3_kernel<MODE, DEPTH>,
+        hipError_t e = hipFuncSetAttribute((const void*)rows_mfma3_kernel<MODE, DEPTH, F16>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         lds_limit = lds;
     }
-    hipLaunchKernelGGL((rows_mfma3_kernel<MODE, DEPTH>), dim3(n_tiles), dim3(512), lds, s, p);
+    hipLaunchKernelGGL((rows_mfma3_kernel<MODE, DEPTH, F16>), dim3(n_tiles), dim3(512), lds, s, p);
     return hipGetLastError();
 }
 
 static int g_rows_depth = 0;  // tuning hook (kernel_bench): > 0 forces the number of stripes in flight
 void rows_fused_depth(int d) { g_rows_depth = d; }
 
-template <int MODE>
+template <int MODE, bool F16>
 static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
 {
     const int n_tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
     // few tiles -> few blocks per CU -> each block keeps more stripes in flight
     const int depth = g_rows_depth > 0 ? g_rows_depth : (n_tiles <= 512 ? 3 : (MODE == RM_SWIGLU ? 2 : 1));
     switch (depth) {
-        case 1: return launch_mfma3<MODE, 1>(p, n_tiles, s);
-        case 2: return launch_mfma3<MODE, 2>(p, n_tiles, s);
-        case 3: return launch_mfma3<MODE, 3>(p, n_tiles, s);
-        default: return launch_mfma3<MODE, 4>(p, n_tiles, s);
+        case 1: return launch_mfma3<MODE, 1, F16>(p, n_tiles, s);
+        case 2: return launch_mfma3<MODE, 2, F16>(p, n_tiles, s);
+        case 3: return launch_mfma3<MODE, 3, F16>(p, n_tiles, s);
+        default: return launch_mfma3<MODE, 4, F16>(p, n_tiles, s);
     }
 }
 
@@ -1080,7 +1130,7 @@ static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
 constexpr int M6_CK = 128;
 constexpr int M6_PITCH = M6_CK * 2 + 16;
 
-template <int M6_D>
+template <int M6_D, bool F16>
 __global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __restrict__ w, int K,
                                                           const uint16_t* __restrict__ bh, const uint16_t* __restrict__ bl,
                                                           int ldb, int M, float* __restrict__ y, int ldy)
@@ -1139,19 +1189,20 @@ __global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __rest
         for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     auto multiply = [&]() {
         const int off = kq * 64 + g * 16;
-        bf16x8_t a[2];
+        u32x4_t a[2];
 #pragma unroll
         for (int i = 0; i < 2; i++)
-            a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(As + ((nh * 2 + i) * 16 + r16) * M6_PITCH + off));
+            a[i] = *reinterpret_cast<const u32x4_t*>(As + ((nh * 2 + i) * 16 + r16) * M6_PITCH + off);
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             if (j < MT) {   // uniform
-                const bf16x8_t h = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bh + (j * 16 + r16) * M6_PITCH + off));
-                const bf16x8_t l = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(Bl + (j * 16 + r16) * M6_PITCH + off));
+                const u32x4_t h = *reinterpret_cast<const u32x4_t*>(Bh + (j * 16 + r16) * M6_PITCH + off);
+                const u32x4_t l = *reinterpret_cast<const u32x4_t*>(Bl + (j * 16 + r16) * M6_PITCH + off);
+                // two independent accumulators between the two updates of any one of them
 #pragma unroll
-                for (int i = 0; i < 2; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], h, acc[i][j], 0, 0, 0);
+                for (int i = 0; i < 2; i++) acc[i][j] = mfma_h16<F16>(a[i], h, acc[i][j]);
 #pragma unroll
-                for (int i = 0; i < 2; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], l, acc[i][j], 0, 0, 0);
+                for (int i = 0; i < 2; i++) acc[i][j] = mfma_h16<F16>(a[i], l, acc[i][j]);
             }
         }
     };
@@ -1212,7 +1263,7 @@ __global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __rest
 
 bool rows_many_supported(const Dims& D, int N, int K)
 {
-    return D.wt == WT_BF16 && N % 64 == 0 && K % M6_CK == 0 && K >= M6_CK;
+    return D.wt != WT_F32 && N % 64 == 0 && K % M6_CK == 0 && K >= M6_CK;
 }
 
 static int g_many_depth = 1;  // tuning hook (1 measured best: three blocks per CU already overlap)
@@ -1223,26 +1274,33 @@ hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t*
 {
     if (!rows_many_supported(D, N, K) || M < 1 || M > 64 || ldy % 4) return hipErrorInvalidValue;
     const size_t lds = (size_t)3 * 64 * M6_PITCH;
-    static bool attr[4] = {false, false, false, false};
     const int d = g_many_depth < 1 ? 1 : (g_many_depth > 3 ? 3 : g_many_depth);
-    const void* fn = d == 1 ? (const void*)rows_mfma64_kernel<1> : d == 2 ? (const void*)rows_mfma64_kernel<2>
-                                                                          : (const void*)rows_mfma64_kernel<3>;
-    if (!attr[d]) {
+    const bool f16 = D.wt == WT_F16;
+    const void* fn = f16 ? (d == 1 ? (const void*)rows_mfma64_kernel<1, true> : d == 2 ? (const void*)rows_mfma64_kernel<2, true>
+                                                                                       : (const void*)rows_mfma64_kernel<3, true>)
+                         : (d == 1 ? (const void*)rows_mfma64_kernel<1, false> : d == 2 ? (const void*)rows_mfma64_kernel<2, false>
+                                                                                        : (const void*)rows_mfma64_kernel<3, false>);
+    static bool attr[2][4] = {{false, false, false, false}, {false, false, false, false}};
+    if (lds > 64 * 1024 && !attr[f16][d]) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr[d] = true;
+        attr[f16][d] = true;
     }
     const dim3 grid(N / 64), block(512);
     const uint16_t* wp = (const uint16_t*)w;
-    if (d == 1) hipLaunchKernelGGL((rows_mfma64_kernel<1>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy);
-    else if (d == 2) hipLaunchKernelGGL((rows_mfma64_kernel<2>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy);
-    else hipLaunchKernelGGL((rows_mfma64_kernel<3>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy);
+#define SSD_LAUNCH_MANY(DD, FF) hipLaunchKernelGGL((rows_mfma64_kernel<DD, FF>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy)
+    if (f16) {
+        if (d == 1) SSD_LAUNCH_MANY(1, true); else if (d == 2) SSD_LAUNCH_MANY(2, true); else SSD_LAUNCH_MANY(3, true);
+    } else {
+        if (d == 1) SSD_LAUNCH_MANY(1, false); else if (d == 2) SSD_LAUNCH_MANY(2, false); else SSD_LAUNCH_MANY(3, false);
+    }
+#undef SSD_LAUNCH_MANY
     return hipGetLastError();
 }
 
 bool rows_fused_supported(const Dims& D)
 {
-    return D.wt == WT_BF16 && D.d % 64 == 0 && D.dq % 64 == 0 && D.f % 64 == 0;
+    return D.wt != WT_F32 && D.d % 64 == 0 && D.dq % 64 == 0 && D.f % 64 == 0;
 }
 
 hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s)
@@ -1257,17 +1315,18 @@ hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s)
     if (f.ssq && (f.mode == RM_RESID || f.n_ssq < 1)) return hipErrorInvalidValue;
     if (f.gain_out && (f.mode != RM_RESID || !f.oh || !f.ol || !f.ssq_out)) return hipErrorInvalidValue;
     switch (f.mode) {
-        case RM_STORE: return rows_fused_mode<RM_STORE>(p, s);
-        case RM_RESID: return rows_fused_mode<RM_RESID>(p, s);
-        case RM_SWIGLU: return rows_fused_mode<RM_SWIGLU>(p, s);
-        case RM_QKV: return rows_fused_mode<RM_QKV>(p, s);
+        case RM_STORE: return D.wt == WT_F16 ? rows_fused_mode<RM_STORE, true>(p, s) : rows_fused_mode<RM_STORE, false>(p, s);
+        case RM_RESID: return D.wt == WT_F16 ? rows_fused_mode<RM_RESID, true>(p, s) : rows_fused_mode<RM_RESID, false>(p, s);
+        case RM_SWIGLU: return D.wt == WT_F16 ? rows_fused_mode<RM_SWIGLU, true>(p, s) : rows_fused_mode<RM_SWIGLU, false>(p, s);
+        case RM_QKV: return D.wt == WT_F16 ? rows_fused_mode<RM_QKV, true>(p, s) : rows_fused_mode<RM_QKV, false>(p, s);
     }
     return hipErrorInvalidValue;
 }
 
 // hi/lo bf16 split of M rows of length K, optionally RMS-normalised first (gain != nullptr)
 __global__ __launch_bounds__(256) void rows_prep_kernel(const float* __restrict__ in, int ldx, const float* __restrict__ gain,
-                                                        int K, float eps, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo)
+                                                        int K, float eps, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
+                                                        bool f16)
 {
     __shared__ float red[4];
     const float* x = in + (size_t)blockIdx.x * ldx;
@@ -1287,15 +1346,15 @@ __global__ __launch_bounds__(256) void rows_prep_kernel(const float* __restrict_
             v.x = v.x * sc * g.x; v.y = v.y * sc * g.y; v.z = v.z * sc * g.z; v.w = v.w * sc * g.w;
         }
         const size_t o = (size_t)blockIdx.x * K + i;
-        split_store(v.x, hi, lo, o); split_store(v.y, hi, lo, o + 1);
-        split_store(v.z, hi, lo, o + 2); split_store(v.w, hi, lo, o + 3);
+        split_store(v.x, hi, lo, o, f16); split_store(v.y, hi, lo, o + 1, f16);
+        split_store(v.z, hi, lo, o + 2, f16); split_store(v.w, hi, lo, o + 3, f16);
     }
 }
 
-hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi, uint16_t* lo,
-                     hipStream_t s)
+hipError_t rows_prep(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi,
+                     uint16_t* lo, hipStream_t s)
 {
-    hipLaunchKernelGGL(rows_prep_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, eps, hi, lo);
+    hipLaunchKernelGGL(rows_prep_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, eps, hi, lo, D.wt == WT_F16);
     return hipGetLastError();
 }
 
@@ -1305,7 +1364,7 @@ hipError_t rows_prep(const float* in, int ldx, const float* gain, int M, int K, 
 __global__ __launch_bounds__(256) void rows_gain_split_kernel(const float* __restrict__ in, int ldx,
                                                               const float* __restrict__ gain, int K,
                                                               uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
-                                                              float* __restrict__ ssq)
+                                                              float* __restrict__ ssq, bool f16)
 {
     const float* x = in + (size_t)blockIdx.x * ldx;
     const int n_t = K >> 4;
@@ -1318,18 +1377,18 @@ __global__ __launch_bounds__(256) void rows_gain_split_kernel(const float* __res
             const float4 g = *reinterpret_cast<const float4*>(gain + i);
             sq += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
             const size_t o = (size_t)blockIdx.x * K + i;
-            split_store(v.x * g.x, hi, lo, o); split_store(v.y * g.y, hi, lo, o + 1);
-            split_store(v.z * g.z, hi, lo, o + 2); split_store(v.w * g.w, hi, lo, o + 3);
+            split_store(v.x * g.x, hi, lo, o, f16); split_store(v.y * g.y, hi, lo, o + 1, f16);
+            split_store(v.z * g.z, hi, lo, o + 2, f16); split_store(v.w * g.w, hi, lo, o + 3, f16);
         }
         ssq[(size_t)blockIdx.x * n_t + t] = sq;
     }
 }
 
-hipError_t rows_gain_split(const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo, float* ssq,
-                           hipStream_t s)
+hipError_t rows_gain_split(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo,
+                           float* ssq, hipStream_t s)
 {
     if (K % 16 || !gain) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(rows_gain_split_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, hi, lo, ssq);
+    hipLaunchKernelGGL(rows_gain_split_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, hi, lo, ssq, D.wt == WT_F16);
     return hipGetLastError();
 }
 
@@ -1379,6 +1438,9 @@ hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int*
     if (D.wt == WT_BF16)
         hipLaunchKernelGGL(rope_kv_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, qkv, rope, pos_dev, pos_off, M,
                            D.H, D.Hkv, D.hd, D.max_seq, (uint16_t*)kc, (uint16_t*)vc);
+    else if (D.wt == WT_F16)
+        hipLaunchKernelGGL(rope_kv_rows_kernel<f16_t>, dim3(blocks), dim3(256), 0, s, qkv, rope, pos_dev, pos_off, M,
+                           D.H, D.Hkv, D.hd, D.max_seq, (f16_t*)kc, (f16_t*)vc);
     else
         hipLaunchKernelGGL(rope_kv_rows_kernel<float>, dim3(blocks), dim3(256), 0, s, qkv, rope, pos_dev, pos_off, M, D.H,
                            D.Hkv, D.hd, D.max_seq, (float*)kc, (float*)vc);
@@ -1543,7 +1605,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
             const float mx = ml[qi * 2], ls = ml[qi * 2 + 1];
             if (n_splits == 1) {
                 const size_t oo = (size_t)r * dq + (size_t)head * HD + dd;
-                if (out_hi) split_store(o / ls, out_hi, out_lo, oo);
+                if (out_hi) split_store(o / ls, out_hi, out_lo, oo, IsF16<KT>::value);
                 else outp[oo] = o / ls;
             } else {
                 float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
@@ -1566,7 +1628,7 @@ static size_t attn_lds_bytes()
 // multi-XCD part cost far more than this extra launch.)
 template <int HD>
 __global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n_splits, float* __restrict__ out, int dq,
-                                    uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
+                                    uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo, bool f16)
 {
     const int head = blockIdx.x, r = blockIdx.y, d = threadIdx.x;
     const float* p = part + ((size_t)r * H + head) * n_splits * (HD + 4);
@@ -1583,7 +1645,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int H, int n
         }
     }
     const size_t o = (size_t)r * dq + (size_t)head * HD + d;
-    if (out_hi) split_store(num / den, out_hi, out_lo, o);
+    if (out_hi) split_store(num / den, out_hi, out_lo, o, f16);
     else out[o] = num / den;
 }
 
@@ -1601,6 +1663,12 @@ template <> __device__ __forceinline__ void aw_unpack<uint16_t>(u32x4_t w, float
     o[2] = __uint_as_float(w.y << 16); o[3] = __uint_as_float(w.y & 0xffff0000u);
     o[4] = __uint_as_float(w.z << 16); o[5] = __uint_as_float(w.z & 0xffff0000u);
     o[6] = __uint_as_float(w.w << 16); o[7] = __uint_as_float(w.w & 0xffff0000u);
+}
+template <> __device__ __forceinline__ void aw_unpack<f16_t>(u32x4_t w, float (&o)[8])
+{
+    const f16x8_t h = __builtin_bit_cast(f16x8_t, w);
+#pragma unroll
+    for (int i = 0; i < 8; i++) o[i] = (float)h[i];
 }
 template <> __device__ __forceinline__ void aw_unpack<float>(u32x4_t w, float (&o)[4])
 {
@@ -1791,7 +1859,7 @@ __global__ __launch_bounds__(NW * 64) void attn_wide_kernel(const float* __restr
         const int qg = q0 + qi, r = qg / G, head = kvh * G + qg % G;
         if (n_splits == 1) {
             const size_t oo = (size_t)r * dq + (size_t)head * HD + d;
-            if (out_hi) split_store(num / den, out_hi, out_lo, oo);
+            if (out_hi) split_store(num / den, out_hi, out_lo, oo, IsF16<KT>::value);
             else outp[oo] = num / den;
         } else {
             float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
@@ -1893,7 +1961,7 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_splits == 1 || pl.defer_fold) return e;
     hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(D.H, M), dim3(HD), 0, s, part, D.H, n_splits, out, D.dq, out_hi,
-                       out_lo);
+                       out_lo, IsF16<KT>::value);
     return hipGetLastError();
 }
 
@@ -1912,6 +1980,9 @@ hipError_t attention(const Dims& D, const float* q, int ldq, const void* kc, con
     if (D.wt == WT_BF16) {
         if (D.hd == 128) return attention_t<uint16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
         if (D.hd == 64) return attention_t<uint16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
+    } else if (D.wt == WT_F16) {
+        if (D.hd == 128) return attention_t<f16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
+        if (D.hd == 64) return attention_t<f16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
     } else {
         if (D.hd == 128) return attention_t<float, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
         if (D.hd == 64) return attention_t<float, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
@@ -2046,6 +2117,9 @@ hipError_t kv_poison(const Dims& D, void* kv_all, const int* pos_dev, hipStream_
     if (D.wt == WT_BF16)
         hipLaunchKernelGGL(kv_poison_kernel<uint16_t>, dim3(1024), dim3(256), 0, s, (uint16_t*)kv_all, planes, D.max_seq,
                            D.hd, pos_dev);
+    else if (D.wt == WT_F16)
+        hipLaunchKernelGGL(kv_poison_kernel<f16_t>, dim3(1024), dim3(256), 0, s, (f16_t*)kv_all, planes, D.max_seq, D.hd,
+                           pos_dev);
     else
         hipLaunchKernelGGL(kv_poison_kernel<float>, dim3(1024), dim3(256), 0, s, (float*)kv_all, planes, D.max_seq, D.hd,
                            pos_dev);

@@ -82,6 +82,10 @@ WORKLOADS: Dict[str, Workload] = {
         note="grouped-query attention, ~138 GB of bf16 weights"),
     # beyond the five benchmark configurations: the second model family of Section 4.1.1 (grouped heads,
     # 128 256-entry vocabulary: a 1 GB LM head, so the confidence pass is four times dearer per row)
+    "llama7b_f16": Workload(
+        "llama7b_f16", ModelShape(32, 4096, 32, 32, 11008, 32000, dtype="fp16"),
+        seed=2, prompt_len=512, new_tokens=256, k=4,
+        note="the 7B shape in the paper's own precision (FP16 weights and cache)"),
     "llama3_8b": Workload(
         "llama3_8b", ModelShape(32, 4096, 32, 8, 14336, 128256, rope_base=500000.0),
         seed=5, prompt_len=512, new_tokens=128, k=4,

@@ -34,7 +34,7 @@ def _cfg(**kw):
 
 
 @pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_kv_heads=3), dict(d_model=250), dict(vocab=1001),
-                                 dict(max_k=0), dict(max_k=16), dict(weight_dtype=2), dict(conf_taps=3),
+                                 dict(max_k=0), dict(max_k=16), dict(weight_dtype=3), dict(conf_taps=3),
                                  dict(n_layers=0), dict(max_seq=1), dict(rms_eps=0.0)])
 def test_create_rejects_bad_config(bad):
     h = C.c_void_p()

@@ -4,14 +4,17 @@ import pytest
 
 from oracle import OracleModel, OracleSSD, SelectParams, generate_vanilla, select_skip
 from synth import ModelShape, WORKLOADS, make_prompt, make_weights
-from tests._parity import TOL, assert_logits_close, decisive, lockstep_ssd, make_pair, to_gpu
+from tests._parity import CONF_TOL, PROB_RTOL, TOL, assert_logits_close, decisive, lockstep_ssd, make_pair, to_gpu
 
 pytestmark = pytest.mark.gpu
 
 MINI = ModelShape(4, 512, 8, 8, 1408, 2048)                     # bf16, head_dim 64
 GQA = ModelShape(3, 1024, 8, 2, 2816, 4096)                     # bf16, head_dim 128, 4 q-heads per kv-head
 GQA32 = ModelShape(2, 256, 4, 2, 688, 1024, dtype="fp32")       # fp32 weights, grouped heads
-SHAPES = {"tiny": WORKLOADS["tiny"].shape, "mini": MINI, "gqa": GQA, "gqa32": GQA32}
+MINI16 = ModelShape(4, 512, 8, 8, 1408, 2048, dtype="fp16")     # fp16 (the paper's precision), head_dim 64, MFMA path
+GQA16 = ModelShape(3, 512, 4, 2, 688, 1024, dtype="fp16")       # fp16, head_dim 128, grouped heads, FFN not a
+                                                                 # multiple of 64: the plain multi-row path
+SHAPES = {"tiny": WORKLOADS["tiny"].shape, "mini": MINI, "gqa": GQA, "gqa32": GQA32, "mini16": MINI16, "gqa16": GQA16}
 
 
 @pytest.fixture(scope="module")
@@ -23,7 +26,7 @@ def ssd():
     return lib
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16"])
 @pytest.mark.parametrize("plen", [1, 16, 17, 45])
 def test_prefill_logits_and_first_token(ssd, name, plen):
     shape = SHAPES[name]
@@ -38,7 +41,7 @@ def test_prefill_logits_and_first_token(ssd, name, plen):
     assert ctx.ssd_get_stats()["n_tokens"] == plen + 1
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16"])
 def test_vanilla_decode_lockstep(ssd, name):
     shape = SHAPES[name]
     orc, ctx = make_pair(shape, 9, 96, norm_gain_std=0.1)
@@ -65,10 +68,12 @@ MASKS = {
     "mini": [[0, 0, 0, 0], [0, 1, 1, 0]],
     "gqa": [[0, 0, 0], [0, 1, 0]],
     "gqa32": [[0, 0], [1, 0]],
+    "mini16": [[0, 0, 0, 0], [0, 1, 1, 0]],
+    "gqa16": [[0, 0, 0], [0, 1, 0]],
 }
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16"])
 @pytest.mark.parametrize("k", [1, 4, 8])
 def test_ssd_lockstep(ssd, name, k):
     shape = SHAPES[name]
@@ -131,20 +136,20 @@ def test_tiny_workload_end_to_end_matches_oracle_tokens(ssd):
     print("tiny end-to-end: mask", mask_o.tolist(), "gpu-conf mask", mask_g.tolist(), "stats", ctx.ssd_get_stats())
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "mini16", "gqa16"])
 def test_layer_confidence_matches_oracle(ssd, name):
     shape = SHAPES[name]
     # larger init => intermediate distributions far from uniform, confidences spread over (0, 1)
-    orc, ctx = make_pair(shape, 17, 64, norm_gain_std=0.1, init_std=0.08 if shape.dtype == "bf16" else 0.2)
+    orc, ctx = make_pair(shape, 17, 64, norm_gain_std=0.1, init_std=0.2 if shape.dtype == "fp32" else 0.08)
     prompt = make_prompt(shape.vocab, 18, 2).tolist()
     o = OracleSSD(orc)
     o.prefill(prompt)
     ctx.ssd_prefill(prompt)
     conf_o, per_o = o.layer_confidence(0)
     conf_g, per_g = ctx.ssd_layer_confidence(0, 1, detail=True)
-    tol = 5e-3 if shape.dtype == "bf16" else 2e-5   # bf16: logit tolerance 2e-2 moves H by up to ~2x that, over log V
+    tol = CONF_TOL[shape.dtype]   # a logit tolerance t moves H by up to ~2t, over log V
     np.testing.assert_allclose(conf_g[0], conf_o, atol=tol)
-    np.testing.assert_allclose(per_g["maxprob"][0], per_o["maxprob"], rtol=0.05 if shape.dtype == "bf16" else 1e-3)
+    np.testing.assert_allclose(per_g["maxprob"][0], per_o["maxprob"], rtol=PROB_RTOL[shape.dtype] * 1.25)
     zero = np.zeros(shape.n_layers, np.uint8)
     d = o.draft(zero, 3)
     ctx.ssd_draft_step(zero, 3)
@@ -307,6 +312,8 @@ LONG_SHAPES = {
     "gqa2_128_bf16": ModelShape(2, 512, 4, 2, 1024, 1024),
     "gqa4_128_bf16": ModelShape(2, 512, 4, 1, 1024, 1024),
     "gqa2_128_f32": ModelShape(1, 512, 4, 2, 768, 1024, dtype="fp32"),
+    "gqa4_128_f16": ModelShape(2, 512, 4, 1, 1024, 1024, dtype="fp16"),
+    "mha64_f16": ModelShape(2, 256, 4, 4, 512, 1024, dtype="fp16"),
 }
 
 
@@ -343,7 +350,7 @@ def test_long_context_decode_and_verify(ssd, name, plen):
     print("long", name, plen, "max err %.2e" % worst)
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "mini16"])
 def test_confidence_aware_drafting_lockstep(ssd, name):
     """ssd_draft_adaptive against the oracle's draft rule: same tokens, same max-probabilities, and the same draft
     length whenever no max-probability of the cycle lies within the tolerance of gamma (p < gamma decides an
@@ -358,7 +365,7 @@ def test_confidence_aware_drafting_lockstep(ssd, name):
     # calibrate gamma on the oracle so that the rule stops some drafts early and lets others run
     _, probe = o.draft(mask, 8, want_maxprob=True)
     gamma = float(np.median(probe))
-    rel = 4e-2 if shape.dtype == "bf16" else 1e-3          # |dp| <= p * 2 * (logit tolerance)
+    rel = PROB_RTOL[shape.dtype]
     lens, compared = [], 0
     for cycle in range(10):
         d_o, p_o = o.draft_adaptive(mask, 8, gamma)
@@ -386,7 +393,7 @@ def test_confidence_aware_drafting_lockstep(ssd, name):
     assert st["drafted"] == sum(lens) or compared < 10
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "mini16", "gqa16"])
 def test_longest_draft_fills_the_row_block(ssd, name):
     """k = 15 (the library's maximum): verification runs all 16 rows of a row block."""
     shape = SHAPES[name]

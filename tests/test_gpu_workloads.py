@@ -58,7 +58,7 @@ def test_small_workload_full_config(ssd):
 
 
 @pytest.mark.parametrize("name,layers,mask", [("llama7b", 3, [0, 1, 0]), ("llama70b", 2, [0, 1]),
-                                              ("llama3_8b", 2, [0, 1])])
+                                              ("llama3_8b", 2, [0, 1]), ("llama7b_f16", 3, [0, 1, 0])])
 def test_large_shapes_at_reduced_depth(ssd, name, layers, mask):
     """Real widths (7B: d 4096, FFN 11008, MHA; 70B: d 8192, FFN 28672, 64 query / 8 KV heads), few layers."""
     wl = WORKLOADS[name]
@@ -132,7 +132,8 @@ def test_7b_full_depth_short_prompt(ssd):
           "%.0f s" % (time.time() - t0))
 
 
-@pytest.mark.parametrize("name,n_new", [("llama7b", 40), ("llama13b", 16), ("llama70b", 12), ("llama3_8b", 24)])
+@pytest.mark.parametrize("name,n_new", [("llama7b", 40), ("llama13b", 16), ("llama70b", 12), ("llama3_8b", 24),
+                                        ("llama7b_f16", 24)])
 def test_full_workload_properties(ssd, name, n_new):
     """Configs 3-5 at full size in bench.py's launch configuration (full prompt, graphs on): properties that hold
     at any size.  Empty skip set => everything accepted; greedy SSD reproduces the library's own vanilla tokens
