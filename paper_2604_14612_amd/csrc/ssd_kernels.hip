@@ -1,13 +1,15 @@
 // gfx950 (CDNA4, wave64) kernels of the self-speculative decoding hot path.
 //
-// Single-row path (draft model of Section 3 and vanilla decoding): bf16/fp32 weight-streaming
-// GEMV kernels -- every lane issues 128-bit loads along K, fp32 FMAs against the activation
-// vector held in LDS, wave-shuffle reduction; RMSNorm is fused into the prologue, rotary
-// embedding + KV-cache write / residual add / SwiGLU into the epilogues.
+// Single-row path (draft model of Section 3 and vanilla decoding): weight-streaming GEMV kernels for
+// bf16 / fp16 / fp32 weights -- every lane issues 128-bit loads along K, fp32 FMAs against the
+// activation vector held in LDS, wave-shuffle reduction; RMSNorm is fused into the prologue, rotary
+// embedding + KV-cache write / residual add / SwiGLU into the epilogues.  Attention over the cache
+// runs out of registers on ranges of ~128 positions; the output projection folds the range partials.
 // Multi-row path (verification of k+1 rows, prompt rows, per-layer confidence rows): the same
-// weight stream feeds 16x16x32 bf16 MFMA tiles, activations entering as an exact bf16 hi+lo
-// split of their fp32 values.
-// Attention reads the cache through LDS-staged K/V tiles, split over the sequence.
+// weight stream, staged through LDS, feeds 16x16x32 MFMA tiles; activations enter as an exact hi+lo
+// split of their fp32 values in the weights' 16-bit type, and RMSNorm is folded into the epilogue
+// of the producing and the consuming projection.  Models whose shapes do not fit the MFMA tiling
+// (and fp32 models) take a plain FMA path with separate norm / rotary kernels.
 #include "ssd_kernels.h"
 
 #include <hip/hip_ext.h>

@@ -28,6 +28,7 @@ class ModelShape:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     init_depth: int = 0          # depth the residual-projection init is scaled for (0 = n_layers)
+    resid_scale: float = 1.0     # extra factor on the two projections that write into the residual stream
 
     @property
     def head_dim(self) -> int:
@@ -82,6 +83,13 @@ WORKLOADS: Dict[str, Workload] = {
         note="grouped-query attention, ~138 GB of bf16 weights"),
     # beyond the five benchmark configurations: the second model family of Section 4.1.1 (grouped heads,
     # 128 256-entry vocabulary: a 1 GB LM head, so the confidence pass is four times dearer per row)
+    # A model in which depth is redundant, as it is in trained LLMs and is not in a random-init one: every layer
+    # writes 20 times less into the residual stream, so a draft model with half the layers mostly agrees with the
+    # full model.  Shows the pipeline at high acceptance (search reaching its goal, SSD faster than vanilla).
+    "llama7b_redundant": Workload(
+        "llama7b_redundant", ModelShape(32, 4096, 32, 32, 11008, 32000, resid_scale=0.001),
+        seed=2, prompt_len=512, new_tokens=256, k=4,
+        note="7B shape, residual contributions scaled by 0.05"),
     "llama7b_f16": Workload(
         "llama7b_f16", ModelShape(32, 4096, 32, 32, 11008, 32000, dtype="fp16"),
         seed=2, prompt_len=512, new_tokens=256, k=4,
@@ -125,7 +133,8 @@ def make_weights(shape: ModelShape, seed: int, device: str = "cpu",
     """Random-init decoder weights.
 
     All matrices are row-major [out_features][in_features] and ~N(0, init_std); the two
-    projections that write into the residual stream (wo, wd) are scaled by 1/sqrt(2*depth), depth = init_depth or n_layers.
+    projections that write into the residual stream (wo, wd) are scaled by resid_scale/sqrt(2*depth),
+    depth = init_depth or n_layers.
     Norm gains are 1 (+ norm_gain_std * N(0,1) when a test wants them non-trivial).
     bf16 / fp16 models are rounded to their type once (round-to-nearest-even) and that rounded tensor is
     what every consumer sees.  The stream differs between CPU and GPU generators: move the
@@ -134,7 +143,7 @@ def make_weights(shape: ModelShape, seed: int, device: str = "cpu",
     dt = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[shape.dtype]
     L, d, f, V = shape.n_layers, shape.d_model, shape.d_ffn, shape.vocab
     dq, dkv = shape.n_heads * shape.head_dim, shape.d_kv
-    res_std = init_std / math.sqrt(2.0 * (shape.init_depth or L))
+    res_std = shape.resid_scale * init_std / math.sqrt(2.0 * (shape.init_depth or L))
 
     def gain(layer, tid):
         if norm_gain_std == 0.0:
