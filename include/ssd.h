@@ -42,7 +42,8 @@ enum {
 };
 
 #define SSD_MAX_K 15        /* largest draft length: k + 1 rows fill one 16-column MFMA tile */
-#define SSD_PREFILL_ROWS 16 /* prompt rows processed per pass of the weights */
+#define SSD_PREFILL_ROWS 64 /* most prompt rows processed per pass of the weights (16 where a shape does not fit the
+                               64-row tiling: widths not multiples of 128, fp32 weights) */
 
 typedef struct ssd_ctx ssd_ctx;
 
@@ -110,7 +111,7 @@ int ssd_get_stats(const ssd_ctx *ctx, ssd_stats *out);
 
 /* ---- generation step (Figure 2, "generation") ----------------------------------------- */
 
-/* Full-model forward over the n prompt tokens (host int32), SSD_PREFILL_ROWS rows per pass.
+/* Full-model forward over the n prompt tokens (host int32), at most SSD_PREFILL_ROWS rows per pass.
  * Fills the cache for positions 0..n-1, keeps the hidden-state taps of the last row, and
  * commits the greedy first new token (returned in *first_token_out, host). n + 1 tokens are
  * then committed.  SSD_ECAPACITY if n + 1 > max_seq. */

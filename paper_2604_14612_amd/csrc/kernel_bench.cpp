@@ -60,7 +60,7 @@ int main(int argc, char** argv)
     }
     float *x, *gain, *act, *q, *rope, *logits, *part, *sink, *big_a, *big_b;
     int* pos;
-    uint16_t *kc, *vc, *hi, *lo;
+    uint16_t *kc, *vc, *hi, *lo, *hi64, *lo64;
     const size_t act_floats = (size_t)16 * 32000;
     CK(hipMalloc(&x, act_floats * 4)); CK(hipMalloc(&gain, 1 << 20)); CK(hipMalloc(&act, act_floats * 4));
     CK(hipMalloc(&q, act_floats * 4)); CK(hipMalloc(&logits, act_floats * 4)); CK(hipMalloc(&part, 64 << 20));
@@ -68,6 +68,8 @@ int main(int argc, char** argv)
     const size_t kv_layer = (size_t)32 * 1024 * 128;  // elements of K (or V) of one layer; one copy per timed launch so the cache is cold
     CK(hipMalloc(&kc, 12 * kv_layer * 2)); CK(hipMalloc(&vc, 12 * kv_layer * 2));
     CK(hipMalloc(&hi, act_floats * 2)); CK(hipMalloc(&lo, act_floats * 2));
+    CK(hipMalloc(&hi64, (size_t)64 * 11008 * 2)); CK(hipMalloc(&lo64, (size_t)64 * 11008 * 2));
+    CK(hipMemset(hi64, 0, (size_t)64 * 11008 * 2)); CK(hipMemset(lo64, 0, (size_t)64 * 11008 * 2));
     CK(hipMalloc(&big_a, (size_t)256 << 20)); CK(hipMalloc(&big_b, (size_t)256 << 20));
     CK(hipMemset(x, 0, act_floats * 4)); CK(hipMemset(gain, 0, 1 << 20)); CK(hipMemset(act, 0, act_floats * 4));
     CK(hipMemset(q, 0, act_floats * 4)); CK(hipMemset(rope, 0, (size_t)1024 * 64 * 2 * 4));
@@ -172,14 +174,37 @@ int main(int argc, char** argv)
     timeit("rows_down (resid)", gu * 2.0, n, [&](int i) { fused(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, x, 4096); });
     timeit("rows_lmhead", lm * 2.0, n, [&](int i) { fused(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, logits, 32000); });
     }
-    for (int depth : {1, 2, 3}) for (int rows : {16, 64}) {
-        rows_many_depth(depth);
+    for (int rows : {16, 64}) {
         char nm[96];
-        std::snprintf(nm, sizeof nm, "rows_many lmhead %d rows, depth %d", rows, depth);
+        std::snprintf(nm, sizeof nm, "rows_many lmhead %d rows", rows);
         timeit(nm, lm * 2.0, n, [&](int i) {
             CK(rows_many(D, W + (size_t)i * lm, 32000, 4096, hi, lo, 4096, rows, big_a, 32000, 0)); });
     }
-    rows_many_depth(1);
+    {
+        const int M0 = M;
+        (void)M0;
+        auto wide = [&](int mode, const uint16_t* w0, const uint16_t* w1, const uint16_t* w2, int n0, int n1, int n2, int K,
+                        float* y, int ldy) {
+            RowsFused f = {};
+            f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
+            f.bh = hi64; f.bl = lo64; f.ldb = K; f.y = y; f.ldy = ldy; f.oh = hi64; f.ol = lo64; f.ldo = 11008; f.M = 64; f.mode = mode;
+            f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
+            CK(rows_wide(D, f, 0));
+        };
+        for (int depth : {0, 1, 2, 4}) {
+        rows_wide_depth(depth);
+        std::printf("-- 64-row pass (prompt blocks), stripes in flight %d (0 = library's choice)\n", depth);
+        timeit("wide_qkv", 3 * qk * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 3 * qk;
+            wide(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, big_a, 4096); });
+        timeit("wide_o (resid)", qk * 2.0, n, [&](int i) { wide(1, W + (size_t)i * qk, nullptr, nullptr, 4096, 0, 0, 4096, big_b, 4096); });
+        timeit("wide_gateup (swiglu)", 2 * gu * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 2 * gu;
+            wide(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
+        timeit("wide_down (resid)", gu * 2.0, n, [&](int i) { wide(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, big_b, 4096); });
+        }
+        rows_wide_depth(0);
+    }
     for (int kind : {1, 0}) {
         attention_force_kernel(kind);
         for (int sp : {0, 2, 4, 8, 16}) {

@@ -24,7 +24,8 @@ size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
     size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, ssq, small, total;
-    int rows;       // activation rows: max(max_k + 1, SSD_PREFILL_ROWS)
+    int rows;       // activation rows: max(max_k + 1, prompt rows per pass)
+    int prefill_rows;  // prompt rows per pass: SSD_PREFILL_ROWS where the shape fits the wide tiling, else 16
     int conf_rows;  // rows of one confidence pass: 2 * L
     int logit_rows;
     size_t kv_layer_elems;  // elements of K (or V) of one layer
@@ -61,7 +62,8 @@ Layout make_layout(const ssd_config& c)
     Dims D = make_dims(c);
     Layout l;
     size_t esz = c.weight_dtype == 0 ? 4 : 2;
-    l.rows = c.max_k + 1 > SSD_PREFILL_ROWS ? c.max_k + 1 : SSD_PREFILL_ROWS;
+    l.prefill_rows = rows_wide_supported(D) ? SSD_PREFILL_ROWS : 16;
+    l.rows = c.max_k + 1 > l.prefill_rows ? c.max_k + 1 : l.prefill_rows;
     l.conf_rows = 2 * c.n_layers;
     l.logit_rows = l.rows > l.conf_rows ? l.rows : l.conf_rows;
     l.kv_layer_elems = (size_t)D.Hkv * D.max_seq * D.hd;
@@ -92,8 +94,9 @@ Layout make_layout(const ssd_config& c)
 }
 
 // offsets (in 4-byte words) inside the "small" region
-enum { SM_POS = 0, SM_TOK = 8 /* 17 ints: pending + drafts */, SM_TARGET = 32 /* 16 */, SM_RES = 56 /* 2 */,
-       SM_MAXPROB = 64 /* 16 floats */, SM_VTOK = 80 /* 16: tokens of a row block */, SM_SINK = 96, SM_CONF = 128 /* conf_rows floats x3 follow */ };
+enum { SM_POS = 0, SM_TOK = 8 /* 17 ints: pending + drafts */, SM_RES = 56 /* 2 */, SM_MAXPROB = 64 /* 16 floats */,
+       SM_SINK = 96, SM_CONF = 128 /* conf_rows floats x3 follow (at most 3 x 160) */,
+       SM_VTOK = 896 /* 64: tokens of a row block */, SM_TARGET = 960 /* 64: greedy token after each row of a block */ };
 
 }  // namespace
 
@@ -231,8 +234,9 @@ int forward_single(ssd_ctx* c, const uint8_t* skip, int slot, int slot_out, int 
     return SSD_OK;
 }
 
-// Full-model forward of the M tokens in SM_VTOK (M <= 16) at positions *pos + pos_off + r; taps into tap rows 0..M-1;
-// logits (when want_logits) into logits rows 0..M-1 and greedy tokens into SM_TARGET.
+// Full-model forward of the M tokens in SM_VTOK (M <= 16, or <= 64 where the wide tiling applies) at positions
+// *pos + pos_off + r; taps into tap rows 0..M-1; logits (when want_logits) into logits rows 0..M-1 and greedy tokens
+// into SM_TARGET -- for a block of more than 16 rows (a prompt block) only the last row's.
 int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
 {
     const Dims& D = c->D;
@@ -241,8 +245,59 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
     float* h = c->f(Y.h);
     HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_VTOK, M, x, c->stream), "embed");
     const int tap_ld = D.L * 2 * D.d;
+    if (M > 16) {
+        // prompt block of up to 64 rows: the same sequence as the 16-row path below on 64-row weight tiles
+        if (!rows_wide_supported(D) || M > 64) return fail(c, SSD_ECAPACITY, "row block too large for this shape");
+        uint16_t* hi = c->h16(Y.hi);
+        uint16_t* lo = c->h16(Y.lo);
+        uint16_t* xh = c->h16(Y.h);
+        uint16_t* xl = xh + (size_t)Y.rows * D.d;
+        float* ssq = c->f(Y.ssq);
+        const int n_ssq = D.d / 64;
+        HIPCHK(rows_gain_split(D, x, D.d, c->attn_norm[0], M, D.d, xh, xl, ssq, 64, c->stream), "rows_gain_split");
+        for (int l = 0; l < D.L; l++) {
+            RowsFused q = {};
+            q.w[0] = c->wq[l]; q.w[1] = c->wk[l]; q.w[2] = c->wv[l]; q.n[0] = D.dq; q.n[1] = D.dkv; q.n[2] = D.dkv;
+            q.K = D.d; q.bh = xh; q.bl = xl; q.ldb = D.d; q.ssq = ssq; q.n_ssq = n_ssq; q.y = c->f(Y.qkv); q.ldy = D.dq;
+            q.M = M; q.mode = 3;
+            q.rope = c->f(Y.rope); q.pos_dev = c->pos_dev(); q.pos_off = pos_off; q.kc = c->kcache(l); q.vc = c->vcache(l);
+            TIMED(SSD_K_ROWS_QKV, rows_wide(D, q, c->stream), "wide_qkv");
+            TIMED(SSD_K_ATTENTION, attention(D, c->f(Y.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
+                                             pos_host, M, c->f(Y.part), nullptr, hi, lo, c->stream), "attention");
+            RowsFused o = {};
+            o.w[0] = c->wo[l]; o.n[0] = D.d; o.K = D.dq; o.bh = hi; o.bl = lo; o.ldb = D.dq; o.y = x; o.ldy = D.d; o.M = M;
+            o.mode = 1; o.tap = c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d; o.tap_ld = tap_ld;
+            o.gain_out = c->mlp_norm[l]; o.oh = xh; o.ol = xl; o.ldo = D.d; o.ssq_out = ssq;
+            TIMED(SSD_K_ROWS_O, rows_wide(D, o, c->stream), "wide_o");
+            RowsFused gu = {};
+            gu.w[0] = c->wg[l]; gu.w[1] = c->wu[l]; gu.n[0] = D.f; gu.n[1] = D.f; gu.K = D.d; gu.bh = xh; gu.bl = xl;
+            gu.ldb = D.d; gu.ssq = ssq; gu.n_ssq = n_ssq;
+            gu.oh = c->h16(Y.act); gu.ol = c->h16(Y.act) + (size_t)Y.rows * D.f; gu.ldo = D.f; gu.M = M;
+            gu.mode = 2;
+            TIMED(SSD_K_ROWS_GATEUP, rows_wide(D, gu, c->stream), "wide_gateup");
+            RowsFused dn = {};
+            dn.w[0] = c->wd[l]; dn.n[0] = D.d; dn.K = D.f; dn.bh = gu.oh; dn.bl = gu.ol; dn.ldb = D.f; dn.y = x; dn.ldy = D.d;
+            dn.M = M; dn.mode = 1; dn.tap = c->f(Y.taps) + ((size_t)l * 2 + 1) * D.d; dn.tap_ld = tap_ld;
+            if (l + 1 < D.L || want_logits) {
+                dn.gain_out = l + 1 < D.L ? c->attn_norm[l + 1] : c->w.final_norm;
+                dn.oh = xh; dn.ol = xl; dn.ldo = D.d; dn.ssq_out = ssq;
+            }
+            TIMED(SSD_K_ROWS_DOWN, rows_wide(D, dn, c->stream), "wide_down");
+        }
+        if (want_logits) {   // last row only, through the 16-row kernel with one row
+            const int r = M - 1;
+            RowsFused lm = {};
+            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = xh + (size_t)r * D.d; lm.bl = xl + (size_t)r * D.d;
+            lm.ldb = D.d; lm.ssq = ssq + (size_t)r * n_ssq; lm.n_ssq = n_ssq; lm.y = c->f(Y.logits) + (size_t)r * D.V;
+            lm.ldy = D.V; lm.M = 1; lm.mode = 0;
+            TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows_lmhead");
+            HIPCHK(vocab_reduce(c->f(Y.logits) + (size_t)r * D.V, 1, D.V, c->cfg.conf_clamp, c->cfg.conf_eps,
+                                c->small_i() + SM_TARGET + r, 1, nullptr, nullptr, nullptr, c->stream), "vocab_reduce");
+        }
+        return SSD_OK;
+    }
     if (rows_fused_supported(D)) {
-        // bf16 fast path: activations travel between the GEMMs as bf16 hi/lo pairs.  The residual rows exist
+        // 16-bit fast path: activations travel between the GEMMs as hi/lo pairs of the weights' type.  The residual rows exist
         // twice: x (fp32) and xh/xl = split(x * gain of the norm that reads them next) with their per-tile
         // sums of squares in ssq, both left behind by the projection that last updated x.
         uint16_t* hi = c->h16(Y.hi);
@@ -251,7 +306,7 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
         uint16_t* xl = xh + (size_t)Y.rows * D.d;
         float* ssq = c->f(Y.ssq);
         const int n_ssq = D.d / 16;
-        HIPCHK(rows_gain_split(D, x, D.d, c->attn_norm[0], M, D.d, xh, xl, ssq, c->stream), "rows_gain_split");
+        HIPCHK(rows_gain_split(D, x, D.d, c->attn_norm[0], M, D.d, xh, xl, ssq, 16, c->stream), "rows_gain_split");
         for (int l = 0; l < D.L; l++) {
             RowsFused q = {};
             q.w[0] = c->wq[l]; q.w[1] = c->wk[l]; q.w[2] = c->wv[l]; q.n[0] = D.dq; q.n[1] = D.dkv; q.n[2] = D.dkv;
@@ -501,8 +556,9 @@ int ssd_prefill(ssd_ctx* c, const int32_t* tokens, int n, int32_t* first_token_o
         if (tokens[i] < 0 || tokens[i] >= c->D.V) return fail(c, SSD_EINVAL, "prompt token id out of range");
     HIPCHK(set_state(c->small_i() + SM_TOK, 0, c->pos_dev(), 0, c->stream), "set_state");
     int last_M = 0;
-    for (int p0 = 0; p0 < n; p0 += SSD_PREFILL_ROWS) {
-        int M = n - p0 < SSD_PREFILL_ROWS ? n - p0 : SSD_PREFILL_ROWS;
+    const int block = c->lay.prefill_rows;
+    for (int p0 = 0; p0 < n; p0 += block) {
+        int M = n - p0 < block ? n - p0 : block;
         TokArg t = {};
         for (int r = 0; r < M; r++) t.t[r] = tokens[p0 + r];
         bool last = p0 + M == n;

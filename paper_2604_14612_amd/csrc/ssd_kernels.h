@@ -17,7 +17,7 @@ struct Dims {
 };
 
 // x[r][:] = embed[tok_dev[r]][:] widened to fp32 (token ids in device memory, clamped to the vocabulary).
-struct TokArg { int32_t t[16]; };
+struct TokArg { int32_t t[64]; };
 hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok_dev, int M, float* x, hipStream_t s);
 // dst[i] = toks.t[i] for i < n, except dst[0] = first_dev[0] when first_dev != nullptr
 hipError_t set_tokens(TokArg toks, int n, const int32_t* first_dev, int32_t* dst, hipStream_t s);
@@ -102,15 +102,19 @@ hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s);
 bool rows_many_supported(const Dims& D, int N, int K);
 hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t* bh, const uint16_t* bl, int ldb, int M,
                      float* y, int ldy, hipStream_t s);
-void rows_many_depth(int d);  // tuning hook: stripes in flight (1..3)
+// The modes of rows_fused for up to 64 rows per pass (prompt blocks): 64-row weight tiles, n[] multiples of 64,
+// K a multiple of 128; the sums of squares it reads / writes are per 64-column tile.
+bool rows_wide_supported(const Dims& D);
+hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s);
+void rows_wide_depth(int d);  // tuning hook: > 0 forces the number of weight stripes a block keeps in flight
 // hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
 // gain first when gain != nullptr
 hipError_t rows_prep(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi,
                      uint16_t* lo, hipStream_t s);
-// hi/lo = split(in * gain) (no norm scale) and ssq[r][t] = sum of in[r][16t..16t+16)^2: the form in which a
-// RESID projection with gain_out hands rows to its consumer
+// hi/lo = split(in * gain) (no norm scale) and ssq[r][t] = sum of in[r][group t .. group (t+1))^2, group = 16
+// (rows_fused) or 64 (rows_wide): the form in which a RESID projection with gain_out hands rows to its consumer
 hipError_t rows_gain_split(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo,
-                           float* ssq, hipStream_t s);
+                           float* ssq, int group, hipStream_t s);
 // rotary on q,k rows + cache write for the multi-row path. qkv: [M][dq + 2 dkv]; q is rotated in place.
 hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int* pos_dev, int pos_off, int M,
                         void* kcache_l, void* vcache_l, hipStream_t s);

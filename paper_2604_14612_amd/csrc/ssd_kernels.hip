@@ -1121,33 +1121,65 @@ static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
     }
 }
 
-// --- many-row variant for the per-layer confidence contraction (2L tap rows against the LM head) --------
-// With up to 64 activation rows a 16-row weight tile would pull eight times more activation bytes out
-// of the cache than weight bytes out of HBM.  Here a block owns 64 weight rows and all (<= 64) rows.
-// 64 x 128-k stripes of the weights (non-temporal) and of the hi/lo rows go through LDS; a stripe has four
-// 32-wide k-steps: wave w takes k-step w & 3 for the weight rows 32 (w >> 2) .. +31 and all rows, so
-// every staged byte is read twice only, and the four k-step partials are summed through LDS at the end.
-// 52 KB of LDS per block: three blocks share a CU and cover each other's load / stage / multiply phases.
-// M6_D stripes are in flight in registers while one is multiplied.
+// --- wide-block variant: up to 64 activation rows per pass (prompt blocks, the 2L confidence rows) -------
+// With that many rows a 16-row weight tile would pull eight times more activation bytes out of the cache
+// than weight bytes out of HBM.  Here a block owns 64 weight rows (64 of each matrix in SwiGLU mode) and all
+// (<= 64) rows.  64 x 128-k stripes of the weights (non-temporal) and of the hi/lo rows go through LDS; a
+// stripe has four 32-wide k-steps: wave w takes k-step w & 3 for the weight rows 32 (w >> 2) .. +31 and all
+// rows, so every staged byte is read twice only, and the four k-step partials are summed through LDS at the
+// end, band by band of 16 rows, where the mode's epilogue is applied.  52 KB of LDS per block (70 KB for
+// SwiGLU): two to three blocks share a CU and cover each other's load / stage / multiply phases, which
+// measured better than a deeper register ring.  Same modes, same RMSNorm folding and the same rotary-pair
+// row order (here 32 pairs per tile) as the 16-row kernel.
 constexpr int M6_CK = 128;
 constexpr int M6_PITCH = M6_CK * 2 + 16;
 
-template <int M6_D, bool F16>
-__global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __restrict__ w, int K,
-                                                          const uint16_t* __restrict__ bh, const uint16_t* __restrict__ bl,
-                                                          int ldb, int M, float* __restrict__ y, int ldy)
+// weight row of logical row r64 of tile `tile`
+template <int MODE>
+__device__ __forceinline__ const uint16_t* m6_row(const RowsP2& p, int tile, int r64, int which /*SWIGLU: 0 gate, 1 up*/)
 {
+    if (MODE == RM_SWIGLU) return (const uint16_t*)p.w[which] + (size_t)(tile * 64 + r64) * p.K;
+    if (MODE == RM_QKV) {
+        const int tq = p.dq >> 6, tk = p.dkv >> 6;
+        if (tile < tq + tk) {
+            const uint16_t* base = (const uint16_t*)p.w[0];
+            int tt = tile;
+            if (tile >= tq) { base = (const uint16_t*)p.w[1]; tt = tile - tq; }
+            const int tph = p.hd >> 6, head = tt / tph, th = tt % tph;
+            const int row = head * p.hd + th * 32 + (r64 & 31) + (r64 >> 5) * (p.hd >> 1);
+            return base + (size_t)row * p.K;
+        }
+        return (const uint16_t*)p.w[2] + (size_t)((tile - tq - tk) * 64 + r64) * p.K;
+    }
+    int row = tile * 64 + r64;
+    if (row < p.n[0]) return (const uint16_t*)p.w[0] + (size_t)row * p.K;
+    row -= p.n[0];
+    if (row < p.n[1]) return (const uint16_t*)p.w[1] + (size_t)row * p.K;
+    return (const uint16_t*)p.w[2] + (size_t)(row - p.n[1]) * p.K;
+}
+
+template <int MODE, bool F16, int M6_D>  // M6_D = stripes in flight per block
+__global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
+{
+    constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     extern __shared__ __align__(16) unsigned char sm6[];
-    unsigned char* As = sm6;                       // [64][PITCH]
-    unsigned char* Bh = sm6 + 64 * M6_PITCH;       // [64][PITCH]
+    __shared__ float rs[64];
+    __shared__ float fin[MODE == RM_QKV ? 1024 : 1];
+    unsigned char* As = sm6;                            // [NT * 64][PITCH]
+    unsigned char* Bh = sm6 + NT * 64 * M6_PITCH;       // [64][PITCH]
     unsigned char* Bl = Bh + 64 * M6_PITCH;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
-    const int n0 = blockIdx.x * 64;
+    const int tile = blockIdx.x, n0 = tile * 64;
+    const int K = p.K, M = p.M;
     const int NC = K / M6_CK;
-    // weights: wave w loads rows 8w .. 8w+7; instruction j covers rows 8w+4j .. 8w+4j+3 (16 lanes = 256 B per row)
+    // weights: wave w loads logical rows 8w .. 8w+7; instruction j covers rows 8w+4j .. 8w+4j+3 (16 lanes = 256 B per row)
     const int arow = 8 * wave + (lane >> 4), acol = (lane & 15) * 8;
-    const uint16_t* ap = w + (size_t)(n0 + arow) * K + acol;
+    const uint16_t* ap[NT][2];
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) ap[t][j] = m6_row<MODE>(p, tile, arow + 4 * j, t) + acol;
     // activations: 64 rows x 16 vectors per array; thread takes vectors tid and tid + 512 (row clamped to M - 1)
     const uint16_t* bhp[2];
     const uint16_t* blp[2];
@@ -1155,15 +1187,17 @@ __global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __rest
 #pragma unroll
     for (int u = 0; u < 2; u++) {
         const int v = tid + u * 512, row = v >> 4, kk = (v & 15) * 8;
-        const size_t off = (size_t)min(row, M - 1) * ldb + kk;
-        bhp[u] = bh + off; blp[u] = bl + off;
+        const size_t off = (size_t)min(row, M - 1) * p.ldb + kk;
+        bhp[u] = p.bh + off; blp[u] = p.bl + off;
         bdst[u] = row * M6_PITCH + kk * 2;
     }
-    u32x4_t ra[M6_D][2], rh[M6_D][2], rl[M6_D][2];
+    u32x4_t ra[M6_D][NT][2], rh[M6_D][2], rl[M6_D][2];
     auto gload = [&](int slot, int ck) {
         const int k0 = ck * M6_CK;
 #pragma unroll
-        for (int j = 0; j < 2; j++) ra[slot][j] = gv_load(ap + (size_t)(4 * j) * K + k0);
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) ra[slot][t][j] = gv_load(ap[t][j] + k0);
 #pragma unroll
         for (int u = 0; u < 2; u++) {
             rh[slot][u] = *reinterpret_cast<const u32x4_t*>(bhp[u] + k0);
@@ -1173,8 +1207,10 @@ __global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __rest
     auto stage = [&](int slot) {
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 2; j++)
-            *reinterpret_cast<u32x4_t*>(As + (arow + 4 * j) * M6_PITCH + acol * 2) = ra[slot][j];
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+                *reinterpret_cast<u32x4_t*>(As + (t * 64 + arow + 4 * j) * M6_PITCH + acol * 2) = ra[slot][t][j];
 #pragma unroll
         for (int u = 0; u < 2; u++) {
             *reinterpret_cast<u32x4_t*>(Bh + bdst[u]) = rh[slot][u];
@@ -1184,33 +1220,52 @@ __global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __rest
     };
     const int kq = wave & 3, nh = wave >> 2;             // k-step of the stripe, half of the weight rows
     const int MT = (M + 15) >> 4;                        // live 16-row groups of activation rows
-    f32x4_t acc[2][4];
+    f32x4_t acc[NT][2][4];
 #pragma unroll
-    for (int i = 0; i < 2; i++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    auto multiply = [&]() {
-        const int off = kq * 64 + g * 16;
-        u32x4_t a[2];
+    for (int t = 0; t < NT; t++)
 #pragma unroll
         for (int i = 0; i < 2; i++)
-            a[i] = *reinterpret_cast<const u32x4_t*>(As + ((nh * 2 + i) * 16 + r16) * M6_PITCH + off);
+#pragma unroll
+            for (int j = 0; j < 4; j++) acc[t][i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&]() {
+        const int off = kq * 64 + g * 16;
+        u32x4_t a[NT][2];
+#pragma unroll
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int i = 0; i < 2; i++)
+                a[t][i] = *reinterpret_cast<const u32x4_t*>(As + (t * 64 + (nh * 2 + i) * 16 + r16) * M6_PITCH + off);
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             if (j < MT) {   // uniform
                 const u32x4_t h = *reinterpret_cast<const u32x4_t*>(Bh + (j * 16 + r16) * M6_PITCH + off);
                 const u32x4_t l = *reinterpret_cast<const u32x4_t*>(Bl + (j * 16 + r16) * M6_PITCH + off);
-                // two independent accumulators between the two updates of any one of them
+                // independent accumulators between the two updates of any one of them
 #pragma unroll
-                for (int i = 0; i < 2; i++) acc[i][j] = mfma_h16<F16>(a[i], h, acc[i][j]);
+                for (int t = 0; t < NT; t++)
 #pragma unroll
-                for (int i = 0; i < 2; i++) acc[i][j] = mfma_h16<F16>(a[i], l, acc[i][j]);
+                    for (int i = 0; i < 2; i++) acc[t][i][j] = mfma_h16<F16>(a[t][i], h, acc[t][i][j]);
+#pragma unroll
+                for (int t = 0; t < NT; t++)
+#pragma unroll
+                    for (int i = 0; i < 2; i++) acc[t][i][j] = mfma_h16<F16>(a[t][i], l, acc[t][i][j]);
             }
         }
     };
 #pragma unroll
     for (int sl = 0; sl < M6_D; sl++)
         if (sl < NC) gload(sl, sl);
+    // RMS scale of every activation row from the producer's per-tile sums of squares (read by the epilogue)
+    if (tid < 64) rs[tid] = 1.0f;
+    if (MODE != RM_RESID && p.ssq) {
+        __syncthreads();
+        for (int c = wave; c < M; c += 8) {
+            float sq = 0.f;
+            for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)c * p.n_ssq + i];
+            sq = wave_sum(sq);
+            if (lane == 0) rs[c] = 1.0f / sqrtf(sq / (float)K + p.eps);
+        }
+    }
     int ck0 = 0;
     for (; ck0 + 2 * M6_D <= NC; ck0 += M6_D) {   // steady state: every step refills its slot
 #pragma unroll
@@ -1231,34 +1286,86 @@ __global__ __launch_bounds__(512) void rows_mfma64_kernel(const uint16_t* __rest
         }
     }
     // Sum the four k-step partials of every output, one band of 16 activation rows at a time, through LDS:
-    // red[wave][i][256], element row * 16 + column of the D layout (lane (c = lane % 16, g) holds weight rows
-    // 4g .. 4g+3 of activation row c).
-    float* red = reinterpret_cast<float*>(sm6);   // 8 x 2 x 256 floats = 16 KB
+    // red[t][wave][i][256], element row * 16 + column of the D layout (lane (c = lane % 16, g) holds weight
+    // rows 4g .. 4g+3 of activation row c), then the epilogue: thread -> (weight row nn, activation row c).
+    float* red = reinterpret_cast<float*>(sm6);   // NT x 8 x 2 x 256 floats = NT x 16 KB
+    const int tq = p.dq >> 6, tk = p.dkv >> 6;
     for (int j = 0; j < MT; j++) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 2; i++)
+        for (int t = 0; t < NT; t++)
 #pragma unroll
-            for (int e = 0; e < 4; e++) {
-                float v;
-                switch (j) {  // acc is indexed by compile-time constants only
-                    case 0: v = acc[i][0][e]; break;
-                    case 1: v = acc[i][1][e]; break;
-                    case 2: v = acc[i][2][e]; break;
-                    default: v = acc[i][3][e]; break;
+            for (int i = 0; i < 2; i++)
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    float v;
+                    switch (j) {  // acc is indexed by compile-time constants only
+                        case 0: v = acc[t][i][0][e]; break;
+                        case 1: v = acc[t][i][1][e]; break;
+                        case 2: v = acc[t][i][2][e]; break;
+                        default: v = acc[t][i][3][e]; break;
+                    }
+                    red[((t * 8 + wave) * 2 + i) * 256 + (g * 4 + e) * 16 + r16] = v;
                 }
-                red[(wave * 2 + i) * 256 + (g * 4 + e) * 16 + r16] = v;
-            }
         __syncthreads();
-        // 64 weight rows x 16 activation rows = 1024 outputs, two per thread; consecutive threads -> consecutive n
-        for (int o = tid; o < 1024; o += 512) {
-            const int nn = o & 63, c = o >> 6;     // weight row inside the tile, activation row inside the band
-            const int st = nn >> 4, hh = st >> 1, ii = st & 1;
-            float t = 0.f;
+        float val[2], val2[2];
 #pragma unroll
-            for (int q = 0; q < 4; q++) t += red[((hh * 4 + q) * 2 + ii) * 256 + (nn & 15) * 16 + c];
+        for (int it = 0; it < 2; it++) {   // 64 weight rows x 16 activation rows = 1024 outputs, two per thread
+            const int o = tid + it * 512;
+            const int nn = o & 63, c = o >> 6;
+            const int st = nn >> 4, hh = st >> 1, ii = st & 1;
+            float v = 0.f, v2 = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                v += red[((hh * 4 + q) * 2 + ii) * 256 + (nn & 15) * 16 + c];
+                if (MODE == RM_SWIGLU) v2 += red[(((8 + hh * 4 + q) * 2) + ii) * 256 + (nn & 15) * 16 + c];
+            }
             const int m = j * 16 + c;
-            if (m < M) y[(size_t)m * ldy + n0 + nn] = t;
+            if (MODE != RM_RESID) { v *= rs[m]; v2 *= rs[m]; }
+            val[it] = v; val2[it] = v2;
+            if (MODE == RM_QKV) fin[nn * 16 + c] = v;
+        }
+        if (MODE == RM_QKV) __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 2; it++) {
+            const int o = tid + it * 512;
+            const int nn = o & 63, c = o >> 6;      // c (and so m) is uniform over a wave, nn = lane
+            const int m = j * 16 + c;
+            if (m >= M) continue;
+            const float v = val[it];
+            const size_t colx = (size_t)n0 + nn;
+            if (MODE == RM_STORE) {
+                p.y[(size_t)m * p.ldy + colx] = v;
+            } else if (MODE == RM_SWIGLU) {
+                split_store(v / (1.0f + __expf(-v)) * val2[it], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
+            } else if (MODE == RM_RESID) {
+                float* dst = p.y + (size_t)m * p.ldy + colx;
+                const float tv = *dst + v;
+                *dst = tv;
+                if (p.tap) p.tap[(size_t)m * p.tap_ld + colx] = tv;
+                if (p.gain_out) {
+                    split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
+                    const float sq = wave_sum(tv * tv);   // the wave holds the tile's 64 columns of row m
+                    if (lane == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile] = sq;
+                }
+            } else {  // QKV: rotary pairs are (nn, nn + 32) for nn < 32
+                const int pos = p.pos_dev[0] + p.pos_off + m;
+                if (tile < tq + tk) {
+                    const bool is_q = tile < tq;
+                    const int tt = is_q ? tile : tile - tq;
+                    const int tph = p.hd >> 6, head = tt / tph, th = tt % tph, half = p.hd >> 1;
+                    const int i = th * 32 + (nn & 31);
+                    const float av = fin[(nn & 31) * 16 + c], bv = fin[((nn & 31) + 32) * 16 + c];
+                    const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+                    const float ov = nn < 32 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
+                    const int e = nn < 32 ? i : i + half;
+                    if (is_q) p.y[(size_t)m * p.ldy + (size_t)head * p.hd + e] = ov;
+                    else ((uint16_t*)p.kc)[((size_t)head * p.max_seq + pos) * p.hd + e] = f32_to_h16_bits(ov, F16);
+                } else {
+                    const int e = (tile - tq - tk) * 64 + nn;
+                    ((uint16_t*)p.vc)[((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd)] = f32_to_h16_bits(v, F16);
+                }
+            }
         }
     }
 }
@@ -1268,36 +1375,81 @@ bool rows_many_supported(const Dims& D, int N, int K)
     return D.wt != WT_F32 && N % 64 == 0 && K % M6_CK == 0 && K >= M6_CK;
 }
 
-static int g_many_depth = 1;  // tuning hook (1 measured best: three blocks per CU already overlap)
-void rows_many_depth(int d) { g_many_depth = d; }
+// every GEMM of a layer and the LM head fit the 64 x 64 x 128 tiling
+bool rows_wide_supported(const Dims& D)
+{
+    return D.wt != WT_F32 && D.d % 128 == 0 && D.dq % 128 == 0 && D.f % 128 == 0 && D.dkv % 64 == 0 && D.V % 64 == 0 &&
+           (D.hd == 64 || D.hd == 128);
+}
+
+template <int MODE, bool F16, int DEPTH>
+static hipError_t launch_wide_d(const RowsP2& p, int n_tiles, hipStream_t s)
+{
+    constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
+    const size_t lds = (size_t)(NT * 64 + 128) * M6_PITCH;
+    static bool attr_set = false;  // per instantiation
+    if (lds > 64 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)rows_wide_kernel<MODE, F16, DEPTH>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((rows_wide_kernel<MODE, F16, DEPTH>), dim3(n_tiles), dim3(512), lds, s, p);
+    return hipGetLastError();
+}
+
+static int g_wide_depth = 0;  // tuning hook (kernel_bench): > 0 forces the number of stripes in flight
+void rows_wide_depth(int d) { g_wide_depth = d; }
+
+// One stripe in flight per block measured best or equal everywhere: what bounds a block is the 40 GB/s or so
+// that a single CU pulls from the cache (a stripe is 48-64 KB of weights and rows), not latency.
+template <int MODE, bool F16>
+static hipError_t launch_wide(const RowsP2& p, int n_tiles, hipStream_t s)
+{
+    (void)n_tiles;
+    const int depth = g_wide_depth > 0 ? g_wide_depth : 1;
+    if (depth >= 4) return launch_wide_d<MODE, F16, 4>(p, n_tiles, s);
+    if (depth >= 2) return launch_wide_d<MODE, F16, 2>(p, n_tiles, s);
+    return launch_wide_d<MODE, F16, 1>(p, n_tiles, s);
+}
+
+static void fill_rows_params(const Dims& D, const RowsFused& f, RowsP2& p)
+{
+    for (int i = 0; i < 3; i++) { p.w[i] = f.w[i]; p.n[i] = f.n[i]; }
+    p.K = f.K; p.bh = f.bh; p.bl = f.bl; p.ldb = f.ldb; p.y = f.y; p.ldy = f.ldy; p.oh = f.oh; p.ol = f.ol; p.ldo = f.ldo;
+    p.tap = f.tap; p.tap_ld = f.tap_ld; p.M = f.M; p.rope = f.rope; p.pos_dev = f.pos_dev; p.pos_off = f.pos_off;
+    p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq; p.kc = f.kc; p.vc = f.vc;
+    p.ssq = f.ssq; p.n_ssq = f.n_ssq; p.eps = D.eps; p.gain_out = f.gain_out; p.ssq_out = f.ssq_out;
+}
+
+hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
+{
+    if (D.wt == WT_F32 || f.M < 1 || f.M > 64 || f.K % M6_CK || f.K < M6_CK) return hipErrorInvalidValue;
+    if (f.n[0] % 64 || f.n[1] % 64 || f.n[2] % 64) return hipErrorInvalidValue;
+    if (f.ssq && (f.mode == RM_RESID || f.n_ssq < 1)) return hipErrorInvalidValue;
+    if (f.gain_out && (f.mode != RM_RESID || !f.oh || !f.ol || !f.ssq_out)) return hipErrorInvalidValue;
+    if (f.mode == RM_QKV && (f.n[0] != D.dq || f.n[1] != D.dkv || f.n[2] != D.dkv || (D.hd != 64 && D.hd != 128)))
+        return hipErrorInvalidValue;
+    RowsP2 p = {};
+    fill_rows_params(D, f, p);
+    const int n_tiles = f.mode == RM_SWIGLU ? f.n[0] / 64 : (f.n[0] + f.n[1] + f.n[2]) / 64;
+    const bool f16 = D.wt == WT_F16;
+    switch (f.mode) {
+        case RM_STORE: return f16 ? launch_wide<RM_STORE, true>(p, n_tiles, s) : launch_wide<RM_STORE, false>(p, n_tiles, s);
+        case RM_RESID: return f16 ? launch_wide<RM_RESID, true>(p, n_tiles, s) : launch_wide<RM_RESID, false>(p, n_tiles, s);
+        case RM_SWIGLU: return f16 ? launch_wide<RM_SWIGLU, true>(p, n_tiles, s) : launch_wide<RM_SWIGLU, false>(p, n_tiles, s);
+        case RM_QKV: return f16 ? launch_wide<RM_QKV, true>(p, n_tiles, s) : launch_wide<RM_QKV, false>(p, n_tiles, s);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t* bh, const uint16_t* bl, int ldb, int M,
                      float* y, int ldy, hipStream_t s)
 {
-    if (!rows_many_supported(D, N, K) || M < 1 || M > 64 || ldy % 4) return hipErrorInvalidValue;
-    const size_t lds = (size_t)3 * 64 * M6_PITCH;
-    const int d = g_many_depth < 1 ? 1 : (g_many_depth > 3 ? 3 : g_many_depth);
-    const bool f16 = D.wt == WT_F16;
-    const void* fn = f16 ? (d == 1 ? (const void*)rows_mfma64_kernel<1, true> : d == 2 ? (const void*)rows_mfma64_kernel<2, true>
-                                                                                       : (const void*)rows_mfma64_kernel<3, true>)
-                         : (d == 1 ? (const void*)rows_mfma64_kernel<1, false> : d == 2 ? (const void*)rows_mfma64_kernel<2, false>
-                                                                                        : (const void*)rows_mfma64_kernel<3, false>);
-    static bool attr[2][4] = {{false, false, false, false}, {false, false, false, false}};
-    if (lds > 64 * 1024 && !attr[f16][d]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr[f16][d] = true;
-    }
-    const dim3 grid(N / 64), block(512);
-    const uint16_t* wp = (const uint16_t*)w;
-#define SSD_LAUNCH_MANY(DD, FF) hipLaunchKernelGGL((rows_mfma64_kernel<DD, FF>), grid, block, lds, s, wp, K, bh, bl, ldb, M, y, ldy)
-    if (f16) {
-        if (d == 1) SSD_LAUNCH_MANY(1, true); else if (d == 2) SSD_LAUNCH_MANY(2, true); else SSD_LAUNCH_MANY(3, true);
-    } else {
-        if (d == 1) SSD_LAUNCH_MANY(1, false); else if (d == 2) SSD_LAUNCH_MANY(2, false); else SSD_LAUNCH_MANY(3, false);
-    }
-#undef SSD_LAUNCH_MANY
-    return hipGetLastError();
+    if (!rows_many_supported(D, N, K)) return hipErrorInvalidValue;
+    RowsFused f = {};
+    f.w[0] = w; f.n[0] = N; f.K = K; f.bh = bh; f.bl = bl; f.ldb = ldb; f.y = y; f.ldy = ldy; f.M = M; f.mode = RM_STORE;
+    return rows_wide(D, f, s);
 }
 
 bool rows_fused_supported(const Dims& D)
@@ -1309,11 +1461,7 @@ hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s)
 {
     if (!rows_fused_supported(D) || f.M < 1 || f.M > 16 || f.K % 64) return hipErrorInvalidValue;
     RowsP2 p = {};
-    for (int i = 0; i < 3; i++) { p.w[i] = f.w[i]; p.n[i] = f.n[i]; }
-    p.K = f.K; p.bh = f.bh; p.bl = f.bl; p.ldb = f.ldb; p.y = f.y; p.ldy = f.ldy; p.oh = f.oh; p.ol = f.ol; p.ldo = f.ldo;
-    p.tap = f.tap; p.tap_ld = f.tap_ld; p.M = f.M; p.rope = f.rope; p.pos_dev = f.pos_dev; p.pos_off = f.pos_off;
-    p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq; p.kc = f.kc; p.vc = f.vc;
-    p.ssq = f.ssq; p.n_ssq = f.n_ssq; p.eps = D.eps; p.gain_out = f.gain_out; p.ssq_out = f.ssq_out;
+    fill_rows_params(D, f, p);
     if (f.ssq && (f.mode == RM_RESID || f.n_ssq < 1)) return hipErrorInvalidValue;
     if (f.gain_out && (f.mode != RM_RESID || !f.oh || !f.ol || !f.ssq_out)) return hipErrorInvalidValue;
     switch (f.mode) {
@@ -1361,20 +1509,19 @@ hipError_t rows_prep(const Dims& D, const float* in, int ldx, const float* gain,
 }
 
 // Entry of the fused path (rows straight from the embedding): hi/lo = split(x * gain) without the
-// norm scale, and the sums of squares of every 16 consecutive elements, i.e. exactly what a RESID
-// projection leaves behind for its consumer.
+// norm scale, and the sums of squares of every `group` (16 or 64) consecutive elements, i.e. exactly what a
+// RESID projection with tiles of that width leaves behind for its consumer.
 __global__ __launch_bounds__(256) void rows_gain_split_kernel(const float* __restrict__ in, int ldx,
                                                               const float* __restrict__ gain, int K,
                                                               uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
-                                                              float* __restrict__ ssq, bool f16)
+                                                              float* __restrict__ ssq, bool f16, int group)
 {
     const float* x = in + (size_t)blockIdx.x * ldx;
-    const int n_t = K >> 4;
+    const int n_t = K / group;
     for (int t = threadIdx.x; t < n_t; t += 256) {
         float sq = 0.f;
-#pragma unroll
-        for (int u = 0; u < 16; u += 4) {
-            const int i = t * 16 + u;
+        for (int u = 0; u < group; u += 4) {
+            const int i = t * group + u;
             const float4 v = *reinterpret_cast<const float4*>(x + i);
             const float4 g = *reinterpret_cast<const float4*>(gain + i);
             sq += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
@@ -1387,10 +1534,10 @@ __global__ __launch_bounds__(256) void rows_gain_split_kernel(const float* __res
 }
 
 hipError_t rows_gain_split(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, uint16_t* hi, uint16_t* lo,
-                           float* ssq, hipStream_t s)
+                           float* ssq, int group, hipStream_t s)
 {
-    if (K % 16 || !gain) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(rows_gain_split_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, hi, lo, ssq, D.wt == WT_F16);
+    if ((group != 16 && group != 64) || K % group || !gain) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rows_gain_split_kernel, dim3(M), dim3(256), 0, s, in, ldx, gain, K, hi, lo, ssq, D.wt == WT_F16, group);
     return hipGetLastError();
 }
 

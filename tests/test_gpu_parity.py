@@ -27,10 +27,10 @@ def ssd():
 
 
 @pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16"])
-@pytest.mark.parametrize("plen", [1, 16, 17, 45])
+@pytest.mark.parametrize("plen", [1, 16, 17, 45, 64, 65, 150])   # 16-row and 64-row prompt blocks, ragged tails
 def test_prefill_logits_and_first_token(ssd, name, plen):
     shape = SHAPES[name]
-    orc, ctx = make_pair(shape, 5, 64, norm_gain_std=0.1)
+    orc, ctx = make_pair(shape, 5, 160, norm_gain_std=0.1)
     prompt = make_prompt(shape.vocab, plen, 3).tolist()
     ref = orc.forward(prompt, 0)["logits"][-1]
     tok = ctx.ssd_prefill(prompt)
