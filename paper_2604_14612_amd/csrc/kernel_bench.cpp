@@ -189,11 +189,12 @@ int main(int argc, char** argv)
             f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
             f.bh = hi64; f.bl = lo64; f.ldb = K; f.y = y; f.ldy = ldy; f.oh = hi64; f.ol = lo64; f.ldo = 11008; f.M = 64; f.mode = mode;
             f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
+            f.kpart = part; f.kpart_floats = (size_t)16 << 20;
             CK(rows_wide(D, f, 0));
         };
-        for (int depth : {0, 1, 2, 4}) {
-        rows_wide_depth(depth);
-        std::printf("-- 64-row pass (prompt blocks), stripes in flight %d (0 = library's choice)\n", depth);
+        for (int ks : {0, 1, 2, 4, 8}) {
+        rows_wide_ksplit(ks);
+        std::printf("-- 64-row pass (prompt blocks), K slices of the projections back to d_model: %d (0 = library's choice, 1 = none)\n", ks);
         timeit("wide_qkv", 3 * qk * 2.0, n, [&](int i) {
             const uint16_t* w = W + (size_t)i * 3 * qk;
             wide(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, big_a, 4096); });
@@ -203,7 +204,7 @@ int main(int argc, char** argv)
             wide(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
         timeit("wide_down (resid)", gu * 2.0, n, [&](int i) { wide(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, big_b, 4096); });
         }
-        rows_wide_depth(0);
+        rows_wide_ksplit(0);
     }
     for (int kind : {1, 0}) {
         attention_force_kernel(kind);
@@ -220,5 +221,12 @@ int main(int argc, char** argv)
     }
     attention_force_splits(0);
     attention_force_kernel(0);
+    for (int rows : {16, 64}) {
+        char nm[96];
+        std::snprintf(nm, sizeof nm, "attention %d rows ctx 640+rows (prompt block)", rows);
+        timeit(nm, 2.0 * (640 + rows) * 4096 * 2, n, [&](int i) {
+            CK(attention(D, big_a, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, rows, part, nullptr,
+                         hi64, lo64, 0)); });
+    }
     return 0;
 }

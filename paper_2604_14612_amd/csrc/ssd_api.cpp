@@ -29,6 +29,7 @@ struct Layout {
     int conf_rows;  // rows of one confidence pass: 2 * L
     int logit_rows;
     size_t kv_layer_elems;  // elements of K (or V) of one layer
+    size_t part_floats;     // floats in the attention scratch (also the K-split scratch of the 64-row projections)
 };
 
 bool valid_cfg(const ssd_config* c)
@@ -76,7 +77,8 @@ Layout make_layout(const ssd_config& c)
     l.qkv = o;    o += align_up((size_t)l.rows * (D.dq + 2 * D.dkv) * sizeof(float));
     l.att = o;    o += align_up((size_t)l.rows * D.dq * sizeof(float));
     l.act = o;    o += align_up((size_t)l.rows * D.f * sizeof(float));
-    l.part = o;   o += align_up(attention_scratch_floats(D, l.rows) * sizeof(float));
+    l.part_floats = attention_scratch_floats(D, l.rows);
+    l.part = o;   o += align_up(l.part_floats * sizeof(float));
     l.logits = o; o += align_up((size_t)l.logit_rows * D.V * sizeof(float));
     l.taps = o;   o += align_up((size_t)l.rows * D.L * 2 * D.d * sizeof(float));
     l.tapn = o;   o += align_up((size_t)l.conf_rows * D.d * sizeof(float));
@@ -268,6 +270,7 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
             o.w[0] = c->wo[l]; o.n[0] = D.d; o.K = D.dq; o.bh = hi; o.bl = lo; o.ldb = D.dq; o.y = x; o.ldy = D.d; o.M = M;
             o.mode = 1; o.tap = c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d; o.tap_ld = tap_ld;
             o.gain_out = c->mlp_norm[l]; o.oh = xh; o.ol = xl; o.ldo = D.d; o.ssq_out = ssq;
+            o.kpart = c->f(Y.part); o.kpart_floats = Y.part_floats;   // attention is done with its scratch
             TIMED(SSD_K_ROWS_O, rows_wide(D, o, c->stream), "wide_o");
             RowsFused gu = {};
             gu.w[0] = c->wg[l]; gu.w[1] = c->wu[l]; gu.n[0] = D.f; gu.n[1] = D.f; gu.K = D.d; gu.bh = xh; gu.bl = xl;
@@ -282,6 +285,7 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
                 dn.gain_out = l + 1 < D.L ? c->attn_norm[l + 1] : c->w.final_norm;
                 dn.oh = xh; dn.ol = xl; dn.ldo = D.d; dn.ssq_out = ssq;
             }
+            dn.kpart = c->f(Y.part); dn.kpart_floats = Y.part_floats;
             TIMED(SSD_K_ROWS_DOWN, rows_wide(D, dn, c->stream), "wide_down");
         }
         if (want_logits) {   // last row only, through the 16-row kernel with one row

@@ -845,6 +845,7 @@ struct RowsP2 {
     void* kc; void* vc;
     const float* ssq; int n_ssq; float eps;     // consumer: partial sums of squares [M][n_ssq] of the input rows (or null)
     const float* gain_out; float* ssq_out;      // RESID producer: gain of the next norm -> oh/ol = split(x * gain), ssq_out [M][n/16]
+    int ksplit; float* kpart;                   // wide RESID only: K cut into ksplit slices (grid.y), raw sums to kpart [ksplit][M][n]
 };
 
 // hi = rne(v), lo = rne(v - hi) in the 16-bit storage type (bf16, or fp16 when f16 is set)
@@ -1172,7 +1173,11 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
     const int r16 = lane & 15, g = lane >> 4;
     const int tile = blockIdx.x, n0 = tile * 64;
     const int K = p.K, M = p.M;
-    const int NC = K / M6_CK;
+    // this block's stripes: all of K, or slice blockIdx.y of ksplit (projections with few tiles are cut along K so
+    // that every CU has a block; their raw sums go to kpart and rows_finish_resid_kernel adds them up in order)
+    const int NCall = K / M6_CK;
+    const int S = MODE == RM_RESID && p.ksplit > 1 ? p.ksplit : 1;
+    const int c_begin = (int)((long)NCall * blockIdx.y / S), NC = (int)((long)NCall * (blockIdx.y + 1) / S) - c_begin;
     // weights: wave w loads logical rows 8w .. 8w+7; instruction j covers rows 8w+4j .. 8w+4j+3 (16 lanes = 256 B per row)
     const int arow = 8 * wave + (lane >> 4), acol = (lane & 15) * 8;
     const uint16_t* ap[NT][2];
@@ -1193,7 +1198,7 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
     }
     u32x4_t ra[M6_D][NT][2], rh[M6_D][2], rl[M6_D][2];
     auto gload = [&](int slot, int ck) {
-        const int k0 = ck * M6_CK;
+        const int k0 = (c_begin + ck) * M6_CK;
 #pragma unroll
         for (int t = 0; t < NT; t++)
 #pragma unroll
@@ -1339,6 +1344,10 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
             } else if (MODE == RM_SWIGLU) {
                 split_store(v / (1.0f + __expf(-v)) * val2[it], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
             } else if (MODE == RM_RESID) {
+                if (S > 1) {
+                    p.kpart[((size_t)blockIdx.y * M + m) * p.n[0] + colx] = v;
+                    continue;
+                }
                 float* dst = p.y + (size_t)m * p.ldy + colx;
                 const float tv = *dst + v;
                 *dst = tv;
@@ -1370,6 +1379,25 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
     }
 }
 
+// Second half of a K-split RESID projection: one wave per (row, 64-column tile) adds the slices in order, then
+// does what the unsplit epilogue does (residual add, tap, hi/lo of x * gain, sum of squares of the tile).
+__global__ __launch_bounds__(64) void rows_finish_resid_kernel(RowsP2 p, bool f16)
+{
+    const int tile = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
+    const size_t colx = (size_t)tile * 64 + lane;
+    float v = 0.f;
+    for (int sl = 0; sl < p.ksplit; sl++) v += p.kpart[((size_t)sl * p.M + m) * p.n[0] + colx];
+    float* dst = p.y + (size_t)m * p.ldy + colx;
+    const float tv = *dst + v;
+    *dst = tv;
+    if (p.tap) p.tap[(size_t)m * p.tap_ld + colx] = tv;
+    if (p.gain_out) {
+        split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, f16);
+        const float sq = wave_sum(tv * tv);
+        if (lane == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile] = sq;
+    }
+}
+
 bool rows_many_supported(const Dims& D, int N, int K)
 {
     return D.wt != WT_F32 && N % 64 == 0 && K % M6_CK == 0 && K >= M6_CK;
@@ -1394,12 +1422,18 @@ static hipError_t launch_wide_d(const RowsP2& p, int n_tiles, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((rows_wide_kernel<MODE, F16, DEPTH>), dim3(n_tiles), dim3(512), lds, s, p);
+    const int S = MODE == RM_RESID && p.ksplit > 1 ? p.ksplit : 1;
+    hipLaunchKernelGGL((rows_wide_kernel<MODE, F16, DEPTH>), dim3(n_tiles, S), dim3(512), lds, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || S == 1) return e;
+    hipLaunchKernelGGL(rows_finish_resid_kernel, dim3(n_tiles, p.M), dim3(64), 0, s, p, F16);
     return hipGetLastError();
 }
 
 static int g_wide_depth = 0;  // tuning hook (kernel_bench): > 0 forces the number of stripes in flight
 void rows_wide_depth(int d) { g_wide_depth = d; }
+static int g_wide_ksplit = 0;  // tuning hook: 1 = never cut K, > 1 forces the number of slices
+void rows_wide_ksplit(int n) { g_wide_ksplit = n; }
 
 // One stripe in flight per block measured best or equal everywhere: what bounds a block is the 40 GB/s or so
 // that a single CU pulls from the cache (a stripe is 48-64 KB of weights and rows), not latency.
@@ -1434,6 +1468,17 @@ hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
     fill_rows_params(D, f, p);
     const int n_tiles = f.mode == RM_SWIGLU ? f.n[0] / 64 : (f.n[0] + f.n[1] + f.n[2]) / 64;
     const bool f16 = D.wt == WT_F16;
+    // A block is bound by what one CU pulls from the cache (about 40 GB/s), so a projection with fewer tiles than
+    // CUs is cut along K until there are about 256 blocks; needs scratch for ksplit x M x n partial sums.
+    p.ksplit = 1; p.kpart = nullptr;
+    if (f.mode == RM_RESID && f.kpart && f.n[1] == 0 && f.n[2] == 0 && g_wide_ksplit != 1) {
+        int ks = g_wide_ksplit > 1 ? g_wide_ksplit : 256 / n_tiles;
+        const int nc = f.K / M6_CK;
+        if (ks > 8) ks = 8;
+        if (ks > nc) ks = nc;
+        if ((size_t)ks * f.M * f.n[0] > f.kpart_floats) ks = (int)(f.kpart_floats / ((size_t)f.M * f.n[0]));
+        if (ks > 1) { p.ksplit = ks; p.kpart = f.kpart; }
+    }
     switch (f.mode) {
         case RM_STORE: return f16 ? launch_wide<RM_STORE, true>(p, n_tiles, s) : launch_wide<RM_STORE, false>(p, n_tiles, s);
         case RM_RESID: return f16 ? launch_wide<RM_RESID, true>(p, n_tiles, s) : launch_wide<RM_RESID, false>(p, n_tiles, s);
