@@ -407,3 +407,25 @@ def test_longest_draft_fills_the_row_block(ssd, name):
         if not any(mask) and st["unpinned_cycles"] == 0:
             assert all(a == 15 for a in st["accepted"])
         ctx.ssd_reset()
+
+
+def test_generation_loops_agree_on_the_library(ssd):
+    """generate_conflayers (search active, then with the confidence-aware draft exit) against generate_vanilla on
+    the same context: lossless verification makes the two token streams equal up to the first near-tie that the
+    single-row and the multi-row kernels round differently."""
+    shape = WORKLOADS["tiny"].shape
+    w = to_gpu(make_weights(shape, 3))
+    ctx = ssd.Context(shape, w, 400, max_k=6)
+    prompt = make_prompt(shape.vocab, 20, 9).tolist()
+    van = ssd.generate_vanilla(ctx, prompt, 120)
+    for gamma in (None, 0.003):
+        ctx.ssd_reset()
+        sr = ssd.Search(shape.n_layers, ssd.search_defaults(opt_interval=6, max_rounds=4), ssd.select_defaults(protect_ends=0))
+        got, st = ssd.generate_conflayers(ctx, prompt, 120, k=6, search=sr, gamma=gamma)
+        first_diff = next((i for i, (a, b) in enumerate(zip(got, van)) if a != b), 120)
+        print("generate gamma", gamma, "cycles", st["cycles"], "drafted", st["drafted"], "accepted", st["accepted"],
+              "rounds", st["search_rounds"], "first diff", first_diff)
+        assert len(got) == 120 and first_diff >= 60
+        assert st["search_rounds"] >= 1 and st["drafted"] >= st["cycles"]
+        if gamma is not None:
+            assert st["drafted"] < 6 * st["cycles"]          # the exit rule shortened some drafts
