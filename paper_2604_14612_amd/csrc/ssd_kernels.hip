@@ -2083,9 +2083,11 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     AttnPlan pl;
     pl.defer_fold = false;
     const int Q = (D.H / D.Hkv) * M;
-    // a few rows of a model without grouped heads: still the register-resident kernel, one block per row (the
-    // rows re-read a range's K/V from the cache, which at up to AW_MAX_ROWS rows is cheaper than the LDS-staged kernel)
-    pl.wide = Q <= AW_MAXQ_TOTAL || (D.H == D.Hkv && M <= AW_MAX_ROWS);
+    // a few rows with at most 4 query heads per KV head: still the register-resident kernel, one block per row
+    // and range serving the row's group of heads (the rows re-read a range's K/V from the cache, which at up to
+    // AW_MAX_ROWS rows is cheaper than the LDS-staged kernel)
+    const int G = D.H / D.Hkv;
+    pl.wide = Q <= AW_MAXQ_TOTAL || ((G == 1 || G == 2 || G == 4) && M <= AW_MAX_ROWS);
     if (g_force_attn == 1) pl.wide = false;
     if (pl.wide) {
         // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
@@ -2133,13 +2135,14 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
     if (n_splits < 1 || (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK))) return hipErrorInvalidValue;
     if (pl.wide) {
         int Q = (D.H / D.Hkv) * M, zq = 1;
-        if (Q > AW_MAXQ_TOTAL) { zq = Q; Q = 1; }  // one block per query vector: K/V of a range re-read from cache per row
+        if (Q > AW_MAXQ_TOTAL) { zq = M; Q = D.H / D.Hkv; }  // one block per row (its group of heads) and range
         const int span = ceil_div(ctx, n_splits) * (HD / (16 / (int)sizeof(KT)));  // lanes' worth of 16-byte vectors per range
         if (Q == 1 && span <= 8 * 64 * 4) launch_attn_wide<KT, HD, 1, 8, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
         else if (Q == 1 && span <= 16 * 64 * 4) launch_attn_wide<KT, HD, 1, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
         else if (Q == 1) launch_attn_wide<KT, HD, 1, 8, 16>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
-        else if (Q == 2) launch_attn_wide<KT, HD, 2, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
-        else launch_attn_wide<KT, HD, 4, 8, 8>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, 1, M, part, out, out_hi, out_lo, s);
+        else if (Q == 2) launch_attn_wide<KT, HD, 2, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
+        else if (span <= 8 * 64 * 4) launch_attn_wide<KT, HD, 4, 8, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
+        else launch_attn_wide<KT, HD, 4, 8, 8>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
     } else {
         const size_t lds = attn_lds_bytes<KT, HD>();
         static bool attr_set = false;  // per instantiation
