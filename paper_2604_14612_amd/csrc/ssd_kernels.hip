@@ -2083,11 +2083,11 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     AttnPlan pl;
     pl.defer_fold = false;
     const int Q = (D.H / D.Hkv) * M;
-    // a few rows with at most 4 query heads per KV head: still the register-resident kernel, one block per row
-    // and range serving the row's group of heads (the rows re-read a range's K/V from the cache, which at up to
+    // a few rows with 1, 2, 4 or 8 query heads per KV head: still the register-resident kernel, one block per row
+    // and range serving the row's group of heads (two blocks for a group of 8) (the rows re-read a range's K/V from the cache, which at up to
     // AW_MAX_ROWS rows is cheaper than the LDS-staged kernel)
     const int G = D.H / D.Hkv;
-    pl.wide = Q <= AW_MAXQ_TOTAL || ((G == 1 || G == 2 || G == 4) && M <= AW_MAX_ROWS);
+    pl.wide = Q <= AW_MAXQ_TOTAL || ((G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
     if (g_force_attn == 1) pl.wide = false;
     if (pl.wide) {
         // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
@@ -2135,7 +2135,11 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
     if (n_splits < 1 || (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK))) return hipErrorInvalidValue;
     if (pl.wide) {
         int Q = (D.H / D.Hkv) * M, zq = 1;
-        if (Q > AW_MAXQ_TOTAL) { zq = M; Q = D.H / D.Hkv; }  // one block per row (its group of heads) and range
+        if (Q > AW_MAXQ_TOTAL) {  // one block per row (its group of heads, or half of a group of 8) and range
+            const int G = D.H / D.Hkv;
+            Q = G > 4 ? 4 : G;
+            zq = M * (G / Q);
+        }
         const int span = ceil_div(ctx, n_splits) * (HD / (16 / (int)sizeof(KT)));  // lanes' worth of 16-byte vectors per range
         if (Q == 1 && span <= 8 * 64 * 4) launch_attn_wide<KT, HD, 1, 8, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
         else if (Q == 1 && span <= 16 * 64 * 4) launch_attn_wide<KT, HD, 1, 16, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
