@@ -2092,6 +2092,9 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     if (pl.wide) {
         // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
         int ns = ceil_div(ctx, AW_RANGE);
+        // single row: up to 4 K positions, ranges grow rather than exceed what the output projection folds itself
+        // (a longer range costs the attention kernel about 1 us, a separate fold launch 5)
+        if (M == 1 && ns > GV_FOLD_MAX && ctx <= GV_FOLD_MAX * 512) ns = GV_FOLD_MAX;
         if (ns > AW_MAX_RANGES) ns = AW_MAX_RANGES;
         if (g_force_splits > 0) ns = g_force_splits;
         if (ns > ctx) ns = ctx;
