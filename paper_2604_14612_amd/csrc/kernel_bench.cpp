@@ -154,15 +154,19 @@ int main(int argc, char** argv)
         CK(vocab_reduce(logits, 1, 32000, 1e4f, 1e-10f, pos + 8, 1, nullptr, sink, nullptr, 0)); });
 
     // multi-row (verify) kernels, M rows
+    bool with_ssq = false;
     auto fused = [&](int mode, const uint16_t* w0, const uint16_t* w1, const uint16_t* w2, int n0, int n1, int n2, int K,
                      float* y, int ldy) {
         RowsFused f = {};
         f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
         f.bh = hi; f.bl = lo; f.ldb = K; f.y = y; f.ldy = ldy; f.oh = hi; f.ol = lo; f.ldo = 11008; f.M = M; f.mode = mode;
         f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
+        if (with_ssq && mode != 1) { f.ssq = gain; f.n_ssq = K / 16; }   // gain is a zeroed 1 MB buffer: values do not matter here
         CK(rows_fused(D, f, 0));
     };
-    {
+    for (int v : {0, 1}) {
+    with_ssq = v != 0;
+    std::printf("-- 16-row kernels%s\n", v ? ", consumers summing 256 sum-of-squares partials per row (RMSNorm folded in)" : "");
     timeit("rows_prep (norm+split)", M * 4096 * 8.0, n, [&](int) { CK(rows_prep(D, x, 4096, gain, M, 4096, 1e-5f, hi, lo, 0)); });
     timeit("rows_qkv", 3 * qk * 2.0, n, [&](int i) {
         const uint16_t* w = W + (size_t)i * 3 * qk;
