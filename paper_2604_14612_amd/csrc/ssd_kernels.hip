@@ -1049,17 +1049,19 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 #pragma unroll
     for (int sl = 0; sl < M3_D; sl++)
         if (sl < NC) gload(sl, sl);
-    // RMS scale of every activation row from the producer's per-tile sums of squares (read by the epilogue,
-    // many barriers from here)
-    if (tid < 16) rs[tid] = 1.0f;
-    if (MODE != RM_RESID && p.ssq) {
+    // RMS scale of every activation row from the producer's per-tile sums of squares (read by the epilogue).
+    // Measured per mode: gate/up (long-lived blocks, two stripes in flight) loses least when the partials are
+    // summed after the weight stream, the short-lived blocks of QKV and the LM head when it happens up front.
+    auto row_scales = [&]() {
         for (int c = wave; c < M; c += 8) {
             float sq = 0.f;
             for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)c * p.n_ssq + i];
             sq = wave_sum(sq);
             if (lane == 0) rs[c] = 1.0f / sqrtf(sq / (float)K + p.eps);
         }
-    }
+    };
+    if (tid < 16) rs[tid] = 1.0f;
+    if (MODE != RM_RESID && MODE != RM_SWIGLU && p.ssq) row_scales();
     int ck0 = 0;
     for (; ck0 + 2 * M3_D <= NC; ck0 += M3_D) {  // steady state: every step refills its slot, no conditions
 #pragma unroll
@@ -1079,6 +1081,7 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
             }
         }
     }
+    if (MODE == RM_SWIGLU && p.ssq) row_scales();
     __syncthreads();
     float* red = reinterpret_cast<float*>(sm3);  // [8][NT][256] floats fit inside the weight stripe area
 #pragma unroll
