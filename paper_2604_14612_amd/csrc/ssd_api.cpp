@@ -229,10 +229,11 @@ int forward_single(ssd_ctx* c, const uint8_t* skip, int slot, int slot_out, int 
         if (rc) return rc;
     }
     float* logits = c->f(c->lay.logits) + (size_t)lrow * D.V;
-    TIMED(SSD_K_GEMV_LMHEAD, gemv_lmhead(D, c->w.lm_head, c->w.final_norm, c->f(c->lay.x), logits, c->stream),
-          "gemv_lmhead");
-    TIMED(SSD_K_VOCAB, vocab_reduce(logits, 1, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, c->small_i() + SM_TOK + slot_out, 1, nullptr,
-                                    c->small_f() + SM_MAXPROB + lrow, nullptr, c->stream), "vocab_reduce");
+    // LM head with the greedy token and its soft-max probability folded in (block statistics in the attention
+    // scratch, which is idle here, then a one-block fold)
+    TIMED(SSD_K_GEMV_LMHEAD, gemv_lmhead_argmax(D, c->w.lm_head, c->w.final_norm, c->f(c->lay.x), logits, c->cfg.conf_clamp,
+                                                c->f(c->lay.part), c->small_i() + SM_TOK + slot_out,
+                                                c->small_f() + SM_MAXPROB + lrow, c->stream), "gemv_lmhead");
     return SSD_OK;
 }
 

@@ -48,6 +48,13 @@ hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const 
 void gemv_time_next_launch(hipEvent_t start, hipEvent_t stop);
 void gemv_block_cap(int n);  // tuning hook: > 0 overrides the block cap of the GEMV launches
 
+// The same with the vocabulary reduction of a greedy step folded in: every block also leaves (max, sum of exp,
+// arg-max) of its clamped logits in vstat (3 floats per block, GEMV_MAX_BLOCKS blocks at most) and a one-block
+// kernel combines them into the greedy token (lowest index among equal maxima) and its soft-max probability.
+constexpr int GEMV_MAX_BLOCKS = 1024;
+hipError_t gemv_lmhead_argmax(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits, float clamp,
+                              float* vstat, int32_t* tok_out, float* maxprob_out, hipStream_t s);
+
 // ---- multi-row (verify / prefill / confidence) path ------------------------------------------
 // out[r][:] = rmsnorm(in[r][:], gain) for r < M   (rows of length K)
 hipError_t rmsnorm_rows(const float* in, const float* gain, int M, int K, float eps, float* out, hipStream_t s);

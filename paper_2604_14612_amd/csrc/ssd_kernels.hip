@@ -188,6 +188,8 @@ struct GemvP {
     const float* rope;  // [max_seq][hd/2][2] (cos, sin)
     const int* pos_dev; int pos_off;
     int hd, dq, dkv, max_seq;
+    float* vstat;       // STORE only, may be null: per block (max, sum of exp relative to it, arg-max) of the clamped outputs
+    float clamp;
 };
 
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
@@ -252,9 +254,27 @@ __device__ __forceinline__ const WT* gv_row_ptr(const GemvP& p, int j)
     }
 }
 
+// running soft-max statistics of the rows a lane has finished: maximum, its lowest row index, sum of exp(v - max)
+struct VStat { float m; float z; int arg; };
+__device__ __forceinline__ void vstat_add(VStat& a, float v, int idx)
+{
+    if (v > a.m) { a.z = a.z * __expf(a.m - v) + 1.0f; a.m = v; a.arg = idx; }   // first row: exp(-inf) = 0
+    else a.z += __expf(v - a.m);
+}
+// merge b into a; equal maxima keep the lower index
+__device__ __forceinline__ void vstat_merge(VStat& a, const VStat& b)
+{
+    if (b.m > a.m || (b.m == a.m && b.arg < a.arg)) {
+        a.z = (a.m > -INFINITY ? a.z * __expf(a.m - b.m) : 0.f) + b.z;
+        a.m = b.m; a.arg = b.arg;
+    } else if (b.m > -INFINITY) {
+        a.z += b.z * __expf(b.m - a.m);
+    }
+}
+
 // finished sums s[0..R) of logical rows j0.. ; sc = RMS scale (1 when no norm)
 template <typename WT, int EPI, int R>
-__device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float (&s)[R], float sc)
+__device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float (&s)[R], float sc, VStat& vs)
 {
     if (EPI == EPI_QKV) {
         const int half = p.hd >> 1;
@@ -300,7 +320,11 @@ __device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float 
         }
     } else {
 #pragma unroll
-        for (int t = 0; t < R; t++) p.y[j0 + t] = s[t] * sc;
+        for (int t = 0; t < R; t++) {
+            const float v = s[t] * sc;
+            p.y[j0 + t] = v;
+            if (p.vstat) vstat_add(vs, fminf(fmaxf(v, -p.clamp), p.clamp), j0 + t);   // rows arrive in ascending order
+        }
     }
 }
 
@@ -408,6 +432,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
     }
 
     const float* xp = xs + lane_off;
+    VStat vs = {-INFINITY, 0.f, 0x7fffffff};
     int rc = 0, cc = 0;
     float acc[R];
 #pragma unroll
@@ -435,7 +460,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
 #pragma unroll
                     for (int r = 0; r < R; r++) acc[r] = wave_sum(acc[r]);
                     if (KS == 1) {
-                        if (act && lane == 0) gv_epilogue<WT, EPI, R>(p, g * R, acc, sc);
+                        if (act && lane == 0) gv_epilogue<WT, EPI, R>(p, g * R, acc, sc, vs);
                     } else {
                         if (lane == 0) {
 #pragma unroll
@@ -451,7 +476,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
                                 for (int j = 0; j < KS; j++) t += part[grp * KS + j][r];
                                 sm[r] = t;
                             }
-                            gv_epilogue<WT, EPI, R>(p, g * R, sm, sc);
+                            gv_epilogue<WT, EPI, R>(p, g * R, sm, sc, vs);
                         }
                         __syncthreads();
                     }
@@ -463,8 +488,52 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
             }
         }
     }
+    if (EPI == EPI_STORE && p.vstat) {   // block partial of the soft-max statistics: lane 0 of every wave holds one
+        __shared__ float vred[GV_WAVES * 3];
+        if (lane == 0) { vred[wave * 3] = vs.m; vred[wave * 3 + 1] = vs.z; vred[wave * 3 + 2] = __int_as_float(vs.arg); }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            VStat a = {vred[0], vred[1], __float_as_int(vred[2])};
+#pragma unroll
+            for (int w = 1; w < GV_WAVES; w++) {
+                const VStat b = {vred[w * 3], vred[w * 3 + 1], __float_as_int(vred[w * 3 + 2])};
+                vstat_merge(a, b);
+            }
+            p.vstat[blockIdx.x * 3] = a.m; p.vstat[blockIdx.x * 3 + 1] = a.z; p.vstat[blockIdx.x * 3 + 2] = __int_as_float(a.arg);
+        }
+    }
 }
 
+// Combines the per-block statistics of an LM-head launch: arg-max (lowest index among equal maxima) and the
+// soft-max probability of that token, 1 / sum exp(z - max).
+__global__ __launch_bounds__(256) void vocab_finish_kernel(const float* __restrict__ vstat, int n_blocks, int32_t* tok_out,
+                                                           float* maxprob_out)
+{
+    __shared__ float sm[256 * 3];
+    VStat a = {-INFINITY, 0.f, 0x7fffffff};
+    for (int i = threadIdx.x; i < n_blocks; i += 256) {
+        const VStat b = {vstat[i * 3], vstat[i * 3 + 1], __float_as_int(vstat[i * 3 + 2])};
+        vstat_merge(a, b);
+    }
+    sm[threadIdx.x * 3] = a.m; sm[threadIdx.x * 3 + 1] = a.z; sm[threadIdx.x * 3 + 2] = __int_as_float(a.arg);
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            VStat x = {sm[threadIdx.x * 3], sm[threadIdx.x * 3 + 1], __float_as_int(sm[threadIdx.x * 3 + 2])};
+            const int j = threadIdx.x + o;
+            const VStat y = {sm[j * 3], sm[j * 3 + 1], __float_as_int(sm[j * 3 + 2])};
+            vstat_merge(x, y);
+            sm[threadIdx.x * 3] = x.m; sm[threadIdx.x * 3 + 1] = x.z; sm[threadIdx.x * 3 + 2] = __int_as_float(x.arg);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (tok_out) tok_out[0] = __float_as_int(sm[2]);
+        if (maxprob_out) maxprob_out[0] = 1.0f / sm[1];
+    }
+}
+
+static int g_last_gemv_blocks = 0;  // grid of the most recent GEMV launch (host bookkeeping for the statistics fold)
 static hipEvent_t g_gemv_ev_start = nullptr, g_gemv_ev_stop = nullptr;
 void gemv_time_next_launch(hipEvent_t start, hipEvent_t stop) { g_gemv_ev_start = start; g_gemv_ev_stop = stop; }
 
@@ -495,6 +564,7 @@ static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
         const int rounds = ceil_div(blocks, cap);
         blocks = ceil_div(blocks, rounds);
     }
+    g_last_gemv_blocks = blocks;
     if (g_gemv_ev_start) {
         // timing request for this one launch: the events take the kernel's own begin and end timestamps
         hipExtLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, g_gemv_ev_start,
@@ -568,6 +638,21 @@ hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const 
     GemvP p = {};
     p.w0 = wlm; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = D.V; p.y = logits;
     return launch_gemv<EPI_STORE>(D.wt, p, s);
+}
+
+hipError_t gemv_lmhead_argmax(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits, float clamp,
+                              float* vstat, int32_t* tok_out, float* maxprob_out, hipStream_t s)
+{
+    if (!vstat) return hipErrorInvalidValue;
+    GemvP p = {};
+    p.w0 = wlm; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = D.V; p.y = logits;
+    p.vstat = vstat; p.clamp = clamp;
+    g_last_gemv_blocks = 0;
+    hipError_t e = launch_gemv<EPI_STORE>(D.wt, p, s);
+    if (e != hipSuccess) return e;
+    if (g_last_gemv_blocks < 1 || g_last_gemv_blocks > GEMV_MAX_BLOCKS) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(vocab_finish_kernel, dim3(1), dim3(256), 0, s, vstat, g_last_gemv_blocks, tok_out, maxprob_out);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
