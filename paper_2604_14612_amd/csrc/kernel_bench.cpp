@@ -198,7 +198,7 @@ int main(int argc, char** argv)
         };
         for (int ks : {0, 1, 2, 4, 8}) {
         rows_wide_ksplit(ks);
-        std::printf("-- 64-row pass (prompt blocks), K slices of the projections back to d_model: %d (0 = library's choice, 1 = none)\n", ks);
+        std::printf("-- 64-row pass (prompt blocks), K slices: %d (0 = library's choice, 1 = none)\n", ks);
         timeit("wide_qkv", 3 * qk * 2.0, n, [&](int i) {
             const uint16_t* w = W + (size_t)i * 3 * qk;
             wide(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, big_a, 4096); });

@@ -264,6 +264,7 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
             q.K = D.d; q.bh = xh; q.bl = xl; q.ldb = D.d; q.ssq = ssq; q.n_ssq = n_ssq; q.y = c->f(Y.qkv); q.ldy = D.dq;
             q.M = M; q.mode = 3;
             q.rope = c->f(Y.rope); q.pos_dev = c->pos_dev(); q.pos_off = pos_off; q.kc = c->kcache(l); q.vc = c->vcache(l);
+            q.kpart = c->f(Y.part); q.kpart_floats = Y.part_floats;   // the attention scratch is idle outside attention
             TIMED(SSD_K_ROWS_QKV, rows_wide(D, q, c->stream), "wide_qkv");
             TIMED(SSD_K_ATTENTION, attention(D, c->f(Y.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
                                              pos_host, M, c->f(Y.part), nullptr, hi, lo, c->stream), "attention");
@@ -278,6 +279,7 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
             gu.ldb = D.d; gu.ssq = ssq; gu.n_ssq = n_ssq;
             gu.oh = c->h16(Y.act); gu.ol = c->h16(Y.act) + (size_t)Y.rows * D.f; gu.ldo = D.f; gu.M = M;
             gu.mode = 2;
+            gu.kpart = c->f(Y.part); gu.kpart_floats = Y.part_floats;
             TIMED(SSD_K_ROWS_GATEUP, rows_wide(D, gu, c->stream), "wide_gateup");
             RowsFused dn = {};
             dn.w[0] = c->wd[l]; dn.n[0] = D.d; dn.K = D.f; dn.bh = gu.oh; dn.bl = gu.ol; dn.ldb = D.f; dn.y = x; dn.ldy = D.d;

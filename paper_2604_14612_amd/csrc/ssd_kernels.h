@@ -99,7 +99,7 @@ struct RowsFused {
     void* kc; void* vc;
     const float* ssq; int n_ssq;
     const float* gain_out; float* ssq_out;
-    float* kpart; size_t kpart_floats;  // rows_wide, mode 1: scratch for a split along K (may be null: no split)
+    float* kpart; size_t kpart_floats;  // rows_wide: scratch for a split along K (may be null: no split)
 };
 bool rows_fused_supported(const Dims& D);
 // tuning hook: > 0 forces the number of weight stripes a block keeps in flight
@@ -115,7 +115,7 @@ hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t*
 bool rows_wide_supported(const Dims& D);
 hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s);
 void rows_wide_depth(int d);  // tuning hook: > 0 forces the number of weight stripes a block keeps in flight
-void rows_wide_ksplit(int n);  // tuning hook: 1 = never cut K, > 1 forces the number of K slices of a mode-1 launch
+void rows_wide_ksplit(int n);  // tuning hook: 1 = never cut K, > 1 forces the number of K slices
 // hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
 // gain first when gain != nullptr
 hipError_t rows_prep(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi,

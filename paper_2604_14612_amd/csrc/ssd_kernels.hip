@@ -1247,13 +1247,56 @@ __device__ __forceinline__ const uint16_t* m6_row(const RowsP2& p, int tile, int
     return (const uint16_t*)p.w[2] + (size_t)(row - p.n[1]) * p.K;
 }
 
+// Epilogue of one output of the 64-row tiling: activation row m, weight row nn (= lane: a wave holds the 64
+// weight rows of tile `tile` for one m) with finished, scaled sums v (and v2 of the second matrix in SwiGLU mode).
+// Called by whole waves with m uniform (the RESID branch reduces over the wave, the QKV branch exchanges the two
+// rows of a rotary pair, nn and nn ^ 32, by a shuffle).
+template <int MODE, bool F16>
+__device__ __forceinline__ void m6_epilogue(const RowsP2& p, int tile, int m, int nn, float v, float v2)
+{
+    const size_t colx = (size_t)tile * 64 + nn;
+    if (MODE == RM_STORE) {
+        p.y[(size_t)m * p.ldy + colx] = v;
+    } else if (MODE == RM_SWIGLU) {
+        split_store(v / (1.0f + __expf(-v)) * v2, p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
+    } else if (MODE == RM_RESID) {
+        float* dst = p.y + (size_t)m * p.ldy + colx;
+        const float tv = *dst + v;
+        *dst = tv;
+        if (p.tap) p.tap[(size_t)m * p.tap_ld + colx] = tv;
+        if (p.gain_out) {
+            split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
+            const float sq = wave_sum(tv * tv);   // the wave holds the tile's 64 columns of row m
+            if (nn == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile] = sq;
+        }
+    } else {  // QKV: rotary pairs are (nn, nn + 32) for nn < 32
+        const int tq = p.dq >> 6, tk = p.dkv >> 6;
+        const int pos = p.pos_dev[0] + p.pos_off + m;
+        const float other = __shfl_xor(v, 32, 64);
+        if (tile < tq + tk) {
+            const bool is_q = tile < tq;
+            const int tt = is_q ? tile : tile - tq;
+            const int tph = p.hd >> 6, head = tt / tph, th = tt % tph, half = p.hd >> 1;
+            const int i = th * 32 + (nn & 31);
+            const float av = nn < 32 ? v : other, bv = nn < 32 ? other : v;
+            const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+            const float ov = nn < 32 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
+            const int e = nn < 32 ? i : i + half;
+            if (is_q) p.y[(size_t)m * p.ldy + (size_t)head * p.hd + e] = ov;
+            else ((uint16_t*)p.kc)[((size_t)head * p.max_seq + pos) * p.hd + e] = f32_to_h16_bits(ov, F16);
+        } else {
+            const int e = (tile - tq - tk) * 64 + nn;
+            ((uint16_t*)p.vc)[((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd)] = f32_to_h16_bits(v, F16);
+        }
+    }
+}
+
 template <int MODE, bool F16, int M6_D>  // M6_D = stripes in flight per block
 __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     extern __shared__ __align__(16) unsigned char sm6[];
     __shared__ float rs[64];
-    __shared__ float fin[MODE == RM_QKV ? 1024 : 1];
     unsigned char* As = sm6;                            // [NT * 64][PITCH]
     unsigned char* Bh = sm6 + NT * 64 * M6_PITCH;       // [64][PITCH]
     unsigned char* Bl = Bh + 64 * M6_PITCH;
@@ -1264,7 +1307,7 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
     // this block's stripes: all of K, or slice blockIdx.y of ksplit (projections with few tiles are cut along K so
     // that every CU has a block; their raw sums go to kpart and rows_finish_resid_kernel adds them up in order)
     const int NCall = K / M6_CK;
-    const int S = MODE == RM_RESID && p.ksplit > 1 ? p.ksplit : 1;
+    const int S = p.ksplit > 1 ? p.ksplit : 1;
     const int c_begin = (int)((long)NCall * blockIdx.y / S), NC = (int)((long)NCall * (blockIdx.y + 1) / S) - c_begin;
     // weights: wave w loads logical rows 8w .. 8w+7; instruction j covers rows 8w+4j .. 8w+4j+3 (16 lanes = 256 B per row)
     const int arow = 8 * wave + (lane >> 4), acol = (lane & 15) * 8;
@@ -1350,7 +1393,7 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
         if (sl < NC) gload(sl, sl);
     // RMS scale of every activation row from the producer's per-tile sums of squares (read by the epilogue)
     if (tid < 64) rs[tid] = 1.0f;
-    if (MODE != RM_RESID && p.ssq) {
+    if (MODE != RM_RESID && p.ssq && S == 1) {   // (a K-split launch leaves the scaling to its finishing kernel)
         __syncthreads();
         for (int c = wave; c < M; c += 8) {
             float sq = 0.f;
@@ -1382,7 +1425,6 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
     // red[t][wave][i][256], element row * 16 + column of the D layout (lane (c = lane % 16, g) holds weight
     // rows 4g .. 4g+3 of activation row c), then the epilogue: thread -> (weight row nn, activation row c).
     float* red = reinterpret_cast<float*>(sm6);   // NT x 8 x 2 x 256 floats = NT x 16 KB
-    const int tq = p.dq >> 6, tk = p.dkv >> 6;
     for (int j = 0; j < MT; j++) {
         __syncthreads();
 #pragma unroll
@@ -1401,11 +1443,10 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
                     red[((t * 8 + wave) * 2 + i) * 256 + (g * 4 + e) * 16 + r16] = v;
                 }
         __syncthreads();
-        float val[2], val2[2];
 #pragma unroll
         for (int it = 0; it < 2; it++) {   // 64 weight rows x 16 activation rows = 1024 outputs, two per thread
             const int o = tid + it * 512;
-            const int nn = o & 63, c = o >> 6;
+            const int nn = o & 63, c = o >> 6;      // c (and so m) is uniform over a wave, nn = lane
             const int st = nn >> 4, hh = st >> 1, ii = st & 1;
             float v = 0.f, v2 = 0.f;
 #pragma unroll
@@ -1414,76 +1455,39 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
                 if (MODE == RM_SWIGLU) v2 += red[(((8 + hh * 4 + q) * 2) + ii) * 256 + (nn & 15) * 16 + c];
             }
             const int m = j * 16 + c;
-            if (MODE != RM_RESID) { v *= rs[m]; v2 *= rs[m]; }
-            val[it] = v; val2[it] = v2;
-            if (MODE == RM_QKV) fin[nn * 16 + c] = v;
-        }
-        if (MODE == RM_QKV) __syncthreads();
-#pragma unroll
-        for (int it = 0; it < 2; it++) {
-            const int o = tid + it * 512;
-            const int nn = o & 63, c = o >> 6;      // c (and so m) is uniform over a wave, nn = lane
-            const int m = j * 16 + c;
             if (m >= M) continue;
-            const float v = val[it];
-            const size_t colx = (size_t)n0 + nn;
-            if (MODE == RM_STORE) {
-                p.y[(size_t)m * p.ldy + colx] = v;
-            } else if (MODE == RM_SWIGLU) {
-                split_store(v / (1.0f + __expf(-v)) * val2[it], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
-            } else if (MODE == RM_RESID) {
-                if (S > 1) {
-                    p.kpart[((size_t)blockIdx.y * M + m) * p.n[0] + colx] = v;
-                    continue;
-                }
-                float* dst = p.y + (size_t)m * p.ldy + colx;
-                const float tv = *dst + v;
-                *dst = tv;
-                if (p.tap) p.tap[(size_t)m * p.tap_ld + colx] = tv;
-                if (p.gain_out) {
-                    split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
-                    const float sq = wave_sum(tv * tv);   // the wave holds the tile's 64 columns of row m
-                    if (lane == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile] = sq;
-                }
-            } else {  // QKV: rotary pairs are (nn, nn + 32) for nn < 32
-                const int pos = p.pos_dev[0] + p.pos_off + m;
-                if (tile < tq + tk) {
-                    const bool is_q = tile < tq;
-                    const int tt = is_q ? tile : tile - tq;
-                    const int tph = p.hd >> 6, head = tt / tph, th = tt % tph, half = p.hd >> 1;
-                    const int i = th * 32 + (nn & 31);
-                    const float av = fin[(nn & 31) * 16 + c], bv = fin[((nn & 31) + 32) * 16 + c];
-                    const float* cs = p.rope + ((size_t)pos * half + i) * 2;
-                    const float ov = nn < 32 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
-                    const int e = nn < 32 ? i : i + half;
-                    if (is_q) p.y[(size_t)m * p.ldy + (size_t)head * p.hd + e] = ov;
-                    else ((uint16_t*)p.kc)[((size_t)head * p.max_seq + pos) * p.hd + e] = f32_to_h16_bits(ov, F16);
-                } else {
-                    const int e = (tile - tq - tk) * 64 + nn;
-                    ((uint16_t*)p.vc)[((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd)] = f32_to_h16_bits(v, F16);
-                }
+            if (S > 1) {   // raw sums of this K slice: [slice][matrix][M][n_total]
+                const size_t nt = (size_t)gridDim.x * 64;
+                p.kpart[(((size_t)blockIdx.y * NT + 0) * M + m) * nt + n0 + nn] = v;
+                if (MODE == RM_SWIGLU) p.kpart[(((size_t)blockIdx.y * NT + 1) * M + m) * nt + n0 + nn] = v2;
+                continue;
             }
+            if (MODE != RM_RESID) { v *= rs[m]; v2 *= rs[m]; }
+            m6_epilogue<MODE, F16>(p, tile, m, nn, v, v2);
         }
     }
 }
 
-// Second half of a K-split RESID projection: one wave per (row, 64-column tile) adds the slices in order, then
-// does what the unsplit epilogue does (residual add, tap, hi/lo of x * gain, sum of squares of the tile).
-__global__ __launch_bounds__(64) void rows_finish_resid_kernel(RowsP2 p, bool f16)
+// Second half of a K-split launch: one wave per (row, 64-column tile) adds the slices in a fixed order, applies
+// the RMS scale of the row (summing the producer's partials itself) and runs the mode's epilogue.
+template <int MODE, bool F16>
+__global__ __launch_bounds__(64) void rows_finish_kernel(RowsP2 p)
 {
+    constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     const int tile = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
-    const size_t colx = (size_t)tile * 64 + lane;
-    float v = 0.f;
-    for (int sl = 0; sl < p.ksplit; sl++) v += p.kpart[((size_t)sl * p.M + m) * p.n[0] + colx];
-    float* dst = p.y + (size_t)m * p.ldy + colx;
-    const float tv = *dst + v;
-    *dst = tv;
-    if (p.tap) p.tap[(size_t)m * p.tap_ld + colx] = tv;
-    if (p.gain_out) {
-        split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, f16);
-        const float sq = wave_sum(tv * tv);
-        if (lane == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile] = sq;
+    const size_t nt = (size_t)gridDim.x * 64, colx = (size_t)tile * 64 + lane;
+    float v = 0.f, v2 = 0.f;
+    for (int sl = 0; sl < p.ksplit; sl++) {
+        v += p.kpart[(((size_t)sl * NT + 0) * p.M + m) * nt + colx];
+        if (MODE == RM_SWIGLU) v2 += p.kpart[(((size_t)sl * NT + 1) * p.M + m) * nt + colx];
     }
+    if (MODE != RM_RESID && p.ssq) {
+        float sq = 0.f;
+        for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)m * p.n_ssq + i];
+        const float sc = 1.0f / sqrtf(wave_sum(sq) / (float)p.K + p.eps);
+        v *= sc; v2 *= sc;
+    }
+    m6_epilogue<MODE, F16>(p, tile, m, lane, v, v2);
 }
 
 bool rows_many_supported(const Dims& D, int N, int K)
@@ -1510,11 +1514,11 @@ static hipError_t launch_wide_d(const RowsP2& p, int n_tiles, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int S = MODE == RM_RESID && p.ksplit > 1 ? p.ksplit : 1;
+    const int S = p.ksplit > 1 ? p.ksplit : 1;
     hipLaunchKernelGGL((rows_wide_kernel<MODE, F16, DEPTH>), dim3(n_tiles, S), dim3(512), lds, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
-    hipLaunchKernelGGL(rows_finish_resid_kernel, dim3(n_tiles, p.M), dim3(64), 0, s, p, F16);
+    hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(n_tiles, p.M), dim3(64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -1556,15 +1560,18 @@ hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
     fill_rows_params(D, f, p);
     const int n_tiles = f.mode == RM_SWIGLU ? f.n[0] / 64 : (f.n[0] + f.n[1] + f.n[2]) / 64;
     const bool f16 = D.wt == WT_F16;
-    // A block is bound by what one CU pulls from the cache (about 40 GB/s), so a projection with fewer tiles than
-    // CUs is cut along K until there are about 256 blocks; needs scratch for ksplit x M x n partial sums.
+    // A block is bound by what one CU pulls from the cache (about 40 GB/s), so a launch with far fewer tiles than
+    // CUs (the projections back to d_model) is cut along K until there are about 256 blocks; needs scratch for
+    // ksplit x matrices x M x n sums.  With 170 tiles or more (QKV, gate/up at 7B) the cut measured equal or worse.
     p.ksplit = 1; p.kpart = nullptr;
-    if (f.mode == RM_RESID && f.kpart && f.n[1] == 0 && f.n[2] == 0 && g_wide_ksplit != 1) {
-        int ks = g_wide_ksplit > 1 ? g_wide_ksplit : 256 / n_tiles;
+    if (f.kpart && g_wide_ksplit != 1 && f.M > 16) {
+        const int nmat = f.mode == RM_SWIGLU ? 2 : 1;
+        const size_t per_slice = (size_t)nmat * f.M * n_tiles * 64;
+        int ks = g_wide_ksplit > 1 ? g_wide_ksplit : (n_tiles <= 128 ? 256 / n_tiles : 1);
         const int nc = f.K / M6_CK;
         if (ks > 8) ks = 8;
         if (ks > nc) ks = nc;
-        if ((size_t)ks * f.M * f.n[0] > f.kpart_floats) ks = (int)(f.kpart_floats / ((size_t)f.M * f.n[0]));
+        if ((size_t)ks * per_slice > f.kpart_floats) ks = (int)(f.kpart_floats / per_slice);
         if (ks > 1) { p.ksplit = ks; p.kpart = f.kpart; }
     }
     switch (f.mode) {
