@@ -179,3 +179,30 @@ def test_full_workload_properties(ssd, name, n_new):
     assert s["n_tokens"] >= wl.prompt_len + n_new
     del ctx, w
     torch.cuda.empty_cache()
+
+
+def test_13b_full_iterative_refinement(ssd):
+    """Config 4 at full size: the skip set is refined for up to 10 rounds of 30 cycles while tokens are generated;
+    the stream stays the vanilla stream (lossless verification) and the search ends within its round limit."""
+    import torch
+    from synth import make_weights
+    wl = WORKLOADS["llama13b"]
+    shape = wl.shape
+    w = make_weights(shape, wl.seed, device="cuda")
+    prompt = make_prompt(shape.vocab, wl.prompt_len, wl.seed).tolist()
+    n_new = 330                                                   # > 10 rounds x 30 cycles at one token per cycle
+    ctx = ssd.Context(shape, w, wl.prompt_len + n_new + 64, max_k=wl.k)
+    t0 = time.time()
+    van = ssd.generate_vanilla(ctx, prompt, n_new)
+    ctx.ssd_reset()
+    sr = ssd.Search(shape.n_layers, ssd.search_defaults(max_rounds=10), ssd.select_defaults())
+    got, st = ssd.generate_conflayers(ctx, prompt, n_new, k=wl.k, search=sr)
+    first_diff = next((i for i, (a, b) in enumerate(zip(got, van)) if a != b), n_new)
+    n_skip = int(st["skip_mask"].sum())
+    print("13B refinement: cycles", st["cycles"], "rounds", st["search_rounds"], "best", st["search_best_score"],
+          "skipped", n_skip, "accepted", st["accepted"], "first diff vs vanilla", first_diff, "%.0f s" % (time.time() - t0))
+    assert 1 <= st["search_rounds"] <= 10 and not sr.active
+    assert 0.4 * shape.n_layers - 1e-9 <= n_skip <= 0.6 * shape.n_layers + 1e-9
+    assert first_diff >= 32
+    del ctx, w
+    torch.cuda.empty_cache()
