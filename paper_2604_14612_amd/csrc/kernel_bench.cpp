@@ -225,12 +225,17 @@ int main(int argc, char** argv)
     }
     attention_force_splits(0);
     attention_force_kernel(0);
-    for (int rows : {16, 64}) {
+    for (int kind : {3, 1}) for (int rows : {9, 16, 64}) for (int sp : {0, 16}) {
+        if (sp && (kind == 3 || rows != 64)) continue;
+        attention_force_kernel(kind);
+        attention_force_splits(sp);
         char nm[96];
-        std::snprintf(nm, sizeof nm, "attention %d rows ctx 640+rows (prompt block)", rows);
+        std::snprintf(nm, sizeof nm, "attention %d rows ctx 640+rows, LDS-staged %s, splits %d", rows, kind == 3 ? "plain" : "MFMA", sp);
         timeit(nm, 2.0 * (640 + rows) * 4096 * 2, n, [&](int i) {
             CK(attention(D, big_a, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, rows, part, nullptr,
                          hi64, lo64, 0)); });
     }
+    attention_force_kernel(0);
+    attention_force_splits(0);
     return 0;
 }

@@ -144,7 +144,7 @@ size_t attention_scratch_floats(const Dims& D, int max_rows);
 int attention_splits(const Dims& D, int ctx, int M);
 // tuning hook: n > 0 forces the split count (scratch must have been sized for it), 0 restores the heuristic
 void attention_force_splits(int n);
-// tuning hook: 0 heuristic, 1 LDS-staged kernel always
+// tuning hook: 0 heuristic, 1 LDS-staged kernel always, 3 the same in its plain (non-MFMA) form
 void attention_force_kernel(int v);
 
 // ---- vocabulary reduction ------------------------------------------------------------------------

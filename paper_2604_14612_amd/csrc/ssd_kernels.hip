@@ -30,10 +30,7 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);                                            // round to nearest even
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, (__bf16)f);   // round to nearest even; gfx950 converts in hardware
 }
 
 template <typename T> struct Elem;
@@ -983,6 +980,17 @@ __device__ __forceinline__ float row16_sum(float v)
     v = dpp_add<0x122>(v);  // row_ror:2
     return dpp_add<0x121>(v);  // row_ror:1
 }
+template <int CTRL> __device__ __forceinline__ float dpp_max(float v)
+{
+    return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false)));
+}
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = dpp_max<0x128>(v);
+    v = dpp_max<0x124>(v);
+    v = dpp_max<0x122>(v);
+    return dpp_max<0x121>(v);
+}
 
 // Final step of a tile: sum the KS per-wave partial tiles held in LDS (layout [wave][NT][256], element
 // row*16 + column) and apply the mode's epilogue.  Executed by the whole block (it contains barriers in QKV mode).
@@ -1905,6 +1913,213 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
     }
 }
 
+// MFMA form of the kernel above for 16-bit caches: one block per KV head, chunk of positions and group of 16
+// query vectors; same staging of K, same softmax statistics and the same partial layout, but the two
+// contractions run on the matrix cores.  Scores: A = 16 query vectors (fp32 -> hi + lo in the cache's 16-bit
+// type), B = K rows read from LDS in fragment order.  P.V: A = the 16 x 96 exponentials (hi + lo), B = V, which
+// is therefore staged transposed ([dim][position]) so that a fragment is one 128-bit LDS read.
+constexpr int AM_VPITCH = AT_CHUNK * 2 + 16;   // bytes per row of the transposed V tile
+
+// 8 consecutive fp32 values -> two packed fragments hi = rne(x), lo = rne(x - hi)
+template <bool F16>
+__device__ __forceinline__ void split8(const float* x, u32x4_t& hi, u32x4_t& lo)
+{
+    // two 128-bit reads (x is 32-byte aligned), not eight dependent scalar ones
+    const float4 a = *reinterpret_cast<const float4*>(x), b = *reinterpret_cast<const float4*>(x + 4);
+    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    unsigned h[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const uint16_t hb = f32_to_h16_bits(v[i], F16);
+        h[i] = hb;
+        l[i] = f32_to_h16_bits(v[i] - h16_bits_to_f32(hb, F16), F16);
+    }
+    hi = u32x4_t{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    lo = u32x4_t{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+}
+
+template <typename KT, int HD>
+__global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __restrict__ q, int ldq,
+                                                               const KT* __restrict__ kc, const KT* __restrict__ vc,
+                                                               const int* pos_dev, int pos_off, int M, int H, int Hkv,
+                                                               int max_seq, int n_splits, float* __restrict__ part,
+                                                               float* __restrict__ outp, int dq,
+                                                               uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
+{
+    static_assert(sizeof(KT) == 2, "16-bit caches only");
+    constexpr bool F16 = IsF16<KT>::value;
+    constexpr int ROWB = HD * 2 + 16;
+    constexpr int VPR = HD / 8;                // 16-byte vectors per cache row
+    constexpr int KSTEPS = HD / 32;            // MFMA k-steps of a score
+    constexpr int PT = AT_CHUNK / 16;          // position tiles of the chunk (6)
+    constexpr int PS = AT_CHUNK / 32;          // k-steps of P.V (3)
+    constexpr int DT = HD / 16;                // output dim tiles (8 or 4)
+    constexpr int DTW = DT / 4;                // dim tiles per wave
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* ktile = smem;                                       // [AT_CHUNK][ROWB]
+    unsigned char* vT = smem + AT_CHUNK * ROWB;                        // [HD][AM_VPITCH]
+    float* qs = reinterpret_cast<float*>(vT + HD * AM_VPITCH);         // [16][HD], pre-scaled
+    float* sc = qs + AT_QPASS * HD;                                    // [16][AT_CHUNK]
+    float* ml = sc + AT_QPASS * AT_CHUNK;                              // [16][2]
+
+    const int split = blockIdx.x, kvh = blockIdx.y;
+    const int G = H / Hkv, Q = G * M;
+    const int p0 = pos_dev[0] + pos_off;
+    const int total = p0 + M;
+    const int chunk = min((total + n_splits - 1) / n_splits, AT_CHUNK);
+    const int j0 = split * chunk;
+    const int n = min(chunk, total - j0);                      // may be <= 0
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    // the block's group of 16 query vectors (blockIdx.z): loads issued first, they are the furthest away
+    const int q0 = blockIdx.z * AT_QPASS;
+    const int nq = min(AT_QPASS, Q - q0);
+    constexpr int QPT = AT_QPASS * HD / AT_THREADS;   // query elements per thread
+    float qreg[QPT];
+#pragma unroll
+    for (int t = 0; t < QPT; t++) {
+        const int e = tid + t * AT_THREADS, qg = q0 + min(e / HD, nq - 1);
+        qreg[t] = q[(size_t)(qg / G) * ldq + (size_t)(kvh * G + qg % G) * HD + (e % HD)];
+    }
+    if (n > 0) {  // stage K (row-major) and V (transposed); every load is issued before the first is used
+        const KT* kbase = kc + ((size_t)kvh * max_seq + j0) * HD;
+        const KT* vbase = vc + ((size_t)kvh * max_seq + j0) * HD;
+        constexpr int NV = (AT_CHUNK * VPR + AT_THREADS - 1) / AT_THREADS;
+        u32x4_t kr[NV], vr[NV];
+        const int vmax = n * VPR - 1;
+        // K: consecutive lanes take consecutive vectors of a row.  V: consecutive lanes take consecutive POSITIONS
+        // (vector v -> position v % AT_CHUNK, dims 8 (v / AT_CHUNK) ..), so that the 2-byte stores of the transpose
+        // below fall on consecutive addresses of one V^T row instead of colliding in two banks.
+#pragma unroll
+        for (int t = 0; t < NV; t++) {
+            const int v = min(tid + t * AT_THREADS, vmax);
+            kr[t] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)(v / VPR) * HD + (v % VPR) * 8);
+            const int w = min(tid + t * AT_THREADS, AT_CHUNK * VPR - 1);
+            vr[t] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min(w % AT_CHUNK, n - 1) * HD + (w / AT_CHUNK) * 8);
+        }
+#pragma unroll
+        for (int t = 0; t < NV; t++) {
+            const int v = tid + t * AT_THREADS;
+            if (v < AT_CHUNK * VPR) {
+                const int pos = v / VPR, d0 = (v % VPR) * 8;
+                // positions past the chunk: zero keys and values
+                *reinterpret_cast<u32x4_t*>(ktile + pos * ROWB + d0 * 2) = v <= vmax ? kr[t] : u32x4_t{0u, 0u, 0u, 0u};
+                const int vpos = v % AT_CHUNK, vd0 = (v / AT_CHUNK) * 8;
+                const u32x4_t vv = vpos < n ? vr[t] : u32x4_t{0u, 0u, 0u, 0u};
+                const unsigned w4[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    *reinterpret_cast<uint16_t*>(vT + (vd0 + e) * AM_VPITCH + vpos * 2) = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+            }
+        }
+    }
+    const float scale = 1.0f / sqrtf((float)HD);
+    {   // one group of 16 query vectors per block: the groups of a head run side by side on different CUs instead of
+        // one after the other, each re-staging the chunk out of the cache
+#pragma unroll
+        for (int t = 0; t < QPT; t++) {   // rows past nq: zero queries (their results are never stored)
+            const int e = tid + t * AT_THREADS;
+            qs[e] = e / HD < nq ? qreg[t] * scale : 0.f;
+        }
+        __syncthreads();   // K, V^T and the query vectors are staged
+        if (n > 0) {
+            // phase A: scores.  Wave w takes position tiles w, w + 4; D: lane (c = position, g) holds queries 4g .. 4g+3
+            u32x4_t qh[KSTEPS], ql[KSTEPS];
+#pragma unroll
+            for (int st = 0; st < KSTEPS; st++) split8<F16>(qs + r16 * HD + st * 32 + g * 8, qh[st], ql[st]);
+            for (int pt = wave; pt < PT; pt += 4) {
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int st = 0; st < KSTEPS; st++) {
+                    const u32x4_t kf = *reinterpret_cast<const u32x4_t*>(ktile + (pt * 16 + r16) * ROWB + (st * 32 + g * 8) * 2);
+                    acc = mfma_h16<F16>(qh[st], kf, acc);
+                    acc = mfma_h16<F16>(ql[st], kf, acc);
+                }
+#pragma unroll
+                for (int jx = 0; jx < 4; jx++) sc[(g * 4 + jx) * AT_CHUNK + pt * 16 + r16] = acc[jx];
+            }
+        }
+        __syncthreads();
+        // phase B: causal mask, max, exp, sum.  Wave w owns queries 4w .. 4w+3, one per 16-lane row, so the two
+        // reductions are DPP row operations; entries past the visible range (and rows past nq) become 0
+        {
+            const int qi = wave * 4 + g;
+            int vis = 0;
+            if (qi < nq) vis = min(n, p0 + (q0 + qi) / G + 1 - j0);   // positions of this chunk the row may see
+            float sv[AT_CHUNK / 16];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < AT_CHUNK / 16; t++) {
+                const int j = r16 + 16 * t;
+                sv[t] = sc[qi * AT_CHUNK + j];
+                if (j < vis) mx = fmaxf(mx, sv[t]);
+            }
+            mx = row16_max(mx);
+            float ls = 0.f;
+#pragma unroll
+            for (int t = 0; t < AT_CHUNK / 16; t++) {
+                const int j = r16 + 16 * t;
+                const float e = j < vis ? __expf(sv[t] - mx) : 0.f;
+                sc[qi * AT_CHUNK + j] = e;
+                ls += e;
+            }
+            ls = row16_sum(ls);
+            if (r16 == 0) { ml[qi * 2] = mx; ml[qi * 2 + 1] = ls; }
+        }
+        __syncthreads();
+        // phase C: O = P.V.  Wave w takes output dim tiles w, w + 4, ...; A: lane (r = query, g) holds P[r][32 s + 8g ..],
+        // B: lane (c = dim, g) holds V^T[dim][32 s + 8g ..]; D: lane (c = dim, g) holds queries 4g .. 4g+3
+        u32x4_t ph[PS], pl[PS];
+#pragma unroll
+        for (int st = 0; st < PS; st++) split8<F16>(sc + r16 * AT_CHUNK + st * 32 + g * 8, ph[st], pl[st]);
+#pragma unroll
+        for (int t = 0; t < DTW; t++) {
+            const int dt = wave + 4 * t;
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            if (n > 0) {
+#pragma unroll
+                for (int st = 0; st < PS; st++) {
+                    const u32x4_t vf = *reinterpret_cast<const u32x4_t*>(vT + (dt * 16 + r16) * AM_VPITCH + (st * 32 + g * 8) * 2);
+                    acc = mfma_h16<F16>(ph[st], vf, acc);
+                    acc = mfma_h16<F16>(pl[st], vf, acc);
+                }
+            }
+            // the tile goes back through LDS (the query buffer is free by now) so that the block can write whole
+            // rows: scattered 4-byte stores straight from the D layout kept every block waiting on the write path
+#pragma unroll
+            for (int jx = 0; jx < 4; jx++) qs[(g * 4 + jx) * HD + dt * 16 + r16] = acc[jx];
+        }
+        __syncthreads();
+        for (int f = tid; f < nq * (HD / 4); f += AT_THREADS) {
+            const int qi = f / (HD / 4), dd = (f % (HD / 4)) * 4;
+            const float4 o = *reinterpret_cast<const float4*>(qs + qi * HD + dd);
+            const int qg = q0 + qi, r = qg / G, head = kvh * G + qg % G;
+            const float mx = ml[qi * 2], ls = ml[qi * 2 + 1];
+            if (n_splits == 1) {
+                const size_t oo = (size_t)r * dq + (size_t)head * HD + dd;
+                const float inv = 1.0f / ls;
+                if (out_hi) {
+                    split_store(o.x * inv, out_hi, out_lo, oo, F16); split_store(o.y * inv, out_hi, out_lo, oo + 1, F16);
+                    split_store(o.z * inv, out_hi, out_lo, oo + 2, F16); split_store(o.w * inv, out_hi, out_lo, oo + 3, F16);
+                } else {
+                    *reinterpret_cast<float4*>(outp + oo) = make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+                }
+            } else {
+                float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
+                *reinterpret_cast<float4*>(mine + dd) = o;
+                if (dd == 0) { mine[HD] = n > 0 ? mx : -INFINITY; mine[HD + 1] = n > 0 ? ls : 0.f; }
+            }
+        }
+    }
+}
+
+template <typename KT, int HD>
+static size_t attn_mfma_lds_bytes()
+{
+    return (size_t)AT_CHUNK * (HD * 2 + 16) + (size_t)HD * AM_VPITCH + (size_t)AT_QPASS * HD * 4 +
+           (size_t)AT_QPASS * AT_CHUNK * 4 + (size_t)AT_QPASS * 2 * 4;
+}
+
 template <typename KT, int HD>
 static size_t attn_lds_bytes()
 {
@@ -2167,7 +2382,7 @@ constexpr int AW_MAX_ROWS = 8;
 constexpr int AW_RANGE = 128;
 constexpr int AW_MAX_RANGES = 16;
 static int g_force_splits = 0;  // tuning hook (kernel_bench): > 0 overrides the heuristic
-static int g_force_attn = 0;    // tuning hook: 1 = LDS-staged kernel always
+static int g_force_attn = 0;    // tuning hook: 1 = LDS-staged kernel always, 3 = the same in its plain (non-MFMA) form
 void attention_force_splits(int n) { g_force_splits = n; }
 void attention_force_kernel(int v) { g_force_attn = v; }
 
@@ -2183,7 +2398,7 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     // AW_MAX_ROWS rows is cheaper than the LDS-staged kernel)
     const int G = D.H / D.Hkv;
     pl.wide = Q <= AW_MAXQ_TOTAL || ((G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
-    if (g_force_attn == 1) pl.wide = false;
+    if (g_force_attn == 1 || g_force_attn == 3) pl.wide = false;
     if (pl.wide) {
         // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
         int ns = ceil_div(ctx, AW_RANGE);
@@ -2224,6 +2439,41 @@ static void launch_attn_wide(const Dims& D, const float* q, int ldq, const void*
                        out_hi, out_lo);
 }
 
+// LDS-staged kernel: MFMA form for 16-bit caches, plain form for fp32 caches
+template <typename KT, int HD>
+static void launch_attn_staged(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
+                               int pos_off, int n_splits, int M, float* part, float* out, uint16_t* out_hi, uint16_t* out_lo,
+                               hipStream_t s)
+{
+    if constexpr (sizeof(KT) == 2) {
+        if (g_force_attn != 3) {
+            const size_t lds = attn_mfma_lds_bytes<KT, HD>();
+            static bool attr_set = false;  // per instantiation
+            if (!attr_set && lds > 64 * 1024) {
+                if (hipFuncSetAttribute((const void*)attn_mfma_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)lds) != hipSuccess)
+                    return;   // the launch below then fails and reports
+                attr_set = true;
+            }
+            const int Q = (D.H / D.Hkv) * M;
+            hipLaunchKernelGGL((attn_mfma_kernel<KT, HD>), dim3(n_splits, D.Hkv, ceil_div(Q, AT_QPASS)), dim3(AT_THREADS), lds, s, q, ldq,
+                               (const KT*)kc, (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq,
+                               out_hi, out_lo);
+            return;
+        }
+    }
+    const size_t lds = attn_lds_bytes<KT, HD>();
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set && lds > 64 * 1024) {
+        if (hipFuncSetAttribute((const void*)attn_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+            hipSuccess)
+            return;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.Hkv, 1), dim3(AT_THREADS), lds, s, q, ldq, (const KT*)kc,
+                       (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo);
+}
+
 template <typename KT, int HD>
 static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void* kc, const void* vc, const int* pos_dev,
                               int pos_off, AttnPlan pl, int ctx, int M, float* part, float* out, uint16_t* out_hi,
@@ -2246,16 +2496,7 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
         else if (span <= 8 * 64 * 4) launch_attn_wide<KT, HD, 4, 8, 4>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
         else launch_attn_wide<KT, HD, 4, 8, 8>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, zq, M, part, out, out_hi, out_lo, s);
     } else {
-        const size_t lds = attn_lds_bytes<KT, HD>();
-        static bool attr_set = false;  // per instantiation
-        if (!attr_set && lds > 64 * 1024) {
-            hipError_t ea = hipFuncSetAttribute((const void*)attn_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                (int)lds);
-            if (ea != hipSuccess) return ea;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.Hkv, 1), dim3(AT_THREADS), lds, s, q, ldq, (const KT*)kc,
-                           (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo);
+        launch_attn_staged<KT, HD>(D, q, ldq, kc, vc, pos_dev, pos_off, n_splits, M, part, out, out_hi, out_lo, s);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_splits == 1 || pl.defer_fold) return e;
