@@ -2393,11 +2393,12 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     AttnPlan pl;
     pl.defer_fold = false;
     const int Q = (D.H / D.Hkv) * M;
-    // a few rows with 1, 2, 4 or 8 query heads per KV head: still the register-resident kernel, one block per row
-    // and range serving the row's group of heads (two blocks for a group of 8) (the rows re-read a range's K/V from the cache, which at up to
-    // AW_MAX_ROWS rows is cheaper than the LDS-staged kernel)
+    // More than 4 query vectors per KV head: 16-bit caches take the MFMA form of the LDS-staged kernel (12.9 us
+    // against 14.5 us at 5 rows, 7B shape, fold included).  fp32 caches have no MFMA form; there a few rows with 1, 2,
+    // 4 or 8 query heads per KV head still run the register-resident kernel, one block per row and range serving
+    // the row's group of heads (two blocks for a group of 8), re-reading a range's K/V from the cache.
     const int G = D.H / D.Hkv;
-    pl.wide = Q <= AW_MAXQ_TOTAL || ((G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
+    pl.wide = Q <= AW_MAXQ_TOTAL || (D.wt == WT_F32 && (G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
     if (g_force_attn == 1 || g_force_attn == 3) pl.wide = false;
     if (pl.wide) {
         // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
