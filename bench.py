@@ -20,7 +20,7 @@ HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the draft gate/up GEMV at Llama-2-7B shape: rocprofv3 FETCH_SIZE + WRITE_SIZE per
 # dispatch, scaled by the factors a known-size read / copy kernel gives (FETCH_SIZE x2.000, WRITE_SIZE x1.000);
 # the run and the arithmetic are in profiles/kernel_bench_llama7b_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"llama7b": 180.77e6}
+MEASURED_TRAFFIC_BYTES = {"llama7b": 180.76e6}
 
 
 def layer_bytes(s):
