@@ -2,6 +2,9 @@
 // every launch, so nothing is served from the caches) and prints the time per launch.  Used for tuning
 // and, under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`, for the HBM traffic of each kernel; the
 // read probe and the fp32 copy move a known number of bytes and calibrate those counters.
+// Environment switches select other runs: KB_SWEEP (launch time against size), KB_PAIR (a kernel reading what the
+// kernel before it wrote), KB_LAYER (the five launches of a decode layer in sequence), KB_LONG (three seconds of
+// back-to-back gate/up launches: clock drift).
 #include "ssd_kernels.h"
 
 #include <cstdio>
@@ -84,6 +87,52 @@ int main(int argc, char** argv)
     timeit("read_probe 256 MiB", 268435456.0, 4, [&](int i) { CK(read_probe(W + (size_t)i * (134217728), (size_t)256 << 20, sink, 0)); });
     timeit("copy_f32 256 MiB", 2 * 268435456.0, 4, [&](int) { CK(copy_f32(big_a, big_b, (size_t)64 << 20, 0)); });
 
+    if (std::getenv("KB_LONG")) {   // sustained streaming: does the per-launch time drift once the chip has been busy for a while?
+        for (int rep = 0; rep < 40; rep++) {
+            hipEvent_t a, b;
+            CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
+            CK(hipEventRecord(a, 0));
+            const int launches = 2400;
+            for (int i = 0; i < launches; i++) {
+                const uint16_t* w = W + (size_t)(i % 12) * 2 * gu;
+                CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0));
+            }
+            CK(hipEventRecord(b, 0)); CK(hipEventSynchronize(b));
+            float ms; CK(hipEventElapsedTime(&ms, a, b));
+            std::printf("gemv_gateup sustained, %d launches: %.2f us per launch\n", launches, ms * 1e3 / launches);
+            std::fflush(stdout);
+        }
+        return 0;
+    }
+    if (std::getenv("KB_PAIR")) {   // a kernel that reads what the kernel before it has just written (as in the layer pipeline)
+        timeit("gemv_o alone", qk * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, q, x, nullptr, 0)); });
+        timeit("gemv_gateup alone", 2 * gu * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 2 * gu;
+            CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0)); });
+        timeit("gemv_o then gemv_gateup (x handed over)", qk * 2.0 + 2 * gu * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 3 * gu;
+            CK(gemv_resid(D, w + 2 * gu, 4096, 4096, q, x, nullptr, 0));
+            CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0)); });
+        timeit("gemv_gateup then gemv_down (act handed over)", 3 * gu * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 3 * gu;
+            CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0));
+            CK(gemv_resid(D, w + 2 * gu, 4096, 11008, act, x, nullptr, 0)); });
+        return 0;
+    }
+    if (std::getenv("KB_LAYER")) {   // the five launches of a decode layer in sequence, 12 different layers' worth of weights
+        const size_t layer_elems = 4 * qk + 3 * gu;
+        timeit("decode layer: qkv, attention, o (fold), gate/up, down", layer_elems * 2.0 + 2.0 * 641 * 4096 * 2, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * layer_elems;
+            CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, 0));
+            int fold = 0;
+            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0,
+                         &fold));
+            if (fold > 0) CK(gemv_resid_attn(D, w + 3 * qk, part, fold, x, nullptr, 0));
+            else CK(gemv_resid(D, w + 3 * qk, 4096, 4096, act, x, nullptr, 0));
+            CK(gemv_swiglu(D, w + 4 * qk, w + 4 * qk + gu, gain, x, act, 0));
+            CK(gemv_resid(D, w + 4 * qk + 2 * gu, 4096, 11008, act, x, nullptr, 0)); });
+        return 0;
+    }
     if (std::getenv("KB_SWEEP")) {   // launch time against size: fixed cost and streaming rate of probe and GEMV
         for (int mb : {16, 32, 64, 128, 256}) {
             char nm[64];
