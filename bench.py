@@ -53,6 +53,8 @@ def cpu_baseline(shape, weights_gpu, prompt, k, mask, n_prompt=8, n_cycles=8):
     from oracle import OracleModel, OracleSSD
     w_cpu = {}
     for key, v in weights_gpu.items():
+        if key.startswith("_"):
+            continue
         w_cpu[key] = [t.cpu() for t in v] if isinstance(v, list) else v.cpu()
     m = OracleModel(shape, w_cpu, n_prompt + n_cycles * (k + 1) + 4)
     o = OracleSSD(m)
@@ -102,6 +104,12 @@ def main():
     L = shape.n_layers
 
     weights = make_weights(shape, wl.seed, device="cuda")
+    w_bytes = sum(t.numel() * t.element_size() for v in weights.values() for t in (v if isinstance(v, list) else [v]))
+    if w_bytes < 100e9:                         # (skipped where two copies would not fit during the packing)
+        packed = ssd.pack_weights(weights)      # one allocation, forward order: the layout the library is fed in HBM
+        weights.clear()
+        weights = packed
+        torch.cuda.empty_cache()
     prompt = make_prompt(shape.vocab, wl.prompt_len, wl.seed).tolist()
     max_seq = wl.prompt_len + (W + K + 4) * (k + 1) + 16
     ctx = ssd.Context(shape, weights, max_seq, max_k=k)
