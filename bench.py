@@ -105,11 +105,12 @@ def main():
 
     weights = make_weights(shape, wl.seed, device="cuda")
     w_bytes = sum(t.numel() * t.element_size() for v in weights.values() for t in (v if isinstance(v, list) else [v]))
-    if w_bytes < 100e9:                         # (skipped where two copies would not fit during the packing)
-        packed = ssd.pack_weights(weights)      # one allocation, forward order: the layout the library is fed in HBM
-        weights.clear()
-        weights = packed
-        torch.cuda.empty_cache()
+    # one allocation in forward order (one per layer where two copies of the model would not fit during the packing):
+    # the layout the library is fed in HBM
+    packed = ssd.pack_weights(weights, per_layer=w_bytes >= 100e9)
+    weights.clear()
+    weights = packed
+    torch.cuda.empty_cache()
     prompt = make_prompt(shape.vocab, wl.prompt_len, wl.seed).tolist()
     max_seq = wl.prompt_len + (W + K + 4) * (k + 1) + 16
     ctx = ssd.Context(shape, weights, max_seq, max_k=k)
