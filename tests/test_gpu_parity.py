@@ -429,3 +429,24 @@ def test_generation_loops_agree_on_the_library(ssd):
         assert st["search_rounds"] >= 1 and st["drafted"] >= st["cycles"]
         if gamma is not None:
             assert st["drafted"] < 6 * st["cycles"]          # the exit rule shortened some drafts
+
+
+def test_packed_weights_give_identical_results(ssd):
+    """pack_weights only moves the tensors (one arena, or one per layer): logits and tokens are bit-identical."""
+    shape = MINI
+    w = to_gpu(make_weights(shape, 4))
+    prompt = make_prompt(shape.vocab, 33, 2).tolist()
+    ref = None
+    for mode in ("separate", "arena", "per_layer"):
+        ww = w if mode == "separate" else ssd.pack_weights({k: (list(v) if isinstance(v, list) else v) for k, v in w.items()},
+                                                           per_layer=mode == "per_layer")
+        ctx = ssd.Context(shape, ww, 80, max_k=4)
+        toks = [ctx.ssd_prefill(prompt)] + [ctx.ssd_decode() for _ in range(6)]
+        d = ctx.ssd_draft_step(np.array([0, 1, 0, 0], np.uint8), 4)
+        y = ctx.ssd_verify(d)
+        lg = ctx.ssd_copy_logits(0, 5).copy()
+        if ref is None:
+            ref = (toks, d, y, lg)
+        else:
+            assert toks == ref[0] and d == ref[1] and y == ref[2] and np.array_equal(lg, ref[3])
+        ctx.close()
