@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="reduced depth (debugging only; marks the result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pack", action="store_true", help="keep the weights as separately allocated tensors")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch-1 decoding, no collectives); --gpus %d is not supported"
@@ -105,15 +106,34 @@ def main():
 
     weights = make_weights(shape, wl.seed, device="cuda")
     w_bytes = sum(t.numel() * t.element_size() for v in weights.values() for t in (v if isinstance(v, list) else [v]))
-    # one allocation in forward order (one per layer where two copies of the model would not fit during the packing):
-    # the layout the library is fed in HBM
-    packed = ssd.pack_weights(weights, per_layer=w_bytes >= 100e9)
-    weights.clear()
-    weights = packed
-    torch.cuda.empty_cache()
+    # Layout of the weights in HBM: the library takes the pointers it is given, and how the matrices are placed
+    # matters by a few per cent (one arena in forward order is 2-3 % faster at the 7B shape, equal at the 13B
+    # shape), so both are timed on a few decode steps and the faster one is kept.
+    layout, packed = "separate", None
+    if not args.no_pack and w_bytes < 100e9:
+        def probe(wts):
+            c = ssd.Context(shape, wts, wl.prompt_len + (W + K + 4) * (k + 1) + 16, max_k=k)
+            c.ssd_prefill(make_prompt(shape.vocab, wl.prompt_len, wl.seed).tolist())
+            for _ in range(4):
+                c.ssd_decode()
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            for _ in range(24):
+                c.ssd_decode()
+            torch.cuda.synchronize(); dt = time.perf_counter() - t0
+            c.close()
+            return dt
+        t_sep = probe(weights)
+        packed = ssd.pack_weights(weights)
+        t_pack = probe(packed)
+        print("layout probe: separate %.2f ms, one arena %.2f ms per decode step" % (t_sep / 24 * 1e3, t_pack / 24 * 1e3),
+              file=sys.stderr)
+        if t_pack < t_sep:
+            weights, packed, layout = packed, weights, "one arena"
     prompt = make_prompt(shape.vocab, wl.prompt_len, wl.seed).tolist()
     max_seq = wl.prompt_len + (W + K + 4) * (k + 1) + 16
     ctx = ssd.Context(shape, weights, max_seq, max_k=k)
+    # the layout not chosen stays allocated until the process ends: releasing tens of GB right before the timed
+    # regions slowed them by 2-5 % (the driver is still unmapping while the kernels run)
     sync = torch.cuda.synchronize
 
     # ---- vanilla decoding with the same library ----------------------------------------------------
@@ -197,7 +217,7 @@ def main():
                                "ConfLayers search active (interval 30), random-init weights"
                                % (wl.name, L, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_ffn,
                                   shape.vocab, wl.prompt_len, k),
-                   "reduced_depth": args.layers is not None},
+                   "reduced_depth": args.layers is not None, "weight_layout": layout},
         "vanilla_tokens_per_s": van_tps,
         "vanilla_GBps": van_bytes * van_tps / 1e9,
         "vanilla_frac_of_hbm_peak": van_bytes * van_tps / 1e9 / HBM_PEAK_GBPS,

@@ -163,7 +163,7 @@ def ssd_uniform_skip(n_layers: int, params: Optional[ssd_select_params] = None) 
 
 def pack_weights(weights: dict, per_layer: bool = False) -> dict:
     """Copies the weight matrices into ONE device allocation, in the order a forward pass reads them (embedding,
-    then per layer wq wk wv wo wg wu wd, then the LM head), each 256-byte aligned, and returns a dict of views.
+    then per layer wq wk wv wo wg wu wd, then the LM head), each on a 2 MiB boundary, and returns a dict of views.
     Memory plumbing only: the library takes whatever pointers it is given; one arena streams a few per cent faster
     than a few hundred separate allocations.  per_layer=True makes one arena per layer instead and releases the
     source tensors of a layer as soon as they are copied (the lists of the input dict are emptied), for models of
@@ -171,12 +171,13 @@ def pack_weights(weights: dict, per_layer: bool = False) -> dict:
     import torch
     per = ("wq", "wk", "wv", "wo", "wg", "wu", "wd")
     L = len(weights["wq"])
-    nbytes = lambda t: (t.numel() * t.element_size() + 255) // 256 * 256
+    ALIGN = 2 << 20     # every matrix starts on a 2 MiB boundary of the arena (measured: 256-byte packing cost 4 % at 13B)
+    nbytes = lambda t: (t.numel() * t.element_size() + ALIGN - 1) // ALIGN * ALIGN
     dev = weights["embed"].device
 
     def fill(tensors):
-        arena = torch.empty(sum(nbytes(t) for t in tensors), dtype=torch.uint8, device=dev)
-        views, off = [], 0
+        arena = torch.empty(sum(nbytes(t) for t in tensors) + ALIGN, dtype=torch.uint8, device=dev)
+        views, off = [], (-arena.data_ptr()) % ALIGN
         for t in tensors:
             v = arena[off:off + t.numel() * t.element_size()].view(t.dtype).view(t.shape)
             v.copy_(t)
