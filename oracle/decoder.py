@@ -18,7 +18,14 @@ class _Cfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
                 ("vocab", C.c_int32), ("max_seq", C.c_int32),
-                ("rms_eps", C.c_double), ("rope_base", C.c_double), ("weight_dtype", C.c_int32)]
+                ("rms_eps", C.c_double), ("rope_base", C.c_double), ("weight_dtype", C.c_int32),
+                ("kv_storage", C.c_int32)]
+
+
+# K/V cache storage of the reference model: "model" = rounded to the weight type (the reading of Section 4.1.1:
+# a half-precision model's cache holds half-precision numbers), "exact" = kept in fp64 (nothing rounded: the
+# plain definition of attention), or an explicit type
+KV_STORAGE = {"exact": -1, "fp32": 0, "bf16": 1, "fp16": 2}
 
 
 _lib = None
@@ -75,11 +82,13 @@ DEFAULT_EPS = 1e-10     # epsilon of Eq. 2, not given in the paper
 class OracleModel:
     """Reference decoder over caller-supplied weights (dict as produced by synth.make_weights)."""
 
-    def __init__(self, shape, weights, max_seq: int):
+    def __init__(self, shape, weights, max_seq: int, kv_storage: str = "model"):
         lib = _load()
         self.shape = shape
         self.max_seq = int(max_seq)
         wt = {"fp32": 0, "bf16": 1, "fp16": 2}[shape.dtype]
+        self.kv_storage = shape.dtype if kv_storage == "model" else kv_storage
+        kvs = KV_STORAGE[self.kv_storage]
         self._keep = []
 
         def mat(t):
@@ -101,7 +110,7 @@ class OracleModel:
             return C.cast(ptrs, C.c_void_p)
 
         cfg = _Cfg(L, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
-                   shape.vocab, self.max_seq, shape.rms_eps, shape.rope_base, wt)
+                   shape.vocab, self.max_seq, shape.rms_eps, shape.rope_base, wt, kvs)
         self._h = lib.orc_create(C.byref(cfg), mat(weights["embed"]), mat(weights["lm_head"]),
                                  vec(weights["final_norm"]), arr("attn_norm", vec), arr("wq", mat),
                                  arr("wk", mat), arr("wv", mat), arr("wo", mat), arr("mlp_norm", vec),

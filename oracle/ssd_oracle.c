@@ -21,12 +21,15 @@
  * Matrices are row-major [out][in]; weights arrive as fp32 or as raw bf16 / fp16 bit patterns
  * (uint16) and are widened exactly.
  *
- * Storage precision: the evaluated models are held in half precision (Section 4.1.1), so the
- * K/V cache of such a model holds half-precision numbers.  The cache therefore stores each K
- * (after the rotary embedding) and V element rounded to the weight storage type -- bf16, fp16 or
- * fp32, round-to-nearest-even, via an fp32 intermediate as a half-precision tensor is produced
- * from fp32 compute -- and attention reads those stored values, for the rows of the current
- * block too.  Everything else stays in double.
+ * Storage precision of the K/V cache is a stated model parameter, orc_config.kv_storage:
+ *   ORC_KV_EXACT (-1): the cache holds the fp64 values -- the plain definition of attention over
+ *       the keys and values of Section 1 / Section 3, nothing rounded;
+ *   0 / 1 / 2: the cache stores each K (after the rotary embedding) and V element rounded to
+ *       fp32 / bf16 / fp16, round-to-nearest-even, via an fp32 intermediate as a half-precision
+ *       tensor is produced from fp32 compute -- the reading of Section 4.1.1 (models evaluated in
+ *       half precision, so the cache of such a model holds half-precision numbers) -- and
+ *       attention reads those stored values, for the rows of the current block too.
+ * Everything else stays in double in both modes.  Both modes are pinned by the CPU tests.
  */
 #include <math.h>
 #include <stdint.h>
@@ -37,7 +40,10 @@ typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, max_seq;
     double rms_eps, rope_base;
     int32_t weight_dtype; /* 0 = float32, 1 = bf16 stored as uint16, 2 = IEEE fp16 stored as uint16 */
+    int32_t kv_storage;   /* ORC_KV_EXACT = cache in fp64; 0 / 1 / 2 = K, V rounded to fp32 / bf16 / fp16 when stored */
 } orc_config;
+
+#define ORC_KV_EXACT (-1)
 
 typedef struct {
     orc_config c;
@@ -99,9 +105,10 @@ double orc_round_bf16(double x)
     return (double)f;
 }
 
-static double round_storage(double x, int dtype)
+static double round_storage(double x, int kv_storage)
 {
-    return dtype == 0 ? (double)(float)x : dtype == 1 ? orc_round_bf16(x) : orc_round_fp16(x);
+    if (kv_storage == ORC_KV_EXACT) return x;
+    return kv_storage == 0 ? (double)(float)x : kv_storage == 1 ? orc_round_bf16(x) : orc_round_fp16(x);
 }
 
 /* Y[r][n] = sum_k W[n][k] * X[r][k]   (W: N x K row-major, X: R x K, Y: R x N) */
@@ -156,6 +163,7 @@ orc_model *orc_create(const orc_config *cfg, const void *embed, const void *lm_h
                       const void **wg, const void **wu, const void **wd)
 {
     if (!cfg || cfg->n_heads % cfg->n_kv_heads || cfg->head_dim % 2) return NULL;
+    if (cfg->kv_storage < ORC_KV_EXACT || cfg->kv_storage > 2) return NULL;
     orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
     m->c = *cfg;
     int L = cfg->n_layers;
@@ -257,8 +265,8 @@ int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint
             for (int hh = 0; hh < H; hh++) rope_head(q + (size_t)r * dq + hh * hd, hd, p, c->rope_base);
             for (int hh = 0; hh < Hkv; hh++) rope_head(kk + (size_t)r * dkv + hh * hd, hd, p, c->rope_base);
             for (int i = 0; i < dkv; i++) {
-                Kc[(size_t)p * dkv + i] = round_storage(kk[(size_t)r * dkv + i], wt);
-                Vc[(size_t)p * dkv + i] = round_storage(vv[(size_t)r * dkv + i], wt);
+                Kc[(size_t)p * dkv + i] = round_storage(kk[(size_t)r * dkv + i], c->kv_storage);
+                Vc[(size_t)p * dkv + i] = round_storage(vv[(size_t)r * dkv + i], c->kv_storage);
             }
         }
 #pragma omp parallel for schedule(static) collapse(2)

@@ -1,9 +1,10 @@
 """Pins of the reference decoder against library routines, closed forms and invariants.
 
-None of these tests touches the HIP library.  The independent reference below is built from
+None of these tests touches the HIP library.  The independent reference (tests/_reference.py) is built from
 PyTorch library ops in float64 (rms_norm, scaled_dot_product_attention, silu, linear,
 embedding) with the rotary embedding written as a complex multiplication, i.e. a different
-formulation from the oracle's pairwise rotation.
+formulation from the oracle's pairwise rotation.  Both K/V storage modes of the oracle are pinned:
+"exact" (cache in fp64, the plain definition) and "model" (cache rounded to the weight type).
 """
 import dataclasses
 
@@ -14,39 +15,7 @@ import torch.nn.functional as F
 
 from oracle import OracleModel, OracleSSD, generate_ssd, generate_vanilla
 from synth import ModelShape, WORKLOADS, make_prompt, make_weights
-
-
-def torch_reference_logits(shape, w, tokens):
-    """Full-sequence recompute with library ops, float64; K and V pass through the model's storage type
-    (the half-precision cache of Section 4.1.1) by the library's own casts. Returns logits [T][V]."""
-    dd = torch.float64
-    st = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[shape.dtype]
-    T = len(tokens)
-    H, Hkv, hd = shape.n_heads, shape.n_kv_heads, shape.head_dim
-    x = F.embedding(torch.tensor(tokens, dtype=torch.long), w["embed"].to(dd))
-    pos = torch.arange(T, dtype=dd)
-    inv = shape.rope_base ** (-torch.arange(0, hd, 2, dtype=dd) / hd)       # base^(-2i/hd)
-    rot = torch.polar(torch.ones(T, hd // 2, dtype=dd), pos[:, None] * inv[None, :])  # e^{i p theta_i}
-
-    def rope(t):                       # t: [T][heads][hd], pairs (i, i+hd/2)
-        z = torch.complex(t[..., : hd // 2], t[..., hd // 2:]) * rot[:, None, :]
-        return torch.cat([z.real, z.imag], dim=-1)
-
-    for l in range(shape.n_layers):
-        h = F.rms_norm(x, (shape.d_model,), w["attn_norm"][l].to(dd), eps=shape.rms_eps)
-        q = rope(F.linear(h, w["wq"][l].to(dd)).view(T, H, hd))
-        k = rope(F.linear(h, w["wk"][l].to(dd)).view(T, Hkv, hd)).to(torch.float32).to(st).to(dd)
-        v = F.linear(h, w["wv"][l].to(dd)).view(T, Hkv, hd).to(torch.float32).to(st).to(dd)
-        k = k.repeat_interleave(H // Hkv, dim=1)
-        v = v.repeat_interleave(H // Hkv, dim=1)
-        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
-                                           v.transpose(0, 1)[None], is_causal=True)[0]
-        x = x + F.linear(o.transpose(0, 1).reshape(T, H * hd), w["wo"][l].to(dd))
-        h = F.rms_norm(x, (shape.d_model,), w["mlp_norm"][l].to(dd), eps=shape.rms_eps)
-        x = x + F.linear(F.silu(F.linear(h, w["wg"][l].to(dd))) * F.linear(h, w["wu"][l].to(dd)),
-                         w["wd"][l].to(dd))
-    h = F.rms_norm(x, (shape.d_model,), w["final_norm"].to(dd), eps=shape.rms_eps)
-    return F.linear(h, w["lm_head"].to(dd)).numpy()
+from tests._reference import reference_forward, reference_logits
 
 
 SHAPES = [
@@ -57,25 +26,49 @@ SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("kv", ["exact", "model"])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_matches_library_op_reference(shape):
+def test_matches_library_op_reference(shape, kv):
     # init_std 0.3 and jittered gains make every term (gain, rope, softmax scale) visible
     w = make_weights(shape, 11, norm_gain_std=0.2, init_std=0.3)
     toks = make_prompt(shape.vocab, 13, 5).tolist()
-    ref = torch_reference_logits(shape, w, toks)
-    m = OracleModel(shape, w, 32)
-    got = m.forward(toks, 0)["logits"]
-    assert np.abs(got - ref).max() <= 1e-9 * max(1.0, np.abs(ref).max())
+    ref, ref_taps = reference_forward(shape, w, toks, kv_storage=kv)
+    m = OracleModel(shape, w, 32, kv_storage=kv)
+    out = m.forward(toks, 0, want_taps=True)
+    assert np.abs(out["logits"] - ref).max() <= 1e-9 * max(1.0, np.abs(ref).max())
+    assert np.abs(out["taps"] - ref_taps).max() <= 1e-9 * max(1.0, np.abs(ref_taps).max())
     assert np.abs(ref).max() > 0.1        # the comparison is not vacuous
+    if kv == "model" and shape.dtype != "fp32":
+        # the storage mode matters: the two readings differ by far more than the pin's tolerance
+        assert np.abs(ref - reference_logits(shape, w, toks, "exact")).max() > 1e-6
 
 
-def test_tiny_workload_matches_library_op_reference(tiny_workload):
+@pytest.mark.parametrize("kv", ["exact", "model"])
+def test_tiny_workload_matches_library_op_reference(tiny_workload, kv):
     wl = tiny_workload
     w = make_weights(wl.shape, wl.seed)
     toks = make_prompt(wl.shape.vocab, wl.prompt_len, wl.seed).tolist()
-    ref = torch_reference_logits(wl.shape, w, toks)
-    got = OracleModel(wl.shape, w, 64).forward(toks, 0)["logits"]
+    ref = reference_logits(wl.shape, w, toks, kv)
+    got = OracleModel(wl.shape, w, 64, kv_storage=kv).forward(toks, 0)["logits"]
     assert np.abs(got - ref).max() <= 1e-11
+
+
+def test_draft_rows_match_library_op_reference():
+    """Draft model of Section 3 by full recompute: rows after the verified prefix leave out the skipped layers and
+    attend the full model's K/V of the prefix plus their own; both storage modes."""
+    shape = SHAPES[1]
+    w = make_weights(shape, 4, norm_gain_std=0.2, init_std=0.3)
+    toks = make_prompt(shape.vocab, 11, 8).tolist()
+    mask = np.array([1, 0], np.uint8)
+    for kv in ("exact", "model"):
+        ref, _ = reference_forward(shape, w, toks, kv, skip_mask=mask, n_verified=7)
+        m = OracleModel(shape, w, 16, kv_storage=kv)
+        m.forward(toks[:7], 0)
+        for p in range(7, 11):
+            z = m.forward([toks[p]], p, skip_mask=mask)["logits"][0]
+            assert np.abs(z - ref[p]).max() <= 1e-9 * max(1.0, np.abs(ref).max())
+        full = reference_logits(shape, w, toks, kv)
+        assert np.abs(full[7:] - ref[7:]).max() > 1e-3     # the skip set changes the result
 
 
 def test_cache_rounding_is_the_library_cast_and_is_applied():
@@ -156,16 +149,19 @@ def test_rope_is_identity_at_position_zero_and_preserves_norm():
     e = w["embed"][3].double()
     h = F.rms_norm(e, (64,), w["attn_norm"][0].double(), eps=shape.rms_eps)
     k_raw = F.linear(h, w["wk"][0].double()).view(2, 32).numpy()
-    K = m.kcache()[0]
-    # the cache of an fp32 model stores fp32 numbers: agreement to one fp32 rounding (2^-24 relative)
-    np.testing.assert_allclose(K[0], k_raw, rtol=6e-8, atol=1e-14)           # angle 0
-    for p in range(1, 4):                                                   # same token => same raw k
-        np.testing.assert_allclose(np.linalg.norm(K[p], axis=-1), np.linalg.norm(k_raw, axis=-1), rtol=6e-8)
-        assert np.abs(K[p] - k_raw).max() > 1e-3
-    # V is never rotated
     v_raw = F.linear(h, w["wv"][0].double()).view(2, 32).numpy()
-    for p in range(4):
-        np.testing.assert_allclose(m.vcache()[0][p], v_raw, rtol=6e-8, atol=1e-14)
+    # exact storage: the cache holds the fp64 values; model storage: the cache of an fp32 model stores fp32
+    # numbers, agreement to one fp32 rounding (2^-24 relative)
+    for kv, rtol in (("exact", 1e-12), ("model", 6e-8)):
+        mm = OracleModel(shape, w, 8, kv_storage=kv)
+        mm.forward(toks, 0)
+        K = mm.kcache()[0]
+        np.testing.assert_allclose(K[0], k_raw, rtol=rtol, atol=1e-14)           # angle 0
+        for p in range(1, 4):                                                   # same token => same raw k
+            np.testing.assert_allclose(np.linalg.norm(K[p], axis=-1), np.linalg.norm(k_raw, axis=-1), rtol=rtol)
+            assert np.abs(K[p] - k_raw).max() > 1e-3
+        for p in range(4):                                                      # V is never rotated
+            np.testing.assert_allclose(mm.vcache()[0][p], v_raw, rtol=rtol, atol=1e-14)
 
 
 def test_gqa_equals_mha_with_replicated_kv_heads():
