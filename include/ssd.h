@@ -13,7 +13,7 @@
  *     the device: KV cache, activations and scratch live in the caller's workspace buffer.
  *   - All device work is enqueued on the stream given to ssd_create.  Calls that return
  *     values through host pointers synchronise that stream before returning.
- *   - Matrices are row-major [out_features][in_features], fp32 or bf16.
+ *   - Matrices are row-major [out_features][in_features], fp32, bf16 or fp16.
  *   - Decoding state: committed tokens t_0..t_{n-1}; the cache holds verified K/V for
  *     positions 0..n-2; the last committed token is "pending" (not yet in the cache).
  *   - Call order: create -> set_workspace + load_weights -> prefill ->
@@ -32,6 +32,9 @@
 extern "C" {
 #endif
 
+/* The shared library is built with hidden visibility: exactly the functions declared here are exported. */
+#define SSD_API __attribute__((visibility("default")))
+
 enum {
     SSD_OK = 0,
     SSD_EINVAL = -1,    /* bad argument */
@@ -42,24 +45,27 @@ enum {
 };
 
 #define SSD_MAX_K 15        /* largest draft length: k + 1 rows fill one 16-column MFMA tile */
+#define SSD_MAX_LAYERS 128  /* deepest model a context accepts (fixed-size per-layer result slots in the workspace) */
 #define SSD_PREFILL_ROWS 64 /* most prompt rows processed per pass of the weights (16 where a shape does not fit the
                                64-row tiling: widths not multiples of 128, fp32 weights) */
 
 typedef struct ssd_ctx ssd_ctx;
 
 /* Decoder shape and numeric options.  d_model = n_heads * head_dim is not required, but
- * head_dim must be 64 or 128, n_heads a multiple of n_kv_heads, and d_model, d_ffn,
- * n_heads*head_dim, n_kv_heads*head_dim and vocab multiples of 16. */
+ * head_dim must be 64 or 128, n_heads a multiple of n_kv_heads, n_layers at most SSD_MAX_LAYERS, and d_model,
+ * d_ffn, n_heads*head_dim, n_kv_heads*head_dim and vocab multiples of 16. */
 typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, max_seq;
     float rms_eps, rope_base;
     int32_t weight_dtype; /* 0 = fp32, 1 = bf16, 2 = fp16 (the precision of Section 4.1.1): element type of the
-                             weight matrices and of the KV cache */
+                             weight matrices */
     int32_t conf_taps;    /* 2: confidence of a layer = mean over its post-attention and post-MLP hidden
                              states (Section 3.1: "FFNN and Attention" hidden states); 1: post-MLP only */
     float conf_clamp;     /* logits are clamped to [-conf_clamp, conf_clamp] before Eq. 1 */
     float conf_eps;       /* epsilon of Eq. 2 */
     int32_t max_k;        /* largest k that draft_step / verify will be called with (1..SSD_MAX_K) */
+    int32_t kv_dtype;     /* 0 = fp32, 1 = bf16, 2 = fp16: element type of the KV cache (K after the rotary embedding and V
+                             are rounded to it, nearest-even, when stored); independent of weight_dtype */
 } ssd_config;
 
 /* Device pointers to the weights.  The per-layer members are HOST arrays of n_layers DEVICE
@@ -87,27 +93,27 @@ typedef struct {
 
 /* Validates cfg and creates a host-side context bound to hip_stream (a hipStream_t, may be
  * NULL for the default stream).  No device memory is touched. */
-int ssd_create(const ssd_config *cfg, void *hip_stream, ssd_ctx **out);
+SSD_API int ssd_create(const ssd_config *cfg, void *hip_stream, ssd_ctx **out);
 
 /* Bytes of device workspace a context with this cfg needs (KV cache for max_seq positions,
  * rotary table, activations for max(max_k + 1, SSD_PREFILL_ROWS) rows, hidden-state taps,
  * logits, split-attention partials).  0 if cfg is invalid. */
-size_t ssd_workspace_bytes(const ssd_config *cfg);
+SSD_API size_t ssd_workspace_bytes(const ssd_config *cfg);
 
 /* Hands the context its workspace: device memory, 256-byte aligned, at least
  * ssd_workspace_bytes(cfg) long, borrowed until ssd_destroy.  Uploads the rotary table.
  * SSD_ENOMEM if dev is NULL or bytes too small. */
-int ssd_set_workspace(ssd_ctx *ctx, void *dev, size_t bytes);
+SSD_API int ssd_set_workspace(ssd_ctx *ctx, void *dev, size_t bytes);
 
 /* Section 3 / Figure 2: the same weights serve the draft and the target model.  Borrows the
  * device pointers (no copy, no repack); the caller keeps the tensors alive. */
-int ssd_load_weights(ssd_ctx *ctx, const ssd_weights *w);
+SSD_API int ssd_load_weights(ssd_ctx *ctx, const ssd_weights *w);
 
 /* Forget the sequence (back to the state after load_weights); weights and workspace stay. */
-int ssd_reset(ssd_ctx *ctx);
-void ssd_destroy(ssd_ctx *ctx);
-const char *ssd_last_error(const ssd_ctx *ctx);
-int ssd_get_stats(const ssd_ctx *ctx, ssd_stats *out);
+SSD_API int ssd_reset(ssd_ctx *ctx);
+SSD_API void ssd_destroy(ssd_ctx *ctx);
+SSD_API const char *ssd_last_error(const ssd_ctx *ctx);
+SSD_API int ssd_get_stats(const ssd_ctx *ctx, ssd_stats *out);
 
 /* ---- generation step (Figure 2, "generation") ----------------------------------------- */
 
@@ -115,11 +121,11 @@ int ssd_get_stats(const ssd_ctx *ctx, ssd_stats *out);
  * Fills the cache for positions 0..n-1, keeps the hidden-state taps of the last row, and
  * commits the greedy first new token (returned in *first_token_out, host). n + 1 tokens are
  * then committed.  SSD_ECAPACITY if n + 1 > max_seq. */
-int ssd_prefill(ssd_ctx *ctx, const int32_t *tokens, int n, int32_t *first_token_out);
+SSD_API int ssd_prefill(ssd_ctx *ctx, const int32_t *tokens, int n, int32_t *first_token_out);
 
 /* One vanilla autoregressive step with the full model (the baseline of Section 4.1.1):
  * feeds the pending token, commits and returns the greedy next token. */
-int ssd_decode(ssd_ctx *ctx, int32_t *token_out);
+SSD_API int ssd_decode(ssd_ctx *ctx, int32_t *token_out);
 
 /* Draft model of Section 3: the target model without the layers in the skip set S
  * (skip_mask[l] != 0 means layer l is in S; a skipped layer leaves the residual stream
@@ -127,7 +133,7 @@ int ssd_decode(ssd_ctx *ctx, int32_t *token_out);
  * starting from the pending token; executed layers write draft K/V at positions n-1..n+k-2.
  * draft_out: host [k]; draft_maxprob_out: host [k] or NULL (softmax max-probability of each
  * drafted token).  SSD_ECAPACITY if n + k > max_seq or k > max_k. */
-int ssd_draft_step(ssd_ctx *ctx, const uint8_t *skip_mask, int k, int32_t *draft_out,
+SSD_API int ssd_draft_step(ssd_ctx *ctx, const uint8_t *skip_mask, int k, int32_t *draft_out,
                    float *draft_maxprob_out);
 
 /* Confidence-aware drafting (Section 3: once a skip set is found the candidate tokens are
@@ -139,7 +145,7 @@ int ssd_draft_step(ssd_ctx *ctx, const uint8_t *skip_mask, int k, int32_t *draft
  * number of tokens drafted (1..k_max), which is the k to pass to ssd_verify / ssd_accept.
  * The comparison p < gamma is taken in fp32 on the max-probability the device computed.
  * SSD_ECAPACITY if n + k_max > max_seq or k_max > max_k; SSD_EINVAL if gamma is NaN. */
-int ssd_draft_adaptive(ssd_ctx *ctx, const uint8_t *skip_mask, int k_max, float gamma,
+SSD_API int ssd_draft_adaptive(ssd_ctx *ctx, const uint8_t *skip_mask, int k_max, float gamma,
                        int32_t *draft_out, float *draft_maxprob_out, int32_t *k_out);
 
 /* Verification (Section 1: drafted tokens "verified by the target model in a single forward
@@ -148,23 +154,24 @@ int ssd_draft_adaptive(ssd_ctx *ctx, const uint8_t *skip_mask, int k_max, float 
  * the hidden-state taps of all k+1 rows.  target_out: host [k+1], the greedy token after
  * each row.  Must follow ssd_draft_step / ssd_draft_adaptive with the same k; the draft tokens passed here are
  * the ones verified. */
-int ssd_verify(ssd_ctx *ctx, const int32_t *draft, int k, int32_t *target_out);
+SSD_API int ssd_verify(ssd_ctx *ctx, const int32_t *draft, int k, int32_t *target_out);
 
 /* Greedy acceptance: a = largest m with draft_j == target_{j-1} for all 1 <= j <= m; commits
  * draft_1..draft_a and target_a (a + 1 tokens), which becomes the pending token; cache
- * entries beyond position n-1+a are stale and never read again. Host in, host out. */
-int ssd_accept(ssd_ctx *ctx, const int32_t *draft, const int32_t *target, int k,
+ * entries beyond position n-1+a are stale and never read again. Host in, host out; the device-side
+ * state update is enqueued on the stream, the call does not synchronise. */
+SSD_API int ssd_accept(ssd_ctx *ctx, const int32_t *draft, const int32_t *target, int k,
                int32_t *n_accepted_out, int32_t *next_token_out);
 
 /* Test hook: after ssd_verify, commit n_accepted drafted tokens and next_token regardless of
  * what the device computed (re-synchronises with an external reference after a sub-tolerance
  * arg-max tie).  draft: host [k] as passed to ssd_verify. */
-int ssd_force_commit(ssd_ctx *ctx, const int32_t *draft, int k, int n_accepted, int32_t next_token);
+SSD_API int ssd_force_commit(ssd_ctx *ctx, const int32_t *draft, int k, int n_accepted, int32_t next_token);
 
 /* Copies fp32 logits rows [row_begin, row_begin + n_rows) of the last prefill (1 row),
  * decode (1 row), draft_step (k rows, one per drafted token) or verify (k+1 rows) to host
  * memory [n_rows][vocab]. */
-int ssd_copy_logits(ssd_ctx *ctx, int row_begin, int n_rows, float *logits_out);
+SSD_API int ssd_copy_logits(ssd_ctx *ctx, int row_begin, int n_rows, float *logits_out);
 
 /* ---- layer optimisation search step (Section 3.1) -------------------------------------- */
 
@@ -175,7 +182,7 @@ int ssd_copy_logits(ssd_ctx *ctx, int row_begin, int n_rows, float *logits_out);
  *   conf_out       host [n_rows][n_layers]: mean over the layer's taps (conf_taps of them)
  *   tap_conf_out   host [n_rows][n_layers][2] or NULL: post-attention, post-MLP confidence
  *   tap_maxprob_out, tap_argmax_out  host [n_rows][n_layers][2] or NULL */
-int ssd_layer_confidence(ssd_ctx *ctx, int row_begin, int n_rows, float *conf_out,
+SSD_API int ssd_layer_confidence(ssd_ctx *ctx, int row_begin, int n_rows, float *conf_out,
                          float *tap_conf_out, float *tap_maxprob_out, int32_t *tap_argmax_out);
 
 /* Eq. 5-10 parameters.  Defaults (ssd_select_defaults): lambda 0.3, w_base 2, kappa 1,
@@ -192,7 +199,7 @@ typedef struct {
     double fixed_w_max; /* >= 0: use this w_max instead (0 = constant window, Section 4.3.2) */
 } ssd_select_params;
 
-void ssd_select_defaults(ssd_select_params *p);
+SSD_API void ssd_select_defaults(ssd_select_params *p);
 
 /* Section 3.2: standardise the confidences (Eq. 5), second-order discrete gradient rescaled
  * to [0,1] (Eq. 6), per-layer window w_i (Eq. 7), local mean / std excluding the layer
@@ -201,11 +208,11 @@ void ssd_select_defaults(ssd_select_params *p);
  * [n_layers], 1 = skip, implicitly sorted by index; n_skipped_out may be NULL;
  * margin_out: host [n_layers] or NULL, c_hat_i - (mu_local - lambda sigma_local), 0 for
  * non-candidates. */
-int ssd_select_skip(const double *conf, int n_layers, const ssd_select_params *p,
+SSD_API int ssd_select_skip(const double *conf, int n_layers, const ssd_select_params *p,
                     uint8_t *mask_out, int32_t *n_skipped_out, double *margin_out);
 
 /* Initial draft model: uniform layer skipping (Section 3), every second candidate layer. */
-int ssd_uniform_skip(int n_layers, const ssd_select_params *p, uint8_t *mask_out);
+SSD_API int ssd_uniform_skip(int n_layers, const ssd_select_params *p, uint8_t *mask_out);
 
 /* ---- search check (Section 3.3) --------------------------------------------------------- */
 
@@ -217,29 +224,29 @@ typedef struct {
     int32_t window;       /* confidence vectors of the last `window` cycles are averaged (100) */
 } ssd_search_params;
 
-void ssd_search_defaults(ssd_search_params *p);
-int ssd_search_create(int n_layers, const ssd_search_params *sp, const ssd_select_params *sel,
+SSD_API void ssd_search_defaults(ssd_search_params *p);
+SSD_API int ssd_search_create(int n_layers, const ssd_search_params *sp, const ssd_select_params *sel,
                       ssd_search **out);
-void ssd_search_destroy(ssd_search *s);
+SSD_API void ssd_search_destroy(ssd_search *s);
 /* Current skip set (host [n_layers]); starts as the uniform set. */
-int ssd_search_mask(const ssd_search *s, uint8_t *mask_out);
+SSD_API int ssd_search_mask(const ssd_search *s, uint8_t *mask_out);
 /* Feed one finished cycle: its accepted count and (optionally, may be NULL) its per-layer
  * confidences, host [n_layers] doubles.  Every opt_interval cycles the set is scored by its
  * mean accepted tokens, the best set is kept, and either the search halts (goal reached or
  * max_rounds) and the best set is adopted for good, or a new set is selected from the
  * averaged confidences.  mask_out receives the set for the next cycle; *active_out is 0
  * once the search has halted. */
-int ssd_search_observe(ssd_search *s, int n_accepted, const double *conf, uint8_t *mask_out,
+SSD_API int ssd_search_observe(ssd_search *s, int n_accepted, const double *conf, uint8_t *mask_out,
                        int32_t *active_out);
 /* rounds scored so far, best score so far (either may be NULL) */
-int ssd_search_status(const ssd_search *s, int32_t *rounds_out, double *best_score_out);
+SSD_API int ssd_search_status(const ssd_search *s, int32_t *rounds_out, double *best_score_out);
 
 /* ---- measurement helpers ----------------------------------------------------------------- */
 
 /* Streams `bytes` of device memory once through a read-only kernel `iters` times and
  * returns the mean time per pass in milliseconds (the practical HBM read ceiling of the
  * box).  dev: device pointer, 16-byte aligned; stream as in ssd_create. */
-int ssd_hbm_read_probe(const void *dev, size_t bytes, int iters, void *hip_stream, float *ms_out);
+SSD_API int ssd_hbm_read_probe(const void *dev, size_t bytes, int iters, void *hip_stream, float *ms_out);
 
 /* Per-kernel timing for roofline measurements: while a kernel id is selected, every launch of
  * that kernel is bracketed by HIP events on the context's stream (this perturbs the stream, so
@@ -261,16 +268,16 @@ enum {
     SSD_K_ROWS_LMHEAD = 11, /* verify / confidence: LM head MFMA GEMM */
     SSD_K_COUNT = 12
 };
-int ssd_profile_select(ssd_ctx *ctx, int kernel_id);
+SSD_API int ssd_profile_select(ssd_ctx *ctx, int kernel_id);
 /* Launch mode: 1 (default) replays decode / draft / verify launch sequences as HIP graphs once a
  * sequence has been seen twice (needs a non-default stream); 0 launches kernel by kernel.  Both
  * modes run the same kernels with the same arguments and give bit-identical results. */
-int ssd_set_graphs(ssd_ctx *ctx, int enable);
-int ssd_profile_read(ssd_ctx *ctx, int64_t *launches_out, double *total_ms_out);
+SSD_API int ssd_set_graphs(ssd_ctx *ctx, int enable);
+SSD_API int ssd_profile_read(ssd_ctx *ctx, int64_t *launches_out, double *total_ms_out);
 
 /* Test hook: overwrite every cache entry at positions >= the number of valid positions
  * (n - 1) with NaN, to prove stale entries are never read. */
-int ssd_kv_poison_stale(ssd_ctx *ctx);
+SSD_API int ssd_kv_poison_stale(ssd_ctx *ctx);
 
 #ifdef __cplusplus
 }

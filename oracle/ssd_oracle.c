@@ -73,6 +73,17 @@ static double widen_fp16(uint16_t h)
     return sign ? -v : v;
 }
 
+/* The same conversion for all 65 536 bit patterns, tabulated once per process (the formula above, evaluated
+ * ahead of the matrix products instead of inside their inner loop); filled by orc_create before any use. */
+static double fp16_value[65536];
+static int fp16_value_ready = 0;
+static void fill_fp16_table(void)
+{
+    if (fp16_value_ready) return;
+    for (int h = 0; h < 65536; h++) fp16_value[h] = widen_fp16((uint16_t)h);
+    fp16_value_ready = 1;
+}
+
 /* x rounded to fp32 and then to fp16 (round-to-nearest-even both times), returned as a double.
  * The fp16 step rounds the fp32 value on the fp16 grid: spacing 2^(e-10) for |x| in [2^e, 2^(e+1)),
  * e >= -14, and 2^-24 below 2^-14; values that round to 65520 or more become infinity. */
@@ -127,7 +138,7 @@ static void matmul_wt(const void *W, int dtype, int N, int K, const double *X, i
                 for (int k = 0; k < K; k++) acc += widen_bf16(w[k]) * x[k];
             } else {
                 const uint16_t *w = (const uint16_t *)W + (size_t)n * K;
-                for (int k = 0; k < K; k++) acc += widen_fp16(w[k]) * x[k];
+                for (int k = 0; k < K; k++) acc += fp16_value[w[k]] * x[k];
             }
             Y[(size_t)r * N + n] = acc;
         }
@@ -166,6 +177,7 @@ orc_model *orc_create(const orc_config *cfg, const void *embed, const void *lm_h
     if (cfg->kv_storage < ORC_KV_EXACT || cfg->kv_storage > 2) return NULL;
     orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
     m->c = *cfg;
+    fill_fp16_table();
     int L = cfg->n_layers;
     m->embed = embed; m->lm_head = lm_head; m->final_norm = final_norm;
 #define COPYP(field, type) m->field = (type)malloc(sizeof(void *) * L); memcpy((void *)m->field, field, sizeof(void *) * L)
@@ -241,7 +253,7 @@ int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint
             size_t o = (size_t)tokens[r] * d + i;
             x[(size_t)r * d + i] = wt == 0   ? (double)((const float *)m->embed)[o]
                                    : wt == 1 ? widen_bf16(((const uint16_t *)m->embed)[o])
-                                             : widen_fp16(((const uint16_t *)m->embed)[o]);
+                                             : fp16_value[((const uint16_t *)m->embed)[o]];
         }
 
     for (int l = 0; l < L; l++) {

@@ -13,7 +13,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libssd.so")
+# SSD_LIB_PATH names another build of the same library (the sanitizer build of the CPU tests); default: in-tree
+LIB_PATH = os.environ.get("SSD_LIB_PATH") or os.path.join(_HERE, "libssd.so")
 
 SSD_OK, SSD_EINVAL, SSD_ESTATE, SSD_ECAPACITY, SSD_ENOMEM, SSD_EHIP = 0, -1, -2, -3, -4, -5
 SSD_MAX_K = 15
@@ -34,7 +35,7 @@ class ssd_config(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
                 ("vocab", C.c_int32), ("max_seq", C.c_int32), ("rms_eps", C.c_float),
                 ("rope_base", C.c_float), ("weight_dtype", C.c_int32), ("conf_taps", C.c_int32),
-                ("conf_clamp", C.c_float), ("conf_eps", C.c_float), ("max_k", C.c_int32)]
+                ("conf_clamp", C.c_float), ("conf_eps", C.c_float), ("max_k", C.c_int32), ("kv_dtype", C.c_int32)]
 
 
 class ssd_weights(C.Structure):
@@ -256,11 +257,21 @@ class Search:
 
 # ---- device context --------------------------------------------------------------------------
 
+_DTYPE_CODE = {"fp32": 0, "bf16": 1, "fp16": 2}
+
+
+def default_kv_dtype(shape) -> str:
+    """Element type of the KV cache when the caller names none: fp32 for fp32 models, fp16 for 16-bit models -- the
+    paper's own precision (Section 4.1.1); three more mantissa bits than bf16 at the same size."""
+    return "fp32" if shape.dtype == "fp32" else "fp16"
+
+
 def make_config(shape, max_seq: int, max_k: int = 8, conf_taps: int = 2, conf_clamp: float = 1e4,
-                conf_eps: float = 1e-10) -> ssd_config:
+                conf_eps: float = 1e-10, kv_dtype: Optional[str] = None) -> ssd_config:
     return ssd_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                       shape.d_ffn, shape.vocab, int(max_seq), shape.rms_eps, shape.rope_base,
-                      {"fp32": 0, "bf16": 1, "fp16": 2}[shape.dtype], conf_taps, conf_clamp, conf_eps, max_k)
+                      _DTYPE_CODE[shape.dtype], conf_taps, conf_clamp, conf_eps, max_k,
+                      _DTYPE_CODE[kv_dtype or default_kv_dtype(shape)])
 
 
 class Context:
@@ -275,6 +286,7 @@ class Context:
         self._l = lib()
         self.shape = shape
         self.cfg = make_config(shape, max_seq, max_k, **cfg_kw)
+        self.kv_dtype = {v: k for k, v in _DTYPE_CODE.items()}[self.cfg.kv_dtype]
         h = C.c_void_p()
         # a stream of its own (default priority): the legacy default stream cannot be graph-captured
         self.stream = torch.cuda.Stream()

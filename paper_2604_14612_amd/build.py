@@ -8,7 +8,7 @@ LIB = os.path.join(HERE, "libssd.so")
 KERNEL_BENCH = os.path.join(HERE, "kernel_bench")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
                 "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
@@ -22,7 +22,7 @@ def build(verbose: bool = False) -> str:
         obj = os.path.splitext(src)[0] + ".o"
         if src.endswith("ssd_policy.cpp"):
             # pure host arithmetic: no contraction, so results do not depend on the build
-            cmd = [HIPCC, "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-c", src, "-o", obj]
+            cmd = [HIPCC, "-O2", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=off", "-c", src, "-o", obj]
         elif src.endswith(".hip"):
             cmd = [HIPCC] + DEVICE_FLAGS + ["-c", src, "-o", obj]
         else:
@@ -36,7 +36,8 @@ def build(verbose: bool = False) -> str:
         if verbose and err.strip():
             print(err)
         objs.append(obj)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,--version-script=" + os.path.join(CSRC, "libssd.map"),
+           "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)

@@ -51,7 +51,9 @@ int main(int argc, char** argv)
     if (M < 1 || M > 16) { std::printf("rows must be 1..16\n"); return 1; }
     Dims D;
     D.L = 32; D.d = 4096; D.H = 32; D.Hkv = 32; D.hd = 128; D.dq = 4096; D.dkv = 4096; D.f = 11008; D.V = 32000;
-    D.max_seq = 1024; D.eps = 1e-5f; D.wt = WT_BF16;
+    D.max_seq = 1024; D.eps = 1e-5f; D.wt = WT_BF16; D.kt = WT_BF16;
+    LaunchOpts opts;   // tuning hooks of this run
+    D.opt = &opts;
     const size_t wbig = (size_t)3 << 30;  // 6 GB of bf16 weights to walk through
     uint16_t* W;
     CK(hipMalloc(&W, wbig * 2));
@@ -154,7 +156,7 @@ int main(int argc, char** argv)
     }
     // single-row (draft / vanilla decode) kernels
     for (int cap : {0, 1024, 512}) {
-    gemv_block_cap(cap);
+    opts.gemv_block_cap = cap;
     std::printf("-- gemv block cap %d\n", cap);
     timeit("gemv_qkv", 3 * qk * 2.0, n, [&](int i) {
         const uint16_t* w = W + (size_t)i * 3 * qk;
@@ -166,12 +168,12 @@ int main(int argc, char** argv)
     timeit("gemv_down (resid)", gu * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * gu, 4096, 11008, act, x, nullptr, 0)); });
     timeit("gemv_lmhead", lm * 2.0, n, [&](int i) { CK(gemv_lmhead(D, W + (size_t)i * lm, gain, x, logits, 0)); });
     }
-    gemv_block_cap(0);
+    opts.gemv_block_cap = 0;
     for (int kind : {1, 0}) {   // 1 = LDS-staged kernel forced, 0 = launch plan (register-resident kernel for few queries)
-        attention_force_kernel(kind);
+        opts.attn_kernel = kind;
         for (int sp : {0, 1, 2, 4, 8}) {
             if (kind == 1 && sp != 0 && sp < 8) continue;   // the LDS-staged kernel needs ctx / 96 ranges at least
-            attention_force_splits(sp);
+            opts.attn_splits = sp;
             char nm[96];
             std::snprintf(nm, sizeof nm, "attention 1 row ctx 641, %s, splits %s%d", kind ? "lds-staged" : "planned",
                           sp ? "" : "auto=", sp ? sp : std::abs(attention_splits(D, ctx + 1, 1)));
@@ -180,14 +182,14 @@ int main(int argc, char** argv)
                              nullptr, 0)); });
         }
     }
-    attention_force_splits(0);
-    attention_force_kernel(0);
+    opts.attn_splits = 0;
+    opts.attn_kernel = 0;
     timeit("attention + gemv_o, fold kernel", 2.0 * 641 * 4096 * 2 + qk * 2.0, n, [&](int i) {
         CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0));
         CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
     for (int cap : {0, 512}) for (int sp : {0, 4, 8}) {
-        attention_force_splits(sp);
-        gemv_block_cap(cap);
+        opts.attn_splits = sp;
+        opts.gemv_block_cap = cap;
         char nm[96];
         std::snprintf(nm, sizeof nm, "attention + gemv_o, fold in gemv, splits %d cap %d", sp, cap);
         timeit(nm, 2.0 * 641 * 4096 * 2 + qk * 2.0, n, [&](int i) {
@@ -197,8 +199,8 @@ int main(int argc, char** argv)
             if (fold > 0) CK(gemv_resid_attn(D, W + (size_t)i * qk, part, fold, x, nullptr, 0));
             else CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
     }
-    attention_force_splits(0);
-    gemv_block_cap(0);
+    opts.attn_splits = 0;
+    opts.gemv_block_cap = 0;
     timeit("vocab_reduce 1 row", 32000 * 4.0, n, [&](int) {
         CK(vocab_reduce(logits, 1, 32000, 1e4f, 1e-10f, pos + 8, 1, nullptr, sink, nullptr, 0)); });
 
@@ -246,7 +248,7 @@ int main(int argc, char** argv)
             CK(rows_wide(D, f, 0));
         };
         for (int ks : {0, 1, 2, 4, 8}) {
-        rows_wide_ksplit(ks);
+        opts.wide_ksplit = ks;
         std::printf("-- 64-row pass (prompt blocks), K slices: %d (0 = library's choice, 1 = none)\n", ks);
         timeit("wide_qkv", 3 * qk * 2.0, n, [&](int i) {
             const uint16_t* w = W + (size_t)i * 3 * qk;
@@ -257,13 +259,13 @@ int main(int argc, char** argv)
             wide(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
         timeit("wide_down (resid)", gu * 2.0, n, [&](int i) { wide(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, big_b, 4096); });
         }
-        rows_wide_ksplit(0);
+        opts.wide_ksplit = 0;
     }
     for (int kind : {1, 0}) {
-        attention_force_kernel(kind);
+        opts.attn_kernel = kind;
         for (int sp : {0, 2, 4, 8, 16}) {
             if (kind == 1 && sp != 0) continue;
-            attention_force_splits(sp);
+            opts.attn_splits = sp;
             char nm[96];
             std::snprintf(nm, sizeof nm, "attention M rows ctx 640+M, %s, splits %s%d", kind ? "lds-staged" : "planned",
                           sp ? "" : "auto=", sp ? sp : std::abs(attention_splits(D, ctx + M, M)));
@@ -272,19 +274,19 @@ int main(int argc, char** argv)
                              lo, 0)); });
         }
     }
-    attention_force_splits(0);
-    attention_force_kernel(0);
+    opts.attn_splits = 0;
+    opts.attn_kernel = 0;
     for (int kind : {3, 1}) for (int rows : {9, 16, 64}) for (int sp : {0, 16}) {
         if (sp && (kind == 3 || rows != 64)) continue;
-        attention_force_kernel(kind);
-        attention_force_splits(sp);
+        opts.attn_kernel = kind;
+        opts.attn_splits = sp;
         char nm[96];
         std::snprintf(nm, sizeof nm, "attention %d rows ctx 640+rows, LDS-staged %s, splits %d", rows, kind == 3 ? "plain" : "MFMA", sp);
         timeit(nm, 2.0 * (640 + rows) * 4096 * 2, n, [&](int i) {
             CK(attention(D, big_a, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, rows, part, nullptr,
                          hi64, lo64, 0)); });
     }
-    attention_force_kernel(0);
-    attention_force_splits(0);
+    opts.attn_kernel = 0;
+    opts.attn_splits = 0;
     return 0;
 }

@@ -35,7 +35,7 @@ struct Layout {
 bool valid_cfg(const ssd_config* c)
 {
     if (!c) return false;
-    if (c->n_layers < 1 || c->d_model < 16 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 16 ||
+    if (c->n_layers < 1 || c->n_layers > SSD_MAX_LAYERS || c->d_model < 16 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 16 ||
         c->vocab < 16 || c->max_seq < 2)
         return false;
     if (c->head_dim != 64 && c->head_dim != 128) return false;
@@ -43,6 +43,7 @@ bool valid_cfg(const ssd_config* c)
     long dq = (long)c->n_heads * c->head_dim, dkv = (long)c->n_kv_heads * c->head_dim;
     if (c->d_model % 16 || c->d_ffn % 16 || dq % 16 || dkv % 16 || c->vocab % 16) return false;
     if (c->weight_dtype < 0 || c->weight_dtype > 2) return false;
+    if (c->kv_dtype < 0 || c->kv_dtype > 2) return false;
     if (c->conf_taps != 1 && c->conf_taps != 2) return false;
     if (c->max_k < 1 || c->max_k > SSD_MAX_K) return false;
     if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f) || !(c->conf_clamp > 0.f) || !(c->conf_eps >= 0.f)) return false;
@@ -54,7 +55,7 @@ Dims make_dims(const ssd_config& c)
     Dims D;
     D.L = c.n_layers; D.d = c.d_model; D.H = c.n_heads; D.Hkv = c.n_kv_heads; D.hd = c.head_dim;
     D.dq = c.n_heads * c.head_dim; D.dkv = c.n_kv_heads * c.head_dim; D.f = c.d_ffn; D.V = c.vocab;
-    D.max_seq = c.max_seq; D.eps = c.rms_eps; D.wt = c.weight_dtype;
+    D.max_seq = c.max_seq; D.eps = c.rms_eps; D.wt = c.weight_dtype; D.kt = c.kv_dtype;
     return D;
 }
 
@@ -62,7 +63,7 @@ Layout make_layout(const ssd_config& c)
 {
     Dims D = make_dims(c);
     Layout l;
-    size_t esz = c.weight_dtype == 0 ? 4 : 2;
+    size_t esz = c.kv_dtype == 0 ? 4 : 2;
     l.prefill_rows = rows_wide_supported(D) ? SSD_PREFILL_ROWS : 16;
     l.rows = c.max_k + 1 > l.prefill_rows ? c.max_k + 1 : l.prefill_rows;
     l.conf_rows = 2 * c.n_layers;
@@ -97,7 +98,7 @@ Layout make_layout(const ssd_config& c)
 
 // offsets (in 4-byte words) inside the "small" region
 enum { SM_POS = 0, SM_TOK = 8 /* 17 ints: pending + drafts */, SM_RES = 56 /* 2 */, SM_MAXPROB = 64 /* 16 floats */,
-       SM_SINK = 96, SM_CONF = 128 /* conf_rows floats x3 follow (at most 3 x 160) */,
+       SM_SINK = 96, SM_CONF = 128 /* conf_rows floats x3 follow (at most 3 x 2 x SSD_MAX_LAYERS, checked where used) */,
        SM_VTOK = 896 /* 64: tokens of a row block */, SM_TARGET = 960 /* 64: greedy token after each row of a block */ };
 
 }  // namespace
@@ -105,6 +106,7 @@ enum { SM_POS = 0, SM_TOK = 8 /* 17 ints: pending + drafts */, SM_RES = 56 /* 2 
 struct ssd_ctx {
     ssd_config cfg;
     Dims D;
+    LaunchOpts opts;   // D.opt points here
     Layout lay;
     hipStream_t stream;
     State state;
@@ -135,12 +137,12 @@ struct ssd_ctx {
     int* pos_dev() const { return small_i() + SM_POS; }
     void* kcache(int l) const
     {
-        size_t esz = cfg.weight_dtype == 0 ? 4 : 2;
+        size_t esz = cfg.kv_dtype == 0 ? 4 : 2;
         return ws + lay.kv + ((size_t)l * 2 + 0) * lay.kv_layer_elems * esz;
     }
     void* vcache(int l) const
     {
-        size_t esz = cfg.weight_dtype == 0 ? 4 : 2;
+        size_t esz = cfg.kv_dtype == 0 ? 4 : 2;
         return ws + lay.kv + ((size_t)l * 2 + 1) * lay.kv_layer_elems * esz;
     }
 };
@@ -182,7 +184,8 @@ static inline bool is_gemv_kid(int kid)
                 c->prof_ev.emplace_back(a__, b__);                                         \
             }                                                                              \
             if (is_gemv_kid(kid)) {                                                        \
-                gemv_time_next_launch(c->prof_ev[c->prof_used].first, c->prof_ev[c->prof_used].second); \
+                c->opts.time_start = c->prof_ev[c->prof_used].first;                       \
+                c->opts.time_stop = c->prof_ev[c->prof_used].second;                       \
                 HIPCHK(call, where);                                                       \
             } else {                                                                       \
                 HIPCHK(hipEventRecord(c->prof_ev[c->prof_used].first, c->stream), "event"); \
@@ -449,6 +452,7 @@ int ssd_create(const ssd_config* cfg, void* hip_stream, ssd_ctx** out)
     ssd_ctx* c = new ssd_ctx();
     c->cfg = *cfg;
     c->D = make_dims(*cfg);
+    c->D.opt = &c->opts;
     c->lay = make_layout(*cfg);
     c->stream = (hipStream_t)hip_stream;
     c->state = ST_CREATED;
@@ -712,16 +716,13 @@ int ssd_accept(ssd_ctx* c, const int32_t* draft, const int32_t* target, int k, i
     if (k != c->k_pending) return fail(c, SSD_EINVAL, "accept: k differs from the draft's");
     for (int i = 0; i <= k; i++)
         if (target[i] < 0 || target[i] >= c->D.V) return fail(c, SSD_EINVAL, "target token id out of range");
-    // the target tokens are taken from the host array: upload them next to the device copy
-    HIPCHK(hipMemcpyAsync(c->small_i() + SM_TARGET, target, sizeof(int32_t) * (k + 1), hipMemcpyHostToDevice, c->stream),
-           "target upload");
-    TokArg d = {};
-    for (int i = 0; i < k; i++) d.t[i] = draft[i];
-    HIPCHK(accept_commit(d, c->small_i() + SM_TARGET, k, c->small_i() + SM_RES, c->small_i() + SM_TOK, c->pos_dev(),
-                         c->stream), "accept");
+    // Both token arrays are on the host already: the prefix match is taken here and the device-side state (pending
+    // token, position) is updated by an enqueued kernel -- no read-back, no synchronisation in this call.
     int32_t res[2];
-    int rc = readback(c, c->small_i() + SM_RES, sizeof(res), res);
-    if (rc) return rc;
+    res[0] = 0;
+    while (res[0] < k && draft[res[0]] == target[res[0]]) res[0]++;
+    res[1] = target[res[0]];
+    HIPCHK(set_state(c->small_i() + SM_TOK, res[1], c->pos_dev(), c->n - 1 + res[0] + 1, c->stream), "accept state update");
     *n_accepted_out = res[0];
     *next_token_out = res[1];
     c->n += res[0] + 1;
@@ -767,7 +768,7 @@ int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out,
     const Layout& Y = c->lay;
     const int R = 2 * D.L;
     float* confd = c->small_f() + SM_CONF;            // [R] conf, [R] maxprob, [R] argmax
-    if ((size_t)(SM_CONF + 3 * R) * 4 > 4096) return fail(c, SSD_ECAPACITY, "too many layers for the confidence scratch");
+    static_assert(SM_CONF + 3 * 2 * SSD_MAX_LAYERS <= SM_VTOK, "confidence results of 2 x SSD_MAX_LAYERS rows must end before the token slots");
     for (int r = 0; r < n_rows; r++) {
         const float* taps = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
         if (rows_fused_supported(D)) {

@@ -9,11 +9,28 @@ namespace ssdk {
 
 enum WeightType { WT_F32 = 0, WT_BF16 = 1, WT_F16 = 2 };
 
+// Launch options of one context: tuning hooks (0 = the library's own choice) and the one-shot request to time the
+// next GEMV launch.  Owned by whoever owns the Dims that point to it; nothing here is process-global.
+struct LaunchOpts {
+    int gemv_block_cap = 0;     // > 0 overrides the block cap of the GEMV launches
+    int rows_depth = 0;         // > 0 forces the number of weight stripes a 16-row block keeps in flight
+    int wide_depth = 0;         // the same for the 64-row blocks
+    int wide_ksplit = 0;        // 64-row blocks: 1 = never cut K, > 1 forces the number of K slices
+    int attn_splits = 0;        // > 0 forces the attention split count (scratch must have been sized for it)
+    int attn_kernel = 0;        // 0 heuristic, 1 LDS-staged kernel always, 3 the same in its plain (non-MFMA) form
+    // When set, the next GEMV launch records its own begin / end timestamps into the two events (kernel time as a
+    // profiler reports it, without the dispatch latency a pair of stream events around the launch would include)
+    // and clears the request.
+    hipEvent_t time_start = nullptr, time_stop = nullptr;
+};
+
 // Shape constants shared by all launches of one context.
 struct Dims {
     int L, d, H, Hkv, hd, dq, dkv, f, V, max_seq;
     float eps;
-    int wt;  // WeightType; the KV cache and the hi/lo activation pairs use the same element type
+    int wt;  // WeightType of the matrices; the hi/lo activation pairs of the multi-row path use the same element type
+    int kt;  // WeightType code of the KV cache elements (independent of wt)
+    LaunchOpts* opt = nullptr;  // may be null: library defaults, no timing
 };
 
 // x[r][:] = embed[tok_dev[r]][:] widened to fp32 (token ids in device memory, clamped to the vocabulary).
@@ -41,12 +58,6 @@ hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const floa
 // logits[n] = Wlm[n] . rmsnorm(x, gain)
 hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits,
                        hipStream_t s);
-
-// The next GEMV launch (any of the four below) records its own begin / end timestamps into the two events
-// (kernel time as a profiler reports it, without the dispatch latency a pair of stream events around the
-// launch would include).  One-shot.
-void gemv_time_next_launch(hipEvent_t start, hipEvent_t stop);
-void gemv_block_cap(int n);  // tuning hook: > 0 overrides the block cap of the GEMV launches
 
 // The same with the vocabulary reduction of a greedy step folded in: every block also leaves (max, sum of exp,
 // arg-max) of its clamped logits in vstat (3 floats per block, GEMV_MAX_BLOCKS blocks at most) and a one-block
@@ -102,8 +113,6 @@ struct RowsFused {
     float* kpart; size_t kpart_floats;  // rows_wide: scratch for a split along K (may be null: no split)
 };
 bool rows_fused_supported(const Dims& D);
-// tuning hook: > 0 forces the number of weight stripes a block keeps in flight
-void rows_fused_depth(int d);
 hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s);
 // y[r][n] = sum_k W[n][k] (bh + bl)[r][k] for up to 64 pre-split rows at once (the per-layer confidence rows
 // against the LM head): W is streamed once for all of them.  bf16, N a multiple of 64, K a multiple of 128.
@@ -114,8 +123,6 @@ hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t*
 // K a multiple of 128; the sums of squares it reads / writes are per 64-column tile.
 bool rows_wide_supported(const Dims& D);
 hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s);
-void rows_wide_depth(int d);  // tuning hook: > 0 forces the number of weight stripes a block keeps in flight
-void rows_wide_ksplit(int n);  // tuning hook: 1 = never cut K, > 1 forces the number of K slices
 // hi/lo bf16 split of M rows (row stride ldx) of length K into [M][K] arrays, RMS-normalised with
 // gain first when gain != nullptr
 hipError_t rows_prep(const Dims& D, const float* in, int ldx, const float* gain, int M, int K, float eps, uint16_t* hi,
@@ -142,10 +149,6 @@ size_t attention_scratch_floats(const Dims& D, int max_rows);
 // launch shape attention() uses when the last of M rows sees ctx positions: the number of position ranges,
 // negated for the register-resident kernel (two calls with equal values enqueue identical launches)
 int attention_splits(const Dims& D, int ctx, int M);
-// tuning hook: n > 0 forces the split count (scratch must have been sized for it), 0 restores the heuristic
-void attention_force_splits(int n);
-// tuning hook: 0 heuristic, 1 LDS-staged kernel always, 3 the same in its plain (non-MFMA) form
-void attention_force_kernel(int v);
 
 // ---- vocabulary reduction ------------------------------------------------------------------------
 // Per row of logits [M][V]: arg-max (lowest index on ties), softmax max-probability and, when
@@ -156,10 +159,6 @@ hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float ep
                         hipStream_t s);
 
 // ---- small state kernels ---------------------------------------------------------------------------
-// Greedy acceptance on the device: a = longest prefix with draft[j] == target[j]; writes
-// res[0] = a, res[1] = target[a]; tok0 = target[a]; *pos_dev += a + 1.
-hipError_t accept_commit(TokArg draft, const int32_t* target_dev, int k, int32_t* res, int32_t* tok0,
-                         int* pos_dev, hipStream_t s);
 // tok0 = token, *pos_dev = pos
 hipError_t set_state(int32_t* tok0, int32_t token, int* pos_dev, int pos, hipStream_t s);
 // *pos_dev += delta;  tok0 = src[0] when src != nullptr

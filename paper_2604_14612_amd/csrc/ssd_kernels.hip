@@ -16,6 +16,8 @@
 
 #include <math.h>
 
+#include <atomic>
+
 namespace ssdk {
 
 // ---------------------------------------------------------------------------------------------
@@ -84,6 +86,14 @@ __device__ __forceinline__ float h16_bits_to_f32(uint16_t h, bool f16)
 {
     if (f16) return (float)__builtin_bit_cast(f16_t, h);
     return bf16_bits_to_f32(h);
+}
+
+// one KV-cache element of type kt (WeightType code) from an fp32 value, round to nearest even
+__device__ __forceinline__ void kv_put(void* base, size_t i, float v, int kt)
+{
+    if (kt == WT_F32) reinterpret_cast<float*>(base)[i] = v;
+    else if (kt == WT_F16) reinterpret_cast<f16_t*>(base)[i] = (f16_t)v;
+    else reinterpret_cast<uint16_t*>(base)[i] = f32_to_bf16_bits(v);
 }
 
 __device__ __forceinline__ float wave_sum(float v)
@@ -181,7 +191,7 @@ struct GemvP {
     int n_rows;         // logical rows (QKV: dq + 2 dkv; SWIGLU: 2 f; else N)
     float* y;           // QKV: qbuf; RESID: residual (+=); SWIGLU: act; STORE: logits
     float* tap;
-    void* kc; void* vc;
+    void* kc; void* vc; int kt;   // cache rows of this layer and their element type (WeightType code)
     const float* rope;  // [max_seq][hd/2][2] (cos, sin)
     const int* pos_dev; int pos_off;
     int hd, dq, dkv, max_seq;
@@ -292,14 +302,14 @@ __device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float 
                     q[0] = ra; q[half] = rb;
                 } else {
                     const size_t o = ((size_t)head * p.max_seq + pos) * p.hd + i;
-                    Elem<WT>::put((WT*)p.kc, o, ra);
-                    Elem<WT>::put((WT*)p.kc, o + half, rb);
+                    kv_put(p.kc, o, ra, p.kt);
+                    kv_put(p.kc, o + half, rb, p.kt);
                 }
             } else {
                 const int e = j - p.dq - p.dkv;
                 const size_t o = ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd);
-                Elem<WT>::put((WT*)p.vc, o, a);
-                Elem<WT>::put((WT*)p.vc, o + 1, b);
+                kv_put(p.vc, o, a, p.kt);
+                kv_put(p.vc, o + 1, b, p.kt);
             }
         }
     } else if (EPI == EPI_SWIGLU) {
@@ -530,23 +540,27 @@ __global__ __launch_bounds__(256) void vocab_finish_kernel(const float* __restri
     }
 }
 
-static int g_last_gemv_blocks = 0;  // grid of the most recent GEMV launch (host bookkeeping for the statistics fold)
-static hipEvent_t g_gemv_ev_start = nullptr, g_gemv_ev_stop = nullptr;
-void gemv_time_next_launch(hipEvent_t start, hipEvent_t stop) { g_gemv_ev_start = start; g_gemv_ev_stop = stop; }
+// Largest dynamic LDS size a kernel has been enabled for.  A process-wide cache of an idempotent runtime call
+// (hipFuncSetAttribute): concurrent contexts may both make the call, never skip it wrongly.
+static hipError_t ensure_lds(const void* fn, size_t lds, std::atomic<size_t>& limit)
+{
+    if (lds <= 64 * 1024 || lds <= limit.load(std::memory_order_acquire)) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    size_t cur = limit.load(std::memory_order_relaxed);
+    while (cur < lds && !limit.compare_exchange_weak(cur, lds, std::memory_order_release)) {}
+    return hipSuccess;
+}
 
-static int g_block_cap = 0;  // tuning hook (kernel_bench): > 0 overrides the block cap
-void gemv_block_cap(int n) { g_block_cap = n; }
-
+// blocks_out (may be null) receives the grid size of the launch
 template <typename WT, int EPI, int R, int D, int KS>
-static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
+static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s, LaunchOpts* opt, int* blocks_out)
 {
     size_t lds = (size_t)p.K * sizeof(float);
-    static size_t lds_limit = 0;  // per instantiation
-    if (lds > 64 * 1024 && lds > lds_limit) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemv_kernel<WT, EPI, R, D, KS>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<size_t> lds_limit{0};  // per instantiation
+    {
+        hipError_t e = ensure_lds((const void*)gemv_kernel<WT, EPI, R, D, KS>, lds, lds_limit);
         if (e != hipSuccess) return e;
-        lds_limit = lds;
     }
     constexpr int GPB = GV_WAVES / KS;
     int blocks = ceil_div(p.n_rows / R, GPB);
@@ -554,20 +568,20 @@ static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
     // and leave no second, partial round of blocks.  The variant that folds attention partials in its
     // prologue re-reads them per block, so it runs one block per CU.
     int cap = p.part ? 256 : 768;
-    if (g_block_cap > 0) cap = g_block_cap;
+    if (opt && opt->gemv_block_cap > 0) cap = opt->gemv_block_cap;
     if (blocks > cap) {
         // equal work per block: with r rounds needed, use just enough blocks for r full rounds (gate/up at 7B:
         // 1376 block-rounds -> 688 blocks x 2 rather than 768 blocks of which 160 would do one round only)
         const int rounds = ceil_div(blocks, cap);
         blocks = ceil_div(blocks, rounds);
     }
-    g_last_gemv_blocks = blocks;
-    if (g_gemv_ev_start) {
+    if (blocks_out) *blocks_out = blocks;
+    if (opt && opt->time_start) {
         // timing request for this one launch: the events take the kernel's own begin and end timestamps
-        hipExtLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, g_gemv_ev_start,
-                              g_gemv_ev_stop, 0, p);
-        g_gemv_ev_start = nullptr;
-        g_gemv_ev_stop = nullptr;
+        hipExtLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, opt->time_start,
+                              opt->time_stop, 0, p);
+        opt->time_start = nullptr;
+        opt->time_stop = nullptr;
     } else {
         hipLaunchKernelGGL((gemv_kernel<WT, EPI, R, D, KS>), dim3(blocks), dim3(GV_THREADS), lds, s, p);
     }
@@ -577,21 +591,21 @@ static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s)
 // Work split: many rows -> one wave per row pair, deep pipeline; few rows -> split K over the waves
 // of a group so that every wave still has a handful of chunks and the chip has thousands of waves.
 template <typename WT, int EPI>
-static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s)
+static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s, LaunchOpts* opt, int* blocks_out)
 {
     const int ch = ceil_div(p.K, 64 * Elem<WT>::VEC);
-    if (p.n_rows >= 8192) return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s);
-    if (ch <= 12) return launch_gemv_cfg<WT, EPI, 2, 2, 2>(p, s);
-    if (ch <= 40) return launch_gemv_cfg<WT, EPI, 4, 2, 4>(p, s);
-    return launch_gemv_cfg<WT, EPI, 4, 2, 8>(p, s);
+    if (p.n_rows >= 8192) return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s, opt, blocks_out);
+    if (ch <= 12) return launch_gemv_cfg<WT, EPI, 2, 2, 2>(p, s, opt, blocks_out);
+    if (ch <= 40) return launch_gemv_cfg<WT, EPI, 4, 2, 4>(p, s, opt, blocks_out);
+    return launch_gemv_cfg<WT, EPI, 4, 2, 8>(p, s, opt, blocks_out);
 }
 
 template <int EPI>
-static hipError_t launch_gemv(int wt, const GemvP& p, hipStream_t s)
+static hipError_t launch_gemv(const Dims& D, const GemvP& p, hipStream_t s, int* blocks_out = nullptr)
 {
-    if (wt == WT_BF16) return launch_gemv_t<uint16_t, EPI>(p, s);
-    if (wt == WT_F16) return launch_gemv_t<f16_t, EPI>(p, s);
-    return launch_gemv_t<float, EPI>(p, s);
+    if (D.wt == WT_BF16) return launch_gemv_t<uint16_t, EPI>(p, s, D.opt, blocks_out);
+    if (D.wt == WT_F16) return launch_gemv_t<f16_t, EPI>(p, s, D.opt, blocks_out);
+    return launch_gemv_t<float, EPI>(p, s, D.opt, blocks_out);
 }
 
 hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* wv, const float* gain, const float* x,
@@ -600,16 +614,16 @@ hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* w
     GemvP p = {};
     p.w0 = wq; p.w1 = wk; p.w2 = wv; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d;
     p.n_rows = D.dq + 2 * D.dkv;
-    p.y = qbuf; p.kc = kc; p.vc = vc; p.rope = rope; p.pos_dev = pos_dev; p.pos_off = pos_off;
+    p.y = qbuf; p.kc = kc; p.vc = vc; p.kt = D.kt; p.rope = rope; p.pos_dev = pos_dev; p.pos_off = pos_off;
     p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq;
-    return launch_gemv<EPI_QKV>(D.wt, p, s);
+    return launch_gemv<EPI_QKV>(D, p, s);
 }
 
 hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap, hipStream_t s)
 {
     GemvP p = {};
     p.w0 = w; p.in = in; p.gain = nullptr; p.eps = D.eps; p.K = K; p.n_rows = N; p.y = x; p.tap = tap;
-    return launch_gemv<EPI_RESID>(D.wt, p, s);
+    return launch_gemv<EPI_RESID>(D, p, s);
 }
 
 hipError_t gemv_resid_attn(const Dims& D, const void* w, const float* part, int n_splits, float* x, float* tap,
@@ -619,7 +633,7 @@ hipError_t gemv_resid_attn(const Dims& D, const void* w, const float* part, int 
     GemvP p = {};
     p.w0 = w; p.in = nullptr; p.part = part; p.n_splits = n_splits; p.hd = D.hd; p.gain = nullptr; p.eps = D.eps;
     p.K = D.dq; p.n_rows = D.d; p.y = x; p.tap = tap;
-    return launch_gemv<EPI_RESID>(D.wt, p, s);
+    return launch_gemv<EPI_RESID>(D, p, s);
 }
 
 hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const float* gain, const float* x, float* act,
@@ -627,14 +641,14 @@ hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const floa
 {
     GemvP p = {};
     p.w0 = wg; p.w1 = wu; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = 2 * D.f; p.y = act;
-    return launch_gemv<EPI_SWIGLU>(D.wt, p, s);
+    return launch_gemv<EPI_SWIGLU>(D, p, s);
 }
 
 hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits, hipStream_t s)
 {
     GemvP p = {};
     p.w0 = wlm; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = D.V; p.y = logits;
-    return launch_gemv<EPI_STORE>(D.wt, p, s);
+    return launch_gemv<EPI_STORE>(D, p, s);
 }
 
 hipError_t gemv_lmhead_argmax(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits, float clamp,
@@ -644,11 +658,11 @@ hipError_t gemv_lmhead_argmax(const Dims& D, const void* wlm, const float* gain,
     GemvP p = {};
     p.w0 = wlm; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = D.V; p.y = logits;
     p.vstat = vstat; p.clamp = clamp;
-    g_last_gemv_blocks = 0;
-    hipError_t e = launch_gemv<EPI_STORE>(D.wt, p, s);
+    int blocks = 0;
+    hipError_t e = launch_gemv<EPI_STORE>(D, p, s, &blocks);
     if (e != hipSuccess) return e;
-    if (g_last_gemv_blocks < 1 || g_last_gemv_blocks > GEMV_MAX_BLOCKS) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(vocab_finish_kernel, dim3(1), dim3(256), 0, s, vstat, g_last_gemv_blocks, tok_out, maxprob_out);
+    if (blocks < 1 || blocks > GEMV_MAX_BLOCKS) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(vocab_finish_kernel, dim3(1), dim3(256), 0, s, vstat, blocks, tok_out, maxprob_out);
     return hipGetLastError();
 }
 
@@ -924,7 +938,7 @@ struct RowsP2 {
     int M;
     const float* rope; const int* pos_dev; int pos_off;
     int hd, dq, dkv, max_seq;
-    void* kc; void* vc;
+    void* kc; void* vc; int kt;                 // cache rows of this layer, element type (WeightType code)
     const float* ssq; int n_ssq; float eps;     // consumer: partial sums of squares [M][n_ssq] of the input rows (or null)
     const float* gain_out; float* ssq_out;      // RESID producer: gain of the next norm -> oh/ol = split(x * gain), ssq_out [M][n/16]
     int ksplit; float* kpart;                   // wide RESID only: K cut into ksplit slices (grid.y), raw sums to kpart [ksplit][M][n]
@@ -1026,10 +1040,10 @@ __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float*
                 const float o = rr < 8 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
                 const int e = rr < 8 ? i : i + half;
                 if (is_q) p.y[(size_t)c * p.ldy + (size_t)head * p.hd + e] = o;
-                else ((uint16_t*)p.kc)[((size_t)head * p.max_seq + pos) * p.hd + e] = f32_to_h16_bits(o, F16);
+                else kv_put(p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, o, p.kt);
             } else {
                 const int e = (t - tq - tk) * 16 + rr;
-                ((uint16_t*)p.vc)[((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd)] = f32_to_h16_bits(v, F16);
+                kv_put(p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v, p.kt);
             }
         } else {
             const size_t colx = (size_t)t * 16 + rr;
@@ -1190,26 +1204,22 @@ static hipError_t launch_mfma3(const RowsP2& p, int n_tiles, hipStream_t s)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     const size_t lds = (size_t)(NT * 16 + 2 * p.M) * M3_PITCH;
-    static size_t lds_limit = 0;  // per instantiation
-    if (lds > 64 * 1024 && lds > lds_limit) {
-        hipError_t e = hipFuncSetAttribute((const void*)rows_mfma3_kernel<MODE, DEPTH, F16>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<size_t> lds_limit{0};  // per instantiation
+    {
+        hipError_t e = ensure_lds((const void*)rows_mfma3_kernel<MODE, DEPTH, F16>, lds, lds_limit);
         if (e != hipSuccess) return e;
-        lds_limit = lds;
     }
     hipLaunchKernelGGL((rows_mfma3_kernel<MODE, DEPTH, F16>), dim3(n_tiles), dim3(512), lds, s, p);
     return hipGetLastError();
 }
 
-static int g_rows_depth = 0;  // tuning hook (kernel_bench): > 0 forces the number of stripes in flight
-void rows_fused_depth(int d) { g_rows_depth = d; }
-
 template <int MODE, bool F16>
-static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s)
+static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s, const LaunchOpts* opt)
 {
+    const int forced = opt ? opt->rows_depth : 0;
     const int n_tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
     // few tiles -> few blocks per CU -> each block keeps more stripes in flight
-    const int depth = g_rows_depth > 0 ? g_rows_depth : (n_tiles <= 512 ? 3 : (MODE == RM_SWIGLU ? 2 : 1));
+    const int depth = forced > 0 ? forced : (n_tiles <= 512 ? 3 : (MODE == RM_SWIGLU ? 2 : 1));
     switch (depth) {
         case 1: return launch_mfma3<MODE, 1, F16>(p, n_tiles, s);
         case 2: return launch_mfma3<MODE, 2, F16>(p, n_tiles, s);
@@ -1291,10 +1301,10 @@ __device__ __forceinline__ void m6_epilogue(const RowsP2& p, int tile, int m, in
             const float ov = nn < 32 ? av * cs[0] - bv * cs[1] : bv * cs[0] + av * cs[1];
             const int e = nn < 32 ? i : i + half;
             if (is_q) p.y[(size_t)m * p.ldy + (size_t)head * p.hd + e] = ov;
-            else ((uint16_t*)p.kc)[((size_t)head * p.max_seq + pos) * p.hd + e] = f32_to_h16_bits(ov, F16);
+            else kv_put(p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, ov, p.kt);
         } else {
             const int e = (tile - tq - tk) * 64 + nn;
-            ((uint16_t*)p.vc)[((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd)] = f32_to_h16_bits(v, F16);
+            kv_put(p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v, p.kt);
         }
     }
 }
@@ -1515,12 +1525,10 @@ static hipError_t launch_wide_d(const RowsP2& p, int n_tiles, hipStream_t s)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     const size_t lds = (size_t)(NT * 64 + 128) * M6_PITCH;
-    static bool attr_set = false;  // per instantiation
-    if (lds > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)rows_wide_kernel<MODE, F16, DEPTH>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<size_t> lds_limit{0};  // per instantiation
+    {
+        hipError_t e = ensure_lds((const void*)rows_wide_kernel<MODE, F16, DEPTH>, lds, lds_limit);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     const int S = p.ksplit > 1 ? p.ksplit : 1;
     hipLaunchKernelGGL((rows_wide_kernel<MODE, F16, DEPTH>), dim3(n_tiles, S), dim3(512), lds, s, p);
@@ -1530,18 +1538,12 @@ static hipError_t launch_wide_d(const RowsP2& p, int n_tiles, hipStream_t s)
     return hipGetLastError();
 }
 
-static int g_wide_depth = 0;  // tuning hook (kernel_bench): > 0 forces the number of stripes in flight
-void rows_wide_depth(int d) { g_wide_depth = d; }
-static int g_wide_ksplit = 0;  // tuning hook: 1 = never cut K, > 1 forces the number of slices
-void rows_wide_ksplit(int n) { g_wide_ksplit = n; }
-
 // One stripe in flight per block measured best or equal everywhere: what bounds a block is the 40 GB/s or so
 // that a single CU pulls from the cache (a stripe is 48-64 KB of weights and rows), not latency.
 template <int MODE, bool F16>
-static hipError_t launch_wide(const RowsP2& p, int n_tiles, hipStream_t s)
+static hipError_t launch_wide(const RowsP2& p, int n_tiles, hipStream_t s, const LaunchOpts* opt)
 {
-    (void)n_tiles;
-    const int depth = g_wide_depth > 0 ? g_wide_depth : 1;
+    const int depth = opt && opt->wide_depth > 0 ? opt->wide_depth : 1;
     if (depth >= 4) return launch_wide_d<MODE, F16, 4>(p, n_tiles, s);
     if (depth >= 2) return launch_wide_d<MODE, F16, 2>(p, n_tiles, s);
     return launch_wide_d<MODE, F16, 1>(p, n_tiles, s);
@@ -1552,7 +1554,7 @@ static void fill_rows_params(const Dims& D, const RowsFused& f, RowsP2& p)
     for (int i = 0; i < 3; i++) { p.w[i] = f.w[i]; p.n[i] = f.n[i]; }
     p.K = f.K; p.bh = f.bh; p.bl = f.bl; p.ldb = f.ldb; p.y = f.y; p.ldy = f.ldy; p.oh = f.oh; p.ol = f.ol; p.ldo = f.ldo;
     p.tap = f.tap; p.tap_ld = f.tap_ld; p.M = f.M; p.rope = f.rope; p.pos_dev = f.pos_dev; p.pos_off = f.pos_off;
-    p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq; p.kc = f.kc; p.vc = f.vc;
+    p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq; p.kc = f.kc; p.vc = f.vc; p.kt = D.kt;
     p.ssq = f.ssq; p.n_ssq = f.n_ssq; p.eps = D.eps; p.gain_out = f.gain_out; p.ssq_out = f.ssq_out;
 }
 
@@ -1572,10 +1574,11 @@ hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
     // CUs (the projections back to d_model) is cut along K until there are about 256 blocks; needs scratch for
     // ksplit x matrices x M x n sums.  With 170 tiles or more (QKV, gate/up at 7B) the cut measured equal or worse.
     p.ksplit = 1; p.kpart = nullptr;
-    if (f.kpart && g_wide_ksplit != 1 && f.M > 16) {
+    const int force_ks = D.opt ? D.opt->wide_ksplit : 0;
+    if (f.kpart && force_ks != 1 && f.M > 16) {
         const int nmat = f.mode == RM_SWIGLU ? 2 : 1;
         const size_t per_slice = (size_t)nmat * f.M * n_tiles * 64;
-        int ks = g_wide_ksplit > 1 ? g_wide_ksplit : (n_tiles <= 128 ? 256 / n_tiles : 1);
+        int ks = force_ks > 1 ? force_ks : (n_tiles <= 128 ? 256 / n_tiles : 1);
         const int nc = f.K / M6_CK;
         if (ks > 8) ks = 8;
         if (ks > nc) ks = nc;
@@ -1583,10 +1586,10 @@ hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
         if (ks > 1) { p.ksplit = ks; p.kpart = f.kpart; }
     }
     switch (f.mode) {
-        case RM_STORE: return f16 ? launch_wide<RM_STORE, true>(p, n_tiles, s) : launch_wide<RM_STORE, false>(p, n_tiles, s);
-        case RM_RESID: return f16 ? launch_wide<RM_RESID, true>(p, n_tiles, s) : launch_wide<RM_RESID, false>(p, n_tiles, s);
-        case RM_SWIGLU: return f16 ? launch_wide<RM_SWIGLU, true>(p, n_tiles, s) : launch_wide<RM_SWIGLU, false>(p, n_tiles, s);
-        case RM_QKV: return f16 ? launch_wide<RM_QKV, true>(p, n_tiles, s) : launch_wide<RM_QKV, false>(p, n_tiles, s);
+        case RM_STORE: return f16 ? launch_wide<RM_STORE, true>(p, n_tiles, s, D.opt) : launch_wide<RM_STORE, false>(p, n_tiles, s, D.opt);
+        case RM_RESID: return f16 ? launch_wide<RM_RESID, true>(p, n_tiles, s, D.opt) : launch_wide<RM_RESID, false>(p, n_tiles, s, D.opt);
+        case RM_SWIGLU: return f16 ? launch_wide<RM_SWIGLU, true>(p, n_tiles, s, D.opt) : launch_wide<RM_SWIGLU, false>(p, n_tiles, s, D.opt);
+        case RM_QKV: return f16 ? launch_wide<RM_QKV, true>(p, n_tiles, s, D.opt) : launch_wide<RM_QKV, false>(p, n_tiles, s, D.opt);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1613,10 +1616,10 @@ hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s)
     if (f.ssq && (f.mode == RM_RESID || f.n_ssq < 1)) return hipErrorInvalidValue;
     if (f.gain_out && (f.mode != RM_RESID || !f.oh || !f.ol || !f.ssq_out)) return hipErrorInvalidValue;
     switch (f.mode) {
-        case RM_STORE: return D.wt == WT_F16 ? rows_fused_mode<RM_STORE, true>(p, s) : rows_fused_mode<RM_STORE, false>(p, s);
-        case RM_RESID: return D.wt == WT_F16 ? rows_fused_mode<RM_RESID, true>(p, s) : rows_fused_mode<RM_RESID, false>(p, s);
-        case RM_SWIGLU: return D.wt == WT_F16 ? rows_fused_mode<RM_SWIGLU, true>(p, s) : rows_fused_mode<RM_SWIGLU, false>(p, s);
-        case RM_QKV: return D.wt == WT_F16 ? rows_fused_mode<RM_QKV, true>(p, s) : rows_fused_mode<RM_QKV, false>(p, s);
+        case RM_STORE: return D.wt == WT_F16 ? rows_fused_mode<RM_STORE, true>(p, s, D.opt) : rows_fused_mode<RM_STORE, false>(p, s, D.opt);
+        case RM_RESID: return D.wt == WT_F16 ? rows_fused_mode<RM_RESID, true>(p, s, D.opt) : rows_fused_mode<RM_RESID, false>(p, s, D.opt);
+        case RM_SWIGLU: return D.wt == WT_F16 ? rows_fused_mode<RM_SWIGLU, true>(p, s, D.opt) : rows_fused_mode<RM_SWIGLU, false>(p, s, D.opt);
+        case RM_QKV: return D.wt == WT_F16 ? rows_fused_mode<RM_QKV, true>(p, s, D.opt) : rows_fused_mode<RM_QKV, false>(p, s, D.opt);
     }
     return hipErrorInvalidValue;
 }
@@ -1732,10 +1735,10 @@ hipError_t rope_kv_rows(const Dims& D, float* qkv, const float* rope, const int*
 {
     int per_row = (D.H + D.Hkv) * (D.hd / 2) + D.dkv;
     int blocks = ceil_div(M * per_row, 256);
-    if (D.wt == WT_BF16)
+    if (D.kt == WT_BF16)
         hipLaunchKernelGGL(rope_kv_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, qkv, rope, pos_dev, pos_off, M,
                            D.H, D.Hkv, D.hd, D.max_seq, (uint16_t*)kc, (uint16_t*)vc);
-    else if (D.wt == WT_F16)
+    else if (D.kt == WT_F16)
         hipLaunchKernelGGL(rope_kv_rows_kernel<f16_t>, dim3(blocks), dim3(256), 0, s, qkv, rope, pos_dev, pos_off, M,
                            D.H, D.Hkv, D.hd, D.max_seq, (f16_t*)kc, (f16_t*)vc);
     else
@@ -1775,7 +1778,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
                                                           const int* pos_dev, int pos_off, int M, int H, int Hkv,
                                                           int max_seq, int n_splits, float* __restrict__ part,
                                                           float* __restrict__ outp, int dq,
-                                                          uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
+                                                          uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo,
+                                                          bool out_f16)
 {
     constexpr int ROWB = HD * (int)sizeof(KT) + 16;
     constexpr int EPV = 16 / (int)sizeof(KT);  // elements per 16-byte vector
@@ -1902,7 +1906,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(const float* __restric
             const float mx = ml[qi * 2], ls = ml[qi * 2 + 1];
             if (n_splits == 1) {
                 const size_t oo = (size_t)r * dq + (size_t)head * HD + dd;
-                if (out_hi) split_store(o / ls, out_hi, out_lo, oo, IsF16<KT>::value);
+                if (out_hi) split_store(o / ls, out_hi, out_lo, oo, out_f16);
                 else outp[oo] = o / ls;
             } else {
                 float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
@@ -1944,7 +1948,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
                                                                const int* pos_dev, int pos_off, int M, int H, int Hkv,
                                                                int max_seq, int n_splits, float* __restrict__ part,
                                                                float* __restrict__ outp, int dq,
-                                                               uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
+                                                               uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo,
+                                                               bool out_f16)
 {
     static_assert(sizeof(KT) == 2, "16-bit caches only");
     constexpr bool F16 = IsF16<KT>::value;
@@ -2099,8 +2104,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
                 const size_t oo = (size_t)r * dq + (size_t)head * HD + dd;
                 const float inv = 1.0f / ls;
                 if (out_hi) {
-                    split_store(o.x * inv, out_hi, out_lo, oo, F16); split_store(o.y * inv, out_hi, out_lo, oo + 1, F16);
-                    split_store(o.z * inv, out_hi, out_lo, oo + 2, F16); split_store(o.w * inv, out_hi, out_lo, oo + 3, F16);
+                    split_store(o.x * inv, out_hi, out_lo, oo, out_f16); split_store(o.y * inv, out_hi, out_lo, oo + 1, out_f16);
+                    split_store(o.z * inv, out_hi, out_lo, oo + 2, out_f16); split_store(o.w * inv, out_hi, out_lo, oo + 3, out_f16);
                 } else {
                     *reinterpret_cast<float4*>(outp + oo) = make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
                 }
@@ -2219,7 +2224,8 @@ __global__ __launch_bounds__(NW * 64) void attn_wide_kernel(const float* __restr
                                                             const int* pos_dev, int pos_off, int M, int H, int Hkv,
                                                             int max_seq, int n_splits, float* __restrict__ part,
                                                             float* __restrict__ outp, int dq,
-                                                            uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo)
+                                                            uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo,
+                                                            bool out_f16)
 {
     constexpr int EPV = 16 / (int)sizeof(KT), LPP = HD / EPV, PPL = 64 / LPP, NT = NW * 64;
     constexpr int PASS = NL * NW * PPL;  // positions one pass of the block covers
@@ -2363,7 +2369,7 @@ __global__ __launch_bounds__(NW * 64) void attn_wide_kernel(const float* __restr
         const int qg = q0 + qi, r = qg / G, head = kvh * G + qg % G;
         if (n_splits == 1) {
             const size_t oo = (size_t)r * dq + (size_t)head * HD + d;
-            if (out_hi) split_store(num / den, out_hi, out_lo, oo, IsF16<KT>::value);
+            if (out_hi) split_store(num / den, out_hi, out_lo, oo, out_f16);
             else outp[oo] = num / den;
         } else {
             float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
@@ -2381,15 +2387,11 @@ constexpr int AW_MAXQ_TOTAL = 4;
 constexpr int AW_MAX_ROWS = 8;
 constexpr int AW_RANGE = 128;
 constexpr int AW_MAX_RANGES = 16;
-static int g_force_splits = 0;  // tuning hook (kernel_bench): > 0 overrides the heuristic
-static int g_force_attn = 0;    // tuning hook: 1 = LDS-staged kernel always, 3 = the same in its plain (non-MFMA) form
-void attention_force_splits(int n) { g_force_splits = n; }
-void attention_force_kernel(int v) { g_force_attn = v; }
-
 struct AttnPlan { bool wide; int n_splits; bool defer_fold; };
 
 static AttnPlan attn_plan(const Dims& D, int ctx, int M)
 {
+    const int force_splits = D.opt ? D.opt->attn_splits : 0, force_kernel = D.opt ? D.opt->attn_kernel : 0;
     AttnPlan pl;
     pl.defer_fold = false;
     const int Q = (D.H / D.Hkv) * M;
@@ -2398,8 +2400,8 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     // 4 or 8 query heads per KV head still run the register-resident kernel, one block per row and range serving
     // the row's group of heads (two blocks for a group of 8), re-reading a range's K/V from the cache.
     const int G = D.H / D.Hkv;
-    pl.wide = Q <= AW_MAXQ_TOTAL || (D.wt == WT_F32 && (G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
-    if (g_force_attn == 1 || g_force_attn == 3) pl.wide = false;
+    pl.wide = Q <= AW_MAXQ_TOTAL || (D.kt == WT_F32 && (G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
+    if (force_kernel == 1 || force_kernel == 3) pl.wide = false;
     if (pl.wide) {
         // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
         int ns = ceil_div(ctx, AW_RANGE);
@@ -2407,12 +2409,12 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
         // (a longer range costs the attention kernel about 1 us, a separate fold launch 5)
         if (M == 1 && ns > GV_FOLD_MAX && ctx <= GV_FOLD_MAX * 512) ns = GV_FOLD_MAX;
         if (ns > AW_MAX_RANGES) ns = AW_MAX_RANGES;
-        if (g_force_splits > 0) ns = g_force_splits;
+        if (force_splits > 0) ns = force_splits;
         if (ns > ctx) ns = ctx;
         pl.n_splits = ns;
     } else {
         const int need = ceil_div(ctx, AT_CHUNK);  // a block owns at most AT_CHUNK positions
-        pl.n_splits = g_force_splits > need ? g_force_splits : need;
+        pl.n_splits = force_splits > need ? force_splits : need;
     }
     return pl;
 }
@@ -2437,7 +2439,7 @@ static void launch_attn_wide(const Dims& D, const float* q, int ldq, const void*
 {
     hipLaunchKernelGGL((attn_wide_kernel<KT, HD, NQ, NW, NL>), dim3(n_splits, D.Hkv, zq), dim3(NW * 64), 0, s, q, ldq,
                        (const KT*)kc, (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq,
-                       out_hi, out_lo);
+                       out_hi, out_lo, D.wt == WT_F16);
 }
 
 // LDS-staged kernel: MFMA form for 16-bit caches, plain form for fp32 caches
@@ -2447,32 +2449,24 @@ static void launch_attn_staged(const Dims& D, const float* q, int ldq, const voi
                                hipStream_t s)
 {
     if constexpr (sizeof(KT) == 2) {
-        if (g_force_attn != 3) {
+        if (!(D.opt && D.opt->attn_kernel == 3)) {
             const size_t lds = attn_mfma_lds_bytes<KT, HD>();
-            static bool attr_set = false;  // per instantiation
-            if (!attr_set && lds > 64 * 1024) {
-                if (hipFuncSetAttribute((const void*)attn_mfma_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)lds) != hipSuccess)
-                    return;   // the launch below then fails and reports
-                attr_set = true;
-            }
+            static std::atomic<size_t> lds_limit{0};  // per instantiation
+            if (ensure_lds((const void*)attn_mfma_kernel<KT, HD>, lds, lds_limit) != hipSuccess)
+                return;   // the launch below then fails and reports
             const int Q = (D.H / D.Hkv) * M;
             hipLaunchKernelGGL((attn_mfma_kernel<KT, HD>), dim3(n_splits, D.Hkv, ceil_div(Q, AT_QPASS)), dim3(AT_THREADS), lds, s, q, ldq,
                                (const KT*)kc, (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq,
-                               out_hi, out_lo);
+                               out_hi, out_lo, D.wt == WT_F16);
             return;
         }
     }
     const size_t lds = attn_lds_bytes<KT, HD>();
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set && lds > 64 * 1024) {
-        if (hipFuncSetAttribute((const void*)attn_kernel<KT, HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
-            hipSuccess)
-            return;
-        attr_set = true;
-    }
+    static std::atomic<size_t> lds_limit{0};  // per instantiation
+    if (ensure_lds((const void*)attn_kernel<KT, HD>, lds, lds_limit) != hipSuccess) return;
     hipLaunchKernelGGL((attn_kernel<KT, HD>), dim3(n_splits, D.Hkv, 1), dim3(AT_THREADS), lds, s, q, ldq, (const KT*)kc,
-                       (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo);
+                       (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, n_splits, part, out, D.dq, out_hi, out_lo,
+                       D.wt == WT_F16);
 }
 
 template <typename KT, int HD>
@@ -2502,7 +2496,7 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_splits == 1 || pl.defer_fold) return e;
     hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(D.H, M), dim3(HD), 0, s, part, D.H, n_splits, out, D.dq, out_hi,
-                       out_lo, IsF16<KT>::value);
+                       out_lo, D.wt == WT_F16);
     return hipGetLastError();
 }
 
@@ -2518,10 +2512,10 @@ hipError_t attention(const Dims& D, const float* q, int ldq, const void* kc, con
         pl.defer_fold = pl.n_splits > 1 && pl.n_splits <= GV_FOLD_MAX;
         *deferred_splits = pl.defer_fold ? pl.n_splits : 0;
     }
-    if (D.wt == WT_BF16) {
+    if (D.kt == WT_BF16) {
         if (D.hd == 128) return attention_t<uint16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
         if (D.hd == 64) return attention_t<uint16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
-    } else if (D.wt == WT_F16) {
+    } else if (D.kt == WT_F16) {
         if (D.hd == 128) return attention_t<f16_t, 128>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
         if (D.hd == 64) return attention_t<f16_t, 64>(D, q, ldq, kc, vc, pos_dev, pos_off, pl, ctx, M, part, out, out_hi, out_lo, s);
     } else {
@@ -2598,25 +2592,6 @@ hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float ep
 // ---------------------------------------------------------------------------------------------
 // state kernels
 // ---------------------------------------------------------------------------------------------
-__global__ void accept_kernel(TokArg draft, const int32_t* target, int k, int32_t* res, int32_t* tok0, int* pos_dev)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        int a = 0;
-        while (a < k && draft.t[a] == target[a]) a++;
-        res[0] = a;
-        res[1] = target[a];
-        tok0[0] = target[a];
-        pos_dev[0] += a + 1;
-    }
-}
-
-hipError_t accept_commit(TokArg draft, const int32_t* target_dev, int k, int32_t* res, int32_t* tok0, int* pos_dev,
-                         hipStream_t s)
-{
-    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, draft, target_dev, k, res, tok0, pos_dev);
-    return hipGetLastError();
-}
-
 __global__ void set_state_kernel(int32_t* tok0, int32_t token, int* pos_dev, int pos)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) { tok0[0] = token; pos_dev[0] = pos; }
@@ -2655,10 +2630,10 @@ __global__ void kv_poison_kernel(KT* kv, int planes, int max_seq, int hd, const 
 hipError_t kv_poison(const Dims& D, void* kv_all, const int* pos_dev, hipStream_t s)
 {
     int planes = D.L * 2 * D.Hkv;
-    if (D.wt == WT_BF16)
+    if (D.kt == WT_BF16)
         hipLaunchKernelGGL(kv_poison_kernel<uint16_t>, dim3(1024), dim3(256), 0, s, (uint16_t*)kv_all, planes, D.max_seq,
                            D.hd, pos_dev);
-    else if (D.wt == WT_F16)
+    else if (D.kt == WT_F16)
         hipLaunchKernelGGL(kv_poison_kernel<f16_t>, dim3(1024), dim3(256), 0, s, (f16_t*)kv_all, planes, D.max_seq, D.hd,
                            pos_dev);
     else

@@ -20,22 +20,29 @@ def to_gpu(weights):
 
 
 def make_pair(shape, seed, max_seq, max_k=8, norm_gain_std=0.0, init_std=0.02, **ctx_kw):
-    """Same weights for the oracle (CPU) and a library context (GPU)."""
+    """Same weights for the oracle (CPU) and a library context (GPU); the oracle's K/V storage parameter is set to
+    the context's cache type (ctx_kw may name one with kv_dtype=...)."""
     import paper_2604_14612_amd as ssd
     w = make_weights(shape, seed, norm_gain_std=norm_gain_std, init_std=init_std)
-    orc = OracleModel(shape, w, max_seq)
     ctx = ssd.Context(shape, to_gpu(w), max_seq, max_k, **ctx_kw)
+    orc = OracleModel(shape, w, max_seq, kv_storage=ctx.kv_dtype)
     return orc, ctx
 
 
-def make_pair_gpu_generated(shape, seed, max_seq, max_k=8, **ctx_kw):
+def make_pair_gpu_generated(shape, seed, max_seq, max_k=8, kv_storage="cache", **ctx_kw):
     """Large shapes: weights are drawn on the GPU (fast) and the very same tensors are copied to the host
-    for the oracle -- moved, never regenerated."""
+    for the oracle -- moved, never regenerated.  kv_storage: the oracle's K/V storage parameter -- "cache" = the
+    context's cache type, "exact" = fp64 cache -- or a tuple of such modes (then a dict mode -> OracleModel over the
+    same host tensors is returned in place of the model)."""
     import paper_2604_14612_amd as ssd
     w = make_weights(shape, seed, device="cuda")
     w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w.items()}
-    orc = OracleModel(shape, w_cpu, max_seq)
     ctx = ssd.Context(shape, w, max_seq, max_k, **ctx_kw)
+    mode = lambda m: ctx.kv_dtype if m == "cache" else m
+    if isinstance(kv_storage, str):
+        orc = OracleModel(shape, w_cpu, max_seq, kv_storage=mode(kv_storage))
+    else:
+        orc = {m: OracleModel(shape, w_cpu, max_seq, kv_storage=mode(m)) for m in kv_storage}
     return orc, ctx
 
 
@@ -63,7 +70,8 @@ def decisive(z, dtype):
 
 
 def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None):
-    """Runs greedy SSD on both sides cycle by cycle from the oracle's committed prefix.
+    """Runs greedy SSD on both sides cycle by cycle from the oracle's committed prefix.  k: the draft length, or a
+    list of draft lengths, one per cycle (then exactly len(k) cycles run and n_new is ignored).
 
     Every logit row is compared within tolerance; tokens, accepted counts and next tokens are
     compared bit-exactly wherever the oracle's top-2 margin is decisive; a cycle with a
@@ -81,7 +89,10 @@ def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None):
     else:
         assert first_g == first_o, "prefill arg-max is a sub-tolerance tie for this seed; pick another seed"
     P = len(prompt)
-    while o.n - P < n_new:
+    k_seq = None if isinstance(k, int) else list(k)
+    while (o.n - P < n_new) if k_seq is None else (stats["cycles"] < len(k_seq)):
+        if k_seq is not None:
+            k = k_seq[stats["cycles"]]
         pinned = True
         d_o = o.draft(mask, k)
         d_g = ctx.ssd_draft_step(mask, k)

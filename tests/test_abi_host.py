@@ -23,6 +23,11 @@ def test_library_exports_every_declared_symbol():
     l = ssd.lib()
     for name in declared:
         assert getattr(l, name) is not None
+    # ... and nothing else: kernel stubs, launchers and tuning hooks are not part of the dynamic symbol table
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", ssd.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = {ln.split()[-1] for ln in out.splitlines() if ln.strip()}
+    assert exported == declared, sorted(exported ^ declared)[:10]
 
 
 def _cfg(**kw):
