@@ -7,6 +7,7 @@
 // back-to-back gate/up launches: clock drift).
 #include "ssd_kernels.h"
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -133,6 +134,74 @@ int main(int argc, char** argv)
             else CK(gemv_resid(D, w + 3 * qk, 4096, 4096, act, x, nullptr, 0));
             CK(gemv_swiglu(D, w + 4 * qk, w + 4 * qk + gu, gain, x, act, 0));
             CK(gemv_resid(D, w + 4 * qk + 2 * gu, 4096, 11008, act, x, nullptr, 0)); });
+        return 0;
+    }
+    if (std::getenv("KB_CHAIN")) {
+        // Chained launches: the four GEMVs of a layer (QKV, output projection, gate/up, down; attention left out) on
+        // alternating streams, each waiting for its producer's blocks through a device counter instead of a kernel
+        // boundary, against the same launches in order on one stream.
+        hipStream_t sx, sy;
+        CK(hipStreamCreate(&sx)); CK(hipStreamCreate(&sy));
+        const size_t layer_elems = 4 * qk + 3 * gu;
+        const int nl = 12, nk = 4 * nl;
+        unsigned *flags, *gen, *err;
+        CK(hipMalloc(&flags, (nk + 1) * sizeof(unsigned))); CK(hipMalloc(&gen, 64)); CK(hipMalloc(&err, 64));
+        const unsigned one = 1;
+        CK(hipMemcpy(gen, &one, 4, hipMemcpyHostToDevice)); CK(hipMemset(err, 0, 64));
+        hipEvent_t e0, e1, ej;
+        CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1)); CK(hipEventCreate(&ej));
+        std::vector<int> blocks(nk + 1, 0);
+        // meaningful data, so that the two orders can be compared: small random residual, unit gains
+        std::vector<float> x0(4096), ones(4096, 1.0f), xa(4096), xb(4096);
+        { unsigned st = 777; for (auto& v : x0) { st = st * 1664525u + 1013904223u; v = ((st >> 8) & 0xffff) / 65536.0f - 0.5f; } }
+        CK(hipMemcpy(gain, ones.data(), 4096 * 4, hipMemcpyHostToDevice));
+        auto run = [&](bool chained) {
+            hipStream_t st[2] = {sx, chained ? sy : sx};
+            CK(hipMemcpyAsync(x, x0.data(), 4096 * 4, hipMemcpyHostToDevice, sx));
+            CK(hipMemsetAsync(flags, 0, (nk + 1) * sizeof(unsigned), sx));
+            if (chained) { CK(hipEventRecord(ej, sx)); CK(hipStreamWaitEvent(sy, ej, 0)); }
+            CK(hipEventRecord(e0, sx));
+            int ki = 0;
+            for (int l = 0; l < nl; l++) {
+                const uint16_t* w = W + (size_t)l * layer_elems;
+                for (int j = 0; j < 4; j++, ki++) {
+                    Chain ch = {};
+                    if (chained) {
+                        if (ki > 0) { ch.wait_flag = flags + ki - 1; ch.wait_count = (unsigned)blocks[ki - 1]; }
+                        ch.done_flag = flags + ki; ch.gen = gen; ch.err = err;
+                    }
+                    hipStream_t s = st[ki & 1];
+                    const Chain* c = chained ? &ch : nullptr;
+                    if (j == 0) CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc, vc, s, c, &blocks[ki]));
+                    else if (j == 1) CK(gemv_resid(D, w + 3 * qk, 4096, 4096, q, x, nullptr, s, c, &blocks[ki]));
+                    else if (j == 2) CK(gemv_swiglu(D, w + 4 * qk, w + 4 * qk + gu, gain, x, act, s, c, &blocks[ki]));
+                    else CK(gemv_resid(D, w + 4 * qk + 2 * gu, 4096, 11008, act, x, nullptr, s, c, &blocks[ki]));
+                }
+            }
+            if (chained) { CK(hipEventRecord(ej, sy)); CK(hipStreamWaitEvent(sx, ej, 0)); }
+            CK(hipEventRecord(e1, sx));
+            CK(hipEventSynchronize(e1));
+            float ms; CK(hipEventElapsedTime(&ms, e0, e1));
+            return ms * 1e3 / nl;
+        };
+        for (int rep = 0; rep < 6; rep++) {
+            // Two chained kernels must fit the chip together (a waiting consumer must never hold the slots its
+            // producer's remaining blocks need): each gets at most half of the 768 resident block slots.
+            const int cap = rep < 2 ? 384 : rep < 4 ? 256 : 320;
+            opts.gemv_block_cap = 0;
+            const double a = run(false);
+            CK(hipMemcpy(xa.data(), x, 4096 * 4, hipMemcpyDeviceToHost));
+            opts.gemv_block_cap = cap;
+            const double b = run(true);
+            opts.gemv_block_cap = 0;
+            CK(hipMemcpy(xb.data(), x, 4096 * 4, hipMemcpyDeviceToHost));
+            unsigned e = 0; CK(hipMemcpy(&e, err, 4, hipMemcpyDeviceToHost));
+            int diff = 0; double mag = 0;
+            for (int i = 0; i < 4096; i++) { diff += std::memcmp(&xa[i], &xb[i], 4) != 0; mag += std::fabs(xa[i]); }
+            std::printf("GEMVs of a layer (qkv, o, gate/up, down): one stream %.2f us, chained on two streams (block cap %d) %.2f us per layer, "
+                        "wait timeouts %u, residual elements that differ %d of 4096 (mean |x| %.3g)\n", a, cap, b, e, diff, mag / 4096);
+            std::fflush(stdout);
+        }
         return 0;
     }
     if (std::getenv("KB_SWEEP")) {   // launch time against size: fixed cost and streaming rate of probe and GEMV

@@ -39,22 +39,32 @@ hipError_t embed_rows(const Dims& D, const void* embed, const int32_t* tok_dev, 
 // dst[i] = toks.t[i] for i < n, except dst[0] = first_dev[0] when first_dev != nullptr
 hipError_t set_tokens(TokArg toks, int n, const int32_t* first_dev, int32_t* dst, hipStream_t s);
 
+// Links of a chained launch (experimental overlap of consecutive kernels on two streams): the kernel waits, after its
+// first weight loads are in flight, until *wait_flag >= wait_count * *gen, and every one of its blocks adds 1 to
+// *done_flag when its outputs are visible device-wide.  Null members switch the respective half off.
+struct Chain {
+    unsigned* wait_flag; unsigned wait_count;
+    unsigned* done_flag;
+    const unsigned* gen;
+    unsigned* err;
+};
+
 // ---- single-row (draft / vanilla decode) path: weight-streaming GEMV kernels ----------------
 // h = rmsnorm(x, gain); q,k,v = Wq h, Wk h, Wv h; rotary on q,k at position *pos_dev + pos_off;
 // q -> qbuf (fp32), k,v -> cache rows of this layer.
 hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* wv, const float* gain,
                     const float* x, const float* rope, const int* pos_dev, int pos_off, float* qbuf,
-                    void* kcache_l, void* vcache_l, hipStream_t s);
+                    void* kcache_l, void* vcache_l, hipStream_t s, const Chain* ch = nullptr, int* blocks_out = nullptr);
 // x[n] += W[n][:] . in[:]   (N x K), optional tap copy of the updated x
 hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap,
-                      hipStream_t s);
+                      hipStream_t s, const Chain* ch = nullptr, int* blocks_out = nullptr);
 // x += Wo . att (d x dq), att being the fold of the n_splits attention partials of a single row that
 // attention() left in part when asked to defer the fold
 hipError_t gemv_resid_attn(const Dims& D, const void* w, const float* part, int n_splits, float* x, float* tap,
                            hipStream_t s);
 // act[n] = silu(Wg[n] . h) * (Wu[n] . h), h = rmsnorm(x, gain)
 hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const float* gain, const float* x,
-                       float* act, hipStream_t s);
+                       float* act, hipStream_t s, const Chain* ch = nullptr, int* blocks_out = nullptr);
 // logits[n] = Wlm[n] . rmsnorm(x, gain)
 hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits,
                        hipStream_t s);

@@ -197,7 +197,65 @@ struct GemvP {
     int hd, dq, dkv, max_seq;
     float* vstat;       // STORE only, may be null: per block (max, sum of exp relative to it, arg-max) of the clamped outputs
     float clamp;
+    // Chained launches (all null / 0 = an ordinary launch).  A chained kernel may start while its producer is still
+    // running: it issues its first weight loads, then waits until *wait_flag has reached wait_count * *gen (every
+    // block of the producer adds 1 to its done_flag once its outputs are visible device-wide), and only then reads
+    // its input vector -- with device-coherent loads, as the producer's stores were device-coherent write-throughs.
+    unsigned* wait_flag; unsigned wait_count;
+    unsigned* done_flag;
+    const unsigned* gen;     // replay generation (1, 2, ...): the counters are never reset
+    unsigned* err;           // set to 1 if a wait gave up (every wait is bounded)
 };
+
+// Device-coherent accesses for data handed from one running kernel to another (each XCD has its own L2: ordinary
+// loads may hit a stale line, ordinary stores stay in the writer's L2 until its kernel ends).
+__device__ __forceinline__ float coh_load(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float4 coh_load4(const float* p)   // p 16-byte aligned
+{
+    const unsigned long long a = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long b = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p) + 1, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    return make_float4(__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)), __uint_as_float((unsigned)b),
+                       __uint_as_float((unsigned)(b >> 32)));
+}
+__device__ __forceinline__ void coh_store(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+constexpr int CHAIN_SPIN_MAX = 1 << 20;   // polls before a chained wait gives up (seconds; a healthy wait takes microseconds)
+
+// Block-wide wait for the producer of a chained launch.  Ends for certain: the poll count is bounded.
+__device__ __forceinline__ void chain_wait(const GemvP& p)
+{
+    if (p.wait_flag) {
+        if (threadIdx.x == 0) {
+            const unsigned target = p.wait_count * p.gen[0];
+            int spins = 0;
+            // The counter is polled with a read-modify-write (adding 0): device-scope RMW atomics are carried out at
+            // the memory side, whereas a load may keep hitting a stale line in this XCD's L2.
+            while (__hip_atomic_fetch_add(p.wait_flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (++spins >= CHAIN_SPIN_MAX) { __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+                __builtin_amdgcn_s_sleep(4);
+            }
+            // one acquire per block: drops this CU's L1 and the XCD's stale L2 lines before the inputs are read
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
+        __syncthreads();
+    }
+}
+// Block-wide signal at the end of a chained launch: all of the block's write-through stores have been acknowledged.
+__device__ __forceinline__ void chain_signal(const GemvP& p)
+{
+    if (p.done_flag) {
+        __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0): this wave's stores have completed
+        __syncthreads();
+        if (threadIdx.x == 0) __hip_atomic_fetch_add(p.done_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
 
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -299,7 +357,8 @@ __device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float 
                 const float ra = a * c - b * sn, rb = b * c + a * sn;
                 if (is_q) {
                     float* q = p.y + (size_t)head * p.hd + i;
-                    q[0] = ra; q[half] = rb;
+                    if (p.done_flag) { coh_store(q, ra); coh_store(q + half, rb); }
+                    else { q[0] = ra; q[half] = rb; }
                 } else {
                     const size_t o = ((size_t)head * p.max_seq + pos) * p.hd + i;
                     kv_put(p.kc, o, ra, p.kt);
@@ -316,13 +375,17 @@ __device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float 
 #pragma unroll
         for (int t = 0; t < R; t += 2) {
             const float g = s[t] * sc, u = s[t + 1] * sc;
-            p.y[(j0 + t) >> 1] = g / (1.0f + __expf(-g)) * u;
+            const float a = g / (1.0f + __expf(-g)) * u;
+            if (p.done_flag) coh_store(p.y + ((j0 + t) >> 1), a);
+            else p.y[(j0 + t) >> 1] = a;
         }
     } else if (EPI == EPI_RESID) {
 #pragma unroll
         for (int t = 0; t < R; t++) {
-            const float v = p.y[j0 + t] + s[t];
-            p.y[j0 + t] = v;
+            // chained: the residual was written by a kernel that may still have been running when this one started
+            const float v = (p.wait_flag ? coh_load(p.y + j0 + t) : p.y[j0 + t]) + s[t];
+            if (p.done_flag) coh_store(p.y + j0 + t, v);
+            else p.y[j0 + t] = v;
             if (p.tap) p.tap[j0 + t] = v;
         }
     } else {
@@ -382,6 +445,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
 #pragma unroll
     for (int s = 0; s < D; s++) issue(s);
 
+    chain_wait(p);
     // stage the input vector (times gain); the sum of squares gives the RMS scale
     float ss = 0.f;
     if (EPI == EPI_RESID && p.part) {
@@ -417,7 +481,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
         }
     } else
     for (int i = threadIdx.x * 4; i < K; i += GV_THREADS * 4) {
-        float4 v = *reinterpret_cast<const float4*>(p.in + i);
+        float4 v = p.wait_flag ? coh_load4(p.in + i) : *reinterpret_cast<const float4*>(p.in + i);
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         if (p.gain) {
             const float4 g = *reinterpret_cast<const float4*>(p.gain + i);
@@ -495,6 +559,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
             }
         }
     }
+    chain_signal(p);
     if (EPI == EPI_STORE && p.vstat) {   // block partial of the soft-max statistics: lane 0 of every wave holds one
         __shared__ float vred[GV_WAVES * 3];
         if (lane == 0) { vred[wave * 3] = vs.m; vred[wave * 3 + 1] = vs.z; vred[wave * 3 + 2] = __int_as_float(vs.arg); }
@@ -608,22 +673,32 @@ static hipError_t launch_gemv(const Dims& D, const GemvP& p, hipStream_t s, int*
     return launch_gemv_t<float, EPI>(p, s, D.opt, blocks_out);
 }
 
+static void set_chain(GemvP& p, const Chain* ch)
+{
+    if (!ch) return;
+    p.wait_flag = ch->wait_flag; p.wait_count = ch->wait_count; p.done_flag = ch->done_flag; p.gen = ch->gen; p.err = ch->err;
+}
+
 hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* wv, const float* gain, const float* x,
-                    const float* rope, const int* pos_dev, int pos_off, float* qbuf, void* kc, void* vc, hipStream_t s)
+                    const float* rope, const int* pos_dev, int pos_off, float* qbuf, void* kc, void* vc, hipStream_t s,
+                    const Chain* ch, int* blocks_out)
 {
     GemvP p = {};
+    set_chain(p, ch);
     p.w0 = wq; p.w1 = wk; p.w2 = wv; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d;
     p.n_rows = D.dq + 2 * D.dkv;
     p.y = qbuf; p.kc = kc; p.vc = vc; p.kt = D.kt; p.rope = rope; p.pos_dev = pos_dev; p.pos_off = pos_off;
     p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq;
-    return launch_gemv<EPI_QKV>(D, p, s);
+    return launch_gemv<EPI_QKV>(D, p, s, blocks_out);
 }
 
-hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap, hipStream_t s)
+hipError_t gemv_resid(const Dims& D, const void* w, int N, int K, const float* in, float* x, float* tap, hipStream_t s,
+                      const Chain* ch, int* blocks_out)
 {
     GemvP p = {};
+    set_chain(p, ch);
     p.w0 = w; p.in = in; p.gain = nullptr; p.eps = D.eps; p.K = K; p.n_rows = N; p.y = x; p.tap = tap;
-    return launch_gemv<EPI_RESID>(D, p, s);
+    return launch_gemv<EPI_RESID>(D, p, s, blocks_out);
 }
 
 hipError_t gemv_resid_attn(const Dims& D, const void* w, const float* part, int n_splits, float* x, float* tap,
@@ -637,11 +712,12 @@ hipError_t gemv_resid_attn(const Dims& D, const void* w, const float* part, int 
 }
 
 hipError_t gemv_swiglu(const Dims& D, const void* wg, const void* wu, const float* gain, const float* x, float* act,
-                       hipStream_t s)
+                       hipStream_t s, const Chain* ch, int* blocks_out)
 {
     GemvP p = {};
+    set_chain(p, ch);
     p.w0 = wg; p.w1 = wu; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d; p.n_rows = 2 * D.f; p.y = act;
-    return launch_gemv<EPI_SWIGLU>(D, p, s);
+    return launch_gemv<EPI_SWIGLU>(D, p, s, blocks_out);
 }
 
 hipError_t gemv_lmhead(const Dims& D, const void* wlm, const float* gain, const float* x, float* logits, hipStream_t s)
@@ -2656,24 +2732,29 @@ hipError_t copy_f32(const float* src, float* dst, size_t n, hipStream_t s)
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void read_probe_kernel(const uint4* __restrict__ src, size_t n_vec, float* sink)
+// Read-only streaming probe: every lane keeps eight non-temporal 128-bit loads in flight (the access shape of the
+// weight-streaming kernels, minus their arithmetic); a wave reads 1 KB contiguous per load instruction.
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4_t* __restrict__ src, size_t n_vec, float* sink)
 {
     uint32_t acc = 0;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n_vec; i += 4 * stride) {
-        uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    for (; i + 7 * stride < n_vec; i += 8 * stride) {
+        u32x4_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 8; u++) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (; i < n_vec; i += stride) {
-        uint4 a = src[i];
+        const u32x4_t a = __builtin_nontemporal_load(src + i);
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
     if (acc == 0x9e3779b9u) sink[0] = 1.0f;  // practically never true; keeps the loads alive
 }
 hipError_t read_probe(const void* dev, size_t bytes, float* sink_dev, hipStream_t s)
 {
-    hipLaunchKernelGGL(read_probe_kernel, dim3(256 * 8), dim3(256), 0, s, (const uint4*)dev, bytes / 16, sink_dev);
+    hipLaunchKernelGGL(read_probe_kernel, dim3(256 * 8), dim3(256), 0, s, (const u32x4_t*)dev, bytes / 16, sink_dev);
     return hipGetLastError();
 }
 

@@ -25,20 +25,26 @@ def make_pair(shape, seed, max_seq, max_k=8, norm_gain_std=0.0, init_std=0.02, *
     import paper_2604_14612_amd as ssd
     w = make_weights(shape, seed, norm_gain_std=norm_gain_std, init_std=init_std)
     ctx = ssd.Context(shape, to_gpu(w), max_seq, max_k, **ctx_kw)
-    orc = OracleModel(shape, w, max_seq, kv_storage=ctx.kv_dtype)
+    orc = OracleModel(shape, w, max_seq, kv_storage=oracle_storage_for(ctx))
     return orc, ctx
 
 
-def make_pair_gpu_generated(shape, seed, max_seq, max_k=8, kv_storage="cache", **ctx_kw):
+def oracle_storage_for(ctx):
+    """K/V storage parameter of the oracle a context is compared with: an fp32 cache is held against the plain
+    definition (cache in fp64, nothing rounded); a 16-bit cache against the oracle that stores the same type."""
+    return "exact" if ctx.kv_dtype == "fp32" else ctx.kv_dtype
+
+
+def make_pair_gpu_generated(shape, seed, max_seq, max_k=8, kv_storage="default", **ctx_kw):
     """Large shapes: weights are drawn on the GPU (fast) and the very same tensors are copied to the host
-    for the oracle -- moved, never regenerated.  kv_storage: the oracle's K/V storage parameter -- "cache" = the
-    context's cache type, "exact" = fp64 cache -- or a tuple of such modes (then a dict mode -> OracleModel over the
-    same host tensors is returned in place of the model)."""
+    for the oracle -- moved, never regenerated.  kv_storage: the oracle's K/V storage parameter -- "default" = what
+    oracle_storage_for gives, "cache" = the context's cache type, "exact" = fp64 cache -- or a tuple of such modes
+    (then a dict mode -> OracleModel over the same host tensors is returned in place of the model)."""
     import paper_2604_14612_amd as ssd
     w = make_weights(shape, seed, device="cuda")
     w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w.items()}
     ctx = ssd.Context(shape, w, max_seq, max_k, **ctx_kw)
-    mode = lambda m: ctx.kv_dtype if m == "cache" else m
+    mode = lambda m: ctx.kv_dtype if m == "cache" else oracle_storage_for(ctx) if m == "default" else m
     if isinstance(kv_storage, str):
         orc = OracleModel(shape, w_cpu, max_seq, kv_storage=mode(kv_storage))
     else:

@@ -72,7 +72,7 @@ def test_cache_types(ssd, name, kv):
     attention for 16-bit caches, the plain kernels for fp32), a 70-token prompt (64-row block + tail)."""
     shape = SHAPES[name]
     orc, ctx = make_pair(shape, 13, 160, max_k=8, norm_gain_std=0.1, kv_dtype=kv)
-    assert ctx.kv_dtype == kv and orc.kv_storage == kv
+    assert ctx.kv_dtype == kv and orc.kv_storage == ("exact" if kv == "fp32" else kv)
     prompt = make_prompt(shape.vocab, 70, 6).tolist()
     mask = np.array(MASKS[name][1], np.uint8)
     st = lockstep_ssd(ctx, orc, prompt, 0, [4, 8, 1, 4], mask, shape.dtype)
