@@ -136,6 +136,14 @@ SSD_API int ssd_decode(ssd_ctx *ctx, int32_t *token_out);
 SSD_API int ssd_draft_step(ssd_ctx *ctx, const uint8_t *skip_mask, int k, int32_t *draft_out,
                    float *draft_maxprob_out);
 
+/* The same with the attention and the MLP sub-block of every layer skipped separately -- the two modules whose hidden
+ * states Section 3.1 scores one by one (the layer-skipping baselines of Section 2 skip at this granularity):
+ * sub_mask is host [2 * n_layers], sub_mask[2l] != 0 leaves out the attention sub-block of layer l (no projections, no
+ * cache write at the draft positions), sub_mask[2l+1] != 0 its MLP sub-block.  ssd_draft_step(skip_mask) equals this
+ * call with both entries of every skipped layer set.  Verification is unchanged. */
+SSD_API int ssd_draft_step_sub(ssd_ctx *ctx, const uint8_t *sub_mask, int k, int32_t *draft_out,
+                               float *draft_maxprob_out);
+
 /* Confidence-aware drafting (Section 3: once a skip set is found the candidate tokens are
  * generated with the confidence-aware draft exit of the layer-skipping baseline the paper builds
  * on; the paper gives no threshold, gamma is the caller's).  Same draft model and cache effects as

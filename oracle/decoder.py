@@ -43,9 +43,9 @@ def _load():
         lib.orc_kcache.argtypes = [C.c_void_p]
         lib.orc_vcache.restype = C.c_void_p
         lib.orc_vcache.argtypes = [C.c_void_p]
-        lib.orc_forward.restype = C.c_int
-        lib.orc_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
-                                    C.c_void_p, C.c_void_p, C.c_void_p]
+        for fn in (lib.orc_forward, lib.orc_forward_sub):
+            fn.restype = C.c_int
+            fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.orc_round_bf16.restype = C.c_double
         lib.orc_round_bf16.argtypes = [C.c_double]
         lib.orc_round_fp16.restype = C.c_double
@@ -146,18 +146,23 @@ class OracleModel:
     # -- forward ----------------------------------------------------------------------------
     def forward(self, tokens: Sequence[int], pos0: int, skip_mask=None, want_taps=False,
                 want_logits=True, want_hidden=False):
-        """Run rows `tokens` at positions pos0.. ; returns dict(logits, taps, hidden)."""
+        """Run rows `tokens` at positions pos0.. ; returns dict(logits, taps, hidden).
+
+        skip_mask: n_layers entries (whole layers, the skip set S) or 2 * n_layers entries (attention and MLP
+        sub-block of every layer separately, [2l] and [2l+1])."""
         s = self.shape
         tok = np.ascontiguousarray(np.asarray(tokens, dtype=np.int32))
         R = tok.shape[0]
         skip = None if skip_mask is None else np.ascontiguousarray(np.asarray(skip_mask, dtype=np.uint8))
+        fwd = self._lib.orc_forward
         if skip is not None:
-            assert skip.shape == (s.n_layers,)
+            assert skip.shape in ((s.n_layers,), (2 * s.n_layers,)), skip.shape
+            if skip.shape[0] == 2 * s.n_layers:
+                fwd = self._lib.orc_forward_sub
         taps = np.empty((R, s.n_layers, 2, s.d_model), np.float64) if want_taps else None
         logits = np.empty((R, s.vocab), np.float64) if want_logits else None
         hidden = np.empty((R, s.d_model), np.float64) if want_hidden else None
-        rc = self._lib.orc_forward(self._h, _ptr(tok), R, int(pos0), _ptr(skip), _ptr(taps),
-                                   _ptr(logits), _ptr(hidden))
+        rc = fwd(self._h, _ptr(tok), R, int(pos0), _ptr(skip), _ptr(taps), _ptr(logits), _ptr(hidden))
         if rc != 0:
             raise ValueError("orc_forward: bad arguments (rows, positions or token ids out of range)")
         return {"logits": logits, "taps": taps, "hidden": hidden}

@@ -218,17 +218,19 @@ double *orc_vcache(orc_model *m) { return m->vcache; }
 
 /*
  * Forward R token rows at positions pos0 .. pos0+R-1 (row r sees cache positions
- * 0 .. pos0+r, i.e. causal inside the block).  Layers with skip[l] != 0 are left out
- * entirely: no cache write, residual unchanged.  Executed layers write their K/V rows
- * into the cache at the rows' positions.
+ * 0 .. pos0+r, i.e. causal inside the block).  sub_skip (optional) has two entries per layer:
+ * sub_skip[2l] != 0 leaves out the attention sub-block of layer l (no projections, no cache
+ * write, residual unchanged), sub_skip[2l+1] != 0 its MLP sub-block -- the two modules whose
+ * hidden states Section 3.1 scores separately; a layer of the skip set S of Section 3 has both
+ * set.  Executed attention sub-blocks write their K/V rows into the cache at the rows' positions.
  *   taps   (optional) [R][L][2][d]: residual stream after the attention sub-block and
  *          after the MLP sub-block of every layer (for a skipped layer both equal its input)
  *   logits (optional) [R][V]
  *   hidden (optional) [R][d]: residual stream after the last layer (before the final norm)
  * Returns 0, or -1 on bad arguments.
  */
-int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint8_t *skip,
-                double *taps, double *logits, double *hidden)
+int orc_forward_sub(orc_model *m, const int32_t *tokens, int R, int pos0, const uint8_t *sub_skip,
+                    double *taps, double *logits, double *hidden)
 {
     const orc_config *c = &m->c;
     int L = c->n_layers, d = c->d_model, H = c->n_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
@@ -257,17 +259,11 @@ int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint
         }
 
     for (int l = 0; l < L; l++) {
-        if (skip && skip[l]) {
-            if (taps)
-                for (int r = 0; r < R; r++) {
-                    memcpy(taps + (((size_t)r * L + l) * 2 + 0) * d, x + (size_t)r * d, sizeof(double) * d);
-                    memcpy(taps + (((size_t)r * L + l) * 2 + 1) * d, x + (size_t)r * d, sizeof(double) * d);
-                }
-            continue;
-        }
+        const int skip_attn = sub_skip && sub_skip[2 * l], skip_mlp = sub_skip && sub_skip[2 * l + 1];
         double *Kc = m->kcache + (size_t)l * c->max_seq * dkv;
         double *Vc = m->vcache + (size_t)l * c->max_seq * dkv;
         /* attention sub-block */
+        if (!skip_attn) {
         for (int r = 0; r < R; r++) rmsnorm(x + (size_t)r * d, m->attn_norm[l], d, c->rms_eps, h + (size_t)r * d);
         matmul_wt(m->wq[l], wt, dq, d, h, R, q);
         matmul_wt(m->wk[l], wt, dkv, d, h, R, kk);
@@ -308,16 +304,19 @@ int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint
             }
         matmul_wt(m->wo[l], wt, d, dq, att, R, t1);
         for (size_t i = 0; i < (size_t)R * d; i++) x[i] += t1[i];
+        }
         if (taps)
             for (int r = 0; r < R; r++)
                 memcpy(taps + (((size_t)r * L + l) * 2 + 0) * d, x + (size_t)r * d, sizeof(double) * d);
         /* MLP sub-block: x += Wd (silu(Wg h) * (Wu h)),  silu(z) = z / (1 + exp(-z)) */
+        if (!skip_mlp) {
         for (int r = 0; r < R; r++) rmsnorm(x + (size_t)r * d, m->mlp_norm[l], d, c->rms_eps, h + (size_t)r * d);
         matmul_wt(m->wg[l], wt, f, d, h, R, gt);
         matmul_wt(m->wu[l], wt, f, d, h, R, up);
         for (size_t i = 0; i < (size_t)R * f; i++) gt[i] = gt[i] / (1.0 + exp(-gt[i])) * up[i];
         matmul_wt(m->wd[l], wt, d, f, gt, R, t1);
         for (size_t i = 0; i < (size_t)R * d; i++) x[i] += t1[i];
+        }
         if (taps)
             for (int r = 0; r < R; r++)
                 memcpy(taps + (((size_t)r * L + l) * 2 + 1) * d, x + (size_t)r * d, sizeof(double) * d);
@@ -329,6 +328,19 @@ int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint
     }
     free(x); free(h); free(q); free(kk); free(vv); free(att); free(t1); free(gt); free(up);
     return 0;
+}
+
+/* The draft model of Section 3: layers with skip[l] != 0 (the skip set S) are left out entirely. */
+int orc_forward(orc_model *m, const int32_t *tokens, int R, int pos0, const uint8_t *skip,
+                double *taps, double *logits, double *hidden)
+{
+    if (!skip) return orc_forward_sub(m, tokens, R, pos0, NULL, taps, logits, hidden);
+    int L = m->c.n_layers;
+    uint8_t *sub = (uint8_t *)malloc((size_t)2 * L);
+    for (int l = 0; l < L; l++) sub[2 * l] = sub[2 * l + 1] = skip[l] ? 1 : 0;
+    int rc = orc_forward_sub(m, tokens, R, pos0, sub, taps, logits, hidden);
+    free(sub);
+    return rc;
 }
 
 /* Index of the largest logit; the lowest index wins a tie. */

@@ -77,6 +77,7 @@ SYMBOLS = {
     "ssd_prefill": (C.c_int, [_P, _P, C.c_int, _P]),
     "ssd_decode": (C.c_int, [_P, _P]),
     "ssd_draft_step": (C.c_int, [_P, _P, C.c_int, _P, _P]),
+    "ssd_draft_step_sub": (C.c_int, [_P, _P, C.c_int, _P, _P]),
     "ssd_draft_adaptive": (C.c_int, [_P, _P, C.c_int, C.c_float, _P, _P, _P]),
     "ssd_verify": (C.c_int, [_P, _P, C.c_int, _P]),
     "ssd_accept": (C.c_int, [_P, _P, _P, C.c_int, _P, _P]),
@@ -353,11 +354,13 @@ class Context:
 
     def ssd_draft_step(self, skip_mask, k: int, want_maxprob: bool = False):
         m = np.ascontiguousarray(np.asarray(skip_mask, dtype=np.uint8))
-        if m.shape != (self.shape.n_layers,):
-            raise SsdError(SSD_EINVAL, "skip_mask must have n_layers entries")
+        L = self.shape.n_layers
+        if m.shape not in ((L,), (2 * L,)):
+            raise SsdError(SSD_EINVAL, "skip_mask must have n_layers entries (or 2 * n_layers: attention / MLP sub-blocks)")
         d = np.zeros(max(k, 1), np.int32)
         mp = np.zeros(max(k, 1), np.float32) if want_maxprob else None
-        self._check(self._l.ssd_draft_step(self._h, _np_ptr(m), int(k), _np_ptr(d), _np_ptr(mp)))
+        fn = self._l.ssd_draft_step if m.shape[0] == L else self._l.ssd_draft_step_sub
+        self._check(fn(self._h, _np_ptr(m), int(k), _np_ptr(d), _np_ptr(mp)))
         return (d[:k].tolist(), mp[:k].tolist()) if want_maxprob else d[:k].tolist()
 
     def ssd_draft_adaptive(self, skip_mask, k_max: int, gamma: float):

@@ -198,11 +198,12 @@ static inline bool is_gemv_kid(int kid)
         }                                                                                  \
     } while (0)
 
-// One decoder layer for a single row (draft / vanilla decode path).
-int layer_single(ssd_ctx* c, int l, int pos_off)
+// One decoder layer for a single row (draft / vanilla decode path); either sub-block may be left out.
+int layer_single(ssd_ctx* c, int l, int pos_off, bool do_attn, bool do_mlp)
 {
     const Dims& D = c->D;
     float* x = c->f(c->lay.x);
+    if (do_attn) {
     TIMED(SSD_K_GEMV_QKV, gemv_qkv(D, c->wq[l], c->wk[l], c->wv[l], c->attn_norm[l], x, c->f(c->lay.rope), c->pos_dev(),
                                    pos_off, c->f(c->lay.qkv), c->kcache(l), c->vcache(l), c->stream), "gemv_qkv");
     int fold = 0;  // > 0: attention left that many partials per head for the output projection to fold
@@ -214,6 +215,8 @@ int layer_single(ssd_ctx* c, int l, int pos_off)
     } else {
         TIMED(SSD_K_GEMV_O, gemv_resid(D, c->wo[l], D.d, D.dq, c->f(c->lay.att), x, nullptr, c->stream), "gemv_o");
     }
+    }
+    if (!do_mlp) return SSD_OK;
     TIMED(SSD_K_GEMV_GATEUP, gemv_swiglu(D, c->wg[l], c->wu[l], c->mlp_norm[l], x, c->f(c->lay.act), c->stream),
           "gemv_swiglu");
     TIMED(SSD_K_GEMV_DOWN, gemv_resid(D, c->wd[l], D.d, D.f, c->f(c->lay.act), x, nullptr, c->stream), "gemv_down");
@@ -222,13 +225,15 @@ int layer_single(ssd_ctx* c, int l, int pos_off)
 
 // Single-row forward of the token in tok slot `slot` at position *pos + pos_off; the greedy token goes to
 // tok slot `slot_out`, its logits to logits row `lrow`, its max-probability to SM_MAXPROB[lrow].
-int forward_single(ssd_ctx* c, const uint8_t* skip, int slot, int slot_out, int pos_off, int lrow)
+// sub (may be null): two entries per layer, [2l] != 0 leaves out the attention sub-block, [2l+1] != 0 the MLP sub-block.
+int forward_single(ssd_ctx* c, const uint8_t* sub, int slot, int slot_out, int pos_off, int lrow)
 {
     const Dims& D = c->D;
     HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_TOK + slot, 1, c->f(c->lay.x), c->stream), "embed");
     for (int l = 0; l < D.L; l++) {
-        if (skip && skip[l]) continue;
-        int rc = layer_single(c, l, pos_off);
+        const bool do_attn = !(sub && sub[2 * l]), do_mlp = !(sub && sub[2 * l + 1]);
+        if (!do_attn && !do_mlp) continue;
+        int rc = layer_single(c, l, pos_off, do_attn, do_mlp);
         if (rc) return rc;
     }
     float* logits = c->f(c->lay.logits) + (size_t)lrow * D.V;
@@ -619,18 +624,18 @@ int ssd_decode(ssd_ctx* c, int32_t* token_out)
     return SSD_OK;
 }
 
-int ssd_draft_step(ssd_ctx* c, const uint8_t* skip_mask, int k, int32_t* draft_out, float* draft_maxprob_out)
+// Common body of the two fixed-length draft calls; sub has two entries per layer.
+static int draft_fixed(ssd_ctx* c, const std::vector<uint8_t>& sub, int k, int32_t* draft_out, float* draft_maxprob_out)
 {
-    if (!c || !skip_mask || !draft_out) return c ? fail(c, SSD_EINVAL, "draft_step: bad argument") : SSD_EINVAL;
     if (k < 1) return fail(c, SSD_EINVAL, "k must be at least 1");
     if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "draft_step needs a prefilled sequence with no draft in flight");
     if (k > c->cfg.max_k) return fail(c, SSD_ECAPACITY, "k exceeds max_k");
     if (c->n + k > c->D.max_seq) return fail(c, SSD_ECAPACITY, "draft + verification would exceed max_seq");
-    std::string key = "S|" + std::to_string(k) + "|" + std::string(skip_mask, skip_mask + c->D.L) + "|";
+    std::string key = "S|" + std::to_string(k) + "|" + std::string(sub.begin(), sub.end()) + "|";
     for (int i = 0; i < k; i++) key += std::to_string(attention_splits(c->D, c->n + i, 1)) + ",";
     int rc = run_sequence(c, key, [&]() {
         for (int i = 0; i < k; i++) {
-            int r = forward_single(c, skip_mask, i, i + 1, i, i);
+            int r = forward_single(c, sub.data(), i, i + 1, i, i);
             if (r) return r;
         }
         return (int)SSD_OK;
@@ -650,6 +655,28 @@ int ssd_draft_step(ssd_ctx* c, const uint8_t* skip_mask, int k, int32_t* draft_o
     return SSD_OK;
 }
 
+// whole-layer mask [L] -> sub-block mask [2L] with 0 / 1 entries
+static std::vector<uint8_t> expand_mask(const uint8_t* skip_mask, int L)
+{
+    std::vector<uint8_t> sub((size_t)2 * L);
+    for (int l = 0; l < L; l++) sub[2 * l] = sub[2 * l + 1] = skip_mask[l] ? 1 : 0;
+    return sub;
+}
+
+int ssd_draft_step(ssd_ctx* c, const uint8_t* skip_mask, int k, int32_t* draft_out, float* draft_maxprob_out)
+{
+    if (!c || !skip_mask || !draft_out) return c ? fail(c, SSD_EINVAL, "draft_step: bad argument") : SSD_EINVAL;
+    return draft_fixed(c, expand_mask(skip_mask, c->D.L), k, draft_out, draft_maxprob_out);
+}
+
+int ssd_draft_step_sub(ssd_ctx* c, const uint8_t* sub_mask, int k, int32_t* draft_out, float* draft_maxprob_out)
+{
+    if (!c || !sub_mask || !draft_out) return c ? fail(c, SSD_EINVAL, "draft_step_sub: bad argument") : SSD_EINVAL;
+    std::vector<uint8_t> sub((size_t)2 * c->D.L);
+    for (size_t i = 0; i < sub.size(); i++) sub[i] = sub_mask[i] ? 1 : 0;
+    return draft_fixed(c, sub, k, draft_out, draft_maxprob_out);
+}
+
 int ssd_draft_adaptive(ssd_ctx* c, const uint8_t* skip_mask, int k_max, float gamma, int32_t* draft_out,
                        float* draft_maxprob_out, int32_t* k_out)
 {
@@ -659,13 +686,14 @@ int ssd_draft_adaptive(ssd_ctx* c, const uint8_t* skip_mask, int k_max, float ga
     if (c->state != ST_IDLE) return fail(c, SSD_ESTATE, "draft_adaptive needs a prefilled sequence with no draft in flight");
     if (k_max > c->cfg.max_k) return fail(c, SSD_ECAPACITY, "k_max exceeds max_k");
     if (c->n + k_max > c->D.max_seq) return fail(c, SSD_ECAPACITY, "draft + verification would exceed max_seq");
-    const std::string mask_key(skip_mask, skip_mask + c->D.L);
+    const std::vector<uint8_t> sub = expand_mask(skip_mask, c->D.L);
+    const std::string mask_key(sub.begin(), sub.end());
     int k = 0;
     while (k < k_max) {
         // one draft step per submission: the host reads the step's max-probability before deciding on the next
         const int i = k;
         std::string key = "A|" + std::to_string(i) + "|" + mask_key + "|" + std::to_string(attention_splits(c->D, c->n + i, 1));
-        int rc = run_sequence(c, key, [&]() { return forward_single(c, skip_mask, i, i + 1, i, i); });
+        int rc = run_sequence(c, key, [&]() { return forward_single(c, sub.data(), i, i + 1, i, i); });
         if (rc) return rc;
         float p = 0.f;
         rc = readback(c, c->small_f() + SM_MAXPROB + i, sizeof(float), &p);

@@ -2018,6 +2018,9 @@ __device__ __forceinline__ void split8(const float* x, u32x4_t& hi, u32x4_t& lo)
     lo = u32x4_t{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
 }
 
+// fp32 caches take the same kernel: while a chunk is staged every K / V element is split into two bf16 planes
+// (hi = rne(x), lo = rne(x - hi), 16 mantissa bits together), and each contraction becomes three MFMAs
+// (hi.hi + lo.hi + hi.lo; the lo.lo term is below the 16 bits the planes carry).
 template <typename KT, int HD>
 __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __restrict__ q, int ldq,
                                                                const KT* __restrict__ kc, const KT* __restrict__ vc,
@@ -2027,19 +2030,22 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
                                                                uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo,
                                                                bool out_f16)
 {
-    static_assert(sizeof(KT) == 2, "16-bit caches only");
-    constexpr bool F16 = IsF16<KT>::value;
+    constexpr bool F32 = sizeof(KT) == 4;
+    constexpr bool F16 = IsF16<KT>::value;     // operand type of the MFMAs: fp16 for fp16 caches, else bf16
+    constexpr int NP = F32 ? 2 : 1;            // planes per staged tile
     constexpr int ROWB = HD * 2 + 16;
-    constexpr int VPR = HD / 8;                // 16-byte vectors per cache row
+    constexpr int EPV = 16 / (int)sizeof(KT);  // cache elements per 16-byte vector
+    constexpr int VPR = HD / EPV;              // 16-byte vectors per cache row
     constexpr int KSTEPS = HD / 32;            // MFMA k-steps of a score
     constexpr int PT = AT_CHUNK / 16;          // position tiles of the chunk (6)
     constexpr int PS = AT_CHUNK / 32;          // k-steps of P.V (3)
     constexpr int DT = HD / 16;                // output dim tiles (8 or 4)
     constexpr int DTW = DT / 4;                // dim tiles per wave
+    constexpr int KPLANE = AT_CHUNK * ROWB, VPLANE = HD * AM_VPITCH;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* ktile = smem;                                       // [AT_CHUNK][ROWB]
-    unsigned char* vT = smem + AT_CHUNK * ROWB;                        // [HD][AM_VPITCH]
-    float* qs = reinterpret_cast<float*>(vT + HD * AM_VPITCH);         // [16][HD], pre-scaled
+    unsigned char* ktile = smem;                                       // [NP][AT_CHUNK][ROWB]
+    unsigned char* vT = smem + NP * KPLANE;                            // [NP][HD][AM_VPITCH]
+    float* qs = reinterpret_cast<float*>(vT + NP * VPLANE);            // [16][HD], pre-scaled
     float* sc = qs + AT_QPASS * HD;                                    // [16][AT_CHUNK]
     float* ml = sc + AT_QPASS * AT_CHUNK;                              // [16][2]
 
@@ -2069,28 +2075,47 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
         u32x4_t kr[NV], vr[NV];
         const int vmax = n * VPR - 1;
         // K: consecutive lanes take consecutive vectors of a row.  V: consecutive lanes take consecutive POSITIONS
-        // (vector v -> position v % AT_CHUNK, dims 8 (v / AT_CHUNK) ..), so that the 2-byte stores of the transpose
+        // (vector v -> position v % AT_CHUNK, dims EPV (v / AT_CHUNK) ..), so that the 2-byte stores of the transpose
         // below fall on consecutive addresses of one V^T row instead of colliding in two banks.
 #pragma unroll
         for (int t = 0; t < NV; t++) {
             const int v = min(tid + t * AT_THREADS, vmax);
-            kr[t] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)(v / VPR) * HD + (v % VPR) * 8);
+            kr[t] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)(v / VPR) * HD + (v % VPR) * EPV);
             const int w = min(tid + t * AT_THREADS, AT_CHUNK * VPR - 1);
-            vr[t] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min(w % AT_CHUNK, n - 1) * HD + (w / AT_CHUNK) * 8);
+            vr[t] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min(w % AT_CHUNK, n - 1) * HD + (w / AT_CHUNK) * EPV);
         }
 #pragma unroll
         for (int t = 0; t < NV; t++) {
             const int v = tid + t * AT_THREADS;
             if (v < AT_CHUNK * VPR) {
-                const int pos = v / VPR, d0 = (v % VPR) * 8;
+                const int pos = v / VPR, d0 = (v % VPR) * EPV;
+                const int vpos = v % AT_CHUNK, vd0 = (v / AT_CHUNK) * EPV;
                 // positions past the chunk: zero keys and values
-                *reinterpret_cast<u32x4_t*>(ktile + pos * ROWB + d0 * 2) = v <= vmax ? kr[t] : u32x4_t{0u, 0u, 0u, 0u};
-                const int vpos = v % AT_CHUNK, vd0 = (v / AT_CHUNK) * 8;
+                const u32x4_t kk = v <= vmax ? kr[t] : u32x4_t{0u, 0u, 0u, 0u};
                 const u32x4_t vv = vpos < n ? vr[t] : u32x4_t{0u, 0u, 0u, 0u};
-                const unsigned w4[4] = {vv.x, vv.y, vv.z, vv.w};
+                if constexpr (F32) {
+                    const unsigned kw[4] = {kk.x, kk.y, kk.z, kk.w}, vw[4] = {vv.x, vv.y, vv.z, vv.w};
+                    unsigned kh[4], kl[4];
 #pragma unroll
-                for (int e = 0; e < 8; e++)
-                    *reinterpret_cast<uint16_t*>(vT + (vd0 + e) * AM_VPITCH + vpos * 2) = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+                    for (int e = 0; e < 4; e++) {
+                        const float x = __uint_as_float(kw[e]);
+                        kh[e] = f32_to_bf16_bits(x);
+                        kl[e] = f32_to_bf16_bits(x - bf16_bits_to_f32(kh[e]));
+                        const float y = __uint_as_float(vw[e]);
+                        const uint16_t yh = f32_to_bf16_bits(y);
+                        *reinterpret_cast<uint16_t*>(vT + (vd0 + e) * AM_VPITCH + vpos * 2) = yh;
+                        *reinterpret_cast<uint16_t*>(vT + VPLANE + (vd0 + e) * AM_VPITCH + vpos * 2) =
+                            f32_to_bf16_bits(y - bf16_bits_to_f32(yh));
+                    }
+                    *reinterpret_cast<uint2*>(ktile + pos * ROWB + d0 * 2) = make_uint2(kh[0] | (kh[1] << 16), kh[2] | (kh[3] << 16));
+                    *reinterpret_cast<uint2*>(ktile + KPLANE + pos * ROWB + d0 * 2) = make_uint2(kl[0] | (kl[1] << 16), kl[2] | (kl[3] << 16));
+                } else {
+                    *reinterpret_cast<u32x4_t*>(ktile + pos * ROWB + d0 * 2) = kk;
+                    const unsigned w4[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        *reinterpret_cast<uint16_t*>(vT + (vd0 + e) * AM_VPITCH + vpos * 2) = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+                }
             }
         }
     }
@@ -2112,9 +2137,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
                 f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int st = 0; st < KSTEPS; st++) {
-                    const u32x4_t kf = *reinterpret_cast<const u32x4_t*>(ktile + (pt * 16 + r16) * ROWB + (st * 32 + g * 8) * 2);
+                    const unsigned char* kp = ktile + (pt * 16 + r16) * ROWB + (st * 32 + g * 8) * 2;
+                    const u32x4_t kf = *reinterpret_cast<const u32x4_t*>(kp);
                     acc = mfma_h16<F16>(qh[st], kf, acc);
                     acc = mfma_h16<F16>(ql[st], kf, acc);
+                    if constexpr (F32) acc = mfma_h16<F16>(qh[st], *reinterpret_cast<const u32x4_t*>(kp + KPLANE), acc);
                 }
 #pragma unroll
                 for (int jx = 0; jx < 4; jx++) sc[(g * 4 + jx) * AT_CHUNK + pt * 16 + r16] = acc[jx];
@@ -2160,9 +2187,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
             if (n > 0) {
 #pragma unroll
                 for (int st = 0; st < PS; st++) {
-                    const u32x4_t vf = *reinterpret_cast<const u32x4_t*>(vT + (dt * 16 + r16) * AM_VPITCH + (st * 32 + g * 8) * 2);
+                    const unsigned char* vp = vT + (dt * 16 + r16) * AM_VPITCH + (st * 32 + g * 8) * 2;
+                    const u32x4_t vf = *reinterpret_cast<const u32x4_t*>(vp);
                     acc = mfma_h16<F16>(ph[st], vf, acc);
                     acc = mfma_h16<F16>(pl[st], vf, acc);
+                    if constexpr (F32) acc = mfma_h16<F16>(ph[st], *reinterpret_cast<const u32x4_t*>(vp + VPLANE), acc);
                 }
             }
             // the tile goes back through LDS (the query buffer is free by now) so that the block can write whole
@@ -2197,7 +2226,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
 template <typename KT, int HD>
 static size_t attn_mfma_lds_bytes()
 {
-    return (size_t)AT_CHUNK * (HD * 2 + 16) + (size_t)HD * AM_VPITCH + (size_t)AT_QPASS * HD * 4 +
+    const size_t planes = sizeof(KT) == 4 ? 2 : 1;
+    return planes * ((size_t)AT_CHUNK * (HD * 2 + 16) + (size_t)HD * AM_VPITCH) + (size_t)AT_QPASS * HD * 4 +
            (size_t)AT_QPASS * AT_CHUNK * 4 + (size_t)AT_QPASS * 2 * 4;
 }
 
@@ -2471,16 +2501,18 @@ static AttnPlan attn_plan(const Dims& D, int ctx, int M)
     AttnPlan pl;
     pl.defer_fold = false;
     const int Q = (D.H / D.Hkv) * M;
-    // More than 4 query vectors per KV head: 16-bit caches take the MFMA form of the LDS-staged kernel (12.9 us
-    // against 14.5 us at 5 rows, 7B shape, fold included).  fp32 caches have no MFMA form; there a few rows with 1, 2,
-    // 4 or 8 query heads per KV head still run the register-resident kernel, one block per row and range serving
-    // the row's group of heads (two blocks for a group of 8), re-reading a range's K/V from the cache.
+    // More than 4 query vectors per KV head: the MFMA form of the LDS-staged kernel (12.9 us against 14.5 us at 5 rows,
+    // 7B shape, 16-bit cache, fold included).  A model with fp32 WEIGHTS stays in fp32 arithmetic throughout: there a
+    // few rows with 1, 2, 4 or 8 query heads per KV head run the register-resident kernel, one block per row and range
+    // serving the row's group of heads (two blocks for a group of 8), re-reading a range's K/V from the cache.
     const int G = D.H / D.Hkv;
-    pl.wide = Q <= AW_MAXQ_TOTAL || (D.kt == WT_F32 && (G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
+    pl.wide = Q <= AW_MAXQ_TOTAL ||
+              (D.kt == WT_F32 && D.wt == WT_F32 && (G == 1 || G == 2 || G == 4 || G == 8) && M <= AW_MAX_ROWS);
     if (force_kernel == 1 || force_kernel == 3) pl.wide = false;
     if (pl.wide) {
-        // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them
-        int ns = ceil_div(ctx, AW_RANGE);
+        // ranges of AW_RANGE positions (one pass of the narrowest block shape), at most AW_MAX_RANGES of them; an fp32
+        // cache has twice the bytes per position, so its ranges are shorter (more blocks pulling from the cache)
+        int ns = ceil_div(ctx, D.kt == WT_F32 ? AW_RANGE * 5 / 8 : AW_RANGE);
         // single row: up to 4 K positions, ranges grow rather than exceed what the output projection folds itself
         // (a longer range costs the attention kernel about 1 us, a separate fold launch 5)
         if (M == 1 && ns > GV_FOLD_MAX && ctx <= GV_FOLD_MAX * 512) ns = GV_FOLD_MAX;
@@ -2524,8 +2556,10 @@ static void launch_attn_staged(const Dims& D, const float* q, int ldq, const voi
                                int pos_off, int n_splits, int M, float* part, float* out, uint16_t* out_hi, uint16_t* out_lo,
                                hipStream_t s)
 {
-    if constexpr (sizeof(KT) == 2) {
-        if (!(D.opt && D.opt->attn_kernel == 3)) {
+    {
+        // MFMA form: 16-bit caches always; fp32 caches when the model's weights are 16-bit (its hi/lo planes carry 16
+        // mantissa bits, the precision the multi-row path of such a model works at anyway; an fp32 model keeps fp32)
+        if (!(D.opt && D.opt->attn_kernel == 3) && (sizeof(KT) == 2 || D.wt != WT_F32)) {
             const size_t lds = attn_mfma_lds_bytes<KT, HD>();
             static std::atomic<size_t> lds_limit{0};  // per instantiation
             if (ensure_lds((const void*)attn_mfma_kernel<KT, HD>, lds, lds_limit) != hipSuccess)

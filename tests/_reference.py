@@ -24,8 +24,9 @@ def reference_forward(shape, w, tokens, kv_storage="model", skip_mask=None, n_ve
     kv_storage: "exact" (nothing rounded), "model" (K after the rotary embedding and V pass through the weight
     type, the half-precision cache of Section 4.1.1) or an explicit type name.
     skip_mask / n_verified: the draft model of Section 3 on rows n_verified.. -- those rows leave out the layers of
-    the skip set, and in an executed layer they attend the full model's K/V at positions < n_verified (the verified
-    cache) and the draft rows' own K/V from n_verified on.  Rows < n_verified always run the full model.
+    the skip set (L entries) or single attention / MLP sub-blocks (2L entries, [2l] attention, [2l+1] MLP), and in an
+    executed attention sub-block they attend the full model's K/V at positions < n_verified (the verified cache) and
+    the draft rows' own K/V from n_verified on.  Rows < n_verified always run the full model.
     """
     dd = torch.float64
     if kv_storage == "model":
@@ -33,7 +34,9 @@ def reference_forward(shape, w, tokens, kv_storage="model", skip_mask=None, n_ve
     T = len(tokens)
     L, H, Hkv, hd, d = shape.n_layers, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_model
     nv = T if n_verified is None else n_verified
-    skip = np.zeros(L, bool) if skip_mask is None else np.asarray(skip_mask).astype(bool)
+    skip = np.zeros(2 * L, bool) if skip_mask is None else np.asarray(skip_mask).astype(bool)
+    if skip.shape[0] == L:                 # whole layers: both sub-blocks
+        skip = np.repeat(skip, 2)
     x = F.embedding(torch.tensor(tokens, dtype=torch.long), w["embed"].to(dd))
     pos = torch.arange(T, dtype=dd)
     inv = shape.rope_base ** (-torch.arange(0, hd, 2, dtype=dd) / hd)       # base^(-2i/hd)
@@ -45,10 +48,13 @@ def reference_forward(shape, w, tokens, kv_storage="model", skip_mask=None, n_ve
 
     taps = torch.zeros(T, L, 2, d, dtype=dd)
     for l in range(L):
-        # rows that run this layer: all verified rows, and the draft rows unless the layer is skipped
-        live = torch.ones(T, dtype=torch.bool)
-        if skip[l]:
-            live[nv:] = False
+        # rows that run a sub-block: all verified rows, and the draft rows unless it is skipped
+        live_a = torch.ones(T, dtype=torch.bool)
+        live_m = torch.ones(T, dtype=torch.bool)
+        if skip[2 * l]:
+            live_a[nv:] = False
+        if skip[2 * l + 1]:
+            live_m[nv:] = False
         h = F.rms_norm(x, (d,), w["attn_norm"][l].to(dd), eps=shape.rms_eps)
         q = rope(F.linear(h, w["wq"][l].to(dd)).view(T, H, hd))
         k = _store(rope(F.linear(h, w["wk"][l].to(dd)).view(T, Hkv, hd)), kv_storage)
@@ -58,10 +64,10 @@ def reference_forward(shape, w, tokens, kv_storage="model", skip_mask=None, n_ve
         o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
                                            v.transpose(0, 1)[None], is_causal=True)[0]
         xa = x + F.linear(o.transpose(0, 1).reshape(T, H * hd), w["wo"][l].to(dd))
+        xa = torch.where(live_a[:, None], xa, x)
         h = F.rms_norm(xa, (d,), w["mlp_norm"][l].to(dd), eps=shape.rms_eps)
         xm = xa + F.linear(F.silu(F.linear(h, w["wg"][l].to(dd))) * F.linear(h, w["wu"][l].to(dd)), w["wd"][l].to(dd))
-        xa = torch.where(live[:, None], xa, x)
-        xm = torch.where(live[:, None], xm, x)
+        xm = torch.where(live_m[:, None], xm, xa)
         taps[:, l, 0], taps[:, l, 1] = xa, xm
         x = xm
     h = F.rms_norm(x, (d,), w["final_norm"].to(dd), eps=shape.rms_eps)

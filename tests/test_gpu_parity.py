@@ -109,6 +109,35 @@ def test_ssd_lockstep(ssd, name, k):
         ctx.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa16"])
+def test_sub_block_skip_masks(ssd, name):
+    """ssd_draft_step_sub: attention and MLP sub-blocks skipped separately (two mask entries per layer), in lock-step
+    with the oracle; a whole-layer mask and its expansion give bit-identical drafts."""
+    shape = SHAPES[name]
+    L = shape.n_layers
+    rng = np.random.default_rng(5)
+    subs = [np.tile(np.array([1, 0], np.uint8), L), np.tile(np.array([0, 1], np.uint8), L)]
+    subs += [rng.integers(0, 2, 2 * L).astype(np.uint8) for _ in range(2)]
+    for sub in subs:
+        orc, ctx = make_pair(shape, 13, 128, max_k=8, norm_gain_std=0.1)
+        prompt = make_prompt(shape.vocab, 19, 6).tolist()
+        st = lockstep_ssd(ctx, orc, prompt, 12, 4, sub, shape.dtype)
+        print("sub-block mask", name, sub.tolist(), "max err %.2e" % st["max_err"], "accepted", st["accepted"],
+              "unpinned", st["unpinned_cycles"])
+        assert st["unpinned_cycles"] <= max(1, st["cycles"] // 4)
+        ctx.close()
+    whole = np.array(MASKS[name][1], np.uint8)
+    orc, ctx = make_pair(shape, 13, 128, max_k=8, norm_gain_std=0.1)
+    prompt = make_prompt(shape.vocab, 19, 6).tolist()
+    ctx.ssd_prefill(prompt)
+    d1 = ctx.ssd_draft_step(whole, 4)
+    z1 = ctx.ssd_copy_logits(0, 4).copy()
+    ctx.ssd_reset()
+    ctx.ssd_prefill(prompt)
+    d2 = ctx.ssd_draft_step(np.repeat(whole, 2), 4)
+    assert d1 == d2 and np.array_equal(z1, ctx.ssd_copy_logits(0, 4))
+
+
 def test_tiny_workload_end_to_end_matches_oracle_tokens(ssd):
     """BASELINE config 1: 32-token prompt, 32 new tokens, k = 4, skip set from confidence over all 4 layers."""
     wl = WORKLOADS["tiny"]

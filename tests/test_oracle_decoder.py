@@ -140,6 +140,50 @@ def test_all_layers_skipped_is_embedding_through_head():
     assert not m.kcache().any() and not m.vcache().any()
 
 
+def test_sub_block_skipping():
+    """Attention and MLP sub-blocks skipped separately (two mask entries per layer): against the library-op
+    reference on draft rows, against the whole-layer mask, and against a closed form with every attention
+    sub-block skipped (no token then sees another: the row is its embedding pushed through the MLPs alone)."""
+    shape = SHAPES[1]
+    L = shape.n_layers
+    w = make_weights(shape, 4, norm_gain_std=0.2, init_std=0.3)
+    toks = make_prompt(shape.vocab, 11, 8).tolist()
+    for sub in ([1, 0, 0, 1], [0, 1, 1, 0], [0, 0, 1, 0], [1, 1, 0, 1]):
+        sub = np.array(sub, np.uint8)
+        for kv in ("exact", "model"):
+            ref, ref_taps = reference_forward(shape, w, toks, kv, skip_mask=sub, n_verified=7)
+            m = OracleModel(shape, w, 16, kv_storage=kv)
+            m.forward(toks[:7], 0)
+            out = m.forward(toks[7:], 7, skip_mask=sub, want_taps=True)
+            assert np.abs(out["logits"] - ref[7:]).max() <= 1e-9 * max(1.0, np.abs(ref).max())
+            assert np.abs(out["taps"] - ref_taps[7:]).max() <= 1e-9 * max(1.0, np.abs(ref_taps).max())
+    # a layer of the skip set = both of its sub-blocks
+    whole = np.array([0, 1], np.uint8)
+    a = OracleModel(shape, w, 16)
+    b = OracleModel(shape, w, 16)
+    za = a.forward(toks, 0, skip_mask=whole)["logits"]
+    zb = b.forward(toks, 0, skip_mask=np.repeat(whole, 2))["logits"]
+    assert np.array_equal(za, zb) and np.array_equal(a.kcache(), b.kcache())
+    # every attention sub-block skipped: closed form, and nothing is written to the cache
+    only_mlp = np.tile(np.array([1, 0], np.uint8), L)
+    m = OracleModel(shape, w, 16)
+    z = m.forward(toks[:3], 2, skip_mask=only_mlp)["logits"]
+    assert not m.kcache().any() and not m.vcache().any()
+    for r, t in enumerate(toks[:3]):
+        x = w["embed"][t].double().numpy()
+        for l in range(L):
+            h = x / np.sqrt(np.mean(x * x) + shape.rms_eps) * w["mlp_norm"][l].double().numpy()
+            g, u = w["wg"][l].double().numpy() @ h, w["wu"][l].double().numpy() @ h
+            x = x + w["wd"][l].double().numpy() @ (g / (1.0 + np.exp(-g)) * u)
+        h = x / np.sqrt(np.mean(x * x) + shape.rms_eps) * w["final_norm"].double().numpy()
+        np.testing.assert_allclose(z[r], w["lm_head"].double().numpy() @ h, rtol=1e-11, atol=1e-11)
+    # every MLP sub-block skipped changes the result in another way (both masks differ from the full model)
+    only_attn = np.tile(np.array([0, 1], np.uint8), L)
+    full = OracleModel(shape, w, 16).forward(toks, 0)["logits"]
+    part = OracleModel(shape, w, 16).forward(toks, 0, skip_mask=only_attn)["logits"]
+    assert np.abs(full - part).max() > 1e-3
+
+
 def test_rope_is_identity_at_position_zero_and_preserves_norm():
     shape = ModelShape(1, 64, 2, 2, 96, 30, dtype="fp32")
     w = make_weights(shape, 9, init_std=0.4)
@@ -194,6 +238,7 @@ def test_ssd_is_lossless_for_any_mask(k):
     rng = np.random.default_rng(k)
     masks = [np.zeros(4, np.uint8), np.array([0, 1, 1, 0], np.uint8), np.ones(4, np.uint8)]
     masks += [rng.integers(0, 2, 4).astype(np.uint8) for _ in range(3)]
+    masks += [rng.integers(0, 2, 8).astype(np.uint8) for _ in range(3)]      # attention / MLP sub-blocks separately
     for mask in masks:
         got, st = generate_ssd(OracleModel(wl.shape, w, 128), p, 24, k, mask)
         assert got == van, mask
