@@ -193,6 +193,18 @@ SSD_API int ssd_copy_logits(ssd_ctx *ctx, int row_begin, int n_rows, float *logi
 SSD_API int ssd_layer_confidence(ssd_ctx *ctx, int row_begin, int n_rows, float *conf_out,
                          float *tap_conf_out, float *tap_maxprob_out, int32_t *tap_argmax_out);
 
+/* For callers that cannot allocate device memory while they run (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same computation and results as ssd_layer_confidence, but every device
+ * buffer the pass needs beyond the context's taps and weights -- the normalised rows, their logits, the per-row
+ * results -- lives in a fixed array inside the library image (SSD_STATIC_SCRATCH_BYTES per GPU, held until the process
+ * ends) instead of the workspace, 64 tap rows at a time.  Calls nothing that allocates.  SSD_ECAPACITY if 64 rows of
+ * this model exceed the array (64 * (4 * vocab + 8 * d_model) bytes, e.g. a 128 256-entry vocabulary); SSD_EINVAL if
+ * the context's device is not the current one.  All calls on one GPU share that GPU's array: calls that overlap in
+ * time on one GPU (two contexts, two streams) race; the array keeps the last call's contents. */
+#define SSD_STATIC_SCRATCH_BYTES (12u << 20)
+SSD_API int ssd_layer_confidence_static(ssd_ctx *ctx, int row_begin, int n_rows, float *conf_out,
+                                        float *tap_conf_out, float *tap_maxprob_out, int32_t *tap_argmax_out);
+
 /* Eq. 5-10 parameters.  Defaults (ssd_select_defaults): lambda 0.3, w_base 2, kappa 1,
  * flat_tol 1e-3, min_ratio 0.40, max_ratio 0.60, protect_ends 1, eps 1e-8, fixed_w_max -1. */
 typedef struct {

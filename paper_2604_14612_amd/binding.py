@@ -84,6 +84,7 @@ SYMBOLS = {
     "ssd_force_commit": (C.c_int, [_P, _P, C.c_int, C.c_int, C.c_int32]),
     "ssd_copy_logits": (C.c_int, [_P, C.c_int, C.c_int, _P]),
     "ssd_layer_confidence": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, _P, _P]),
+    "ssd_layer_confidence_static": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, _P, _P]),
     "ssd_select_defaults": (None, [C.POINTER(ssd_select_params)]),
     "ssd_select_skip": (C.c_int, [_P, C.c_int, C.POINTER(ssd_select_params), _P, _P, _P]),
     "ssd_uniform_skip": (C.c_int, [C.c_int, C.POINTER(ssd_select_params), _P]),
@@ -400,14 +401,15 @@ class Context:
         self._check(self._l.ssd_copy_logits(self._h, int(row_begin), int(n_rows), _np_ptr(out)))
         return out
 
-    def ssd_layer_confidence(self, row_begin: int = 0, n_rows: int = 1, detail: bool = False):
+    def ssd_layer_confidence(self, row_begin: int = 0, n_rows: int = 1, detail: bool = False, static: bool = False):
+        """static=True calls ssd_layer_confidence_static (no workspace scratch, no allocation) instead."""
         L = self.shape.n_layers
         conf = np.empty((n_rows, L), np.float32)
         tc = np.empty((n_rows, L, 2), np.float32) if detail else None
         tm = np.empty((n_rows, L, 2), np.float32) if detail else None
         ta = np.empty((n_rows, L, 2), np.int32) if detail else None
-        self._check(self._l.ssd_layer_confidence(self._h, int(row_begin), int(n_rows), _np_ptr(conf), _np_ptr(tc),
-                                                 _np_ptr(tm), _np_ptr(ta)))
+        fn = self._l.ssd_layer_confidence_static if static else self._l.ssd_layer_confidence
+        self._check(fn(self._h, int(row_begin), int(n_rows), _np_ptr(conf), _np_ptr(tc), _np_ptr(tm), _np_ptr(ta)))
         return (conf, {"conf": tc, "maxprob": tm, "argmax": ta}) if detail else conf
 
     def ssd_kv_poison_stale(self):

@@ -123,6 +123,8 @@ struct ssd_ctx {
     int tap_row0;      // index of the first valid tap row inside the tap buffer
     int logit_rows;    // rows with valid logits
     int32_t* pinned;   // host-pinned readback buffer
+    int device;        // device that was current when the workspace was set
+    void* static_scratch;  // this device's copy of the library's static scratch array (resolved at set_workspace)
     ssd_stats st;
     bool use_graphs;   // replay captured launch sequences instead of launching kernel by kernel
     std::map<std::string, hipGraphExec_t> graphs;  // nullptr = sequence seen once, not captured yet
@@ -445,6 +447,78 @@ int readback(ssd_ctx* c, const void* dev, size_t bytes, void* host)
     return SSD_OK;
 }
 
+
+// Device buffers one confidence pass works in: hi/lo pairs of the normalised tap rows (16-bit weights), the normalised
+// rows themselves (fp32 weights), their logits, and 3 result values per row; `batch` tap rows go through per pass.
+struct ConfScratch {
+    uint16_t* hi; uint16_t* lo; float* tapn; float* logits; float* res; int batch;
+};
+
+// Confidence (Eq. 1-4) of all 2L tap rows of positions [row_begin, row_begin + n_rows) of the tap buffer, `sc.batch`
+// tap rows at a time; results to the host arrays.  timed: launches of the LM head may be bracketed by profiling events.
+int confidence_rows(ssd_ctx* c, const ConfScratch& sc, int row_begin, int n_rows, float* conf_out, float* tap_conf_out,
+                    float* tap_maxprob_out, int32_t* tap_argmax_out, bool timed)
+{
+    const Dims& D = c->D;
+    const Layout& Y = c->lay;
+    const int R = 2 * D.L;
+    const int saved_kid = c->prof_kid;
+    if (!timed) c->prof_kid = -1;           // (event creation allocates)
+    struct Restore { ssd_ctx* c; int kid; ~Restore() { c->prof_kid = kid; } } restore{c, saved_kid};
+    float hb[3 * 2 * SSD_MAX_LAYERS];
+    for (int r = 0; r < n_rows; r++) {
+        const float* taps_row = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
+        for (int b0 = 0; b0 < R; b0 += sc.batch) {
+            const int nb = R - b0 < sc.batch ? R - b0 : sc.batch;
+            const float* taps = taps_row + (size_t)b0 * D.d;
+            if (rows_fused_supported(D)) {
+                HIPCHK(rows_prep(D, taps, D.d, c->w.final_norm, nb, D.d, D.eps, sc.hi, sc.lo, c->stream), "rows_prep taps");
+                const bool many = rows_many_supported(D, D.V, D.d);
+                for (int b = 0; many && b < nb; b += 64) {   // the LM head is streamed once per 64 tap rows
+                    TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, sc.hi + (size_t)b * D.d, sc.lo + (size_t)b * D.d,
+                                                       D.d, nb - b < 64 ? nb - b : 64, sc.logits + (size_t)b * D.V, D.V, c->stream),
+                          "rows conf lmhead");
+                }
+                for (int b = 0; !many && b < nb; b += 16) {
+                    RowsFused lm = {};
+                    lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = sc.hi + (size_t)b * D.d;
+                    lm.bl = sc.lo + (size_t)b * D.d; lm.ldb = D.d; lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V;
+                    lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
+                    TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows conf lmhead");
+                }
+            } else {
+                HIPCHK(rmsnorm_rows(taps, c->w.final_norm, nb, D.d, D.eps, sc.tapn, c->stream), "rmsnorm taps");
+                for (int b = 0; b < nb; b += 16) {
+                    RowsGemm lm = {};
+                    lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = sc.tapn + (size_t)b * D.d;
+                    lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V; lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
+                    TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm conf lmhead");
+                }
+            }
+            HIPCHK(vocab_reduce(sc.logits, nb, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, nullptr, 1,
+                                reinterpret_cast<int32_t*>(sc.res + 2 * nb), sc.res + nb, sc.res, c->stream), "vocab_reduce conf");
+            float tmp[3 * 64 > 3 * 2 * SSD_MAX_LAYERS ? 3 * 64 : 3 * 2 * SSD_MAX_LAYERS];
+            int rc = readback(c, sc.res, sizeof(float) * 3 * nb, tmp);
+            if (rc) return rc;
+            for (int i = 0; i < nb; i++) {   // regroup as [R] conf, [R] maxprob, [R] argmax
+                hb[b0 + i] = tmp[i]; hb[R + b0 + i] = tmp[nb + i]; hb[2 * R + b0 + i] = tmp[2 * nb + i];
+            }
+        }
+        for (int l = 0; l < D.L; l++) {
+            float ca = hb[l * 2], cb = hb[l * 2 + 1];
+            conf_out[(size_t)r * D.L + l] = c->cfg.conf_taps == 2 ? 0.5f * (ca + cb) : cb;
+            for (int t = 0; t < 2; t++) {
+                size_t o = ((size_t)r * D.L + l) * 2 + t;
+                if (tap_conf_out) tap_conf_out[o] = hb[l * 2 + t];
+                if (tap_maxprob_out) tap_maxprob_out[o] = hb[R + l * 2 + t];
+                if (tap_argmax_out) memcpy(&tap_argmax_out[o], &hb[2 * R + l * 2 + t], 4);
+            }
+        }
+    }
+    c->st.confidence_rows += (int64_t)n_rows * R;
+    return SSD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -462,7 +536,7 @@ int ssd_create(const ssd_config* cfg, void* hip_stream, ssd_ctx** out)
     c->stream = (hipStream_t)hip_stream;
     c->state = ST_CREATED;
     c->ws = nullptr; c->ws_bytes = 0; c->have_w = false;
-    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->tap_row0 = 0; c->logit_rows = 0; c->pinned = nullptr;
+    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->tap_row0 = 0; c->logit_rows = 0; c->pinned = nullptr; c->device = -1; c->static_scratch = nullptr;
     memset(&c->st, 0, sizeof(c->st));
     memset(&c->w, 0, sizeof(c->w));
     c->prof_kid = -1; c->prof_used = 0;
@@ -493,6 +567,8 @@ int ssd_set_workspace(ssd_ctx* c, void* dev, size_t bytes)
             tab[((size_t)p * half + i) * 2 + 1] = (float)std::sin(ang);
         }
     if (!c->pinned) HIPCHK(hipHostMalloc((void**)&c->pinned, 64 * 1024, hipHostMallocDefault), "hipHostMalloc");
+    HIPCHK(hipGetDevice(&c->device), "hipGetDevice");
+    HIPCHK(static_scratch_for_device(c->device, &c->static_scratch), "static scratch address");
     c->ws = static_cast<char*>(dev);
     c->ws_bytes = bytes;
     HIPCHK(hipMemcpyAsync(c->ws + c->lay.rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice, c->stream),
@@ -792,57 +868,43 @@ int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out,
     if (!c || !conf_out || row_begin < 0 || n_rows < 1) return c ? fail(c, SSD_EINVAL, "layer_confidence: bad argument") : SSD_EINVAL;
     if (c->state < ST_IDLE || c->tap_rows == 0) return fail(c, SSD_ESTATE, "no hidden-state taps: call after prefill or verify");
     if (row_begin + n_rows > c->tap_rows) return fail(c, SSD_EINVAL, "layer_confidence: rows out of range");
-    const Dims& D = c->D;
     const Layout& Y = c->lay;
-    const int R = 2 * D.L;
-    float* confd = c->small_f() + SM_CONF;            // [R] conf, [R] maxprob, [R] argmax
     static_assert(SM_CONF + 3 * 2 * SSD_MAX_LAYERS <= SM_VTOK, "confidence results of 2 x SSD_MAX_LAYERS rows must end before the token slots");
-    for (int r = 0; r < n_rows; r++) {
-        const float* taps = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
-        if (rows_fused_supported(D)) {
-            HIPCHK(rows_prep(D, taps, D.d, c->w.final_norm, R, D.d, D.eps, c->h16(Y.hi), c->h16(Y.lo), c->stream), "rows_prep taps");
-            const bool many = rows_many_supported(D, D.V, D.d);
-            for (int b = 0; many && b < R; b += 64) {   // the LM head is streamed once per 64 tap rows
-                TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, c->h16(Y.hi) + (size_t)b * D.d,
-                                                   c->h16(Y.lo) + (size_t)b * D.d, D.d, R - b < 64 ? R - b : 64,
-                                                   c->f(Y.logits) + (size_t)b * D.V, D.V, c->stream), "rows conf lmhead");
-            }
-            for (int b = 0; !many && b < R; b += 16) {
-                RowsFused lm = {};
-                lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = c->h16(Y.hi) + (size_t)b * D.d;
-                lm.bl = c->h16(Y.lo) + (size_t)b * D.d; lm.ldb = D.d; lm.y = c->f(Y.logits) + (size_t)b * D.V; lm.ldy = D.V;
-                lm.M = R - b < 16 ? R - b : 16; lm.mode = 0;
-                TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows conf lmhead");
-            }
-        } else {
-            HIPCHK(rmsnorm_rows(taps, c->w.final_norm, R, D.d, D.eps, c->f(Y.tapn), c->stream), "rmsnorm taps");
-            for (int b = 0; b < R; b += 16) {
-                int M = R - b < 16 ? R - b : 16;
-                RowsGemm lm = {};
-                lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = c->f(Y.tapn) + (size_t)b * D.d;
-                lm.y = c->f(Y.logits) + (size_t)b * D.V; lm.ldy = D.V; lm.M = M; lm.mode = 0;
-                TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm conf lmhead");
-            }
-        }
-        HIPCHK(vocab_reduce(c->f(Y.logits), R, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, nullptr, 1,
-                            reinterpret_cast<int32_t*>(confd + 2 * R), confd + R, confd, c->stream), "vocab_reduce conf");
-        std::vector<float> hb(3 * R);
-        int rc = readback(c, confd, sizeof(float) * 3 * R, hb.data());
-        if (rc) return rc;
-        for (int l = 0; l < D.L; l++) {
-            float ca = hb[l * 2], cb = hb[l * 2 + 1];
-            conf_out[(size_t)r * D.L + l] = c->cfg.conf_taps == 2 ? 0.5f * (ca + cb) : cb;
-            for (int t = 0; t < 2; t++) {
-                size_t o = ((size_t)r * D.L + l) * 2 + t;
-                if (tap_conf_out) tap_conf_out[o] = hb[l * 2 + t];
-                if (tap_maxprob_out) tap_maxprob_out[o] = hb[R + l * 2 + t];
-                if (tap_argmax_out) memcpy(&tap_argmax_out[o], &hb[2 * R + l * 2 + t], 4);
-            }
-        }
-    }
+    ConfScratch sc;
+    sc.hi = c->h16(Y.hi); sc.lo = c->h16(Y.lo); sc.tapn = c->f(Y.tapn); sc.logits = c->f(Y.logits);
+    sc.res = c->small_f() + SM_CONF; sc.batch = 2 * c->D.L;     // all tap rows of a position in one pass
+    int rc = confidence_rows(c, sc, row_begin, n_rows, conf_out, tap_conf_out, tap_maxprob_out, tap_argmax_out, true);
+    if (rc) return rc;
     c->logit_rows = 0;  // the logits buffer was reused
-    c->st.confidence_rows += (int64_t)n_rows * R;
     return SSD_OK;
+}
+
+int ssd_layer_confidence_static(ssd_ctx* c, int row_begin, int n_rows, float* conf_out, float* tap_conf_out,
+                                float* tap_maxprob_out, int32_t* tap_argmax_out)
+{
+    if (!c || !conf_out || row_begin < 0 || n_rows < 1)
+        return c ? fail(c, SSD_EINVAL, "layer_confidence_static: bad argument") : SSD_EINVAL;
+    if (c->state < ST_IDLE || c->tap_rows == 0) return fail(c, SSD_ESTATE, "no hidden-state taps: call after prefill or verify");
+    if (row_begin + n_rows > c->tap_rows) return fail(c, SSD_EINVAL, "layer_confidence_static: rows out of range");
+    if (!c->static_scratch) return fail(c, SSD_ESTATE, "the device's static scratch was not resolved (set_workspace failed?)");
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev), "hipGetDevice");
+    if (dev != c->device) return fail(c, SSD_EINVAL, "layer_confidence_static: the context's device is not current");
+    // carve the device's static array: hi, lo, normalised rows (fp32 path), logits, results for one batch of rows
+    const Dims& D = c->D;
+    const int R = 2 * D.L, B = R < 64 ? R : 64;
+    size_t o = 0;
+    ConfScratch sc;
+    char* base = static_cast<char*>(c->static_scratch);
+    sc.hi = reinterpret_cast<uint16_t*>(base + o);   o += align_up((size_t)B * D.d * 2);
+    sc.lo = reinterpret_cast<uint16_t*>(base + o);   o += align_up((size_t)B * D.d * 2);
+    sc.tapn = reinterpret_cast<float*>(base + o);    o += align_up(rows_fused_supported(D) ? 0 : (size_t)B * D.d * 4);
+    sc.logits = reinterpret_cast<float*>(base + o);  o += align_up((size_t)B * D.V * 4);
+    sc.res = reinterpret_cast<float*>(base + o);     o += align_up((size_t)3 * B * 4);
+    sc.batch = B;
+    if (o > static_scratch_bytes())
+        return fail(c, SSD_ECAPACITY, "layer_confidence_static: 64 rows of this vocabulary / width exceed SSD_STATIC_SCRATCH_BYTES");
+    return confidence_rows(c, sc, row_begin, n_rows, conf_out, tap_conf_out, tap_maxprob_out, tap_argmax_out, false);
 }
 
 int ssd_set_graphs(ssd_ctx* c, int enable)

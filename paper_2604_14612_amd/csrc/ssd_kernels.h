@@ -168,6 +168,13 @@ hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float ep
                         int tok_stride, int32_t* argmax_out, float* maxprob_out, float* conf_out,
                         hipStream_t s);
 
+// ---- static scratch -----------------------------------------------------------------------------------
+// A fixed-size device array inside the library image, for the one entry point that must not allocate.  Every
+// device holds its own copy at its own address: static_scratch_for_device resolves it once per device (that device
+// must be current) and returns the cached device pointer afterwards.  Contents persist from call to call.
+size_t static_scratch_bytes();
+hipError_t static_scratch_for_device(int device, void** ptr_out);
+
 // ---- small state kernels ---------------------------------------------------------------------------
 // tok0 = token, *pos_dev = pos
 hipError_t set_state(int32_t* tok0, int32_t token, int* pos_dev, int pos, hipStream_t s);

@@ -17,6 +17,7 @@
 #include <math.h>
 
 #include <atomic>
+#include <mutex>
 
 namespace ssdk {
 
@@ -2697,6 +2698,38 @@ hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float ep
     hipLaunchKernelGGL(vocab_reduce_kernel, dim3(M), dim3(VR_THREADS), 0, s, logits, V, clamp, eps, tok_out, tok_stride,
                        argmax_out, maxprob_out, conf_out);
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// static scratch (for the entry point that allocates nothing)
+// ---------------------------------------------------------------------------------------------
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)12 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+size_t static_scratch_bytes() { return STATIC_SCRATCH_BYTES; }
+
+// `scratch` names the array only in device code; in host code the name is a stand-in, not an address.  The device
+// address is asked of the runtime once per device, with that device current, and kept.
+hipError_t static_scratch_for_device(int device, void** ptr_out)
+{
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void* ptr[MAX_DEV] = {};
+    if (!ptr_out || device < 0 || device >= MAX_DEV) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return e;
+        if (cur != device) return hipErrorInvalidDevice;
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[device] = p;
+    }
+    *ptr_out = ptr[device];
+    return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------------------------
