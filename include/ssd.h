@@ -46,6 +46,7 @@ enum {
 
 #define SSD_MAX_K 15        /* largest draft length: k + 1 rows fill one 16-column MFMA tile */
 #define SSD_MAX_LAYERS 128  /* deepest model a context accepts (fixed-size per-layer result slots in the workspace) */
+#define SSD_MAX_WINDOW 4096 /* largest context window of the confidence extraction (positions kept on the device) */
 #define SSD_PREFILL_ROWS 64 /* most prompt rows processed per pass of the weights (16 where a shape does not fit the
                                64-row tiling: widths not multiples of 128, fp32 weights) */
 
@@ -66,6 +67,9 @@ typedef struct {
     int32_t max_k;        /* largest k that draft_step / verify will be called with (1..SSD_MAX_K) */
     int32_t kv_dtype;     /* 0 = fp32, 1 = bf16, 2 = fp16: element type of the KV cache (K after the rotary embedding and V
                              are rounded to it, nearest-even, when stored); independent of weight_dtype */
+    int32_t conf_window;  /* context window of the confidence extraction (100 tokens, Section 4.1.1): the workspace keeps the
+                             hidden-state taps of the last conf_window processed positions for ssd_window_confidence;
+                             0 = none kept (0..SSD_MAX_WINDOW) */
 } ssd_config;
 
 /* Device pointers to the weights.  The per-layer members are HOST arrays of n_layers DEVICE
@@ -192,6 +196,17 @@ SSD_API int ssd_copy_logits(ssd_ctx *ctx, int row_begin, int n_rows, float *logi
  *   tap_maxprob_out, tap_argmax_out  host [n_rows][n_layers][2] or NULL */
 SSD_API int ssd_layer_confidence(ssd_ctx *ctx, int row_begin, int n_rows, float *conf_out,
                          float *tap_conf_out, float *tap_maxprob_out, int32_t *tap_argmax_out);
+
+/* Confidence over the context window (Section 4.1.1, "context window" of 100 tokens; Appendix D): Eq. 1-4 on every
+ * tapped hidden state of each of the last conf_window positions that the full model processed with a committed input
+ * token -- the last prompt position, then rows 0..a of every verification (ssd_accept / ssd_force_commit put them into
+ * a ring in the workspace; vanilla ssd_decode steps capture no taps and leave the window as it is) -- averaged over
+ * those positions.  All window rows go through the LM head in 64-row MFMA passes and one reduction; one read-back.
+ *   conf_out      host [n_layers]: mean over the window of the layer's confidence (mean of its conf_taps taps)
+ *   tap_conf_out  host [n_layers][2] or NULL: window means of the post-attention and post-MLP confidence
+ *   n_positions_out  host or NULL: positions in the window (<= conf_window)
+ * SSD_ESTATE if conf_window is 0, no sequence is prefilled or a draft is in flight. */
+SSD_API int ssd_window_confidence(ssd_ctx *ctx, float *conf_out, float *tap_conf_out, int32_t *n_positions_out);
 
 /* For callers that cannot allocate device memory while they run (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc): the same computation and results as ssd_layer_confidence, but every device

@@ -11,6 +11,7 @@ State convention: committed tokens t_0..t_{n-1}; the cache holds verified K/V fo
 """
 from __future__ import annotations
 
+from collections import deque
 from typing import Callable, List, Optional, Sequence
 
 import numpy as np
@@ -19,8 +20,12 @@ from .decoder import OracleModel, argmax_lowest, DEFAULT_CLAMP, DEFAULT_EPS
 
 
 class OracleSSD:
-    def __init__(self, model: OracleModel):
+    def __init__(self, model: OracleModel, window: int = 100):
         self.m = model
+        # context window of the confidence extraction (Section 4.1.1: 100 tokens): hidden-state taps [L][2][d] of the
+        # last `window` positions that the full model has processed with a committed input token -- the last prompt
+        # position and every verified row whose token was kept
+        self.window_taps = deque(maxlen=int(window))
         self.tokens: List[int] = []
         self.last_taps: Optional[np.ndarray] = None    # [rows][L][2][d] of the last verify / prefill
         self.last_logits: Optional[np.ndarray] = None
@@ -45,6 +50,8 @@ class OracleSSD:
         self.tokens = prompt + [first]
         self.last_taps = out["taps"][-1:]
         self.last_logits = out["logits"][-1:]
+        self.window_taps.clear()
+        self.window_taps.append(self.last_taps[0])
         return first
 
     def decode(self) -> int:
@@ -110,6 +117,10 @@ class OracleSSD:
             a += 1
         self.tokens.extend(int(t) for t in draft[:a])
         self.tokens.append(int(target[a]))
+        # verify rows 0..a were fed committed tokens (the pending one and the accepted drafts): they enter the window
+        if self.last_taps is not None and len(self.last_taps) == k + 1:
+            for j in range(a + 1):
+                self.window_taps.append(self.last_taps[j])
         self.drafted += k
         self.accepted += a
         self.cycles += 1
@@ -132,6 +143,19 @@ class OracleSSD:
         per = {k_: v.reshape(L, 2) for k_, v in r.items()}
         conf = (c[:, 0] + c[:, 1]) / 2.0 if taps == 2 else c[:, 1].copy()
         return conf, per
+
+
+    def window_confidence(self, clamp=DEFAULT_CLAMP, eps=DEFAULT_EPS, taps: int = 2):
+        """Per-layer confidence over the context window (Section 4.1.1): Eq. 1-4 on every tapped hidden state of
+        every position in the window, averaged over the positions; a layer's value is the mean of its two taps
+        (taps=2) or its post-MLP tap (taps=1).  Returns (conf[L], per-tap means [L][2], positions in the window)."""
+        n = len(self.window_taps)
+        t = np.stack(list(self.window_taps))           # [n][L][2][d]
+        L = t.shape[1]
+        c = self.m.confidence(t.reshape(n * L * 2, -1), clamp=clamp, eps=eps)["conf"].reshape(n, L, 2)
+        per_tap = c.mean(axis=0)
+        conf = (per_tap[:, 0] + per_tap[:, 1]) / 2.0 if taps == 2 else per_tap[:, 1].copy()
+        return conf, per_tap, n
 
 
 def generate_vanilla(model: OracleModel, prompt: Sequence[int], n_new: int) -> List[int]:

@@ -35,7 +35,8 @@ class ssd_config(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
                 ("vocab", C.c_int32), ("max_seq", C.c_int32), ("rms_eps", C.c_float),
                 ("rope_base", C.c_float), ("weight_dtype", C.c_int32), ("conf_taps", C.c_int32),
-                ("conf_clamp", C.c_float), ("conf_eps", C.c_float), ("max_k", C.c_int32), ("kv_dtype", C.c_int32)]
+                ("conf_clamp", C.c_float), ("conf_eps", C.c_float), ("max_k", C.c_int32), ("kv_dtype", C.c_int32),
+                ("conf_window", C.c_int32)]
 
 
 class ssd_weights(C.Structure):
@@ -85,6 +86,7 @@ SYMBOLS = {
     "ssd_copy_logits": (C.c_int, [_P, C.c_int, C.c_int, _P]),
     "ssd_layer_confidence": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, _P, _P]),
     "ssd_layer_confidence_static": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, _P, _P]),
+    "ssd_window_confidence": (C.c_int, [_P, _P, _P, _P]),
     "ssd_select_defaults": (None, [C.POINTER(ssd_select_params)]),
     "ssd_select_skip": (C.c_int, [_P, C.c_int, C.POINTER(ssd_select_params), _P, _P, _P]),
     "ssd_uniform_skip": (C.c_int, [C.c_int, C.POINTER(ssd_select_params), _P]),
@@ -270,11 +272,11 @@ def default_kv_dtype(shape) -> str:
 
 
 def make_config(shape, max_seq: int, max_k: int = 8, conf_taps: int = 2, conf_clamp: float = 1e4,
-                conf_eps: float = 1e-10, kv_dtype: Optional[str] = None) -> ssd_config:
+                conf_eps: float = 1e-10, kv_dtype: Optional[str] = None, conf_window: int = 0) -> ssd_config:
     return ssd_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                       shape.d_ffn, shape.vocab, int(max_seq), shape.rms_eps, shape.rope_base,
                       _DTYPE_CODE[shape.dtype], conf_taps, conf_clamp, conf_eps, max_k,
-                      _DTYPE_CODE[kv_dtype or default_kv_dtype(shape)])
+                      _DTYPE_CODE[kv_dtype or default_kv_dtype(shape)], int(conf_window))
 
 
 class Context:
@@ -411,6 +413,15 @@ class Context:
         fn = self._l.ssd_layer_confidence_static if static else self._l.ssd_layer_confidence
         self._check(fn(self._h, int(row_begin), int(n_rows), _np_ptr(conf), _np_ptr(tc), _np_ptr(tm), _np_ptr(ta)))
         return (conf, {"conf": tc, "maxprob": tm, "argmax": ta}) if detail else conf
+
+    def ssd_window_confidence(self, detail: bool = False):
+        """-> conf[L] over the context window (and, with detail, per-tap means [L][2] and the positions in the window)."""
+        L = self.shape.n_layers
+        conf = np.empty(L, np.float32)
+        tc = np.empty((L, 2), np.float32) if detail else None
+        n = C.c_int32()
+        self._check(self._l.ssd_window_confidence(self._h, _np_ptr(conf), _np_ptr(tc), C.addressof(n)))
+        return (conf, tc, n.value) if detail else conf
 
     def ssd_kv_poison_stale(self):
         self._check(self._l.ssd_kv_poison_stale(self._h))

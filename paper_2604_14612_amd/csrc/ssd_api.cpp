@@ -23,7 +23,7 @@ constexpr size_t ALIGN = 256;
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
-    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, ssq, small, total;
+    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, ssq, small, ring, ring_conf, total;
     int rows;       // activation rows: max(max_k + 1, prompt rows per pass)
     int prefill_rows;  // prompt rows per pass: SSD_PREFILL_ROWS where the shape fits the wide tiling, else 16
     int conf_rows;  // rows of one confidence pass: 2 * L
@@ -46,6 +46,7 @@ bool valid_cfg(const ssd_config* c)
     if (c->kv_dtype < 0 || c->kv_dtype > 2) return false;
     if (c->conf_taps != 1 && c->conf_taps != 2) return false;
     if (c->max_k < 1 || c->max_k > SSD_MAX_K) return false;
+    if (c->conf_window < 0 || c->conf_window > SSD_MAX_WINDOW) return false;
     if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f) || !(c->conf_clamp > 0.f) || !(c->conf_eps >= 0.f)) return false;
     return true;
 }
@@ -92,6 +93,10 @@ Layout make_layout(const ssd_config& c)
     }
     l.ssq = o;    o += align_up((size_t)l.rows * (D.d / 16 + 1) * sizeof(float));  // per-tile sums of squares of the residual rows
     l.small = o;  o += align_up(4096);
+    // context window of the confidence extraction: hidden-state taps [window][2L][d] of the last `window` processed
+    // positions, and one confidence value per tap row of the window
+    l.ring = o;       o += align_up((size_t)c.conf_window * 2 * D.L * D.d * sizeof(float));
+    l.ring_conf = o;  o += align_up(((size_t)c.conf_window * 2 * D.L + 2 * D.L) * sizeof(float));
     l.total = o;
     return l;
 }
@@ -120,6 +125,7 @@ struct ssd_ctx {
     int n;             // committed tokens
     int k_pending;     // k of the draft awaiting verification / acceptance
     int tap_rows;      // rows with valid taps (0 = none)
+    long ring_count;   // positions pushed into the context-window ring since the last prefill
     int tap_row0;      // index of the first valid tap row inside the tap buffer
     int logit_rows;    // rows with valid logits
     int32_t* pinned;   // host-pinned readback buffer
@@ -454,6 +460,41 @@ struct ConfScratch {
     uint16_t* hi; uint16_t* lo; float* tapn; float* logits; float* res; int batch;
 };
 
+// Enqueues the confidence (Eq. 1-4) of nb tap rows [nb][d] (nb <= sc.batch): final norm, LM head, vocabulary
+// reduction; one value per row to conf_dev, and to maxprob_dev / argmax_dev when given (device pointers).
+int conf_batch(ssd_ctx* c, const ConfScratch& sc, const float* taps, int nb, float* conf_dev, float* maxprob_dev,
+               int32_t* argmax_dev)
+{
+    const Dims& D = c->D;
+    if (rows_fused_supported(D)) {
+        HIPCHK(rows_prep(D, taps, D.d, c->w.final_norm, nb, D.d, D.eps, sc.hi, sc.lo, c->stream), "rows_prep taps");
+        const bool many = rows_many_supported(D, D.V, D.d);
+        for (int b = 0; many && b < nb; b += 64) {   // the LM head is streamed once per 64 tap rows
+            TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, sc.hi + (size_t)b * D.d, sc.lo + (size_t)b * D.d,
+                                               D.d, nb - b < 64 ? nb - b : 64, sc.logits + (size_t)b * D.V, D.V, c->stream),
+                  "rows conf lmhead");
+        }
+        for (int b = 0; !many && b < nb; b += 16) {
+            RowsFused lm = {};
+            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = sc.hi + (size_t)b * D.d;
+            lm.bl = sc.lo + (size_t)b * D.d; lm.ldb = D.d; lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V;
+            lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
+            TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows conf lmhead");
+        }
+    } else {
+        HIPCHK(rmsnorm_rows(taps, c->w.final_norm, nb, D.d, D.eps, sc.tapn, c->stream), "rmsnorm taps");
+        for (int b = 0; b < nb; b += 16) {
+            RowsGemm lm = {};
+            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = sc.tapn + (size_t)b * D.d;
+            lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V; lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
+            TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm conf lmhead");
+        }
+    }
+    HIPCHK(vocab_reduce(sc.logits, nb, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, nullptr, 1, argmax_dev, maxprob_dev, conf_dev,
+                        c->stream), "vocab_reduce conf");
+    return SSD_OK;
+}
+
 // Confidence (Eq. 1-4) of all 2L tap rows of positions [row_begin, row_begin + n_rows) of the tap buffer, `sc.batch`
 // tap rows at a time; results to the host arrays.  timed: launches of the LM head may be bracketed by profiling events.
 int confidence_rows(ssd_ctx* c, const ConfScratch& sc, int row_begin, int n_rows, float* conf_out, float* tap_conf_out,
@@ -470,35 +511,11 @@ int confidence_rows(ssd_ctx* c, const ConfScratch& sc, int row_begin, int n_rows
         const float* taps_row = c->f(Y.taps) + (size_t)(c->tap_row0 + row_begin + r) * R * D.d;  // [L][2][d]
         for (int b0 = 0; b0 < R; b0 += sc.batch) {
             const int nb = R - b0 < sc.batch ? R - b0 : sc.batch;
-            const float* taps = taps_row + (size_t)b0 * D.d;
-            if (rows_fused_supported(D)) {
-                HIPCHK(rows_prep(D, taps, D.d, c->w.final_norm, nb, D.d, D.eps, sc.hi, sc.lo, c->stream), "rows_prep taps");
-                const bool many = rows_many_supported(D, D.V, D.d);
-                for (int b = 0; many && b < nb; b += 64) {   // the LM head is streamed once per 64 tap rows
-                    TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, sc.hi + (size_t)b * D.d, sc.lo + (size_t)b * D.d,
-                                                       D.d, nb - b < 64 ? nb - b : 64, sc.logits + (size_t)b * D.V, D.V, c->stream),
-                          "rows conf lmhead");
-                }
-                for (int b = 0; !many && b < nb; b += 16) {
-                    RowsFused lm = {};
-                    lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = sc.hi + (size_t)b * D.d;
-                    lm.bl = sc.lo + (size_t)b * D.d; lm.ldb = D.d; lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V;
-                    lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
-                    TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows conf lmhead");
-                }
-            } else {
-                HIPCHK(rmsnorm_rows(taps, c->w.final_norm, nb, D.d, D.eps, sc.tapn, c->stream), "rmsnorm taps");
-                for (int b = 0; b < nb; b += 16) {
-                    RowsGemm lm = {};
-                    lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.x = sc.tapn + (size_t)b * D.d;
-                    lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V; lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
-                    TIMED(SSD_K_ROWS_LMHEAD, gemm_rows(D, lm, c->stream), "gemm conf lmhead");
-                }
-            }
-            HIPCHK(vocab_reduce(sc.logits, nb, D.V, c->cfg.conf_clamp, c->cfg.conf_eps, nullptr, 1,
-                                reinterpret_cast<int32_t*>(sc.res + 2 * nb), sc.res + nb, sc.res, c->stream), "vocab_reduce conf");
+            int rc = conf_batch(c, sc, taps_row + (size_t)b0 * D.d, nb, sc.res, sc.res + nb,
+                                reinterpret_cast<int32_t*>(sc.res + 2 * nb));
+            if (rc) return rc;
             float tmp[3 * 64 > 3 * 2 * SSD_MAX_LAYERS ? 3 * 64 : 3 * 2 * SSD_MAX_LAYERS];
-            int rc = readback(c, sc.res, sizeof(float) * 3 * nb, tmp);
+            rc = readback(c, sc.res, sizeof(float) * 3 * nb, tmp);
             if (rc) return rc;
             for (int i = 0; i < nb; i++) {   // regroup as [R] conf, [R] maxprob, [R] argmax
                 hb[b0 + i] = tmp[i]; hb[R + b0 + i] = tmp[nb + i]; hb[2 * R + b0 + i] = tmp[2 * nb + i];
@@ -519,6 +536,24 @@ int confidence_rows(ssd_ctx* c, const ConfScratch& sc, int row_begin, int n_rows
     return SSD_OK;
 }
 
+// Context window (Section 4.1.1): the taps of tap-buffer rows [first, first + n) -- positions the full model has just
+// processed with committed input tokens -- enter the device ring of the last conf_window positions.
+int ring_push(ssd_ctx* c, int first, int n)
+{
+    const int Wn = c->cfg.conf_window;
+    if (Wn == 0 || n <= 0) return SSD_OK;
+    const size_t row = (size_t)2 * c->D.L * c->D.d;     // floats per position
+    if (n > Wn) { first += n - Wn; c->ring_count += n - Wn; n = Wn; }   // only the last Wn positions can survive
+    while (n > 0) {
+        const int slot = (int)(c->ring_count % Wn);
+        const int run = n < Wn - slot ? n : Wn - slot;  // contiguous slots up to the end of the ring
+        HIPCHK(copy_f32(c->f(c->lay.taps) + (size_t)(c->tap_row0 + first) * row, c->f(c->lay.ring) + (size_t)slot * row,
+                        (size_t)run * row, c->stream), "ring push");
+        c->ring_count += run; first += run; n -= run;
+    }
+    return SSD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -536,7 +571,7 @@ int ssd_create(const ssd_config* cfg, void* hip_stream, ssd_ctx** out)
     c->stream = (hipStream_t)hip_stream;
     c->state = ST_CREATED;
     c->ws = nullptr; c->ws_bytes = 0; c->have_w = false;
-    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->tap_row0 = 0; c->logit_rows = 0; c->pinned = nullptr; c->device = -1; c->static_scratch = nullptr;
+    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->tap_row0 = 0; c->logit_rows = 0; c->ring_count = 0; c->pinned = nullptr; c->device = -1; c->static_scratch = nullptr;
     memset(&c->st, 0, sizeof(c->st));
     memset(&c->w, 0, sizeof(c->w));
     c->prof_kid = -1; c->prof_used = 0;
@@ -613,7 +648,7 @@ int ssd_reset(ssd_ctx* c)
     if (!c) return SSD_EINVAL;
     if (c->state == ST_CREATED) return fail(c, SSD_ESTATE, "nothing to reset");
     c->state = ST_READY;
-    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->logit_rows = 0;
+    c->n = 0; c->k_pending = 0; c->tap_rows = 0; c->logit_rows = 0; c->ring_count = 0;
     memset(&c->st, 0, sizeof(c->st));
     return SSD_OK;
 }
@@ -668,6 +703,9 @@ int ssd_prefill(ssd_ctx* c, const int32_t* tokens, int n, int32_t* first_token_o
     c->state = ST_IDLE;
     c->tap_rows = 1; c->tap_row0 = last_M - 1;
     c->logit_rows = 1;
+    c->ring_count = 0;
+    rc = ring_push(c, 0, 1);    // the last prompt position opens the context window
+    if (rc) return rc;
     // logits of the last row sit at row last_M-1; move them to row 0 so ssd_copy_logits sees one row
     if (last_M > 1) {
         HIPCHK(copy_f32(c->f(c->lay.logits) + (size_t)(last_M - 1) * c->D.V, c->f(c->lay.logits), c->D.V, c->stream),
@@ -827,6 +865,10 @@ int ssd_accept(ssd_ctx* c, const int32_t* draft, const int32_t* target, int k, i
     while (res[0] < k && draft[res[0]] == target[res[0]]) res[0]++;
     res[1] = target[res[0]];
     HIPCHK(set_state(c->small_i() + SM_TOK, res[1], c->pos_dev(), c->n - 1 + res[0] + 1, c->stream), "accept state update");
+    {   // verify rows 0..a were fed committed tokens: their taps enter the context window
+        int rc = ring_push(c, 0, res[0] + 1);
+        if (rc) return rc;
+    }
     *n_accepted_out = res[0];
     *next_token_out = res[1];
     c->n += res[0] + 1;
@@ -843,6 +885,10 @@ int ssd_force_commit(ssd_ctx* c, const int32_t* draft, int k, int n_accepted, in
     if (k != c->k_pending || n_accepted < 0 || n_accepted > k || next_token < 0 || next_token >= c->D.V)
         return fail(c, SSD_EINVAL, "force_commit: bad argument");
     HIPCHK(set_state(c->small_i() + SM_TOK, next_token, c->pos_dev(), c->n - 1 + n_accepted + 1, c->stream), "set_state");
+    {
+        int rc = ring_push(c, 0, n_accepted + 1);
+        if (rc) return rc;
+    }
     HIPCHK(hipStreamSynchronize(c->stream), "sync");
     c->n += n_accepted + 1;
     c->state = ST_IDLE;
@@ -905,6 +951,44 @@ int ssd_layer_confidence_static(ssd_ctx* c, int row_begin, int n_rows, float* co
     if (o > static_scratch_bytes())
         return fail(c, SSD_ECAPACITY, "layer_confidence_static: 64 rows of this vocabulary / width exceed SSD_STATIC_SCRATCH_BYTES");
     return confidence_rows(c, sc, row_begin, n_rows, conf_out, tap_conf_out, tap_maxprob_out, tap_argmax_out, false);
+}
+
+int ssd_window_confidence(ssd_ctx* c, float* conf_out, float* tap_conf_out, int32_t* n_positions_out)
+{
+    if (!c || !conf_out) return c ? fail(c, SSD_EINVAL, "window_confidence: bad argument") : SSD_EINVAL;
+    if (c->cfg.conf_window == 0) return fail(c, SSD_ESTATE, "window_confidence: the context was created with conf_window = 0");
+    if (c->state != ST_IDLE || c->ring_count == 0) return fail(c, SSD_ESTATE, "window_confidence needs an idle prefilled sequence");
+    const Dims& D = c->D;
+    const Layout& Y = c->lay;
+    const int R = 2 * D.L;
+    const int nv = c->ring_count < c->cfg.conf_window ? (int)c->ring_count : c->cfg.conf_window;   // valid slots 0..nv-1
+    const long rows = (long)nv * R;
+    ConfScratch sc;
+    sc.hi = c->h16(Y.hi); sc.lo = c->h16(Y.lo); sc.tapn = c->f(Y.tapn); sc.logits = c->f(Y.logits); sc.res = nullptr;
+    // rows per pass of the LM head: what the staging buffers were sized for (at least the 2L rows of one position)
+    int B = 64;
+    if (B > Y.logit_rows) B = Y.logit_rows;
+    if (B > Y.conf_rows && B > Y.rows) B = Y.conf_rows > Y.rows ? Y.conf_rows : Y.rows;
+    sc.batch = B;
+    float* conf_all = c->f(Y.ring_conf);                  // [nv * R], then R means
+    for (long r0 = 0; r0 < rows; r0 += B) {
+        const int nb = rows - r0 < B ? (int)(rows - r0) : B;
+        int rc = conf_batch(c, sc, c->f(Y.ring) + (size_t)r0 * D.d, nb, conf_all + r0, nullptr, nullptr);
+        if (rc) return rc;
+    }
+    float* means = conf_all + (size_t)c->cfg.conf_window * R;
+    HIPCHK(window_mean(conf_all, nv, R, means, c->stream), "window mean");
+    float hb[2 * SSD_MAX_LAYERS];
+    int rc = readback(c, means, sizeof(float) * R, hb);
+    if (rc) return rc;
+    for (int l = 0; l < D.L; l++) {
+        conf_out[l] = c->cfg.conf_taps == 2 ? 0.5f * (hb[2 * l] + hb[2 * l + 1]) : hb[2 * l + 1];
+        if (tap_conf_out) { tap_conf_out[2 * l] = hb[2 * l]; tap_conf_out[2 * l + 1] = hb[2 * l + 1]; }
+    }
+    if (n_positions_out) *n_positions_out = nv;
+    c->logit_rows = 0;  // the logits buffer was reused
+    c->st.confidence_rows += rows;
+    return SSD_OK;
 }
 
 int ssd_set_graphs(ssd_ctx* c, int enable)

@@ -168,6 +168,9 @@ hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float ep
                         int tok_stride, int32_t* argmax_out, float* maxprob_out, float* conf_out,
                         hipStream_t s);
 
+// means[t] = mean over positions p < n_pos of v[p * n_taps + t] (context-window average of per-row confidences)
+hipError_t window_mean(const float* v, int n_pos, int n_taps, float* means, hipStream_t s);
+
 // ---- static scratch -----------------------------------------------------------------------------------
 // A fixed-size device array inside the library image, for the one entry point that must not allocate.  Every
 // device holds its own copy at its own address: static_scratch_for_device resolves it once per device (that device

@@ -2692,6 +2692,22 @@ __global__ __launch_bounds__(VR_THREADS) void vocab_reduce_kernel(const float* _
     }
 }
 
+// means[t] = mean over p < n_pos of v[p * n_taps + t], summed in position order (one thread per tap row)
+__global__ void window_mean_kernel(const float* __restrict__ v, int n_pos, int n_taps, float* __restrict__ means)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_taps) return;
+    float s = 0.f;
+    for (int p = 0; p < n_pos; p++) s += v[(size_t)p * n_taps + t];
+    means[t] = s / (float)n_pos;
+}
+hipError_t window_mean(const float* v, int n_pos, int n_taps, float* means, hipStream_t s)
+{
+    if (n_pos < 1 || n_taps < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(window_mean_kernel, dim3(ceil_div(n_taps, 64)), dim3(64), 0, s, v, n_pos, n_taps, means);
+    return hipGetLastError();
+}
+
 hipError_t vocab_reduce(const float* logits, int M, int V, float clamp, float eps, int32_t* tok_out, int tok_stride,
                         int32_t* argmax_out, float* maxprob_out, float* conf_out, hipStream_t s)
 {

@@ -84,7 +84,7 @@ def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None):
     sub-tolerance disagreement is counted as unpinned and the library is re-synchronised to the
     oracle with ssd_force_commit.  Returns a dict of counters.
     """
-    o = OracleSSD(orc_model)
+    o = OracleSSD(orc_model, window=max(1, int(ctx.cfg.conf_window)) if ctx.cfg.conf_window else 100)
     first_o = o.prefill(prompt)
     first_g = ctx.ssd_prefill(prompt)
     stats = {"cycles": 0, "unpinned_cycles": 0, "draft_rows": 0, "verify_rows": 0, "max_err": 0.0,

@@ -138,6 +138,44 @@ def test_sub_block_skip_masks(ssd, name):
     assert d1 == d2 and np.array_equal(z1, ctx.ssd_copy_logits(0, 4))
 
 
+@pytest.mark.parametrize("name,W", [("tiny", 7), ("tiny", 100), ("mini", 7), ("gqa", 100), ("gqa16", 5)])
+def test_window_confidence(ssd, name, W):
+    """ssd_window_confidence: the device ring of the last W processed positions (last prompt position, then rows 0..a
+    of every verification) against the oracle's window, after cycles with different accepted counts, incl. wrap-around."""
+    shape = SHAPES[name]
+    from oracle import OracleModel
+    import paper_2604_14612_amd as lib
+    w = make_weights(shape, 13, norm_gain_std=0.1)
+    ctx = lib.Context(shape, to_gpu(w), 160, 8, conf_window=W)
+    orc = OracleModel(shape, w, 160, kv_storage="exact" if ctx.kv_dtype == "fp32" else ctx.kv_dtype)
+    prompt = make_prompt(shape.vocab, 19, 6).tolist()
+    seen = []
+    osd = {}
+
+    def check(o, c, cycle, a):
+        osd["o"] = o
+        if cycle in (0, 2, 5):
+            conf_o, tap_o, n_o = o.window_confidence()
+            conf_g, tap_g, n_g = c.ssd_window_confidence(detail=True)
+            assert n_g == n_o
+            np.testing.assert_allclose(conf_g, conf_o, atol=CONF_TOL[shape.dtype])
+            np.testing.assert_allclose(tap_g, tap_o, atol=CONF_TOL[shape.dtype])
+            seen.append(n_o)
+        return [np.zeros(shape.n_layers, np.uint8), np.array(MASKS[name][1], np.uint8)][cycle % 2]
+
+    st = lockstep_ssd(ctx, orc, prompt, 0, [4, 3, 8, 1, 4, 2], np.zeros(shape.n_layers, np.uint8), shape.dtype,
+                      next_mask=check)
+    print("window", name, W, "positions at the checks", seen, "accepted", st["accepted"])
+    assert len(seen) == 3 and seen[-1] == min(W, 1 + sum(a + 1 for a in st["accepted"]))
+    assert len(set(st["accepted"])) > 1
+    # a context without a window refuses
+    ctx0 = lib.Context(shape, to_gpu(w), 64, 4)
+    ctx0.ssd_prefill(prompt)
+    with pytest.raises(lib.SsdError) as e:
+        ctx0.ssd_window_confidence()
+    assert e.value.code == lib.SSD_ESTATE
+
+
 def test_tiny_workload_end_to_end_matches_oracle_tokens(ssd):
     """BASELINE config 1: 32-token prompt, 32 new tokens, k = 4, skip set from confidence over all 4 layers."""
     wl = WORKLOADS["tiny"]

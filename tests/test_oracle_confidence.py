@@ -126,3 +126,34 @@ def test_taps_of_a_skipped_layer_equal_its_input():
     t = out["taps"]
     assert np.array_equal(t[:, 1, 0], t[:, 0, 1]) and np.array_equal(t[:, 1, 1], t[:, 0, 1])
     assert not np.array_equal(t[:, 2, 0], t[:, 1, 1])
+
+
+def test_window_confidence_is_the_mean_over_the_last_committed_positions():
+    """Context window (Section 4.1.1): the windowed confidence equals the mean of per-position confidences
+    recomputed by brute force -- a full-sequence recompute of the committed tokens with the library-op
+    reference, scipy's softmax for Eq. 1-4 -- over the last W processed positions (from the last prompt position
+    on), whatever mix of accepted and rejected drafts produced them."""
+    from tests._reference import reference_confidence, reference_forward
+    wl = WORKLOADS["tiny"]
+    shape = wl.shape
+    w = make_weights(shape, wl.seed)
+    prompt = make_prompt(shape.vocab, 9, 3).tolist()
+    P = len(prompt)
+    for W in (5, 100):
+        s = OracleSSD(OracleModel(shape, w, 96), window=W)
+        s.prefill(prompt)
+        accepted = []
+        for mask in ([0, 0, 0, 0], [0, 1, 0, 0], [0, 0, 0, 0], [0, 1, 1, 0], [0, 0, 0, 0]):
+            d = s.draft(np.array(mask, np.uint8), 3)
+            accepted.append(s.accept(d, s.verify(d))[0])
+        assert len(set(accepted)) > 1                       # both full and partial acceptance occurred
+        conf, per_tap, n = s.window_confidence()
+        # positions processed with a committed input: P-1 (last prompt token) .. n-2 (the pending token is not yet)
+        first, last = P - 1, s.n - 2
+        assert n == min(W, last - first + 1)
+        _, taps = reference_forward(shape, w, s.tokens[:-1], kv_storage="model")
+        pos = list(range(last - n + 1, last + 1))
+        ref = np.array([[[reference_confidence(shape, w, taps[p, l, t]) for t in range(2)]
+                         for l in range(shape.n_layers)] for p in pos])
+        np.testing.assert_allclose(per_tap, ref.mean(axis=0), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(conf, ref.mean(axis=(0, 2)), rtol=0, atol=1e-12)
