@@ -43,9 +43,16 @@ class OracleSSD:
     def pending(self) -> int:
         return self.tokens[-1]
 
-    def prefill(self, prompt: Sequence[int]) -> int:
+    def prefill(self, prompt: Sequence[int], chunk=None, on_chunk=None) -> int:
+        """Full model over the prompt; commits the first new token.  chunk: feed the prompt in pieces of that many
+        rows (the cache makes this the same computation); on_chunk(rows_done) is called after each piece, so that a
+        caller can report progress on a large model."""
         prompt = [int(t) for t in prompt]
-        out = self.m.forward(prompt, 0, want_taps=True)
+        step = len(prompt) if not chunk else int(chunk)
+        for a in range(0, len(prompt), step):
+            out = self.m.forward(prompt[a:a + step], a, want_taps=True)
+            if on_chunk is not None:
+                on_chunk(min(a + step, len(prompt)))
         first = argmax_lowest(out["logits"][-1])
         self.tokens = prompt + [first]
         self.last_taps = out["taps"][-1:]
@@ -118,9 +125,10 @@ class OracleSSD:
         self.tokens.extend(int(t) for t in draft[:a])
         self.tokens.append(int(target[a]))
         # verify rows 0..a were fed committed tokens (the pending one and the accepted drafts): they enter the window
-        if self.last_taps is not None and len(self.last_taps) == k + 1:
+        taps = getattr(self, "last_taps", None)
+        if taps is not None and len(taps) == k + 1:
             for j in range(a + 1):
-                self.window_taps.append(self.last_taps[j])
+                self.window_taps.append(taps[j])
         self.drafted += k
         self.accepted += a
         self.cycles += 1

@@ -73,17 +73,6 @@ static double widen_fp16(uint16_t h)
     return sign ? -v : v;
 }
 
-/* The same conversion for all 65 536 bit patterns, tabulated once per process (the formula above, evaluated
- * ahead of the matrix products instead of inside their inner loop); filled by orc_create before any use. */
-static double fp16_value[65536];
-static int fp16_value_ready = 0;
-static void fill_fp16_table(void)
-{
-    if (fp16_value_ready) return;
-    for (int h = 0; h < 65536; h++) fp16_value[h] = widen_fp16((uint16_t)h);
-    fp16_value_ready = 1;
-}
-
 /* x rounded to fp32 and then to fp16 (round-to-nearest-even both times), returned as a double.
  * The fp16 step rounds the fp32 value on the fp16 grid: spacing 2^(e-10) for |x| in [2^e, 2^(e+1)),
  * e >= -14, and 2^-24 below 2^-14; values that round to 65520 or more become infinity. */
@@ -122,25 +111,45 @@ static double round_storage(double x, int kv_storage)
     return kv_storage == 0 ? (double)(float)x : kv_storage == 1 ? orc_round_bf16(x) : orc_round_fp16(x);
 }
 
-/* Y[r][n] = sum_k W[n][k] * X[r][k]   (W: N x K row-major, X: R x K, Y: R x N) */
+/* The same conversion for all 65 536 bit patterns, tabulated once per process (the formula above, evaluated
+ * ahead of the matrix products instead of inside their inner loop); filled by orc_create before any use. */
+static double fp16_value[65536];
+static int fp16_value_ready = 0;
+static void fill_fp16_table(void)
+{
+    if (fp16_value_ready) return;
+    for (int h = 0; h < 65536; h++) fp16_value[h] = widen_fp16((uint16_t)h);
+    fp16_value_ready = 1;
+}
+
+/* Y[r][n] = sum_k W[n][k] * X[r][k]   (W: N x K row-major, X: R x K, Y: R x N).
+ * Every output is its own left-to-right sum over k, exactly as written; up to ORC_RB rows r share one pass over the
+ * weight row n (their sums advance side by side, none of them is reassociated), so the weight is widened once per
+ * pass instead of once per row. */
+#define ORC_RB 8
 static void matmul_wt(const void *W, int dtype, int N, int K, const double *X, int R, double *Y)
 {
 #pragma omp parallel for schedule(static)
     for (int n = 0; n < N; n++) {
-        for (int r = 0; r < R; r++) {
-            const double *x = X + (size_t)r * K;
-            double acc = 0.0;
-            if (dtype == 0) {
-                const float *w = (const float *)W + (size_t)n * K;
-                for (int k = 0; k < K; k++) acc += (double)w[k] * x[k];
-            } else if (dtype == 1) {
-                const uint16_t *w = (const uint16_t *)W + (size_t)n * K;
-                for (int k = 0; k < K; k++) acc += widen_bf16(w[k]) * x[k];
+        const float *wf = (const float *)W + (size_t)n * K;
+        const uint16_t *wh = (const uint16_t *)W + (size_t)n * K;
+        for (int r0 = 0; r0 < R; r0 += ORC_RB) {
+            const int nr = R - r0 < ORC_RB ? R - r0 : ORC_RB;
+            double acc[ORC_RB];
+            const double *x[ORC_RB];
+            for (int j = 0; j < nr; j++) { acc[j] = 0.0; x[j] = X + (size_t)(r0 + j) * K; }
+            if (nr == ORC_RB) {
+                for (int k = 0; k < K; k++) {
+                    const double w = dtype == 0 ? (double)wf[k] : dtype == 1 ? widen_bf16(wh[k]) : fp16_value[wh[k]];
+                    for (int j = 0; j < ORC_RB; j++) acc[j] += w * x[j][k];
+                }
             } else {
-                const uint16_t *w = (const uint16_t *)W + (size_t)n * K;
-                for (int k = 0; k < K; k++) acc += fp16_value[w[k]] * x[k];
+                for (int k = 0; k < K; k++) {
+                    const double w = dtype == 0 ? (double)wf[k] : dtype == 1 ? widen_bf16(wh[k]) : fp16_value[wh[k]];
+                    for (int j = 0; j < nr; j++) acc[j] += w * x[j][k];
+                }
             }
-            Y[(size_t)r * N + n] = acc;
+            for (int j = 0; j < nr; j++) Y[(size_t)(r0 + j) * N + n] = acc[j];
         }
     }
 }

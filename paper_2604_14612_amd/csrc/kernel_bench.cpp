@@ -52,7 +52,11 @@ int main(int argc, char** argv)
     if (M < 1 || M > 16) { std::printf("rows must be 1..16\n"); return 1; }
     Dims D;
     D.L = 32; D.d = 4096; D.H = 32; D.Hkv = 32; D.hd = 128; D.dq = 4096; D.dkv = 4096; D.f = 11008; D.V = 32000;
-    D.max_seq = 1024; D.eps = 1e-5f; D.wt = WT_BF16; D.kt = WT_BF16;
+    D.max_seq = 1024; D.eps = 1e-5f; D.wt = WT_BF16;
+    // cache element type: the library's default (fp32) unless KB_KV=bf16
+    const bool kv16 = std::getenv("KB_KV") && !std::strcmp(std::getenv("KB_KV"), "bf16");
+    D.kt = kv16 ? WT_BF16 : WT_F32;
+    const size_t kvb = kv16 ? 2 : 4;
     LaunchOpts opts;   // tuning hooks of this run
     D.opt = &opts;
     const size_t wbig = (size_t)3 << 30;  // 6 GB of bf16 weights to walk through
@@ -66,20 +70,21 @@ int main(int argc, char** argv)
     }
     float *x, *gain, *act, *q, *rope, *logits, *part, *sink, *big_a, *big_b;
     int* pos;
-    uint16_t *kc, *vc, *hi, *lo, *hi64, *lo64;
+    char *kc, *vc;   // KV cache copies, kvb bytes per element
+    uint16_t *hi, *lo, *hi64, *lo64;
     const size_t act_floats = (size_t)16 * 32000;
     CK(hipMalloc(&x, act_floats * 4)); CK(hipMalloc(&gain, 1 << 20)); CK(hipMalloc(&act, act_floats * 4));
     CK(hipMalloc(&q, act_floats * 4)); CK(hipMalloc(&logits, act_floats * 4)); CK(hipMalloc(&part, 64 << 20));
     CK(hipMalloc(&rope, (size_t)1024 * 64 * 2 * 4)); CK(hipMalloc(&pos, 64)); CK(hipMalloc(&sink, 256));
     const size_t kv_layer = (size_t)32 * 1024 * 128;  // elements of K (or V) of one layer; one copy per timed launch so the cache is cold
-    CK(hipMalloc(&kc, 12 * kv_layer * 2)); CK(hipMalloc(&vc, 12 * kv_layer * 2));
+    CK(hipMalloc(&kc, 12 * kv_layer * kvb)); CK(hipMalloc(&vc, 12 * kv_layer * kvb));
     CK(hipMalloc(&hi, act_floats * 2)); CK(hipMalloc(&lo, act_floats * 2));
     CK(hipMalloc(&hi64, (size_t)64 * 11008 * 2)); CK(hipMalloc(&lo64, (size_t)64 * 11008 * 2));
     CK(hipMemset(hi64, 0, (size_t)64 * 11008 * 2)); CK(hipMemset(lo64, 0, (size_t)64 * 11008 * 2));
     CK(hipMalloc(&big_a, (size_t)256 << 20)); CK(hipMalloc(&big_b, (size_t)256 << 20));
     CK(hipMemset(x, 0, act_floats * 4)); CK(hipMemset(gain, 0, 1 << 20)); CK(hipMemset(act, 0, act_floats * 4));
     CK(hipMemset(q, 0, act_floats * 4)); CK(hipMemset(rope, 0, (size_t)1024 * 64 * 2 * 4));
-    CK(hipMemset(kc, 0, 12 * kv_layer * 2)); CK(hipMemset(vc, 0, 12 * kv_layer * 2));
+    CK(hipMemset(kc, 0, 12 * kv_layer * kvb)); CK(hipMemset(vc, 0, 12 * kv_layer * kvb));
     CK(hipMemset(hi, 0, act_floats * 2)); CK(hipMemset(lo, 0, act_floats * 2));
     const int ctx = 640;
     CK(hipMemcpy(pos, &ctx, 4, hipMemcpyHostToDevice));
@@ -124,11 +129,11 @@ int main(int argc, char** argv)
     }
     if (std::getenv("KB_LAYER")) {   // the five launches of a decode layer in sequence, 12 different layers' worth of weights
         const size_t layer_elems = 4 * qk + 3 * gu;
-        timeit("decode layer: qkv, attention, o (fold), gate/up, down", layer_elems * 2.0 + 2.0 * 641 * 4096 * 2, n, [&](int i) {
+        timeit("decode layer: qkv, attention, o (fold), gate/up, down", layer_elems * 2.0 + 2.0 * 641 * 4096 * kvb, n, [&](int i) {
             const uint16_t* w = W + (size_t)i * layer_elems;
-            CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, 0));
+            CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, 0));
             int fold = 0;
-            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0,
+            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0,
                          &fold));
             if (fold > 0) CK(gemv_resid_attn(D, w + 3 * qk, part, fold, x, nullptr, 0));
             else CK(gemv_resid(D, w + 3 * qk, 4096, 4096, act, x, nullptr, 0));
@@ -204,6 +209,53 @@ int main(int argc, char** argv)
         }
         return 0;
     }
+    if (std::getenv("KB_WARM")) {
+        // Does a GEMV run faster on weights that a plain read kernel has just pulled through the 256 MB memory-side
+        // cache?  (If it did, a prefetcher running ahead of the launch sequence could hide launch gaps.)  Every timed
+        // launch is preceded by a read of 1 GB of other data; "warm" re-reads the matrix with plain loads first.
+        hipEvent_t a, b; CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
+        for (int rows : {4096, 8192, 11008, 16384, 22016}) {
+            const size_t bytes = (size_t)rows * 4096 * 2;
+            for (int mode = 0; mode < 3; mode++) {   // 0 cold GEMV, 1 GEMV after a plain-load read of the matrix, 2 plain-load read after the same
+                float tot = 0.f;
+                const int reps = 10;
+                for (int r = 0; r < reps + 1; r++) {
+                    const uint16_t* w = W + (size_t)(r % 10) * ((size_t)96 << 20);
+                    CK(read_probe(W + ((size_t)2 << 30), (size_t)1 << 30, sink, 0));
+                    if (mode) CK(copy_f32((const float*)w, big_a, bytes / 4, 0));   // plain loads (and 1x the bytes written elsewhere)
+                    CK(hipEventRecord(a, 0));
+                    if (mode == 2) CK(copy_f32((const float*)w, big_b, bytes / 4, 0));
+                    else CK(gemv_resid(D, w, rows, 4096, q, logits, nullptr, 0));
+                    CK(hipEventRecord(b, 0)); CK(hipEventSynchronize(b));
+                    float ms; CK(hipEventElapsedTime(&ms, a, b));
+                    if (r) tot += ms;   // the first repetition warms the code path
+                }
+                const char* nm[3] = {"GEMV, cold", "GEMV after a plain read of the same matrix", "plain copy after a plain read (for scale)"};
+                std::printf("%6d x 4096 (%6.1f MB)  %-44s %8.2f us\n", rows, bytes / 1e6, nm[mode], tot * 1e3 / reps);
+                std::fflush(stdout);
+            }
+        }
+        return 0;
+    }
+    if (std::getenv("KB_RESID")) {   // residual projections (output 4096 x 4096, down 4096 x 11008): work split sweep
+        const int ctx1 = 640;
+        for (int cfg : {0, 241, 242, 244, 248, 222, 224, 228, 422, 424, 428, 442, 444}) for (int cap : {0, 512, 1024}) {
+            opts.gemv_resid_cfg = cfg; opts.gemv_block_cap = cap;
+            char nm[96];
+            std::snprintf(nm, sizeof nm, "gemv_o cfg %d cap %d", cfg, cap);
+            timeit(nm, qk * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, q, x, nullptr, 0)); });
+            std::snprintf(nm, sizeof nm, "gemv_down cfg %d cap %d", cfg, cap);
+            timeit(nm, gu * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * gu, 4096, 11008, act, x, nullptr, 0)); });
+            std::snprintf(nm, sizeof nm, "attention + gemv_o (fold) cfg %d cap %d", cfg, cap);
+            timeit(nm, 2.0 * (ctx1 + 1) * 4096 * kvb + qk * 2.0, n, [&](int i) {
+                int fold = 0;
+                CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx1, 1, part, act, nullptr, nullptr,
+                             0, &fold));
+                if (fold > 0) CK(gemv_resid_attn(D, W + (size_t)i * qk, part, fold, x, nullptr, 0));
+                else CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
+        }
+        return 0;
+    }
     if (std::getenv("KB_SWEEP")) {   // launch time against size: fixed cost and streaming rate of probe and GEMV
         for (int mb : {16, 32, 64, 128, 256}) {
             char nm[64];
@@ -246,24 +298,24 @@ int main(int argc, char** argv)
             char nm[96];
             std::snprintf(nm, sizeof nm, "attention 1 row ctx 641, %s, splits %s%d", kind ? "lds-staged" : "planned",
                           sp ? "" : "auto=", sp ? sp : std::abs(attention_splits(D, ctx + 1, 1)));
-            timeit(nm, 2.0 * 641 * 4096 * 2, n, [&](int i) {
-                CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr,
+            timeit(nm, 2.0 * 641 * 4096 * kvb, n, [&](int i) {
+                CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, 1, part, act, nullptr,
                              nullptr, 0)); });
         }
     }
     opts.attn_splits = 0;
     opts.attn_kernel = 0;
-    timeit("attention + gemv_o, fold kernel", 2.0 * 641 * 4096 * 2 + qk * 2.0, n, [&](int i) {
-        CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0));
+    timeit("attention + gemv_o, fold kernel", 2.0 * 641 * 4096 * kvb + qk * 2.0, n, [&](int i) {
+        CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, 1, part, act, nullptr, nullptr, 0));
         CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
     for (int cap : {0, 512}) for (int sp : {0, 4, 8}) {
         opts.attn_splits = sp;
         opts.gemv_block_cap = cap;
         char nm[96];
         std::snprintf(nm, sizeof nm, "attention + gemv_o, fold in gemv, splits %d cap %d", sp, cap);
-        timeit(nm, 2.0 * 641 * 4096 * 2 + qk * 2.0, n, [&](int i) {
+        timeit(nm, 2.0 * 641 * 4096 * kvb + qk * 2.0, n, [&](int i) {
             int fold = 0;
-            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, 1, part, act, nullptr, nullptr,
+            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, 1, part, act, nullptr, nullptr,
                          0, &fold));
             if (fold > 0) CK(gemv_resid_attn(D, W + (size_t)i * qk, part, fold, x, nullptr, 0));
             else CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
@@ -284,6 +336,24 @@ int main(int argc, char** argv)
         if (with_ssq && mode != 1) { f.ssq = gain; f.n_ssq = K / 16; }   // gain is a zeroed 1 MB buffer: values do not matter here
         CK(rows_fused(D, f, 0));
     };
+    if (std::getenv("KB_ROWS")) {   // 16-row kernels: weight stripes in flight per block
+        with_ssq = true;
+        for (int dpt : {0, 1, 2, 3, 4}) {
+            opts.rows_depth = dpt;
+            std::printf("-- 16-row kernels, %d rows, stripes in flight %d (0 = library's choice)\n", M, dpt);
+            timeit("rows_qkv", 3 * qk * 2.0, n, [&](int i) {
+                const uint16_t* w = W + (size_t)i * 3 * qk;
+                fused(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, q, 4096); });
+            timeit("rows_o (resid)", qk * 2.0, n, [&](int i) { fused(1, W + (size_t)i * qk, nullptr, nullptr, 4096, 0, 0, 4096, x, 4096); });
+            timeit("rows_gateup (swiglu)", 2 * gu * 2.0, n, [&](int i) {
+                const uint16_t* w = W + (size_t)i * 2 * gu;
+                fused(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
+            timeit("rows_down (resid)", gu * 2.0, n, [&](int i) { fused(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, x, 4096); });
+            timeit("rows_lmhead", lm * 2.0, n, [&](int i) { fused(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, logits, 32000); });
+        }
+        opts.rows_depth = 0;
+        return 0;
+    }
     for (int v : {0, 1}) {
     with_ssq = v != 0;
     std::printf("-- 16-row kernels%s\n", v ? ", consumers summing 256 sum-of-squares partials per row (RMSNorm folded in)" : "");
@@ -338,8 +408,8 @@ int main(int argc, char** argv)
             char nm[96];
             std::snprintf(nm, sizeof nm, "attention M rows ctx 640+M, %s, splits %s%d", kind ? "lds-staged" : "planned",
                           sp ? "" : "auto=", sp ? sp : std::abs(attention_splits(D, ctx + M, M)));
-            timeit(nm, 2.0 * (640 + M) * 4096 * 2, n, [&](int i) {
-                CK(attention(D, q, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, M, part, nullptr, hi,
+            timeit(nm, 2.0 * (640 + M) * 4096 * kvb, n, [&](int i) {
+                CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, M, part, nullptr, hi,
                              lo, 0)); });
         }
     }
@@ -351,8 +421,8 @@ int main(int argc, char** argv)
         opts.attn_splits = sp;
         char nm[96];
         std::snprintf(nm, sizeof nm, "attention %d rows ctx 640+rows, LDS-staged %s, splits %d", rows, kind == 3 ? "plain" : "MFMA", sp);
-        timeit(nm, 2.0 * (640 + rows) * 4096 * 2, n, [&](int i) {
-            CK(attention(D, big_a, 4096, kc + (size_t)i * kv_layer, vc + (size_t)i * kv_layer, pos, 0, ctx, rows, part, nullptr,
+        timeit(nm, 2.0 * (640 + rows) * 4096 * kvb, n, [&](int i) {
+            CK(attention(D, big_a, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, rows, part, nullptr,
                          hi64, lo64, 0)); });
     }
     opts.attn_kernel = 0;

@@ -13,6 +13,7 @@ enum WeightType { WT_F32 = 0, WT_BF16 = 1, WT_F16 = 2 };
 // next GEMV launch.  Owned by whoever owns the Dims that point to it; nothing here is process-global.
 struct LaunchOpts {
     int gemv_block_cap = 0;     // > 0 overrides the block cap of the GEMV launches
+    int gemv_resid_cfg = 0;     // residual projections: 100 R + 10 D + KS forces rows per group / steps in flight / K split
     int rows_depth = 0;         // > 0 forces the number of weight stripes a 16-row block keeps in flight
     int wide_depth = 0;         // the same for the 64-row blocks
     int wide_ksplit = 0;        // 64-row blocks: 1 = never cut K, > 1 forces the number of K slices

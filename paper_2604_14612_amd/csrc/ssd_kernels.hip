@@ -660,7 +660,31 @@ template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s, LaunchOpts* opt, int* blocks_out)
 {
     const int ch = ceil_div(p.K, 64 * Elem<WT>::VEC);
+    if constexpr (EPI == EPI_RESID && sizeof(WT) == 2) {   // tuning hook (kernel_bench sweeps)
+        switch (opt ? opt->gemv_resid_cfg : 0) {
+            case 241: return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s, opt, blocks_out);
+            case 242: return launch_gemv_cfg<WT, EPI, 2, 4, 2>(p, s, opt, blocks_out);
+            case 244: return launch_gemv_cfg<WT, EPI, 2, 4, 4>(p, s, opt, blocks_out);
+            case 248: return launch_gemv_cfg<WT, EPI, 2, 4, 8>(p, s, opt, blocks_out);
+            case 222: return launch_gemv_cfg<WT, EPI, 2, 2, 2>(p, s, opt, blocks_out);
+            case 224: return launch_gemv_cfg<WT, EPI, 2, 2, 4>(p, s, opt, blocks_out);
+            case 228: return launch_gemv_cfg<WT, EPI, 2, 2, 8>(p, s, opt, blocks_out);
+            case 422: return launch_gemv_cfg<WT, EPI, 4, 2, 2>(p, s, opt, blocks_out);
+            case 424: return launch_gemv_cfg<WT, EPI, 4, 2, 4>(p, s, opt, blocks_out);
+            case 428: return launch_gemv_cfg<WT, EPI, 4, 2, 8>(p, s, opt, blocks_out);
+            case 442: return launch_gemv_cfg<WT, EPI, 4, 4, 2>(p, s, opt, blocks_out);
+            case 444: return launch_gemv_cfg<WT, EPI, 4, 4, 4>(p, s, opt, blocks_out);
+            default: break;
+        }
+    }
     if (p.n_rows >= 8192) return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s, opt, blocks_out);
+    if constexpr (EPI == EPI_RESID && sizeof(WT) == 2) {
+        // measured (work-split sweep of the two residual projections at the 7B shape): the variant that folds
+        // attention partials gains 0.7 us from four rows and four steps in flight per wave, the down projection
+        // 0.4 us from row pairs with K cut four ways
+        if (p.part && ch <= 12) return launch_gemv_cfg<WT, EPI, 4, 4, 2>(p, s, opt, blocks_out);
+        if (ch > 12 && ch <= 40) return launch_gemv_cfg<WT, EPI, 2, 2, 4>(p, s, opt, blocks_out);
+    }
     if (ch <= 12) return launch_gemv_cfg<WT, EPI, 2, 2, 2>(p, s, opt, blocks_out);
     if (ch <= 40) return launch_gemv_cfg<WT, EPI, 4, 2, 4>(p, s, opt, blocks_out);
     return launch_gemv_cfg<WT, EPI, 4, 2, 8>(p, s, opt, blocks_out);

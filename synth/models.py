@@ -81,19 +81,20 @@ WORKLOADS: Dict[str, Workload] = {
         "llama70b", ModelShape(80, 8192, 64, 8, 28672, 32000),
         seed=4, prompt_len=2048, new_tokens=128, k=4,
         note="grouped-query attention, ~138 GB of bf16 weights"),
-    # beyond the five benchmark configurations: the second model family of Section 4.1.1 (grouped heads,
-    # 128 256-entry vocabulary: a 1 GB LM head, so the confidence pass is four times dearer per row)
+    # Beyond the five benchmark configurations.
     # A model in which depth is redundant, as it is in trained LLMs and is not in a random-init one: every layer
-    # writes 20 times less into the residual stream, so a draft model with half the layers mostly agrees with the
-    # full model.  Shows the pipeline at high acceptance (search reaching its goal, SSD faster than vanilla).
+    # writes a thousand times less into the residual stream, so a draft model with half the layers mostly agrees
+    # with the full model.  Shows the pipeline at high acceptance (search reaching its goal, SSD faster than vanilla).
     "llama7b_redundant": Workload(
         "llama7b_redundant", ModelShape(32, 4096, 32, 32, 11008, 32000, resid_scale=0.001),
         seed=2, prompt_len=512, new_tokens=256, k=4,
-        note="7B shape, residual contributions scaled by 0.05"),
+        note="7B shape, o_proj / down_proj scaled by 0.001 (depth made redundant)"),
     "llama7b_f16": Workload(
         "llama7b_f16", ModelShape(32, 4096, 32, 32, 11008, 32000, dtype="fp16"),
         seed=2, prompt_len=512, new_tokens=256, k=4,
         note="the 7B shape in the paper's own precision (FP16 weights and cache)"),
+    # the second model family of Section 4.1.1 (grouped heads, 128 256-entry vocabulary: a 1 GB LM head, so the
+    # confidence pass is four times dearer per row)
     "llama3_8b": Workload(
         "llama3_8b", ModelShape(32, 4096, 32, 8, 14336, 128256, rope_base=500000.0),
         seed=5, prompt_len=512, new_tokens=128, k=4,

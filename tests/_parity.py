@@ -12,6 +12,20 @@ CONF_TOL = {"bf16": 5e-3, "fp16": 6.25e-4, "fp32": 2e-5}      # |d conf| <~ 2 (l
 PROB_RTOL = {"bf16": 4e-2, "fp16": 5e-3, "fp32": 1e-3}         # |dp| <= p * 2 * (logit tolerance)
 
 
+def progress(msg):
+    """One line per finished step of a long test, appended to gpurun_out/test_progress.log (pytest holds back what
+    a test prints until it ends; a file shows from outside that the test is alive and where it is)."""
+    import os
+    import time
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    try:
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write("%s %s\n" % (time.strftime("%H:%M:%S"), msg))
+    except OSError:
+        pass
+
+
 def to_gpu(weights):
     out = {}
     for k, v in weights.items():
@@ -42,7 +56,9 @@ def make_pair_gpu_generated(shape, seed, max_seq, max_k=8, kv_storage="default",
     (then a dict mode -> OracleModel over the same host tensors is returned in place of the model)."""
     import paper_2604_14612_amd as ssd
     w = make_weights(shape, seed, device="cuda")
+    progress("weights drawn on the GPU (%d layers, d_model %d)" % (shape.n_layers, shape.d_model))
     w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w.items()}
+    progress("weights copied to the host")
     ctx = ssd.Context(shape, w, max_seq, max_k, **ctx_kw)
     mode = lambda m: ctx.kv_dtype if m == "cache" else oracle_storage_for(ctx) if m == "default" else m
     if isinstance(kv_storage, str):
@@ -75,25 +91,25 @@ def decisive(z, dtype):
     return margin(z) > 2.0 * (a + r * float(np.abs(z).max()))
 
 
-def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None):
+def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None, report=None):
     """Runs greedy SSD on both sides cycle by cycle from the oracle's committed prefix.  k: the draft length, or a
     list of draft lengths, one per cycle (then exactly len(k) cycles run and n_new is ignored).
 
     Every logit row is compared within tolerance; tokens, accepted counts and next tokens are
     compared bit-exactly wherever the oracle's top-2 margin is decisive; a cycle with a
     sub-tolerance disagreement is counted as unpinned and the library is re-synchronised to the
-    oracle with ssd_force_commit.  Returns a dict of counters.
+    oracle with ssd_force_commit.  Returns a dict of counters.  report: a name; then every finished oracle step
+    of the run (prompt chunks of 8 rows, each draft and verify pass) is logged with progress().
     """
+    say = (lambda m: progress("%s: %s" % (report, m))) if report else (lambda m: None)
     o = OracleSSD(orc_model, window=max(1, int(ctx.cfg.conf_window)) if ctx.cfg.conf_window else 100)
-    first_o = o.prefill(prompt)
+    first_o = o.prefill(prompt, chunk=8 if report else None, on_chunk=lambda n: say("oracle prompt rows %d/%d" % (n, len(prompt))))
     first_g = ctx.ssd_prefill(prompt)
     stats = {"cycles": 0, "unpinned_cycles": 0, "draft_rows": 0, "verify_rows": 0, "max_err": 0.0,
              "accepted": [], "tokens_checked": 0}
     stats["max_err"] = assert_logits_close(ctx.ssd_copy_logits(0, 1)[0], o.last_logits[0], dtype, "prefill logits")
-    if decisive(o.last_logits[0], dtype):
-        assert first_g == first_o
-    else:
-        assert first_g == first_o, "prefill arg-max is a sub-tolerance tie for this seed; pick another seed"
+    assert first_g == first_o, ("prefill token differs at a decisive margin" if decisive(o.last_logits[0], dtype) else
+                                "prefill arg-max is a sub-tolerance tie for this seed; pick another seed")
     P = len(prompt)
     k_seq = None if isinstance(k, int) else list(k)
     while (o.n - P < n_new) if k_seq is None else (stats["cycles"] < len(k_seq)):
@@ -101,6 +117,7 @@ def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None):
             k = k_seq[stats["cycles"]]
         pinned = True
         d_o = o.draft(mask, k)
+        say("cycle %d: oracle draft of %d done" % (stats["cycles"], k))
         d_g = ctx.ssd_draft_step(mask, k)
         zg = ctx.ssd_copy_logits(0, k)
         for j in range(k):
@@ -113,6 +130,7 @@ def lockstep_ssd(ctx, orc_model, prompt, n_new, k, mask, dtype, next_mask=None):
                 break           # later draft steps saw different inputs
             stats["tokens_checked"] += 1
         y_o = o.verify(d_o)
+        say("cycle %d: oracle verify done" % stats["cycles"])
         y_g = ctx.ssd_verify(d_o)
         zv = ctx.ssd_copy_logits(0, k + 1)
         for j in range(k + 1):

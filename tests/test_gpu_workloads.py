@@ -9,7 +9,8 @@ import pytest
 
 from oracle import OracleSSD, SearchDriver, SelectParams, select_skip
 from synth import WORKLOADS, make_prompt, reduced_depth
-from tests._parity import (TOL, assert_logits_close, decisive, lockstep_ssd, make_pair, make_pair_gpu_generated)
+from tests._parity import (TOL, assert_logits_close, decisive, lockstep_ssd, make_pair, make_pair_gpu_generated,
+                           progress)
 
 pytestmark = pytest.mark.gpu
 
@@ -130,10 +131,12 @@ def _full_depth(ssd, name, k_seq, prompt_len=48):
     wl = WORKLOADS[name]
     L = wl.shape.n_layers
     t0 = time.time()
+    progress("%s full depth: drawing weights, copying them to the host" % name)
     orc, ctx = make_pair_gpu_generated(wl.shape, wl.seed, prompt_len + sum(k_seq) + len(k_seq) + 8, max_k=max(k_seq))
     prompt = make_prompt(wl.shape.vocab, prompt_len, wl.seed).tolist()
     t1 = time.time()
-    st = lockstep_ssd(ctx, orc, prompt, 0, k_seq, _uniform_mask(L), wl.shape.dtype)
+    progress("%s full depth: set-up done in %.0f s" % (name, t1 - t0))
+    st = lockstep_ssd(ctx, orc, prompt, 0, k_seq, _uniform_mask(L), wl.shape.dtype, report=name + " full depth")
     print(name, "full depth (%d layers), prompt %d, k" % (L, prompt_len), k_seq, ": max err %.2e" % st["max_err"],
           "accepted", st["accepted"], "unpinned", st["unpinned_cycles"], "tokens checked", st["tokens_checked"],
           "setup %.0f s, lock-step %.0f s" % (t1 - t0, time.time() - t1), flush=True)
@@ -192,7 +195,9 @@ def test_full_workload_properties(ssd, name, n_new):
         (two kernels that are each within tolerance of the exact logits can order such a pair differently)."""
         return abs(float(z[t1]) - float(z[t2])) <= tol_a + tol_r * float(np.abs(z).max())
 
+    progress("%s properties: %d vanilla tokens done at %.0f s" % (name, n_new, time.time() - t0))
     for k, mask in ((4, np.zeros(L, np.uint8)), (8, uniform), (2, uniform)):
+        progress("%s properties: k=%d, %d layers skipped" % (name, k, int(mask.sum())))
         ctx.ssd_reset()
         got = [ctx.ssd_prefill(prompt)]
         assert np.array_equal(ctx.ssd_copy_logits(0, 1), logits0)          # deterministic prefill
