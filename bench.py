@@ -24,15 +24,18 @@ HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "kernel_bench_llama7b_hbm_traffic.md")
 
 
-def measured_traffic_bytes(row_label="gemv gate/up + SwiGLU"):
+def measured_traffic_bytes(row_label="decode: gate/up GEMV + SwiGLU"):
     """HBM bytes per launch of the draft gate/up GEMV at the Llama-2-7B shape as the committed rocprofv3 counter
     summary gives them (FETCH_SIZE + WRITE_SIZE per dispatch, scaled by the factors a known-size read / copy kernel
     gives; the run and the arithmetic are in that file).  None if the file or the row is missing."""
     try:
+        col = None
         for line in open(TRAFFIC_PROFILE):
             cells = [c.strip() for c in line.split("|")]
-            if len(cells) > 6 and row_label in cells[2]:
-                return float(cells[5]) * 1e6        # column "scaled HBM bytes (MB)"
+            if "scaled HBM bytes (MB)" in cells:
+                col = cells.index("scaled HBM bytes (MB)")
+            elif col is not None and len(cells) > col and cells[1].startswith(row_label):
+                return float(cells[col]) * 1e6
     except (OSError, ValueError):
         pass
     return None

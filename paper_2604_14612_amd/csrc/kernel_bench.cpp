@@ -275,6 +275,68 @@ int main(int argc, char** argv)
         }
         return 0;
     }
+    if (std::getenv("KB_COUNTERS")) {
+        // Every kernel of a decode layer and of a verify layer once per line, in the library's own configuration and
+        // nothing else: under `rocprofv3 --pmc` a kernel name (plus grid size) then maps to exactly one of these lines.
+        timeit("gemv_qkv", 3 * qk * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 3 * qk;
+            CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc, vc, 0)); });
+        timeit("attention 1 row ctx 641 + gemv_o folding its partials", 2.0 * 641 * 4096 * kvb + qk * 2.0, n, [&](int i) {
+            int fold = 0;
+            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, 1, part, act, nullptr, nullptr,
+                         0, &fold));
+            if (fold > 0) CK(gemv_resid_attn(D, W + (size_t)i * qk, part, fold, x, nullptr, 0));
+            else CK(gemv_resid(D, W + (size_t)i * qk, 4096, 4096, act, x, nullptr, 0)); });
+        timeit("gemv_gateup (swiglu)", 2 * gu * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 2 * gu;
+            CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0)); });
+        timeit("gemv_down (resid)", gu * 2.0, n, [&](int i) { CK(gemv_resid(D, W + (size_t)i * gu, 4096, 11008, act, x, nullptr, 0)); });
+        timeit("gemv_lmhead", lm * 2.0, n, [&](int i) { CK(gemv_lmhead(D, W + (size_t)i * lm, gain, x, logits, 0)); });
+        auto rows = [&](int mode, const uint16_t* w0, const uint16_t* w1, const uint16_t* w2, int n0, int n1, int n2, int K,
+                        float* y, int ldy) {
+            RowsFused f = {};
+            f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
+            f.bh = hi; f.bl = lo; f.ldb = K; f.y = y; f.ldy = ldy; f.oh = hi; f.ol = lo; f.ldo = 11008; f.M = M; f.mode = mode;
+            f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
+            if (mode != 1) { f.ssq = gain; f.n_ssq = K / 16; }
+            CK(rows_fused(D, f, 0));
+        };
+        timeit("rows_qkv", 3 * qk * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 3 * qk;
+            rows(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, q, 4096); });
+        timeit("attention M rows ctx 640+M (MFMA kernel + fold)", 2.0 * (640 + M) * 4096 * kvb, n, [&](int i) {
+            CK(attention(D, q, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, M, part, nullptr, hi,
+                         lo, 0)); });
+        timeit("rows_o (resid)", qk * 2.0, n, [&](int i) { rows(1, W + (size_t)i * qk, nullptr, nullptr, 4096, 0, 0, 4096, x, 4096); });
+        timeit("rows_gateup (swiglu)", 2 * gu * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 2 * gu;
+            rows(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
+        timeit("rows_down (resid)", gu * 2.0, n, [&](int i) { rows(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, x, 4096); });
+        timeit("rows_lmhead", lm * 2.0, n, [&](int i) { rows(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, logits, 32000); });
+        auto wide64 = [&](int mode, const uint16_t* w0, const uint16_t* w1, const uint16_t* w2, int n0, int n1, int n2, int K,
+                          float* y, int ldy) {
+            RowsFused f = {};
+            f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
+            f.bh = hi64; f.bl = lo64; f.ldb = K; f.y = y; f.ldy = ldy; f.oh = hi64; f.ol = lo64; f.ldo = 11008; f.M = 64; f.mode = mode;
+            f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
+            f.kpart = part; f.kpart_floats = (size_t)16 << 20;
+            CK(rows_wide(D, f, 0));
+        };
+        timeit("wide_qkv (64 rows)", 3 * qk * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 3 * qk;
+            wide64(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, big_a, 4096); });
+        timeit("wide_o (64 rows)", qk * 2.0, n, [&](int i) { wide64(1, W + (size_t)i * qk, nullptr, nullptr, 4096, 0, 0, 4096, big_b, 4096); });
+        timeit("wide_gateup (64 rows)", 2 * gu * 2.0, n, [&](int i) {
+            const uint16_t* w = W + (size_t)i * 2 * gu;
+            wide64(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
+        timeit("wide_down (64 rows)", gu * 2.0, n, [&](int i) { wide64(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, big_b, 4096); });
+        timeit("rows_many lmhead 64 rows", lm * 2.0, n, [&](int i) {
+            CK(rows_many(D, W + (size_t)i * lm, 32000, 4096, hi64, lo64, 4096, 64, big_a, 32000, 0)); });
+        timeit("attention 64 rows ctx 640+64 (MFMA kernel + fold)", 2.0 * (640 + 64) * 4096 * kvb, n, [&](int i) {
+            CK(attention(D, big_a, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, 64, part, nullptr,
+                         hi64, lo64, 0)); });
+        return 0;
+    }
     // single-row (draft / vanilla decode) kernels
     for (int cap : {0, 1024, 512}) {
     opts.gemv_block_cap = cap;
