@@ -47,8 +47,8 @@ enum {
 #define SSD_MAX_K 15        /* largest draft length: k + 1 rows fill one 16-column MFMA tile */
 #define SSD_MAX_LAYERS 128  /* deepest model a context accepts (fixed-size per-layer result slots in the workspace) */
 #define SSD_MAX_WINDOW 4096 /* largest context window of the confidence extraction (positions kept on the device) */
-#define SSD_PREFILL_ROWS 64 /* most prompt rows processed per pass of the weights (16 where a shape does not fit the
-                               64-row tiling: widths not multiples of 128, fp32 weights) */
+#define SSD_PREFILL_ROWS 512 /* most prompt rows processed per pass of the weights (64 or 16 where a shape does not fit
+                                the 128 x 128 or the 64-row tiling: widths not multiples of 128, fp32 weights) */
 
 typedef struct ssd_ctx ssd_ctx;
 

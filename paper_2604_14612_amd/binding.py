@@ -20,7 +20,7 @@ SSD_OK, SSD_EINVAL, SSD_ESTATE, SSD_ECAPACITY, SSD_ENOMEM, SSD_EHIP = 0, -1, -2,
 SSD_MAX_K = 15
 KERNEL_IDS = {"gemv_qkv": 0, "attention": 1, "gemv_o": 2, "gemv_gateup": 3, "gemv_down": 4, "gemv_lmhead": 5,
               "vocab_reduce": 6, "rows_qkv": 7, "rows_o": 8, "rows_gateup": 9, "rows_down": 10, "rows_lmhead": 11}
-SSD_PREFILL_ROWS = 64
+SSD_PREFILL_ROWS = 512
 _ERR_NAMES = {-1: "SSD_EINVAL", -2: "SSD_ESTATE", -3: "SSD_ECAPACITY", -4: "SSD_ENOMEM", -5: "SSD_EHIP"}
 
 

@@ -275,6 +275,71 @@ int main(int argc, char** argv)
         }
         return 0;
     }
+    if (std::getenv("KB_BIG")) {
+        // whole-prompt GEMMs: one launch of the 128 x 128-tile kernel over R rows against R / 64 launches of the 64-row
+        // kernel (flops: one bf16 product per weight and row; the kernels do two, hi and lo)
+        const int pad = std::getenv("KB_PAD") ? std::atoi(std::getenv("KB_PAD")) : 0;   // extra elements per activation row
+        std::printf("activation row pitch = K + %d elements\n", pad);
+        const int only_r = std::getenv("KB_BIG_R") ? std::atoi(std::getenv("KB_BIG_R")) : 0;   // one row count only
+        for (int R : {128, 256, 512, 1024}) {
+            if (only_r && R != only_r) continue;
+            uint16_t *bh, *bl, *oh, *ol;
+            const size_t rb = (size_t)R * (11008 + pad) * 2;
+            CK(hipMalloc(&bh, rb)); CK(hipMalloc(&bl, rb)); CK(hipMalloc(&oh, rb)); CK(hipMalloc(&ol, rb));
+            CK(hipMemset(bh, 0, rb)); CK(hipMemset(bl, 0, rb));
+            float* ssq_out;
+            CK(hipMalloc(&ssq_out, (size_t)R * 64 * 4));
+            auto run = [&](bool big, int mode, const uint16_t* w0, const uint16_t* w1, const uint16_t* w2, int n0, int n1, int n2, int K,
+                           float* y, int ldy, int rows, int row0) {
+                RowsFused f = {};
+                f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
+                f.bh = bh + (size_t)row0 * (K + pad); f.bl = bl + (size_t)row0 * (K + pad); f.ldb = K + pad; f.y = y ? y + (size_t)row0 * ldy : nullptr; f.ldy = ldy;
+                f.oh = oh + (size_t)row0 * 11008; f.ol = ol + (size_t)row0 * 11008; f.ldo = 11008; f.M = rows; f.mode = mode;
+                f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
+                f.kpart = part; f.kpart_floats = (size_t)16 << 20;
+                if (mode != 1) { f.ssq = gain; f.n_ssq = K / 64; }
+                CK(big ? rows_big(D, f, 0) : rows_wide(D, f, 0));
+            };
+            struct Shape { const char* name; int mode; size_t welems; int n0, n1, n2, K, ldy; };
+            const Shape shapes[] = {{"qkv", 3, 3 * qk, 4096, 4096, 4096, 4096, 4096}, {"o (resid)", 1, qk, 4096, 0, 0, 4096, 4096},
+                                    {"gateup (swiglu)", 2, 2 * gu, 11008, 11008, 0, 4096, 0}, {"down (resid)", 1, gu, 4096, 0, 0, 11008, 4096},
+                                    {"lmhead (store)", 0, lm, 32000, 0, 0, 4096, 32000}};
+            for (const Shape& sh : shapes) {
+                if (sh.mode == 3 && R > 256) continue;   // the bench cache copies hold 1024 positions from 640 on
+                const double flops = 2.0 * (double)sh.welems * R;
+                for (int big = 1; big >= 0; big--) {
+                    char nm[96];
+                    std::snprintf(nm, sizeof nm, "%s %4d rows, %s", sh.name, R, big ? "128x128 tiles, 1 launch" : "64-row kernel per 64 rows");
+                    hipEvent_t a, b;
+                    CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
+                    float best = 1e30f;
+                    for (int rep = 0; rep < 3; rep++) {
+                        CK(hipDeviceSynchronize());
+                        CK(hipEventRecord(a, 0));
+                        for (int i = 0; i < 4; i++) {
+                            const uint16_t* w = W + (size_t)i * sh.welems;
+                            const uint16_t* w1 = sh.mode == 3 ? w + qk : sh.mode == 2 ? w + gu : nullptr;
+                            const uint16_t* w2 = sh.mode == 3 ? w + 2 * qk : nullptr;
+                            float* y = sh.mode == 2 ? nullptr : big_a;
+                            if (big) run(true, sh.mode, w, w1, w2, sh.n0, sh.n1, sh.n2, sh.K, y, sh.ldy, R, 0);
+                            else for (int r0 = 0; r0 < R; r0 += 64) run(false, sh.mode, w, w1, w2, sh.n0, sh.n1, sh.n2, sh.K, y, sh.ldy, 64, r0);
+                        }
+                        CK(hipEventRecord(b, 0));
+                        CK(hipEventSynchronize(b));
+                        float ms;
+                        CK(hipEventElapsedTime(&ms, a, b));
+                        if (ms < best) best = ms;
+                    }
+                    const double us = best * 1e3 / 4;
+                    std::printf("%-52s %9.1f us  %7.1f TFLOP/s\n", nm, us, flops / us / 1e6);
+                    std::fflush(stdout);
+                    CK(hipEventDestroy(a)); CK(hipEventDestroy(b));
+                }
+            }
+            CK(hipFree(bh)); CK(hipFree(bl)); CK(hipFree(oh)); CK(hipFree(ol)); CK(hipFree(ssq_out));
+        }
+        return 0;
+    }
     if (std::getenv("KB_COUNTERS")) {
         // Every kernel of a decode layer and of a verify layer once per line, in the library's own configuration and
         // nothing else: under `rocprofv3 --pmc` a kernel name (plus grid size) then maps to exactly one of these lines.

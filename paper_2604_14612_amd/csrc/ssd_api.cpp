@@ -23,9 +23,12 @@ constexpr size_t ALIGN = 256;
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
-    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, ssq, small, ring, ring_conf, total;
+    size_t rope, kv, x, h, qkv, att, act, part, logits, taps, tapn, hi, lo, ssq, small, vtok, ring, ring_conf, total;
     int rows;       // activation rows: max(max_k + 1, prompt rows per pass)
-    int prefill_rows;  // prompt rows per pass: SSD_PREFILL_ROWS where the shape fits the wide tiling, else 16
+    int prefill_rows;  // prompt rows per pass: SSD_PREFILL_ROWS where the shape fits the 128 x 128 tiling, 64 where only the
+                       // 64-row one, else 16
+    int tap_rows;   // rows of the tap buffer: a verify block, or the 16 rows of a short prompt (a longer prompt keeps
+                    // the taps of its last row only)
     int conf_rows;  // rows of one confidence pass: 2 * L
     int logit_rows;
     size_t kv_layer_elems;  // elements of K (or V) of one layer
@@ -65,8 +68,13 @@ Layout make_layout(const ssd_config& c)
     Dims D = make_dims(c);
     Layout l;
     size_t esz = c.kv_dtype == 0 ? 4 : 2;
-    l.prefill_rows = rows_wide_supported(D) ? SSD_PREFILL_ROWS : 16;
+    l.prefill_rows = rows_big_supported(D) ? SSD_PREFILL_ROWS : rows_wide_supported(D) ? 64 : 16;
+    {   // no more rows per pass than a prompt can have (rounded up to whole 64-row groups)
+        const int cap = (c.max_seq + 63) / 64 * 64;
+        if (l.prefill_rows > 64 && l.prefill_rows > cap) l.prefill_rows = cap;
+    }
     l.rows = c.max_k + 1 > l.prefill_rows ? c.max_k + 1 : l.prefill_rows;
+    l.tap_rows = c.max_k + 1 > 16 ? c.max_k + 1 : 16;
     l.conf_rows = 2 * c.n_layers;
     l.logit_rows = l.rows > l.conf_rows ? l.rows : l.conf_rows;
     l.kv_layer_elems = (size_t)D.Hkv * D.max_seq * D.hd;
@@ -82,7 +90,7 @@ Layout make_layout(const ssd_config& c)
     l.part_floats = attention_scratch_floats(D, l.rows);
     l.part = o;   o += align_up(l.part_floats * sizeof(float));
     l.logits = o; o += align_up((size_t)l.logit_rows * D.V * sizeof(float));
-    l.taps = o;   o += align_up((size_t)l.rows * D.L * 2 * D.d * sizeof(float));
+    l.taps = o;   o += align_up((size_t)l.tap_rows * D.L * 2 * D.d * sizeof(float));
     l.tapn = o;   o += align_up((size_t)l.conf_rows * D.d * sizeof(float));
     {   // bf16 hi/lo staging of activation rows for the MFMA path: rows x max(d, dq, f), or the confidence rows x d
         size_t kbig = (size_t)(D.f > (int)kmax ? D.f : (int)kmax);
@@ -93,6 +101,7 @@ Layout make_layout(const ssd_config& c)
     }
     l.ssq = o;    o += align_up((size_t)l.rows * (D.d / 16 + 1) * sizeof(float));  // per-tile sums of squares of the residual rows
     l.small = o;  o += align_up(4096);
+    l.vtok = o;   o += align_up((size_t)l.rows * sizeof(int32_t));   // token ids of a prompt block
     // context window of the confidence extraction: hidden-state taps [window][2L][d] of the last `window` processed
     // positions, and one confidence value per tap row of the window
     l.ring = o;       o += align_up((size_t)c.conf_window * 2 * D.L * D.d * sizeof(float));
@@ -256,17 +265,22 @@ int forward_single(ssd_ctx* c, const uint8_t* sub, int slot, int slot_out, int p
 // Full-model forward of the M tokens in SM_VTOK (M <= 16, or <= 64 where the wide tiling applies) at positions
 // *pos + pos_off + r; taps into tap rows 0..M-1; logits (when want_logits) into logits rows 0..M-1 and greedy tokens
 // into SM_TARGET -- for a block of more than 16 rows (a prompt block) only the last row's.
-int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
+int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits, const int32_t* tok_dev = nullptr)
 {
     const Dims& D = c->D;
     const Layout& Y = c->lay;
     float* x = c->f(Y.x);
     float* h = c->f(Y.h);
-    HIPCHK(embed_rows(D, c->w.embed, c->small_i() + SM_VTOK, M, x, c->stream), "embed");
+    HIPCHK(embed_rows(D, c->w.embed, tok_dev ? tok_dev : c->small_i() + SM_VTOK, M, x, c->stream), "embed");
     const int tap_ld = D.L * 2 * D.d;
     if (M > 16) {
-        // prompt block of up to 64 rows: the same sequence as the 16-row path below on 64-row weight tiles
-        if (!rows_wide_supported(D) || M > 64) return fail(c, SSD_ECAPACITY, "row block too large for this shape");
+        // prompt block: the same sequence as the 16-row path below, on 128 x 128 tiles over all rows of the block at
+        // once (up to SSD_PREFILL_ROWS), or on 64-row weight tiles (up to 64 rows) where the shape does not fit those.
+        // Only the last row of the last block leaves taps (in tap row 0), logits (row 0) and its greedy token
+        // (SM_TARGET[0]) behind.
+        const bool big = rows_big_supported(D);
+        if (big ? M > Y.rows : (!rows_wide_supported(D) || M > 64)) return fail(c, SSD_ECAPACITY, "row block too large for this shape");
+        auto gemm = [&](const RowsFused& f) { return big ? rows_big(D, f, c->stream) : rows_wide(D, f, c->stream); };
         uint16_t* hi = c->h16(Y.hi);
         uint16_t* lo = c->h16(Y.lo);
         uint16_t* xh = c->h16(Y.h);
@@ -281,41 +295,42 @@ int forward_rows(ssd_ctx* c, int M, int pos_off, int pos_host, bool want_logits)
             q.M = M; q.mode = 3;
             q.rope = c->f(Y.rope); q.pos_dev = c->pos_dev(); q.pos_off = pos_off; q.kc = c->kcache(l); q.vc = c->vcache(l);
             q.kpart = c->f(Y.part); q.kpart_floats = Y.part_floats;   // the attention scratch is idle outside attention
-            TIMED(SSD_K_ROWS_QKV, rows_wide(D, q, c->stream), "wide_qkv");
+            TIMED(SSD_K_ROWS_QKV, gemm(q), "wide_qkv");
             TIMED(SSD_K_ATTENTION, attention(D, c->f(Y.qkv), D.dq, c->kcache(l), c->vcache(l), c->pos_dev(), pos_off,
                                              pos_host, M, c->f(Y.part), nullptr, hi, lo, c->stream), "attention");
             RowsFused o = {};
             o.w[0] = c->wo[l]; o.n[0] = D.d; o.K = D.dq; o.bh = hi; o.bl = lo; o.ldb = D.dq; o.y = x; o.ldy = D.d; o.M = M;
-            o.mode = 1; o.tap = c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d; o.tap_ld = tap_ld;
+            o.mode = 1; o.tap = want_logits ? c->f(Y.taps) + ((size_t)l * 2 + 0) * D.d : nullptr; o.tap_ld = tap_ld; o.tap_only = M;
             o.gain_out = c->mlp_norm[l]; o.oh = xh; o.ol = xl; o.ldo = D.d; o.ssq_out = ssq;
             o.kpart = c->f(Y.part); o.kpart_floats = Y.part_floats;   // attention is done with its scratch
-            TIMED(SSD_K_ROWS_O, rows_wide(D, o, c->stream), "wide_o");
+            TIMED(SSD_K_ROWS_O, gemm(o), "wide_o");
             RowsFused gu = {};
             gu.w[0] = c->wg[l]; gu.w[1] = c->wu[l]; gu.n[0] = D.f; gu.n[1] = D.f; gu.K = D.d; gu.bh = xh; gu.bl = xl;
             gu.ldb = D.d; gu.ssq = ssq; gu.n_ssq = n_ssq;
             gu.oh = c->h16(Y.act); gu.ol = c->h16(Y.act) + (size_t)Y.rows * D.f; gu.ldo = D.f; gu.M = M;
             gu.mode = 2;
             gu.kpart = c->f(Y.part); gu.kpart_floats = Y.part_floats;
-            TIMED(SSD_K_ROWS_GATEUP, rows_wide(D, gu, c->stream), "wide_gateup");
+            TIMED(SSD_K_ROWS_GATEUP, gemm(gu), "wide_gateup");
             RowsFused dn = {};
             dn.w[0] = c->wd[l]; dn.n[0] = D.d; dn.K = D.f; dn.bh = gu.oh; dn.bl = gu.ol; dn.ldb = D.f; dn.y = x; dn.ldy = D.d;
-            dn.M = M; dn.mode = 1; dn.tap = c->f(Y.taps) + ((size_t)l * 2 + 1) * D.d; dn.tap_ld = tap_ld;
+            dn.M = M; dn.mode = 1; dn.tap = want_logits ? c->f(Y.taps) + ((size_t)l * 2 + 1) * D.d : nullptr; dn.tap_ld = tap_ld;
+            dn.tap_only = M;
             if (l + 1 < D.L || want_logits) {
                 dn.gain_out = l + 1 < D.L ? c->attn_norm[l + 1] : c->w.final_norm;
                 dn.oh = xh; dn.ol = xl; dn.ldo = D.d; dn.ssq_out = ssq;
             }
             dn.kpart = c->f(Y.part); dn.kpart_floats = Y.part_floats;
-            TIMED(SSD_K_ROWS_DOWN, rows_wide(D, dn, c->stream), "wide_down");
+            TIMED(SSD_K_ROWS_DOWN, gemm(dn), "wide_down");
         }
         if (want_logits) {   // last row only, through the 16-row kernel with one row
             const int r = M - 1;
             RowsFused lm = {};
             lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = xh + (size_t)r * D.d; lm.bl = xl + (size_t)r * D.d;
-            lm.ldb = D.d; lm.ssq = ssq + (size_t)r * n_ssq; lm.n_ssq = n_ssq; lm.y = c->f(Y.logits) + (size_t)r * D.V;
+            lm.ldb = D.d; lm.ssq = ssq + (size_t)r * n_ssq; lm.n_ssq = n_ssq; lm.y = c->f(Y.logits);
             lm.ldy = D.V; lm.M = 1; lm.mode = 0;
             TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows_lmhead");
-            HIPCHK(vocab_reduce(c->f(Y.logits) + (size_t)r * D.V, 1, D.V, c->cfg.conf_clamp, c->cfg.conf_eps,
-                                c->small_i() + SM_TARGET + r, 1, nullptr, nullptr, nullptr, c->stream), "vocab_reduce");
+            HIPCHK(vocab_reduce(c->f(Y.logits), 1, D.V, c->cfg.conf_clamp, c->cfg.conf_eps,
+                                c->small_i() + SM_TARGET, 1, nullptr, nullptr, nullptr, c->stream), "vocab_reduce");
         }
         return SSD_OK;
     }
@@ -458,6 +473,9 @@ int readback(ssd_ctx* c, const void* dev, size_t bytes, void* host)
 // rows themselves (fp32 weights), their logits, and 3 result values per row; `batch` tap rows go through per pass.
 struct ConfScratch {
     uint16_t* hi; uint16_t* lo; float* tapn; float* logits; float* res; int batch;
+    bool one_gemm;   // the context-window pass: a batch of more than 64 rows goes through the 128 x 128-tile GEMM in
+                     // one launch (the per-layer passes keep 64-row launches whatever their batch, so that the two
+                     // entry points for them run the same kernels on the same tiles)
 };
 
 // Enqueues the confidence (Eq. 1-4) of nb tap rows [nb][d] (nb <= sc.batch): final norm, LM head, vocabulary
@@ -468,18 +486,25 @@ int conf_batch(ssd_ctx* c, const ConfScratch& sc, const float* taps, int nb, flo
     const Dims& D = c->D;
     if (rows_fused_supported(D)) {
         HIPCHK(rows_prep(D, taps, D.d, c->w.final_norm, nb, D.d, D.eps, sc.hi, sc.lo, c->stream), "rows_prep taps");
-        const bool many = rows_many_supported(D, D.V, D.d);
-        for (int b = 0; many && b < nb; b += 64) {   // the LM head is streamed once per 64 tap rows
-            TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, sc.hi + (size_t)b * D.d, sc.lo + (size_t)b * D.d,
-                                               D.d, nb - b < 64 ? nb - b : 64, sc.logits + (size_t)b * D.V, D.V, c->stream),
-                  "rows conf lmhead");
-        }
-        for (int b = 0; !many && b < nb; b += 16) {
+        if (sc.one_gemm && nb > 64 && rows_big_supported(D)) {   // a real GEMM: all rows against the LM head in one launch
             RowsFused lm = {};
-            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = sc.hi + (size_t)b * D.d;
-            lm.bl = sc.lo + (size_t)b * D.d; lm.ldb = D.d; lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V;
-            lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
-            TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows conf lmhead");
+            lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = sc.hi; lm.bl = sc.lo; lm.ldb = D.d;
+            lm.y = sc.logits; lm.ldy = D.V; lm.M = nb; lm.mode = 0;
+            TIMED(SSD_K_ROWS_LMHEAD, rows_big(D, lm, c->stream), "rows conf lmhead");
+        } else if (rows_many_supported(D, D.V, D.d)) {
+            for (int b = 0; b < nb; b += 64) {   // the LM head is streamed once per 64 tap rows
+                TIMED(SSD_K_ROWS_LMHEAD, rows_many(D, c->w.lm_head, D.V, D.d, sc.hi + (size_t)b * D.d, sc.lo + (size_t)b * D.d,
+                                                   D.d, nb - b < 64 ? nb - b : 64, sc.logits + (size_t)b * D.V, D.V, c->stream),
+                      "rows conf lmhead");
+            }
+        } else {
+            for (int b = 0; b < nb; b += 16) {
+                RowsFused lm = {};
+                lm.w[0] = c->w.lm_head; lm.n[0] = D.V; lm.K = D.d; lm.bh = sc.hi + (size_t)b * D.d;
+                lm.bl = sc.lo + (size_t)b * D.d; lm.ldb = D.d; lm.y = sc.logits + (size_t)b * D.V; lm.ldy = D.V;
+                lm.M = nb - b < 16 ? nb - b : 16; lm.mode = 0;
+                TIMED(SSD_K_ROWS_LMHEAD, rows_fused(D, lm, c->stream), "rows conf lmhead");
+            }
         }
     } else {
         HIPCHK(rmsnorm_rows(taps, c->w.final_norm, nb, D.d, D.eps, sc.tapn, c->stream), "rmsnorm taps");
@@ -684,31 +709,37 @@ int ssd_prefill(ssd_ctx* c, const int32_t* tokens, int n, int32_t* first_token_o
     HIPCHK(set_state(c->small_i() + SM_TOK, 0, c->pos_dev(), 0, c->stream), "set_state");
     int last_M = 0;
     const int block = c->lay.prefill_rows;
+    int32_t* vtok = reinterpret_cast<int32_t*>(c->ws + c->lay.vtok);
     for (int p0 = 0; p0 < n; p0 += block) {
         int M = n - p0 < block ? n - p0 : block;
-        TokArg t = {};
-        for (int r = 0; r < M; r++) t.t[r] = tokens[p0 + r];
+        for (int r0 = 0; r0 < M; r0 += 64) {   // token ids travel as kernel arguments, 64 at a time
+            TokArg t = {};
+            const int nr = M - r0 < 64 ? M - r0 : 64;
+            for (int r = 0; r < nr; r++) t.t[r] = tokens[p0 + r0 + r];
+            HIPCHK(set_tokens(t, nr, nullptr, vtok + r0, c->stream), "set_tokens");
+        }
         bool last = p0 + M == n;
-        HIPCHK(set_tokens(t, M, nullptr, c->small_i() + SM_VTOK, c->stream), "set_tokens");
-        int rc = forward_rows(c, M, p0, 0, last);
+        int rc = forward_rows(c, M, p0, 0, last, vtok);
         if (rc) return rc;
         last_M = M;
     }
+    // a block of more than 16 rows leaves its last row's results in row 0, a shorter one in the row itself
+    const int res_row = last_M > 16 ? 0 : last_M - 1;
     // pending token = greedy token after the last prompt row; n_cached positions = n
-    HIPCHK(advance_state(c->pos_dev(), n, c->small_i() + SM_TOK, c->small_i() + SM_TARGET + (last_M - 1), c->stream),
+    HIPCHK(advance_state(c->pos_dev(), n, c->small_i() + SM_TOK, c->small_i() + SM_TARGET + res_row, c->stream),
            "advance_state");
-    int rc = readback(c, c->small_i() + SM_TARGET + (last_M - 1), sizeof(int32_t), first_token_out);
+    int rc = readback(c, c->small_i() + SM_TARGET + res_row, sizeof(int32_t), first_token_out);
     if (rc) return rc;
     c->n = n + 1;
     c->state = ST_IDLE;
-    c->tap_rows = 1; c->tap_row0 = last_M - 1;
+    c->tap_rows = 1; c->tap_row0 = res_row;
     c->logit_rows = 1;
     c->ring_count = 0;
     rc = ring_push(c, 0, 1);    // the last prompt position opens the context window
     if (rc) return rc;
-    // logits of the last row sit at row last_M-1; move them to row 0 so ssd_copy_logits sees one row
-    if (last_M > 1) {
-        HIPCHK(copy_f32(c->f(c->lay.logits) + (size_t)(last_M - 1) * c->D.V, c->f(c->lay.logits), c->D.V, c->stream),
+    // logits of the last row sit at row res_row; move them to row 0 so ssd_copy_logits sees one row
+    if (res_row > 0) {
+        HIPCHK(copy_f32(c->f(c->lay.logits) + (size_t)res_row * c->D.V, c->f(c->lay.logits), c->D.V, c->stream),
                "logits move");
     }
     c->st.committed = 1;
@@ -919,6 +950,7 @@ int ssd_layer_confidence(ssd_ctx* c, int row_begin, int n_rows, float* conf_out,
     ConfScratch sc;
     sc.hi = c->h16(Y.hi); sc.lo = c->h16(Y.lo); sc.tapn = c->f(Y.tapn); sc.logits = c->f(Y.logits);
     sc.res = c->small_f() + SM_CONF; sc.batch = 2 * c->D.L;     // all tap rows of a position in one pass
+    sc.one_gemm = false;
     int rc = confidence_rows(c, sc, row_begin, n_rows, conf_out, tap_conf_out, tap_maxprob_out, tap_argmax_out, true);
     if (rc) return rc;
     c->logit_rows = 0;  // the logits buffer was reused
@@ -947,7 +979,7 @@ int ssd_layer_confidence_static(ssd_ctx* c, int row_begin, int n_rows, float* co
     sc.tapn = reinterpret_cast<float*>(base + o);    o += align_up(rows_fused_supported(D) ? 0 : (size_t)B * D.d * 4);
     sc.logits = reinterpret_cast<float*>(base + o);  o += align_up((size_t)B * D.V * 4);
     sc.res = reinterpret_cast<float*>(base + o);     o += align_up((size_t)3 * B * 4);
-    sc.batch = B;
+    sc.batch = B; sc.one_gemm = false;
     if (o > static_scratch_bytes())
         return fail(c, SSD_ECAPACITY, "layer_confidence_static: 64 rows of this vocabulary / width exceed SSD_STATIC_SCRATCH_BYTES");
     return confidence_rows(c, sc, row_begin, n_rows, conf_out, tap_conf_out, tap_maxprob_out, tap_argmax_out, false);
@@ -965,8 +997,9 @@ int ssd_window_confidence(ssd_ctx* c, float* conf_out, float* tap_conf_out, int3
     const long rows = (long)nv * R;
     ConfScratch sc;
     sc.hi = c->h16(Y.hi); sc.lo = c->h16(Y.lo); sc.tapn = c->f(Y.tapn); sc.logits = c->f(Y.logits); sc.res = nullptr;
+    sc.one_gemm = true;
     // rows per pass of the LM head: what the staging buffers were sized for (at least the 2L rows of one position)
-    int B = 64;
+    int B = rows_big_supported(D) ? SSD_PREFILL_ROWS : 64;
     if (B > Y.logit_rows) B = Y.logit_rows;
     if (B > Y.conf_rows && B > Y.rows) B = Y.conf_rows > Y.rows ? Y.conf_rows : Y.rows;
     sc.batch = B;

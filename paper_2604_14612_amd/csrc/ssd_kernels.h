@@ -121,12 +121,17 @@ struct RowsFused {
     void* kc; void* vc;
     const float* ssq; int n_ssq;
     const float* gain_out; float* ssq_out;
-    float* kpart; size_t kpart_floats;  // rows_wide: scratch for a split along K (may be null: no split)
+    float* kpart; size_t kpart_floats;  // rows_wide / rows_big: scratch for a split along K (may be null: no split)
+    int tap_only;                       // > 0: only row tap_only - 1 writes its tap, into tap row 0
 };
 bool rows_fused_supported(const Dims& D);
 hipError_t rows_fused(const Dims& D, const RowsFused& f, hipStream_t s);
 // y[r][n] = sum_k W[n][k] (bh + bl)[r][k] for up to 64 pre-split rows at once (the per-layer confidence rows
 // against the LM head): W is streamed once for all of them.  bf16, N a multiple of 64, K a multiple of 128.
+// The same GEMMs for any number of rows in one launch, on 128 x 128 tiles (prompts, the context window): weights
+// cross the chip once for all rows.  16-bit weights; d, dq, dkv, V multiples of 128, f of 64, K of 64.
+bool rows_big_supported(const Dims& D);
+hipError_t rows_big(const Dims& D, const RowsFused& f, hipStream_t s);
 bool rows_many_supported(const Dims& D, int N, int K);
 hipError_t rows_many(const Dims& D, const void* w, int N, int K, const uint16_t* bh, const uint16_t* bl, int ldb, int M,
                      float* y, int ldy, hipStream_t s);

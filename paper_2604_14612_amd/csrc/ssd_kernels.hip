@@ -125,6 +125,14 @@ __device__ __forceinline__ float block_sum(float v, float* red)
     return t;
 }
 
+// Block barrier for data exchanged through LDS only: waits for this wave's LDS operations and then for the other
+// waves.  __syncthreads() also carries a fence that waits for every global load in flight (loads and stores share
+// one counter on this architecture), which would drain a register prefetch at every staging step; a loaded register
+// is still protected by the wait the compiler places before its first use.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ---------------------------------------------------------------------------------------------
@@ -1043,6 +1051,8 @@ struct RowsP2 {
     const float* ssq; int n_ssq; float eps;     // consumer: partial sums of squares [M][n_ssq] of the input rows (or null)
     const float* gain_out; float* ssq_out;      // RESID producer: gain of the next norm -> oh/ol = split(x * gain), ssq_out [M][n/16]
     int ksplit; float* kpart;                   // wide RESID only: K cut into ksplit slices (grid.y), raw sums to kpart [ksplit][M][n]
+    int tap_only;                               // > 0: only row tap_only - 1 writes its tap (a prompt needs the last row's only)
+    int n_tiles;                                // large-tile kernel: weight tiles of the launch
 };
 
 // hi = rne(v), lo = rne(v - hi) in the 16-bit storage type (bf16, or fp16 when f16 is set)
@@ -1382,7 +1392,7 @@ __device__ __forceinline__ void m6_epilogue(const RowsP2& p, int tile, int m, in
         float* dst = p.y + (size_t)m * p.ldy + colx;
         const float tv = *dst + v;
         *dst = tv;
-        if (p.tap) p.tap[(size_t)m * p.tap_ld + colx] = tv;
+        if (p.tap && (p.tap_only <= 0 || m == p.tap_only - 1)) p.tap[(size_t)(p.tap_only > 0 ? 0 : m) * p.tap_ld + colx] = tv;
         if (p.gain_out) {
             split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
             const float sq = wave_sum(tv * tv);   // the wave holds the tile's 64 columns of row m
@@ -1609,6 +1619,249 @@ __global__ __launch_bounds__(64) void rows_finish_kernel(RowsP2 p)
     m6_epilogue<MODE, F16>(p, tile, m, lane, v, v2);
 }
 
+// --- large-tile variant: any number of activation rows in one launch (whole prompts, the context window) --------
+// With hundreds of rows the work is a real GEMM and the weights should cross the chip once, not once per 64 rows.
+// A block owns 128 logical weight rows (64 gate + 64 up rows in SwiGLU mode) x 128 activation rows (grid.y walks
+// the row blocks, so the blocks that share a weight tile run side by side and all but the first find it in the
+// cache).  64-wide K stripes of the weights and of the hi / lo rows go through LDS (register prefetch of the next
+// stripe while one is multiplied; 54 KB per block, two blocks per CU cover each other's staging); the four waves
+// form a 2 x 2 grid of 64 x 64 sub-tiles, 32 MFMAs (hi and lo) per 12 LDS fragment reads.  The finished tile goes
+// back through LDS in two halves so that the epilogue sees (row, 128 consecutive columns): same modes, same RMSNorm
+// folding as the 64-row kernel; weight rows in natural order (a rotary pair e, e + hd/2 sits in one tile).
+constexpr int MB_TN = 128, MB_TM = 128, MB_CK = 64;
+constexpr int MB_PITCH = MB_CK * 2 + 16;   // bytes per staged row
+constexpr int MB_EP = 132;                 // floats per row of the epilogue tile
+
+template <int MODE>
+__device__ __forceinline__ const uint16_t* mb_row(const RowsP2& p, int tile, int r)
+{
+    if (MODE == RM_SWIGLU) return (const uint16_t*)p.w[r >> 6] + (size_t)(tile * 64 + (r & 63)) * p.K;
+    int row = tile * MB_TN + r;
+    if (row < p.n[0]) return (const uint16_t*)p.w[0] + (size_t)row * p.K;
+    row -= p.n[0];
+    if (row < p.n[1]) return (const uint16_t*)p.w[1] + (size_t)row * p.K;
+    return (const uint16_t*)p.w[2] + (size_t)(row - p.n[1]) * p.K;
+}
+
+template <int MODE, bool F16>
+__global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
+{
+    extern __shared__ __align__(16) unsigned char smb[];
+    __shared__ float rs[MB_TM];
+    unsigned char* Ws = smb;                          // [128][PITCH]
+    unsigned char* Bh = smb + MB_TN * MB_PITCH;       // [128][PITCH]
+    unsigned char* Bl = Bh + MB_TM * MB_PITCH;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int K = p.K, M = p.M;
+    const int NCall = K / MB_CK;
+    const int S = p.ksplit > 1 ? p.ksplit : 1;
+    // Block id -> (weight tile and K slice, row block).  Workgroups go to the eight XCDs round-robin by id and each
+    // XCD has its own L2: ids c, c + 8, c + 16, .. (one XCD, dispatched back to back) take the row blocks of ONE
+    // weight tile, so the tile comes out of HBM once per XCD and the other row blocks find it in that L2.
+    int tile, slice, m0;
+    {
+        const int mb = (M + MB_TM - 1) / MB_TM, units = p.n_tiles * S;
+        const int L = blockIdx.x, full = units & ~7;
+        int unit, y;
+        if (L < full * mb) { const int ch = L / (8 * mb), r = L % (8 * mb); unit = ch * 8 + (r & 7); y = r >> 3; }
+        else { const int r = L - full * mb, rem = units - full; unit = full + r % rem; y = r / rem; }
+        tile = unit % p.n_tiles; slice = unit / p.n_tiles; m0 = y * MB_TM;
+    }
+    const int c_begin = (int)((long)NCall * slice / S), NC = (int)((long)NCall * (slice + 1) / S) - c_begin;
+    // a stripe is 128 rows x 8 vectors of 16 bytes per array; thread takes row tid / 8 + 32 u, vector tid % 8.
+    // Addresses are a block-uniform base plus a 32-bit element offset per thread (few registers: two stripes of
+    // twelve vectors are in flight per thread).
+    const int kk = (tid & 7) * 8;
+    const uint16_t* wb[4];   // uniform over the block
+    int woff[4], boff[4], dst[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+        const int row = (tid >> 3) + 32 * u;
+        wb[u] = mb_row<MODE>(p, tile, 32 * u);
+        woff[u] = (tid >> 3) * K + kk;
+        boff[u] = min(m0 + row, M - 1) * p.ldb + kk;   // rows past M read a valid row, never stored
+        dst[u] = row * MB_PITCH + kk * 2;
+    }
+    constexpr int MB_D = 2;   // stripes in flight
+    u32x4_t rw[MB_D][4], rh[MB_D][4], rl[MB_D][4];
+    auto gload = [&](int slot, int ck) {
+        const int k0 = (c_begin + ck) * MB_CK;
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            rw[slot][u] = *reinterpret_cast<const u32x4_t*>(wb[u] + woff[u] + k0);   // cached: the other row blocks read the same tile
+            rh[slot][u] = *reinterpret_cast<const u32x4_t*>(p.bh + boff[u] + k0);
+            rl[slot][u] = *reinterpret_cast<const u32x4_t*>(p.bl + boff[u] + k0);
+        }
+    };
+    auto stage = [&](int slot) {
+        lds_barrier();   // the previous stripe is fully consumed
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            *reinterpret_cast<u32x4_t*>(Ws + dst[u]) = rw[slot][u];
+            *reinterpret_cast<u32x4_t*>(Bh + dst[u]) = rh[slot][u];
+            *reinterpret_cast<u32x4_t*>(Bl + dst[u]) = rl[slot][u];
+        }
+        lds_barrier();
+    };
+    const int wn = wave & 1, wm = wave >> 1;
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // One stripe = 2 k-steps x 4 groups of 16 activation rows.  The weight fragments of both k-steps are read up
+    // front; the hi / lo fragments of step t + 1 are requested before the eight MFMAs of step t are issued, so the
+    // LDS latency hides behind the matrix pipe.  No conditions inside (row groups past M multiply clamped copies of
+    // the last row; their results are never stored): one straight-line block for the scheduler.
+    const unsigned char* wfrag = Ws + (wn * 64 + r16) * MB_PITCH + g * 16;
+    const unsigned char* hfrag = Bh + (wm * 64 + r16) * MB_PITCH + g * 16;
+    const unsigned char* lfrag = Bl + (wm * 64 + r16) * MB_PITCH + g * 16;
+    auto multiply = [&]() {
+        constexpr int KS = MB_CK / 32, NSTEP = KS * 4;
+        u32x4_t a[KS][4], h[2], l[2];
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) a[ks][i] = *reinterpret_cast<const u32x4_t*>(wfrag + i * 16 * MB_PITCH + ks * 64);
+        h[0] = *reinterpret_cast<const u32x4_t*>(hfrag);
+        l[0] = *reinterpret_cast<const u32x4_t*>(lfrag);
+#pragma unroll
+        for (int t = 0; t < NSTEP; t++) {
+            const int ks = t >> 2, j = t & 3;
+            if (t + 1 < NSTEP) {
+                const int o = ((t + 1) & 3) * 16 * MB_PITCH + ((t + 1) >> 2) * 64;
+                h[(t + 1) & 1] = *reinterpret_cast<const u32x4_t*>(hfrag + o);
+                l[(t + 1) & 1] = *reinterpret_cast<const u32x4_t*>(lfrag + o);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; i++) acc[i][j] = mfma_h16<F16>(a[ks][i], h[t & 1], acc[i][j]);
+#pragma unroll
+            for (int i = 0; i < 4; i++) acc[i][j] = mfma_h16<F16>(a[ks][i], l[t & 1], acc[i][j]);
+        }
+    };
+#pragma unroll
+    for (int sl = 0; sl < MB_D; sl++)
+        if (sl < NC) gload(sl, sl);
+    // RMS scale of the block's activation rows from the producer's per-tile sums of squares (a K-split launch leaves
+    // the scaling to its finishing kernel)
+    if (tid < MB_TM) rs[tid] = 1.0f;
+    if (MODE != RM_RESID && p.ssq && S == 1) {
+        __syncthreads();
+        for (int c = wave; c < MB_TM; c += 4) {
+            const int m = min(m0 + c, M - 1);
+            float sq = 0.f;
+            for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)m * p.n_ssq + i];
+            sq = wave_sum(sq);
+            if (lane == 0) rs[c] = 1.0f / sqrtf(sq / (float)K + p.eps);
+        }
+    }
+    int ck0 = 0;
+    for (; ck0 + 2 * MB_D <= NC; ck0 += MB_D) {   // steady state: every step refills its slot, no conditions
+#pragma unroll
+        for (int sl = 0; sl < MB_D; sl++) {
+            stage(sl);
+            gload(sl, ck0 + sl + MB_D);
+            multiply();
+        }
+    }
+    for (; ck0 < NC; ck0 += MB_D) {               // drain
+#pragma unroll
+        for (int sl = 0; sl < MB_D; sl++) {
+            if (ck0 + sl < NC) {   // uniform
+                stage(sl);
+                if (ck0 + sl + MB_D < NC) gload(sl, ck0 + sl + MB_D);
+                multiply();
+            }
+        }
+    }
+    // epilogue, 64 activation rows at a time: ep[row][column] through LDS, then thread -> (column n, rows mm, mm + 2, ..)
+    float* ep = reinterpret_cast<float*>(smb);
+    const int n = tid & 127, mm = tid >> 7;
+    for (int hf = 0; hf < 2; hf++) {
+        if (m0 + hf * 64 >= M) break;   // uniform over the block
+        __syncthreads();
+        if (wm == hf) {
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    *reinterpret_cast<f32x4_t*>(ep + (j * 16 + r16) * MB_EP + wn * 64 + i * 16 + 4 * g) = acc[i][j];
+        }
+        __syncthreads();
+        for (int it = 0; it < 32; it++) {
+            const int ml = mm + 2 * it, m = m0 + hf * 64 + ml;   // uniform over a wave
+            if (m >= M) break;
+            float v = ep[ml * MB_EP + n];
+            if (S > 1) {   // raw sums of this K slice: [slice][M][n_total] (residual projections only)
+                p.kpart[((size_t)slice * M + m) * ((size_t)p.n_tiles * MB_TN) + (size_t)tile * MB_TN + n] = v;
+                continue;
+            }
+            const float sc = rs[hf * 64 + ml];
+            if (MODE == RM_STORE) {
+                p.y[(size_t)m * p.ldy + (size_t)tile * MB_TN + n] = v * sc;
+            } else if (MODE == RM_SWIGLU) {
+                if (n < 64) {
+                    const float gt = v * sc, up = ep[ml * MB_EP + n + 64] * sc;
+                    split_store(gt / (1.0f + __expf(-gt)) * up, p.oh, p.ol, (size_t)m * p.ldo + (size_t)tile * 64 + n, F16);
+                }
+            } else if (MODE == RM_RESID) {
+                const size_t colx = (size_t)tile * MB_TN + n;
+                float* dsty = p.y + (size_t)m * p.ldy + colx;
+                const float tv = *dsty + v;
+                *dsty = tv;
+                if (p.tap && (p.tap_only <= 0 || m == p.tap_only - 1)) p.tap[(size_t)(p.tap_only > 0 ? 0 : m) * p.tap_ld + colx] = tv;
+                if (p.gain_out) {
+                    split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
+                    const float sq = wave_sum(tv * tv);   // the wave holds 64 consecutive columns of row m
+                    if (lane == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile * 2 + (n >> 6)] = sq;
+                }
+            } else {   // QKV: natural row order, the rotary partner of column n is n ^ (hd / 2) of the same tile
+                const int row = tile * MB_TN + n;
+                const int pos = p.pos_dev[0] + p.pos_off + m;
+                v *= sc;
+                if (row < p.dq + p.dkv) {
+                    const bool is_q = row < p.dq;
+                    const int jj = is_q ? row : row - p.dq;
+                    const int head = jj / p.hd, e = jj % p.hd, half = p.hd >> 1, i = e % half;
+                    const float other = ep[ml * MB_EP + (n ^ half)] * sc;
+                    const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+                    const float ov = e < half ? v * cs[0] - other * cs[1] : v * cs[0] + other * cs[1];
+                    if (is_q) p.y[(size_t)m * p.ldy + (size_t)head * p.hd + e] = ov;
+                    else kv_put(p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, ov, p.kt);
+                } else {
+                    const int e = row - p.dq - p.dkv;
+                    kv_put(p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v, p.kt);
+                }
+            }
+        }
+    }
+}
+
+bool rows_big_supported(const Dims& D)
+{
+    return D.wt != WT_F32 && D.d % 128 == 0 && D.dq % 128 == 0 && D.dkv % 128 == 0 && D.f % 64 == 0 && D.V % 128 == 0 &&
+           (D.hd == 64 || D.hd == 128);
+}
+
+template <int MODE, bool F16>
+static hipError_t launch_big(const RowsP2& p, int n_tiles, hipStream_t s)
+{
+    const size_t lds = (size_t)(MB_TN + 2 * MB_TM) * MB_PITCH;
+    static_assert((size_t)64 * MB_EP * 4 <= (size_t)(MB_TN + 2 * MB_TM) * MB_PITCH, "epilogue tile fits the staging area");
+    static std::atomic<size_t> lds_limit{0};  // per instantiation
+    {
+        hipError_t e = ensure_lds((const void*)rows_big_kernel<MODE, F16>, lds, lds_limit);
+        if (e != hipSuccess) return e;
+    }
+    const int S = p.ksplit > 1 ? p.ksplit : 1;
+    hipLaunchKernelGGL((rows_big_kernel<MODE, F16>), dim3(n_tiles * ((p.M + MB_TM - 1) / MB_TM) * S), dim3(256), lds, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || S == 1) return e;
+    hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(n_tiles * 2, p.M), dim3(64), 0, s, p);
+    return hipGetLastError();
+}
+
 bool rows_many_supported(const Dims& D, int N, int K)
 {
     return D.wt != WT_F32 && N % 64 == 0 && K % M6_CK == 0 && K >= M6_CK;
@@ -1657,6 +1910,7 @@ static void fill_rows_params(const Dims& D, const RowsFused& f, RowsP2& p)
     p.tap = f.tap; p.tap_ld = f.tap_ld; p.M = f.M; p.rope = f.rope; p.pos_dev = f.pos_dev; p.pos_off = f.pos_off;
     p.hd = D.hd; p.dq = D.dq; p.dkv = D.dkv; p.max_seq = D.max_seq; p.kc = f.kc; p.vc = f.vc; p.kt = D.kt;
     p.ssq = f.ssq; p.n_ssq = f.n_ssq; p.eps = D.eps; p.gain_out = f.gain_out; p.ssq_out = f.ssq_out;
+    p.tap_only = f.tap_only;
 }
 
 hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
@@ -1691,6 +1945,43 @@ hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
         case RM_RESID: return f16 ? launch_wide<RM_RESID, true>(p, n_tiles, s, D.opt) : launch_wide<RM_RESID, false>(p, n_tiles, s, D.opt);
         case RM_SWIGLU: return f16 ? launch_wide<RM_SWIGLU, true>(p, n_tiles, s, D.opt) : launch_wide<RM_SWIGLU, false>(p, n_tiles, s, D.opt);
         case RM_QKV: return f16 ? launch_wide<RM_QKV, true>(p, n_tiles, s, D.opt) : launch_wide<RM_QKV, false>(p, n_tiles, s, D.opt);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t rows_big(const Dims& D, const RowsFused& f, hipStream_t s)
+{
+    if (D.wt == WT_F32 || f.M < 1 || f.K % MB_CK || f.K < MB_CK) return hipErrorInvalidValue;
+    if (f.mode == RM_SWIGLU ? (f.n[0] % 64 || f.n[1] != f.n[0]) : (f.n[0] % MB_TN || f.n[1] % MB_TN || f.n[2] % MB_TN))
+        return hipErrorInvalidValue;
+    if (f.ssq && (f.mode == RM_RESID || f.n_ssq < 1)) return hipErrorInvalidValue;
+    if (f.gain_out && (f.mode != RM_RESID || !f.oh || !f.ol || !f.ssq_out)) return hipErrorInvalidValue;
+    if (f.mode == RM_QKV && (f.n[0] != D.dq || f.n[1] != D.dkv || f.n[2] != D.dkv || (D.hd != 64 && D.hd != 128)))
+        return hipErrorInvalidValue;
+    RowsP2 p = {};
+    fill_rows_params(D, f, p);
+    const int n_tiles = f.mode == RM_SWIGLU ? f.n[0] / 64 : (f.n[0] + f.n[1] + f.n[2]) / MB_TN;
+    const int m_blocks = (f.M + MB_TM - 1) / MB_TM;
+    p.n_tiles = n_tiles;
+    const bool f16 = D.wt == WT_F16;
+    // two blocks fit a CU: a residual projection with fewer than 256 blocks is cut along K (its raw sums go to
+    // kpart and rows_finish_kernel adds the slices in a fixed order)
+    p.ksplit = 1; p.kpart = nullptr;
+    const int force_ks = D.opt ? D.opt->wide_ksplit : 0;
+    if (f.kpart && f.mode == RM_RESID && force_ks != 1) {
+        const size_t per_slice = (size_t)f.M * n_tiles * MB_TN;
+        int ks = force_ks > 1 ? force_ks : 384 / (n_tiles * m_blocks);
+        const int nc = f.K / MB_CK;
+        if (ks > 8) ks = 8;
+        if (ks > nc) ks = nc;
+        if ((size_t)ks * per_slice > f.kpart_floats) ks = (int)(f.kpart_floats / per_slice);
+        if (ks > 1) { p.ksplit = ks; p.kpart = f.kpart; }
+    }
+    switch (f.mode) {
+        case RM_STORE: return f16 ? launch_big<RM_STORE, true>(p, n_tiles, s) : launch_big<RM_STORE, false>(p, n_tiles, s);
+        case RM_RESID: return f16 ? launch_big<RM_RESID, true>(p, n_tiles, s) : launch_big<RM_RESID, false>(p, n_tiles, s);
+        case RM_SWIGLU: return f16 ? launch_big<RM_SWIGLU, true>(p, n_tiles, s) : launch_big<RM_SWIGLU, false>(p, n_tiles, s);
+        case RM_QKV: return f16 ? launch_big<RM_QKV, true>(p, n_tiles, s) : launch_big<RM_QKV, false>(p, n_tiles, s);
         default: return hipErrorInvalidValue;
     }
 }

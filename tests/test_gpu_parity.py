@@ -14,7 +14,9 @@ GQA32 = ModelShape(2, 256, 4, 2, 688, 1024, dtype="fp32")       # fp32 weights, 
 MINI16 = ModelShape(4, 512, 8, 8, 1408, 2048, dtype="fp16")     # fp16 (the paper's precision), head_dim 64, MFMA path
 GQA16 = ModelShape(3, 512, 4, 2, 688, 1024, dtype="fp16")       # fp16, head_dim 128, grouped heads, FFN not a
                                                                  # multiple of 64: the plain multi-row path
-SHAPES = {"tiny": WORKLOADS["tiny"].shape, "mini": MINI, "gqa": GQA, "gqa32": GQA32, "mini16": MINI16, "gqa16": GQA16}
+WIDE64 = ModelShape(3, 512, 8, 1, 1408, 2048)                   # bf16, one KV head of 64: fits the 64-row prompt tiling only
+SHAPES = {"tiny": WORKLOADS["tiny"].shape, "mini": MINI, "gqa": GQA, "gqa32": GQA32, "mini16": MINI16, "gqa16": GQA16,
+          "wide64": WIDE64}
 
 
 @pytest.fixture(scope="module")
@@ -26,8 +28,8 @@ def ssd():
     return lib
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16"])
-@pytest.mark.parametrize("plen", [1, 16, 17, 45, 64, 65, 150])   # 16-row and 64-row prompt blocks, ragged tails
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16", "wide64"])
+@pytest.mark.parametrize("plen", [1, 16, 17, 45, 64, 65, 150])   # 16-row blocks, 128 x 128-tile and 64-row blocks, ragged tails
 def test_prefill_logits_and_first_token(ssd, name, plen):
     shape = SHAPES[name]
     orc, ctx = make_pair(shape, 5, 160, norm_gain_std=0.1)
@@ -39,6 +41,21 @@ def test_prefill_logits_and_first_token(ssd, name, plen):
     if decisive(ref, shape.dtype):
         assert tok == int(np.argmax(ref))
     assert ctx.ssd_get_stats()["n_tokens"] == plen + 1
+
+
+@pytest.mark.parametrize("name", ["mini", "gqa", "mini16", "wide64"])
+@pytest.mark.parametrize("plen", [129, 512, 513, 700])
+def test_long_prompt_blocks(ssd, name, plen):
+    """Prompts of several 128-row blocks per pass and of more than one pass (SSD_PREFILL_ROWS = 512 rows), ragged: the
+    last row's logits, the first token, and -- through one draft / verify cycle on top -- the K/V rows the prompt
+    pass wrote and the taps it left behind."""
+    shape = SHAPES[name]
+    orc, ctx = make_pair(shape, 5, plen + 16, max_k=4, norm_gain_std=0.1)
+    prompt = make_prompt(shape.vocab, plen, 3).tolist()
+    mask = np.array(MASKS[name][1], np.uint8)
+    st = lockstep_ssd(ctx, orc, prompt, 0, [4], mask, shape.dtype)
+    print("long prompt", name, plen, "max err %.2e" % st["max_err"], "accepted", st["accepted"])
+    assert st["unpinned_cycles"] <= 1 and st["verify_rows"] == 5
 
 
 @pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16"])
@@ -87,6 +104,7 @@ MASKS = {
     "gqa32": [[0, 0], [1, 0]],
     "mini16": [[0, 0, 0, 0], [0, 1, 1, 0]],
     "gqa16": [[0, 0, 0], [0, 1, 0]],
+    "wide64": [[0, 0, 0], [0, 1, 0]],
 }
 
 
