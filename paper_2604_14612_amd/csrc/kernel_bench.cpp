@@ -276,11 +276,13 @@ int main(int argc, char** argv)
         return 0;
     }
     if (std::getenv("KB_BIG")) {
-        // whole-prompt GEMMs: one launch of the 128 x 128-tile kernel over R rows against R / 64 launches of the 64-row
+        // whole-prompt GEMMs: one launch of the large-tile kernel (256 or 128 weight rows x 128 rows) over R rows against R / 64 launches of the 64-row
         // kernel (flops: one bf16 product per weight and row; the kernels do two, hi and lo)
         const int pad = std::getenv("KB_PAD") ? std::atoi(std::getenv("KB_PAD")) : 0;   // extra elements per activation row
         std::printf("activation row pitch = K + %d elements\n", pad);
         const int only_r = std::getenv("KB_BIG_R") ? std::atoi(std::getenv("KB_BIG_R")) : 0;   // one row count only
+        opts.wide_depth = std::getenv("KB_TN") ? std::atoi(std::getenv("KB_TN")) : 0;   // weight rows per tile: 128, 256, 0 = library's choice
+        std::printf("weight rows per tile: %d (0 = the library's choice)\n", opts.wide_depth);
         for (int R : {128, 256, 512, 1024}) {
             if (only_r && R != only_r) continue;
             uint16_t *bh, *bl, *oh, *ol;
@@ -309,7 +311,7 @@ int main(int argc, char** argv)
                 const double flops = 2.0 * (double)sh.welems * R;
                 for (int big = 1; big >= 0; big--) {
                     char nm[96];
-                    std::snprintf(nm, sizeof nm, "%s %4d rows, %s", sh.name, R, big ? "128x128 tiles, 1 launch" : "64-row kernel per 64 rows");
+                    std::snprintf(nm, sizeof nm, "%s %4d rows, %s", sh.name, R, big ? "large tiles, 1 launch" : "64-row kernel per 64 rows");
                     hipEvent_t a, b;
                     CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
                     float best = 1e30f;

@@ -1628,28 +1628,37 @@ __global__ __launch_bounds__(64) void rows_finish_kernel(RowsP2 p)
 // form a 2 x 2 grid of 64 x 64 sub-tiles, 32 MFMAs (hi and lo) per 12 LDS fragment reads.  The finished tile goes
 // back through LDS in two halves so that the epilogue sees (row, 128 consecutive columns): same modes, same RMSNorm
 // folding as the 64-row kernel; weight rows in natural order (a rotary pair e, e + hd/2 sits in one tile).
-constexpr int MB_TN = 128, MB_TM = 128, MB_CK = 64;
+constexpr int MB_TM = 128, MB_CK = 64;
 constexpr int MB_PITCH = MB_CK * 2 + 16;   // bytes per staged row
-constexpr int MB_EP = 132;                 // floats per row of the epilogue tile
 
-template <int MODE>
+// weight row of logical row r of tile `tile` (TN logical rows per tile; SwiGLU: TN/2 gate rows, then TN/2 up rows)
+template <int MODE, int TN>
 __device__ __forceinline__ const uint16_t* mb_row(const RowsP2& p, int tile, int r)
 {
-    if (MODE == RM_SWIGLU) return (const uint16_t*)p.w[r >> 6] + (size_t)(tile * 64 + (r & 63)) * p.K;
-    int row = tile * MB_TN + r;
+    if (MODE == RM_SWIGLU) return (const uint16_t*)p.w[r / (TN / 2)] + (size_t)(tile * (TN / 2) + r % (TN / 2)) * p.K;
+    int row = tile * TN + r;
     if (row < p.n[0]) return (const uint16_t*)p.w[0] + (size_t)row * p.K;
     row -= p.n[0];
     if (row < p.n[1]) return (const uint16_t*)p.w[1] + (size_t)row * p.K;
     return (const uint16_t*)p.w[2] + (size_t)(row - p.n[1]) * p.K;
 }
 
-template <int MODE, bool F16>
-__global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
+// TN = weight rows per tile: 128 (256 threads, two blocks per CU) or 256 (512 threads, one block per CU: a third
+// fewer bytes per MFMA through the CU's memory path, which is what bounds this kernel; used when the launch still
+// has blocks for most CUs)
+template <int MODE, bool F16, int TN>
+__global__ __launch_bounds__(TN * 2, 2) void rows_big_kernel(RowsP2 p)
 {
+    constexpr int NTH = TN * 2, WN = TN / 64;   // threads; waves along the weight rows (x 2 along the activation rows)
+    constexpr int RPS = NTH / 8;                // rows covered by one load step of the block
+    constexpr int BU = MB_TM / RPS;             // load steps per activation plane
+    constexpr int EP = TN + 4;                  // floats per row of the epilogue tile
+    constexpr int NBUF = TN == 256 ? 2 : 1;     // staging buffers: the large tile (one block per CU) double-buffers in LDS
+    constexpr int BUFB = (TN + 2 * MB_TM) * MB_PITCH;
     extern __shared__ __align__(16) unsigned char smb[];
     __shared__ float rs[MB_TM];
-    unsigned char* Ws = smb;                          // [128][PITCH]
-    unsigned char* Bh = smb + MB_TN * MB_PITCH;       // [128][PITCH]
+    unsigned char* Ws = smb;                          // [TN][PITCH]
+    unsigned char* Bh = smb + TN * MB_PITCH;          // [128][PITCH]
     unsigned char* Bl = Bh + MB_TM * MB_PITCH;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
@@ -1669,42 +1678,49 @@ __global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
         tile = unit % p.n_tiles; slice = unit / p.n_tiles; m0 = y * MB_TM;
     }
     const int c_begin = (int)((long)NCall * slice / S), NC = (int)((long)NCall * (slice + 1) / S) - c_begin;
-    // a stripe is 128 rows x 8 vectors of 16 bytes per array; thread takes row tid / 8 + 32 u, vector tid % 8.
-    // Addresses are a block-uniform base plus a 32-bit element offset per thread (few registers: two stripes of
-    // twelve vectors are in flight per thread).
+    // a stripe is TN + 2 x 128 rows of 8 vectors of 16 bytes; thread takes row tid / 8 + RPS u, vector tid % 8.
+    // Addresses are a block-uniform base plus a 32-bit element offset per thread (few registers: two stripes are in
+    // flight per thread).
     const int kk = (tid & 7) * 8;
     const uint16_t* wb[4];   // uniform over the block
-    int woff[4], boff[4], dst[4];
+    int boff[BU], dstb[BU];
+    const int woff = (tid >> 3) * K + kk, dstw = (tid >> 3) * MB_PITCH + kk * 2;
 #pragma unroll
-    for (int u = 0; u < 4; u++) {
-        const int row = (tid >> 3) + 32 * u;
-        wb[u] = mb_row<MODE>(p, tile, 32 * u);
-        woff[u] = (tid >> 3) * K + kk;
+    for (int u = 0; u < 4; u++) wb[u] = mb_row<MODE, TN>(p, tile, RPS * u);
+#pragma unroll
+    for (int u = 0; u < BU; u++) {
+        const int row = (tid >> 3) + RPS * u;
         boff[u] = min(m0 + row, M - 1) * p.ldb + kk;   // rows past M read a valid row, never stored
-        dst[u] = row * MB_PITCH + kk * 2;
+        dstb[u] = row * MB_PITCH + kk * 2;
     }
     constexpr int MB_D = 2;   // stripes in flight
-    u32x4_t rw[MB_D][4], rh[MB_D][4], rl[MB_D][4];
+    u32x4_t rw[MB_D][4], rh[MB_D][BU], rl[MB_D][BU];
     auto gload = [&](int slot, int ck) {
         const int k0 = (c_begin + ck) * MB_CK;
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            rw[slot][u] = *reinterpret_cast<const u32x4_t*>(wb[u] + woff[u] + k0);   // cached: the other row blocks read the same tile
+        for (int u = 0; u < 4; u++)   // cached loads: the other row blocks read the same tile
+            rw[slot][u] = *reinterpret_cast<const u32x4_t*>(wb[u] + woff + k0);
+#pragma unroll
+        for (int u = 0; u < BU; u++) {
             rh[slot][u] = *reinterpret_cast<const u32x4_t*>(p.bh + boff[u] + k0);
             rl[slot][u] = *reinterpret_cast<const u32x4_t*>(p.bl + boff[u] + k0);
         }
     };
+    auto put = [&](int slot, int buf) {   // registers of `slot` -> staging buffer `buf`
+#pragma unroll
+        for (int u = 0; u < 4; u++) *reinterpret_cast<u32x4_t*>(Ws + buf * BUFB + dstw + u * RPS * MB_PITCH) = rw[slot][u];
+#pragma unroll
+        for (int u = 0; u < BU; u++) {
+            *reinterpret_cast<u32x4_t*>(Bh + buf * BUFB + dstb[u]) = rh[slot][u];
+            *reinterpret_cast<u32x4_t*>(Bl + buf * BUFB + dstb[u]) = rl[slot][u];
+        }
+    };
     auto stage = [&](int slot) {
         lds_barrier();   // the previous stripe is fully consumed
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            *reinterpret_cast<u32x4_t*>(Ws + dst[u]) = rw[slot][u];
-            *reinterpret_cast<u32x4_t*>(Bh + dst[u]) = rh[slot][u];
-            *reinterpret_cast<u32x4_t*>(Bl + dst[u]) = rl[slot][u];
-        }
+        put(slot, 0);
         lds_barrier();
     };
-    const int wn = wave & 1, wm = wave >> 1;
+    const int wn = wave % WN, wm = wave / WN;
     f32x4_t acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; i++)
@@ -1717,20 +1733,21 @@ __global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
     const unsigned char* wfrag = Ws + (wn * 64 + r16) * MB_PITCH + g * 16;
     const unsigned char* hfrag = Bh + (wm * 64 + r16) * MB_PITCH + g * 16;
     const unsigned char* lfrag = Bl + (wm * 64 + r16) * MB_PITCH + g * 16;
-    auto multiply = [&]() {
+    auto multiply = [&](int buf) {
         constexpr int KS = MB_CK / 32, NSTEP = KS * 4;
         u32x4_t a[KS][4], h[2], l[2];
+        const int bo = buf * BUFB;
 #pragma unroll
         for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-            for (int i = 0; i < 4; i++) a[ks][i] = *reinterpret_cast<const u32x4_t*>(wfrag + i * 16 * MB_PITCH + ks * 64);
-        h[0] = *reinterpret_cast<const u32x4_t*>(hfrag);
-        l[0] = *reinterpret_cast<const u32x4_t*>(lfrag);
+            for (int i = 0; i < 4; i++) a[ks][i] = *reinterpret_cast<const u32x4_t*>(wfrag + bo + i * 16 * MB_PITCH + ks * 64);
+        h[0] = *reinterpret_cast<const u32x4_t*>(hfrag + bo);
+        l[0] = *reinterpret_cast<const u32x4_t*>(lfrag + bo);
 #pragma unroll
         for (int t = 0; t < NSTEP; t++) {
             const int ks = t >> 2, j = t & 3;
             if (t + 1 < NSTEP) {
-                const int o = ((t + 1) & 3) * 16 * MB_PITCH + ((t + 1) >> 2) * 64;
+                const int o = bo + ((t + 1) & 3) * 16 * MB_PITCH + ((t + 1) >> 2) * 64;
                 h[(t + 1) & 1] = *reinterpret_cast<const u32x4_t*>(hfrag + o);
                 l[(t + 1) & 1] = *reinterpret_cast<const u32x4_t*>(lfrag + o);
             }
@@ -1748,7 +1765,7 @@ __global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
     if (tid < MB_TM) rs[tid] = 1.0f;
     if (MODE != RM_RESID && p.ssq && S == 1) {
         __syncthreads();
-        for (int c = wave; c < MB_TM; c += 4) {
+        for (int c = wave; c < MB_TM; c += NTH / 64) {
             const int m = min(m0 + c, M - 1);
             float sq = 0.f;
             for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)m * p.n_ssq + i];
@@ -1756,28 +1773,57 @@ __global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
             if (lane == 0) rs[c] = 1.0f / sqrtf(sq / (float)K + p.eps);
         }
     }
-    int ck0 = 0;
-    for (; ck0 + 2 * MB_D <= NC; ck0 += MB_D) {   // steady state: every step refills its slot, no conditions
+    if (NBUF == 1) {
+        int ck0 = 0;
+        for (; ck0 + 2 * MB_D <= NC; ck0 += MB_D) {   // steady state: every step refills its slot, no conditions
 #pragma unroll
-        for (int sl = 0; sl < MB_D; sl++) {
-            stage(sl);
-            gload(sl, ck0 + sl + MB_D);
-            multiply();
-        }
-    }
-    for (; ck0 < NC; ck0 += MB_D) {               // drain
-#pragma unroll
-        for (int sl = 0; sl < MB_D; sl++) {
-            if (ck0 + sl < NC) {   // uniform
+            for (int sl = 0; sl < MB_D; sl++) {
                 stage(sl);
-                if (ck0 + sl + MB_D < NC) gload(sl, ck0 + sl + MB_D);
-                multiply();
+                gload(sl, ck0 + sl + MB_D);
+                multiply(0);
+            }
+        }
+        for (; ck0 < NC; ck0 += MB_D) {               // drain
+#pragma unroll
+            for (int sl = 0; sl < MB_D; sl++) {
+                if (ck0 + sl < NC) {   // uniform
+                    stage(sl);
+                    if (ck0 + sl + MB_D < NC) gload(sl, ck0 + sl + MB_D);
+                    multiply(0);
+                }
+            }
+        }
+    } else {
+        // Two staging buffers: stripe c is multiplied out of buffer c % 2 while stripe c + 1 is written into the other
+        // one and stripe c + 2 is on its way from memory; one barrier per stripe.  (Buffer (c + 1) % 2 was last read
+        // for stripe c - 1, which every wave finished before the barrier that ended step c - 1.)
+        if (NC > 0) put(0, 0);
+        lds_barrier();
+        int ck0 = 0;
+        for (; ck0 + 2 * MB_D <= NC; ck0 += MB_D) {   // steady state, no conditions (MB_D = 2: slot = buffer = parity)
+#pragma unroll
+            for (int sl = 0; sl < MB_D; sl++) {
+                gload(sl, ck0 + sl + MB_D);           // slot sl was stored to LDS one step ago
+                multiply(sl);
+                put(sl ^ 1, sl ^ 1);                  // stripe ck0 + sl + 1, requested two steps ago
+                lds_barrier();
+            }
+        }
+        for (; ck0 < NC; ck0 += MB_D) {               // drain
+#pragma unroll
+            for (int sl = 0; sl < MB_D; sl++) {
+                if (ck0 + sl < NC) {   // uniform
+                    if (ck0 + sl + MB_D < NC) gload(sl, ck0 + sl + MB_D);
+                    multiply(sl);
+                    if (ck0 + sl + 1 < NC) put(sl ^ 1, sl ^ 1);
+                    lds_barrier();
+                }
             }
         }
     }
     // epilogue, 64 activation rows at a time: ep[row][column] through LDS, then thread -> (column n, rows mm, mm + 2, ..)
     float* ep = reinterpret_cast<float*>(smb);
-    const int n = tid & 127, mm = tid >> 7;
+    const int n = tid % TN, mm = tid / TN;
     for (int hf = 0; hf < 2; hf++) {
         if (m0 + hf * 64 >= M) break;   // uniform over the block
         __syncthreads();
@@ -1786,27 +1832,27 @@ __global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
             for (int i = 0; i < 4; i++)
 #pragma unroll
                 for (int j = 0; j < 4; j++)
-                    *reinterpret_cast<f32x4_t*>(ep + (j * 16 + r16) * MB_EP + wn * 64 + i * 16 + 4 * g) = acc[i][j];
+                    *reinterpret_cast<f32x4_t*>(ep + (j * 16 + r16) * EP + wn * 64 + i * 16 + 4 * g) = acc[i][j];
         }
         __syncthreads();
         for (int it = 0; it < 32; it++) {
             const int ml = mm + 2 * it, m = m0 + hf * 64 + ml;   // uniform over a wave
             if (m >= M) break;
-            float v = ep[ml * MB_EP + n];
+            float v = ep[ml * EP + n];
             if (S > 1) {   // raw sums of this K slice: [slice][M][n_total] (residual projections only)
-                p.kpart[((size_t)slice * M + m) * ((size_t)p.n_tiles * MB_TN) + (size_t)tile * MB_TN + n] = v;
+                p.kpart[((size_t)slice * M + m) * ((size_t)p.n_tiles * TN) + (size_t)tile * TN + n] = v;
                 continue;
             }
             const float sc = rs[hf * 64 + ml];
             if (MODE == RM_STORE) {
-                p.y[(size_t)m * p.ldy + (size_t)tile * MB_TN + n] = v * sc;
+                p.y[(size_t)m * p.ldy + (size_t)tile * TN + n] = v * sc;
             } else if (MODE == RM_SWIGLU) {
-                if (n < 64) {
-                    const float gt = v * sc, up = ep[ml * MB_EP + n + 64] * sc;
-                    split_store(gt / (1.0f + __expf(-gt)) * up, p.oh, p.ol, (size_t)m * p.ldo + (size_t)tile * 64 + n, F16);
+                if (n < TN / 2) {
+                    const float gt = v * sc, up = ep[ml * EP + n + TN / 2] * sc;
+                    split_store(gt / (1.0f + __expf(-gt)) * up, p.oh, p.ol, (size_t)m * p.ldo + (size_t)tile * (TN / 2) + n, F16);
                 }
             } else if (MODE == RM_RESID) {
-                const size_t colx = (size_t)tile * MB_TN + n;
+                const size_t colx = (size_t)tile * TN + n;
                 float* dsty = p.y + (size_t)m * p.ldy + colx;
                 const float tv = *dsty + v;
                 *dsty = tv;
@@ -1814,17 +1860,17 @@ __global__ __launch_bounds__(256, 2) void rows_big_kernel(RowsP2 p)
                 if (p.gain_out) {
                     split_store(tv * p.gain_out[colx], p.oh, p.ol, (size_t)m * p.ldo + colx, F16);
                     const float sq = wave_sum(tv * tv);   // the wave holds 64 consecutive columns of row m
-                    if (lane == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile * 2 + (n >> 6)] = sq;
+                    if (lane == 0) p.ssq_out[(size_t)m * (p.n[0] >> 6) + tile * WN + (n >> 6)] = sq;
                 }
             } else {   // QKV: natural row order, the rotary partner of column n is n ^ (hd / 2) of the same tile
-                const int row = tile * MB_TN + n;
+                const int row = tile * TN + n;
                 const int pos = p.pos_dev[0] + p.pos_off + m;
                 v *= sc;
                 if (row < p.dq + p.dkv) {
                     const bool is_q = row < p.dq;
                     const int jj = is_q ? row : row - p.dq;
                     const int head = jj / p.hd, e = jj % p.hd, half = p.hd >> 1, i = e % half;
-                    const float other = ep[ml * MB_EP + (n ^ half)] * sc;
+                    const float other = ep[ml * EP + (n ^ half)] * sc;
                     const float* cs = p.rope + ((size_t)pos * half + i) * 2;
                     const float ov = e < half ? v * cs[0] - other * cs[1] : v * cs[0] + other * cs[1];
                     if (is_q) p.y[(size_t)m * p.ldy + (size_t)head * p.hd + e] = ov;
@@ -1842,24 +1888,6 @@ bool rows_big_supported(const Dims& D)
 {
     return D.wt != WT_F32 && D.d % 128 == 0 && D.dq % 128 == 0 && D.dkv % 128 == 0 && D.f % 64 == 0 && D.V % 128 == 0 &&
            (D.hd == 64 || D.hd == 128);
-}
-
-template <int MODE, bool F16>
-static hipError_t launch_big(const RowsP2& p, int n_tiles, hipStream_t s)
-{
-    const size_t lds = (size_t)(MB_TN + 2 * MB_TM) * MB_PITCH;
-    static_assert((size_t)64 * MB_EP * 4 <= (size_t)(MB_TN + 2 * MB_TM) * MB_PITCH, "epilogue tile fits the staging area");
-    static std::atomic<size_t> lds_limit{0};  // per instantiation
-    {
-        hipError_t e = ensure_lds((const void*)rows_big_kernel<MODE, F16>, lds, lds_limit);
-        if (e != hipSuccess) return e;
-    }
-    const int S = p.ksplit > 1 ? p.ksplit : 1;
-    hipLaunchKernelGGL((rows_big_kernel<MODE, F16>), dim3(n_tiles * ((p.M + MB_TM - 1) / MB_TM) * S), dim3(256), lds, s, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || S == 1) return e;
-    hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(n_tiles * 2, p.M), dim3(64), 0, s, p);
-    return hipGetLastError();
 }
 
 bool rows_many_supported(const Dims& D, int N, int K)
@@ -1949,10 +1977,34 @@ hipError_t rows_wide(const Dims& D, const RowsFused& f, hipStream_t s)
     }
 }
 
+template <int MODE, bool F16, int TN>
+static hipError_t launch_big(const RowsP2& p, hipStream_t s)
+{
+    const size_t lds = (size_t)(TN == 256 ? 2 : 1) * (TN + 2 * MB_TM) * MB_PITCH;
+    static_assert((size_t)64 * (TN + 4) * 4 <= (size_t)(TN + 2 * MB_TM) * MB_PITCH, "epilogue tile fits the staging area");
+    static std::atomic<size_t> lds_limit{0};  // per instantiation
+    {
+        hipError_t e = ensure_lds((const void*)rows_big_kernel<MODE, F16, TN>, lds, lds_limit);
+        if (e != hipSuccess) return e;
+    }
+    const int S = p.ksplit > 1 ? p.ksplit : 1;
+    hipLaunchKernelGGL((rows_big_kernel<MODE, F16, TN>), dim3(p.n_tiles * ((p.M + MB_TM - 1) / MB_TM) * S), dim3(TN * 2), lds, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || S == 1) return e;
+    hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(p.n_tiles * (TN / 64), p.M), dim3(64), 0, s, p);
+    return hipGetLastError();
+}
+
+template <int MODE, bool F16>
+static hipError_t launch_big_tn(const RowsP2& p, int tn, hipStream_t s)
+{
+    return tn == 256 ? launch_big<MODE, F16, 256>(p, s) : launch_big<MODE, F16, 128>(p, s);
+}
+
 hipError_t rows_big(const Dims& D, const RowsFused& f, hipStream_t s)
 {
     if (D.wt == WT_F32 || f.M < 1 || f.K % MB_CK || f.K < MB_CK) return hipErrorInvalidValue;
-    if (f.mode == RM_SWIGLU ? (f.n[0] % 64 || f.n[1] != f.n[0]) : (f.n[0] % MB_TN || f.n[1] % MB_TN || f.n[2] % MB_TN))
+    if (f.mode == RM_SWIGLU ? (f.n[0] % 64 || f.n[1] != f.n[0]) : (f.n[0] % 128 || f.n[1] % 128 || f.n[2] % 128))
         return hipErrorInvalidValue;
     if (f.ssq && (f.mode == RM_RESID || f.n_ssq < 1)) return hipErrorInvalidValue;
     if (f.gain_out && (f.mode != RM_RESID || !f.oh || !f.ol || !f.ssq_out)) return hipErrorInvalidValue;
@@ -1960,17 +2012,25 @@ hipError_t rows_big(const Dims& D, const RowsFused& f, hipStream_t s)
         return hipErrorInvalidValue;
     RowsP2 p = {};
     fill_rows_params(D, f, p);
-    const int n_tiles = f.mode == RM_SWIGLU ? f.n[0] / 64 : (f.n[0] + f.n[1] + f.n[2]) / MB_TN;
     const int m_blocks = (f.M + MB_TM - 1) / MB_TM;
+    const int n_total = f.mode == RM_SWIGLU ? 2 * f.n[0] : f.n[0] + f.n[1] + f.n[2];   // logical weight rows
+    // 256-row tiles (one 512-thread block per CU, staging double-buffered in LDS: measured 20-30 % faster per MFMA, and
+    // a launch fills the CUs with the same granularity as two 128-row blocks per CU would) wherever every stacked
+    // matrix is a whole number of them; else 128-row tiles
+    const int force_tn = D.opt ? D.opt->wide_depth : 0;   // tuning hook: 128 or 256
+    const bool fits256 = f.mode == RM_SWIGLU ? f.n[0] % 128 == 0 : (f.n[0] % 256 == 0 && f.n[1] % 256 == 0 && f.n[2] % 256 == 0);
+    int tn = fits256 ? 256 : 128;
+    if (force_tn == 128 || (force_tn == 256 && fits256)) tn = force_tn;
+    const int n_tiles = n_total / tn;
     p.n_tiles = n_tiles;
     const bool f16 = D.wt == WT_F16;
-    // two blocks fit a CU: a residual projection with fewer than 256 blocks is cut along K (its raw sums go to
-    // kpart and rows_finish_kernel adds the slices in a fixed order)
+    // a residual projection with fewer blocks than resident slots (two per CU for the small tile, one for the large)
+    // is cut along K (its raw sums go to kpart and rows_finish_kernel adds the slices in a fixed order)
     p.ksplit = 1; p.kpart = nullptr;
     const int force_ks = D.opt ? D.opt->wide_ksplit : 0;
     if (f.kpart && f.mode == RM_RESID && force_ks != 1) {
-        const size_t per_slice = (size_t)f.M * n_tiles * MB_TN;
-        int ks = force_ks > 1 ? force_ks : 384 / (n_tiles * m_blocks);
+        const size_t per_slice = (size_t)f.M * n_tiles * tn;
+        int ks = force_ks > 1 ? force_ks : (tn == 256 ? 256 : 512) / (n_tiles * m_blocks);
         const int nc = f.K / MB_CK;
         if (ks > 8) ks = 8;
         if (ks > nc) ks = nc;
@@ -1978,10 +2038,10 @@ hipError_t rows_big(const Dims& D, const RowsFused& f, hipStream_t s)
         if (ks > 1) { p.ksplit = ks; p.kpart = f.kpart; }
     }
     switch (f.mode) {
-        case RM_STORE: return f16 ? launch_big<RM_STORE, true>(p, n_tiles, s) : launch_big<RM_STORE, false>(p, n_tiles, s);
-        case RM_RESID: return f16 ? launch_big<RM_RESID, true>(p, n_tiles, s) : launch_big<RM_RESID, false>(p, n_tiles, s);
-        case RM_SWIGLU: return f16 ? launch_big<RM_SWIGLU, true>(p, n_tiles, s) : launch_big<RM_SWIGLU, false>(p, n_tiles, s);
-        case RM_QKV: return f16 ? launch_big<RM_QKV, true>(p, n_tiles, s) : launch_big<RM_QKV, false>(p, n_tiles, s);
+        case RM_STORE: return f16 ? launch_big_tn<RM_STORE, true>(p, tn, s) : launch_big_tn<RM_STORE, false>(p, tn, s);
+        case RM_RESID: return f16 ? launch_big_tn<RM_RESID, true>(p, tn, s) : launch_big_tn<RM_RESID, false>(p, tn, s);
+        case RM_SWIGLU: return f16 ? launch_big_tn<RM_SWIGLU, true>(p, tn, s) : launch_big_tn<RM_SWIGLU, false>(p, tn, s);
+        case RM_QKV: return f16 ? launch_big_tn<RM_QKV, true>(p, tn, s) : launch_big_tn<RM_QKV, false>(p, tn, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -15,8 +15,11 @@ MINI16 = ModelShape(4, 512, 8, 8, 1408, 2048, dtype="fp16")     # fp16 (the pape
 GQA16 = ModelShape(3, 512, 4, 2, 688, 1024, dtype="fp16")       # fp16, head_dim 128, grouped heads, FFN not a
                                                                  # multiple of 64: the plain multi-row path
 WIDE64 = ModelShape(3, 512, 8, 1, 1408, 2048)                   # bf16, one KV head of 64: fits the 64-row prompt tiling only
+TILE128 = ModelShape(3, 512, 4, 1, 1472, 2176)                  # bf16, head_dim 128, one KV head, FFN 23 x 64, vocab 17 x 128:
+                                                                 # QKV, gate/up and LM head take the 128-row prompt tiles,
+                                                                 # the residual projections the 256-row ones
 SHAPES = {"tiny": WORKLOADS["tiny"].shape, "mini": MINI, "gqa": GQA, "gqa32": GQA32, "mini16": MINI16, "gqa16": GQA16,
-          "wide64": WIDE64}
+          "wide64": WIDE64, "tile128": TILE128}
 
 
 @pytest.fixture(scope="module")
@@ -28,7 +31,7 @@ def ssd():
     return lib
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16", "wide64"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "gqa32", "mini16", "gqa16", "wide64", "tile128"])
 @pytest.mark.parametrize("plen", [1, 16, 17, 45, 64, 65, 150])   # 16-row blocks, 128 x 128-tile and 64-row blocks, ragged tails
 def test_prefill_logits_and_first_token(ssd, name, plen):
     shape = SHAPES[name]
@@ -43,7 +46,7 @@ def test_prefill_logits_and_first_token(ssd, name, plen):
     assert ctx.ssd_get_stats()["n_tokens"] == plen + 1
 
 
-@pytest.mark.parametrize("name", ["mini", "gqa", "mini16", "wide64"])
+@pytest.mark.parametrize("name", ["mini", "gqa", "mini16", "wide64", "tile128"])
 @pytest.mark.parametrize("plen", [129, 512, 513, 700])
 def test_long_prompt_blocks(ssd, name, plen):
     """Prompts of several 128-row blocks per pass and of more than one pass (SSD_PREFILL_ROWS = 512 rows), ragged: the
@@ -105,6 +108,7 @@ MASKS = {
     "mini16": [[0, 0, 0, 0], [0, 1, 1, 0]],
     "gqa16": [[0, 0, 0], [0, 1, 0]],
     "wide64": [[0, 0, 0], [0, 1, 0]],
+    "tile128": [[0, 0, 0], [0, 1, 0]],
 }
 
 
