@@ -138,7 +138,15 @@ static void matmul_wt(const void *W, int dtype, int N, int K, const double *X, i
             double acc[ORC_RB];
             const double *x[ORC_RB];
             for (int j = 0; j < nr; j++) { acc[j] = 0.0; x[j] = X + (size_t)(r0 + j) * K; }
-            if (nr == ORC_RB) {
+            if (nr == 1) {   /* a single row: one scalar running sum */
+                double a0 = 0.0;
+                const double *x0 = x[0];
+                for (int k = 0; k < K; k++) {
+                    const double w = dtype == 0 ? (double)wf[k] : dtype == 1 ? widen_bf16(wh[k]) : fp16_value[wh[k]];
+                    a0 += w * x0[k];
+                }
+                acc[0] = a0;
+            } else if (nr == ORC_RB) {
                 for (int k = 0; k < K; k++) {
                     const double w = dtype == 0 ? (double)wf[k] : dtype == 1 ? widen_bf16(wh[k]) : fp16_value[wh[k]];
                     for (int j = 0; j < ORC_RB; j++) acc[j] += w * x[j][k];

@@ -402,6 +402,33 @@ int main(int argc, char** argv)
         timeit("attention 64 rows ctx 640+64 (MFMA kernel + fold)", 2.0 * (640 + 64) * 4096 * kvb, n, [&](int i) {
             CK(attention(D, big_a, 4096, kc + (size_t)i * kv_layer * kvb, vc + (size_t)i * kv_layer * kvb, pos, 0, ctx, 64, part, nullptr,
                          hi64, lo64, 0)); });
+        {   // a whole prompt of 512 rows at positions 0..511 through the large-tile kernel
+            const int R = 512;
+            uint16_t *bh, *bl, *oh, *ol;
+            int* pos0;
+            const size_t rb = (size_t)R * 11008 * 2;
+            CK(hipMalloc(&bh, rb)); CK(hipMalloc(&bl, rb)); CK(hipMalloc(&oh, rb)); CK(hipMalloc(&ol, rb)); CK(hipMalloc(&pos0, 64));
+            CK(hipMemset(bh, 0, rb)); CK(hipMemset(bl, 0, rb)); CK(hipMemset(pos0, 0, 64));
+            auto big = [&](int mode, const uint16_t* w0, const uint16_t* w1, const uint16_t* w2, int n0, int n1, int n2, int K,
+                           float* y, int ldy) {
+                RowsFused f = {};
+                f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
+                f.bh = bh; f.bl = bl; f.ldb = K; f.y = y; f.ldy = ldy; f.oh = oh; f.ol = ol; f.ldo = 11008; f.M = R; f.mode = mode;
+                f.rope = rope; f.pos_dev = pos0; f.pos_off = 0; f.kc = kc; f.vc = vc;
+                f.kpart = part; f.kpart_floats = (size_t)16 << 20;
+                if (mode != 1) { f.ssq = gain; f.n_ssq = K / 64; }
+                CK(rows_big(D, f, 0));
+            };
+            timeit("big_qkv (512 rows)", 3 * qk * 2.0, n, [&](int i) {
+                const uint16_t* w = W + (size_t)i * 3 * qk;
+                big(3, w, w + qk, w + 2 * qk, 4096, 4096, 4096, 4096, big_a, 4096); });
+            timeit("big_o (512 rows)", qk * 2.0, n, [&](int i) { big(1, W + (size_t)i * qk, nullptr, nullptr, 4096, 0, 0, 4096, big_b, 4096); });
+            timeit("big_gateup (512 rows)", 2 * gu * 2.0, n, [&](int i) {
+                const uint16_t* w = W + (size_t)i * 2 * gu;
+                big(2, w, w + gu, nullptr, 11008, 11008, 0, 4096, nullptr, 0); });
+            timeit("big_down (512 rows)", gu * 2.0, n, [&](int i) { big(1, W + (size_t)i * gu, nullptr, nullptr, 4096, 0, 0, 11008, big_b, 4096); });
+            timeit("big_lmhead (512 rows)", lm * 2.0, n, [&](int i) { big(0, W + (size_t)i * lm, nullptr, nullptr, 32000, 0, 0, 4096, big_a, 32000); });
+        }
         return 0;
     }
     // single-row (draft / vanilla decode) kernels
