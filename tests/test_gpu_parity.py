@@ -55,6 +55,14 @@ def test_long_prompt_blocks(ssd, name, plen):
     shape = SHAPES[name]
     orc, ctx = make_pair(shape, 5, plen + 16, max_k=4, norm_gain_std=0.1)
     prompt = make_prompt(shape.vocab, plen, 3).tolist()
+    if plen in (129, 513):
+        # the taps a prompt leaves behind (its last row's only, wherever that row sits in its 128-row block)
+        o = OracleSSD(orc)
+        o.prefill(prompt)
+        ctx.ssd_prefill(prompt)
+        conf_o, _ = o.layer_confidence(0)
+        np.testing.assert_allclose(ctx.ssd_layer_confidence(0, 1)[0], conf_o, atol=CONF_TOL[shape.dtype])
+        ctx.ssd_reset()
     mask = np.array(MASKS[name][1], np.uint8)
     st = lockstep_ssd(ctx, orc, prompt, 0, [4], mask, shape.dtype)
     print("long prompt", name, plen, "max err %.2e" % st["max_err"], "accepted", st["accepted"])
@@ -242,7 +250,7 @@ def test_tiny_workload_end_to_end_matches_oracle_tokens(ssd):
     print("tiny end-to-end: mask", mask_o.tolist(), "gpu-conf mask", mask_g.tolist(), "stats", ctx.ssd_get_stats())
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "mini16", "gqa16"])
+@pytest.mark.parametrize("name", ["tiny", "mini", "gqa", "mini16", "gqa16", "wide64", "tile128"])
 def test_layer_confidence_matches_oracle(ssd, name):
     shape = SHAPES[name]
     # larger init => intermediate distributions far from uniform, confidences spread over (0, 1)
