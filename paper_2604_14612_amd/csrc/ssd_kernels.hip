@@ -2437,6 +2437,18 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
     // the block's group of 16 query vectors (blockIdx.z): loads issued first, they are the furthest away
     const int q0 = blockIdx.z * AT_QPASS;
     const int nq = min(AT_QPASS, Q - q0);
+    // A chunk that lies wholly behind the causal horizon of the block's LAST query row contributes nothing (in a
+    // prompt pass that is half of all blocks): leave empty partials and go.  Uniform over the block.
+    if (n_splits > 1 && (n <= 0 || j0 > p0 + (q0 + nq - 1) / G)) {
+        for (int f = tid; f < nq * (HD / 4); f += AT_THREADS) {
+            const int qi = f / (HD / 4), dd = (f % (HD / 4)) * 4;
+            const int qg = q0 + qi, r = qg / G, head = kvh * G + qg % G;
+            float* mine = part + (((size_t)r * H + head) * n_splits + split) * (HD + 4);
+            *reinterpret_cast<float4*>(mine + dd) = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (dd == 0) { mine[HD] = -INFINITY; mine[HD + 1] = 0.f; }
+        }
+        return;
+    }
     constexpr int QPT = AT_QPASS * HD / AT_THREADS;   // query elements per thread
     float qreg[QPT];
 #pragma unroll

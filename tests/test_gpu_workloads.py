@@ -140,6 +140,8 @@ def _full_depth(ssd, name, k_seq, prompt_len=48):
     print(name, "full depth (%d layers), prompt %d, k" % (L, prompt_len), k_seq, ": max err %.2e" % st["max_err"],
           "accepted", st["accepted"], "unpinned", st["unpinned_cycles"], "tokens checked", st["tokens_checked"],
           "setup %.0f s, lock-step %.0f s" % (t1 - t0, time.time() - t1), flush=True)
+    progress("%s full depth: max logit err %.2e over %d draft + %d verify rows, accepted %s, unpinned cycles %d" % (
+        name, st["max_err"], st["draft_rows"], st["verify_rows"], st["accepted"], st["unpinned_cycles"]))
     assert st["cycles"] == len(k_seq) and st["verify_rows"] == sum(k_seq) + len(k_seq)
     assert st["unpinned_cycles"] <= 1
     ctx.close()
