@@ -15,9 +15,8 @@ MINI16 = ModelShape(4, 512, 8, 8, 1408, 2048, dtype="fp16")     # fp16 (the pape
 GQA16 = ModelShape(3, 512, 4, 2, 688, 1024, dtype="fp16")       # fp16, head_dim 128, grouped heads, FFN not a
                                                                  # multiple of 64: the plain multi-row path
 WIDE64 = ModelShape(3, 512, 8, 1, 1408, 2048)                   # bf16, one KV head of 64: fits the 64-row prompt tiling only
-TILE128 = ModelShape(3, 512, 4, 1, 1472, 2176)                  # bf16, head_dim 128, one KV head, FFN 23 x 64, vocab 17 x 128:
-                                                                 # QKV, gate/up and LM head take the 128-row prompt tiles,
-                                                                 # the residual projections the 256-row ones
+TILE128 = ModelShape(3, 384, 3, 3, 1472, 2176)                  # bf16, head_dim 128, widths 3 x 128, FFN 23 x 64, vocab 17 x 128:
+                                                                 # every prompt GEMM takes the 128-row tiles (K-split included)
 SHAPES = {"tiny": WORKLOADS["tiny"].shape, "mini": MINI, "gqa": GQA, "gqa32": GQA32, "mini16": MINI16, "gqa16": GQA16,
           "wide64": WIDE64, "tile128": TILE128}
 
