@@ -13,8 +13,8 @@ PROB_RTOL = {"bf16": 4e-2, "fp16": 5e-3, "fp32": 1e-3}         # |dp| <= p * 2 *
 
 
 def progress(msg):
-    """One line per finished step of a long test, appended to gpurun_out/test_progress.log (pytest holds back what
-    a test prints until it ends; a file shows from outside that the test is alive and where it is)."""
+    """One line per finished step of a long test, appended to test_progress.log in the run's output folder (pytest
+    holds back what a test prints until it ends; a file shows from outside that the test is alive and where it is)."""
     import os
     import time
     d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
