@@ -225,6 +225,19 @@ def main():
                 timing["skipped"] += int(m.sum())
         return tokens
 
+    def run_adaptive(c, n_cycles, mask, k_max, gamma):
+        """Cycles with confidence-aware drafting (drafting stops after the first token whose draft max-probability is
+        below gamma) -> (tokens, drafted, accepted, seconds)."""
+        tokens = drafted = accepted = 0
+        sync(); t0 = time.perf_counter()
+        for _ in range(n_cycles):
+            d, _ = c.ssd_draft_adaptive(mask, k_max, gamma)
+            y = c.ssd_verify(d)
+            a, _ = c.ssd_accept(d, y)
+            tokens += a + 1; drafted += len(d); accepted += a
+        sync()
+        return tokens, drafted, accepted, time.perf_counter() - t0
+
     def new_timing():
         return {"draft_s": 0.0, "draft_bytes": 0, "verify_s": 0.0, "verify_bytes": 0, "other_s": 0.0, "accepted": 0,
                 "skipped": 0}
@@ -325,6 +338,15 @@ def main():
                                   "verify_frac_of_hbm_peak": tm["verify_bytes"] / tm["verify_s"] / 1e9 / HBM_PEAK_GBPS,
                                   "mean_accepted_M": tm["accepted"] / n_c}
         out["k_sweep"] = sweep
+        # ---- confidence-aware drafting (Section 3: drafting ends early on a low-confidence token) on the same
+        # random-init model: its drafts are never confident, so a cycle shrinks to one draft step + a two-row verify ----
+        gamma = 0.3
+        ctx.ssd_reset()
+        ctx.ssd_prefill(prompt)
+        run_adaptive(ctx, 4, uniform, 8, gamma)
+        tk, dr, ac, dt = run_adaptive(ctx, 24, uniform, 8, gamma)
+        out["adaptive_drafting"] = {"gamma": gamma, "k_max": 8, "tokens_per_s": tk / dt, "mean_drafted": dr / 24,
+                                    "mean_accepted_M": ac / 24, "cycles": 24, "ssd_over_vanilla": tk / dt / van_tps}
 
         # ---- the same pipeline where drafts ARE accepted: the 7B shape with the residual projections scaled down
         # (depth as redundant as in a trained model), search interval scaled from 30 to 8 cycles so that several
