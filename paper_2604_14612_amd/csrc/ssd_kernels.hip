@@ -2611,6 +2611,228 @@ __global__ __launch_bounds__(AT_THREADS) void attn_mfma_kernel(const float* __re
     }
 }
 
+// ---- prompt passes: one block per KV head and 64 query vectors walks the whole causal range -----------------
+// Four waves of 16 query vectors each share the staged K / V^T chunks (64 positions at a time, the same 16-bit
+// planes as above); a wave keeps its 16 x HD output tile and the running maximum / sum of every query vector in
+// registers and rescales them chunk by chunk (online soft-max), so that nothing is written but the finished
+// output: no partials, no fold kernel, and a chunk is staged once per 64 query vectors instead of once per 16.
+// Layouts as in the kernel above: scores D = lane (c = position, g) holds queries 4g .. 4g+3; output tile D = lane
+// (c = dim, g) holds the same queries, so the rescale factors of a lane's queries apply to both.  The exponentials
+// cross from the first layout to the A operand of P.V through a wave-private LDS tile.
+constexpr int AP_Q = 64;                 // query vectors per block
+constexpr int AP_C = 64;                 // cache positions per step
+constexpr int AP_VPITCH = AP_C * 2 + 16; // bytes per row of the transposed V tile
+
+template <typename KT, int HD>
+static constexpr size_t attn_prompt_lds_bytes()
+{
+    return (sizeof(KT) == 4 ? 2 : 1) * ((size_t)AP_C * (HD * 2 + 16) + (size_t)HD * AP_VPITCH) + (size_t)4 * 16 * HD * 4;
+}
+
+template <typename KT, int HD>
+__global__ __launch_bounds__(AT_THREADS) void attn_prompt_kernel(const float* __restrict__ q, int ldq,
+                                                                 const KT* __restrict__ kc, const KT* __restrict__ vc,
+                                                                 const int* pos_dev, int pos_off, int M, int H, int Hkv,
+                                                                 int max_seq, float* __restrict__ outp, int dq,
+                                                                 uint16_t* __restrict__ out_hi, uint16_t* __restrict__ out_lo,
+                                                                 bool out_f16)
+{
+    constexpr bool F32 = sizeof(KT) == 4;
+    constexpr bool F16 = IsF16<KT>::value;
+    constexpr int NP = F32 ? 2 : 1;
+    constexpr int ROWB = HD * 2 + 16;
+    constexpr int EPV = 16 / (int)sizeof(KT);
+    constexpr int VPR = HD / EPV;
+    constexpr int KSTEPS = HD / 32;
+    constexpr int PT = AP_C / 16;              // position tiles of a chunk (4)
+    constexpr int PS = AP_C / 32;              // k-steps of P.V (2)
+    constexpr int DT = HD / 16;                // output dim tiles per wave (8 or 4)
+    constexpr int KPLANE = AP_C * ROWB, VPLANE = HD * AP_VPITCH;
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* ktile = smem;                                       // [NP][AP_C][ROWB]
+    unsigned char* vT = smem + NP * KPLANE;                            // [NP][HD][AP_VPITCH]
+    float* wbuf = reinterpret_cast<float*>(vT + NP * VPLANE);          // [4 waves][16][HD]: exponentials, then the output tile
+
+    const int kvh = blockIdx.y;
+    const int G = H / Hkv, Q = G * M;
+    const int p0 = pos_dev[0] + pos_off;
+    const int total = p0 + M;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int q0 = blockIdx.x * AP_Q;
+    const int nq = min(AP_Q, Q - q0);
+    const int last_vis = p0 + (q0 + nq - 1) / G;          // last position any query vector of the block may see
+    float* pw = wbuf + wave * 16 * HD;
+    const float scale = 1.0f / sqrtf((float)HD);
+
+    // the wave's 16 query vectors as hi / lo fragments (A operand: lane (r16 = query, g) holds dims 32 st + 8 g ..)
+    u32x4_t qh[KSTEPS], ql[KSTEPS];
+    {
+        const int qv = q0 + min(wave * 16 + r16, nq - 1);      // vectors past nq read a valid one; never stored
+        const float* qp = q + (size_t)(qv / G) * ldq + (size_t)(kvh * G + qv % G) * HD;
+#pragma unroll
+        for (int st = 0; st < KSTEPS; st++) {
+            float x[8];
+            const float4 a = *reinterpret_cast<const float4*>(qp + st * 32 + g * 8), b = *reinterpret_cast<const float4*>(qp + st * 32 + g * 8 + 4);
+            x[0] = a.x * scale; x[1] = a.y * scale; x[2] = a.z * scale; x[3] = a.w * scale;
+            x[4] = b.x * scale; x[5] = b.y * scale; x[6] = b.z * scale; x[7] = b.w * scale;
+            unsigned h[8], l[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const uint16_t hb = f32_to_h16_bits(x[i], F16);
+                h[i] = hb;
+                l[i] = f32_to_h16_bits(x[i] - h16_bits_to_f32(hb, F16), F16);
+            }
+            qh[st] = u32x4_t{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+            ql[st] = u32x4_t{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+        }
+    }
+    // causal horizon of the lane's four query vectors (scores layout: queries 4g .. 4g+3 of the wave); -1 = padding
+    int horizon[4];
+#pragma unroll
+    for (int jx = 0; jx < 4; jx++) {
+        const int qi = wave * 16 + g * 4 + jx;
+        horizon[jx] = qi < nq ? p0 + (q0 + qi) / G : -1;
+    }
+    float mrun[4], lrun[4];
+#pragma unroll
+    for (int jx = 0; jx < 4; jx++) { mrun[jx] = -INFINITY; lrun[jx] = 0.f; }
+    f32x4_t oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) oacc[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int j0 = 0; j0 <= last_vis; j0 += AP_C) {
+        const int n = min(AP_C, total - j0);               // positions of this chunk that exist (>= 1)
+        __syncthreads();                                   // the previous chunk is fully consumed
+        {   // stage K (row-major) and V (transposed); every load is issued before the first is used
+            const KT* kbase = kc + ((size_t)kvh * max_seq + j0) * HD;
+            const KT* vbase = vc + ((size_t)kvh * max_seq + j0) * HD;
+            constexpr int NV = AP_C * VPR / AT_THREADS;
+            u32x4_t kr[NV], vr[NV];
+            const int vmax = n * VPR - 1;
+#pragma unroll
+            for (int t = 0; t < NV; t++) {
+                const int v = min(tid + t * AT_THREADS, vmax);
+                kr[t] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)(v / VPR) * HD + (v % VPR) * EPV);
+                const int w = tid + t * AT_THREADS;
+                vr[t] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min(w % AP_C, n - 1) * HD + (w / AP_C) * EPV);
+            }
+#pragma unroll
+            for (int t = 0; t < NV; t++) {
+                const int v = tid + t * AT_THREADS;
+                const int pos = v / VPR, d0 = (v % VPR) * EPV;
+                const int vpos = v % AP_C, vd0 = (v / AP_C) * EPV;
+                const u32x4_t kk = v <= vmax ? kr[t] : u32x4_t{0u, 0u, 0u, 0u};     // positions past the end: zeros
+                const u32x4_t vv = vpos < n ? vr[t] : u32x4_t{0u, 0u, 0u, 0u};
+                if constexpr (F32) {
+                    const unsigned kw[4] = {kk.x, kk.y, kk.z, kk.w}, vw[4] = {vv.x, vv.y, vv.z, vv.w};
+                    unsigned kh[4], kl[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const float x = __uint_as_float(kw[e]);
+                        kh[e] = f32_to_bf16_bits(x);
+                        kl[e] = f32_to_bf16_bits(x - bf16_bits_to_f32(kh[e]));
+                        const float y = __uint_as_float(vw[e]);
+                        const uint16_t yh = f32_to_bf16_bits(y);
+                        *reinterpret_cast<uint16_t*>(vT + (vd0 + e) * AP_VPITCH + vpos * 2) = yh;
+                        *reinterpret_cast<uint16_t*>(vT + VPLANE + (vd0 + e) * AP_VPITCH + vpos * 2) =
+                            f32_to_bf16_bits(y - bf16_bits_to_f32(yh));
+                    }
+                    *reinterpret_cast<uint2*>(ktile + pos * ROWB + d0 * 2) = make_uint2(kh[0] | (kh[1] << 16), kh[2] | (kh[3] << 16));
+                    *reinterpret_cast<uint2*>(ktile + KPLANE + pos * ROWB + d0 * 2) = make_uint2(kl[0] | (kl[1] << 16), kl[2] | (kl[3] << 16));
+                } else {
+                    *reinterpret_cast<u32x4_t*>(ktile + pos * ROWB + d0 * 2) = kk;
+                    const unsigned w4[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        *reinterpret_cast<uint16_t*>(vT + (vd0 + e) * AP_VPITCH + vpos * 2) = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+                }
+            }
+        }
+        __syncthreads();
+        // scores of the wave's 16 queries against the 64 positions, masked; running maximum
+        float sv[PT][4];
+        float mnew[4];
+#pragma unroll
+        for (int jx = 0; jx < 4; jx++) mnew[jx] = mrun[jx];
+#pragma unroll
+        for (int pt = 0; pt < PT; pt++) {
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < KSTEPS; st++) {
+                const unsigned char* kp = ktile + (pt * 16 + r16) * ROWB + (st * 32 + g * 8) * 2;
+                const u32x4_t kf = *reinterpret_cast<const u32x4_t*>(kp);
+                acc = mfma_h16<F16>(qh[st], kf, acc);
+                acc = mfma_h16<F16>(ql[st], kf, acc);
+                if constexpr (F32) acc = mfma_h16<F16>(qh[st], *reinterpret_cast<const u32x4_t*>(kp + KPLANE), acc);
+            }
+            const int j = j0 + pt * 16 + r16;
+#pragma unroll
+            for (int jx = 0; jx < 4; jx++) {
+                sv[pt][jx] = j <= horizon[jx] ? acc[jx] : -INFINITY;
+                mnew[jx] = fmaxf(mnew[jx], sv[pt][jx]);
+            }
+        }
+        float alpha[4], psum[4];
+#pragma unroll
+        for (int jx = 0; jx < 4; jx++) {
+            mnew[jx] = row16_max(mnew[jx]);                              // over the 16 positions a DPP row holds
+            alpha[jx] = mrun[jx] > -INFINITY ? __expf(mrun[jx] - mnew[jx]) : 0.f;
+            psum[jx] = 0.f;
+        }
+#pragma unroll
+        for (int pt = 0; pt < PT; pt++)
+#pragma unroll
+            for (int jx = 0; jx < 4; jx++) {
+                const float e = sv[pt][jx] > -INFINITY ? __expf(sv[pt][jx] - mnew[jx]) : 0.f;
+                psum[jx] += e;
+                pw[(g * 4 + jx) * AP_C + pt * 16 + r16] = e;
+            }
+#pragma unroll
+        for (int jx = 0; jx < 4; jx++) {
+            lrun[jx] = lrun[jx] * alpha[jx] + row16_sum(psum[jx]);
+            mrun[jx] = mnew[jx];
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+            for (int jx = 0; jx < 4; jx++) oacc[dt][jx] *= alpha[jx];
+        // O += P.V: A = the exponentials (lane (r16 = query, g) holds positions 32 st + 8 g ..), B = V^T fragments
+        u32x4_t ph[PS], pl[PS];
+#pragma unroll
+        for (int st = 0; st < PS; st++) split8<F16>(pw + r16 * AP_C + st * 32 + g * 8, ph[st], pl[st]);
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++) {
+#pragma unroll
+            for (int st = 0; st < PS; st++) {
+                const unsigned char* vp = vT + (dt * 16 + r16) * AP_VPITCH + (st * 32 + g * 8) * 2;
+                const u32x4_t vf = *reinterpret_cast<const u32x4_t*>(vp);
+                oacc[dt] = mfma_h16<F16>(ph[st], vf, oacc[dt]);
+                oacc[dt] = mfma_h16<F16>(pl[st], vf, oacc[dt]);
+                if constexpr (F32) oacc[dt] = mfma_h16<F16>(ph[st], *reinterpret_cast<const u32x4_t*>(vp + VPLANE), oacc[dt]);
+            }
+        }
+    }
+    // finished output: tile -> wave-private LDS ([16 queries][HD]) -> whole rows to memory
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+        for (int jx = 0; jx < 4; jx++) pw[(g * 4 + jx) * HD + dt * 16 + r16] = oacc[dt][jx] / lrun[jx];
+    for (int f = lane; f < 16 * (HD / 4); f += 64) {
+        const int qi = f / (HD / 4), dd = (f % (HD / 4)) * 4;
+        if (wave * 16 + qi >= nq) continue;
+        const float4 o = *reinterpret_cast<const float4*>(pw + qi * HD + dd);
+        const int qg = q0 + wave * 16 + qi, r = qg / G, head = kvh * G + qg % G;
+        const size_t oo = (size_t)r * dq + (size_t)head * HD + dd;
+        if (out_hi) {
+            split_store(o.x, out_hi, out_lo, oo, out_f16); split_store(o.y, out_hi, out_lo, oo + 1, out_f16);
+            split_store(o.z, out_hi, out_lo, oo + 2, out_f16); split_store(o.w, out_hi, out_lo, oo + 3, out_f16);
+        } else {
+            *reinterpret_cast<float4*>(outp + oo) = o;
+        }
+    }
+}
+
 template <typename KT, int HD>
 static size_t attn_mfma_lds_bytes()
 {
@@ -2974,6 +3196,17 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
 {
     const int n_splits = pl.n_splits;
     if (n_splits < 1 || (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK))) return hipErrorInvalidValue;
+    // prompt passes (more than 16 rows) of models with 16-bit weights: one kernel over the whole causal range
+    if (M > 16 && !pl.wide && (sizeof(KT) == 2 || D.wt != WT_F32) && !(D.opt && D.opt->attn_kernel)) {
+        constexpr size_t lds = attn_prompt_lds_bytes<KT, HD>();
+        static std::atomic<size_t> lds_limit{0};  // per instantiation
+        hipError_t e = ensure_lds((const void*)attn_prompt_kernel<KT, HD>, lds, lds_limit);
+        if (e != hipSuccess) return e;
+        const int Q = (D.H / D.Hkv) * M;
+        hipLaunchKernelGGL((attn_prompt_kernel<KT, HD>), dim3(ceil_div(Q, AP_Q), D.Hkv), dim3(AT_THREADS), lds, s, q, ldq, (const KT*)kc,
+                           (const KT*)vc, pos_dev, pos_off, M, D.H, D.Hkv, D.max_seq, out, D.dq, out_hi, out_lo, D.wt == WT_F16);
+        return hipGetLastError();
+    }
     if (pl.wide) {
         int Q = (D.H / D.Hkv) * M, zq = 1;
         if (Q > AW_MAXQ_TOTAL) {  // one block per row (its group of heads, or half of a group of 8) and range
