@@ -3196,8 +3196,11 @@ static hipError_t attention_t(const Dims& D, const float* q, int ldq, const void
 {
     const int n_splits = pl.n_splits;
     if (n_splits < 1 || (n_splits > 64 && n_splits > ceil_div(D.max_seq, AT_CHUNK))) return hipErrorInvalidValue;
-    // prompt passes (more than 16 rows) of models with 16-bit weights: one kernel over the whole causal range
-    if (M > 16 && !pl.wide && (sizeof(KT) == 2 || D.wt != WT_F32) && !(D.opt && D.opt->attn_kernel)) {
+    // prompt passes (more than 16 rows) of models with 16-bit weights: one kernel over the whole causal range, where
+    // it has blocks for a quarter of the CUs at least or the range is short (a block walks the range chunk by chunk:
+    // 64 rows behind 640 cached positions take 62 us in 32 blocks, 40 us through the split kernel and its fold)
+    if (M > 16 && !pl.wide && (sizeof(KT) == 2 || D.wt != WT_F32) && !(D.opt && D.opt->attn_kernel) &&
+        (ceil_div((D.H / D.Hkv) * M, AP_Q) * D.Hkv >= 64 || ctx <= 4 * AP_C)) {
         constexpr size_t lds = attn_prompt_lds_bytes<KT, HD>();
         static std::atomic<size_t> lds_limit{0};  // per instantiation
         hipError_t e = ensure_lds((const void*)attn_prompt_kernel<KT, HD>, lds, lds_limit);
