@@ -74,7 +74,7 @@ int main(int argc, char** argv)
     uint16_t *hi, *lo, *hi64, *lo64;
     const size_t act_floats = (size_t)16 * 32000;
     CK(hipMalloc(&x, act_floats * 4)); CK(hipMalloc(&gain, 1 << 20)); CK(hipMalloc(&act, act_floats * 4));
-    CK(hipMalloc(&q, act_floats * 4)); CK(hipMalloc(&logits, act_floats * 4)); CK(hipMalloc(&part, 64 << 20));
+    CK(hipMalloc(&q, act_floats * 4)); CK(hipMalloc(&logits, act_floats * 4)); CK(hipMalloc(&part, 128 << 20));
     CK(hipMalloc(&rope, (size_t)1024 * 64 * 2 * 4)); CK(hipMalloc(&pos, 64)); CK(hipMalloc(&sink, 256));
     const size_t kv_layer = (size_t)32 * 1024 * 128;  // elements of K (or V) of one layer; one copy per timed launch so the cache is cold
     CK(hipMalloc(&kc, 12 * kv_layer * kvb)); CK(hipMalloc(&vc, 12 * kv_layer * kvb));
@@ -283,6 +283,8 @@ int main(int argc, char** argv)
         const int only_r = std::getenv("KB_BIG_R") ? std::atoi(std::getenv("KB_BIG_R")) : 0;   // one row count only
         opts.wide_depth = std::getenv("KB_TN") ? std::atoi(std::getenv("KB_TN")) : 0;   // weight rows per tile: 128, 256, 0 = library's choice
         std::printf("weight rows per tile: %d (0 = the library's choice)\n", opts.wide_depth);
+        opts.wide_ksplit = std::getenv("KB_KS") ? std::atoi(std::getenv("KB_KS")) : 0;   // K slices: 1 = never, > 1 forced, 0 = library's choice
+        std::printf("K slices: %d (0 = the library's choice)\n", opts.wide_ksplit);
         for (int R : {128, 256, 512, 1024}) {
             if (only_r && R != only_r) continue;
             uint16_t *bh, *bl, *oh, *ol;
@@ -297,8 +299,9 @@ int main(int argc, char** argv)
                 f.w[0] = w0; f.w[1] = w1; f.w[2] = w2; f.n[0] = n0; f.n[1] = n1; f.n[2] = n2; f.K = K;
                 f.bh = bh + (size_t)row0 * (K + pad); f.bl = bl + (size_t)row0 * (K + pad); f.ldb = K + pad; f.y = y ? y + (size_t)row0 * ldy : nullptr; f.ldy = ldy;
                 f.oh = oh + (size_t)row0 * 11008; f.ol = ol + (size_t)row0 * 11008; f.ldo = 11008; f.M = rows; f.mode = mode;
-                f.rope = rope; f.pos_dev = pos; f.pos_off = 0; f.kc = kc; f.vc = vc;
-                f.kpart = part; f.kpart_floats = (size_t)16 << 20;
+                // (the position on the device is 640 and the cache holds 1024: the larger row counts write positions 0 .. rows - 1)
+                f.rope = rope; f.pos_dev = pos; f.pos_off = 640 + rows > 1024 ? -640 : 0; f.kc = kc; f.vc = vc;
+                f.kpart = part; f.kpart_floats = (size_t)32 << 20;
                 if (mode != 1) { f.ssq = gain; f.n_ssq = K / 64; }
                 CK(big ? rows_big(D, f, 0) : rows_wide(D, f, 0));
             };
@@ -307,7 +310,6 @@ int main(int argc, char** argv)
                                     {"gateup (swiglu)", 2, 2 * gu, 11008, 11008, 0, 4096, 0}, {"down (resid)", 1, gu, 4096, 0, 0, 11008, 4096},
                                     {"lmhead (store)", 0, lm, 32000, 0, 0, 4096, 32000}};
             for (const Shape& sh : shapes) {
-                if (sh.mode == 3 && R > 256) continue;   // the bench cache copies hold 1024 positions from 640 on
                 const double flops = 2.0 * (double)sh.welems * R;
                 for (int big = 1; big >= 0; big--) {
                     char nm[96];

@@ -1051,6 +1051,7 @@ struct RowsP2 {
     const float* ssq; int n_ssq; float eps;     // consumer: partial sums of squares [M][n_ssq] of the input rows (or null)
     const float* gain_out; float* ssq_out;      // RESID producer: gain of the next norm -> oh/ol = split(x * gain), ssq_out [M][n/16]
     int ksplit; float* kpart;                   // wide RESID only: K cut into ksplit slices (grid.y), raw sums to kpart [ksplit][M][n]
+    int tile0, fin_tile0;                       // large tiles: first weight tile of this launch; first 64-column output tile of its finishing launch
     int tap_only;                               // > 0: only row tap_only - 1 writes its tap (a prompt needs the last row's only)
     int n_tiles;                                // large-tile kernel: weight tiles of the launch
 };
@@ -1603,8 +1604,8 @@ template <int MODE, bool F16>
 __global__ __launch_bounds__(64) void rows_finish_kernel(RowsP2 p)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
-    const int tile = blockIdx.x, m = blockIdx.y, lane = threadIdx.x;
-    const size_t nt = (size_t)gridDim.x * 64, colx = (size_t)tile * 64 + lane;
+    const int tile = blockIdx.x + p.fin_tile0, m = blockIdx.y, lane = threadIdx.x;   // kpart covers this launch's tiles only
+    const size_t nt = (size_t)gridDim.x * 64, colx = (size_t)blockIdx.x * 64 + lane;
     float v = 0.f, v2 = 0.f;
     for (int sl = 0; sl < p.ksplit; sl++) {
         v += p.kpart[(((size_t)sl * NT + 0) * p.M + m) * nt + colx];
@@ -1621,13 +1622,13 @@ __global__ __launch_bounds__(64) void rows_finish_kernel(RowsP2 p)
 
 // --- large-tile variant: any number of activation rows in one launch (whole prompts, the context window) --------
 // With hundreds of rows the work is a real GEMM and the weights should cross the chip once, not once per 64 rows.
-// A block owns 128 logical weight rows (64 gate + 64 up rows in SwiGLU mode) x 128 activation rows (grid.y walks
-// the row blocks, so the blocks that share a weight tile run side by side and all but the first find it in the
-// cache).  64-wide K stripes of the weights and of the hi / lo rows go through LDS (register prefetch of the next
-// stripe while one is multiplied; 54 KB per block, two blocks per CU cover each other's staging); the four waves
-// form a 2 x 2 grid of 64 x 64 sub-tiles, 32 MFMAs (hi and lo) per 12 LDS fragment reads.  The finished tile goes
-// back through LDS in two halves so that the epilogue sees (row, 128 consecutive columns): same modes, same RMSNorm
-// folding as the 64-row kernel; weight rows in natural order (a rotary pair e, e + hd/2 sits in one tile).
+// A block owns TN logical weight rows (TN / 2 gate + TN / 2 up rows in SwiGLU mode) x 128 activation rows; the blocks
+// that share a weight tile run back to back on one XCD and all but the first find it in that L2.  64-wide K stripes of
+// the weights and of the hi / lo rows go through LDS (register prefetch two stripes ahead; TN = 256 keeps two staging
+// buffers and writes the next stripe while one is multiplied); the waves form a (TN / 64) x 2 grid of 64 x 64
+// sub-tiles, 32 MFMAs (hi and lo) per 12 LDS fragment reads.  The finished tile goes back through LDS in two halves
+// so that the epilogue sees (row, TN consecutive columns): same modes, same RMSNorm folding as the 64-row kernel;
+// weight rows in natural order (a rotary pair e, e + hd/2 sits in one tile).
 constexpr int MB_TM = 128, MB_CK = 64;
 constexpr int MB_PITCH = MB_CK * 2 + 16;   // bytes per staged row
 
@@ -1675,7 +1676,7 @@ __global__ __launch_bounds__(TN * 2, 2) void rows_big_kernel(RowsP2 p)
         int unit, y;
         if (L < full * mb) { const int ch = L / (8 * mb), r = L % (8 * mb); unit = ch * 8 + (r & 7); y = r >> 3; }
         else { const int r = L - full * mb, rem = units - full; unit = full + r % rem; y = r / rem; }
-        tile = unit % p.n_tiles; slice = unit / p.n_tiles; m0 = y * MB_TM;
+        tile = p.tile0 + unit % p.n_tiles; slice = unit / p.n_tiles; m0 = y * MB_TM;
     }
     const int c_begin = (int)((long)NCall * slice / S), NC = (int)((long)NCall * (slice + 1) / S) - c_begin;
     // a stripe is TN + 2 x 128 rows of 8 vectors of 16 bytes; thread takes row tid / 8 + RPS u, vector tid % 8.
@@ -1839,8 +1840,12 @@ __global__ __launch_bounds__(TN * 2, 2) void rows_big_kernel(RowsP2 p)
             const int ml = mm + 2 * it, m = m0 + hf * 64 + ml;   // uniform over a wave
             if (m >= M) break;
             float v = ep[ml * EP + n];
-            if (S > 1) {   // raw sums of this K slice: [slice][M][n_total] (residual projections only)
-                p.kpart[((size_t)slice * M + m) * ((size_t)p.n_tiles * TN) + (size_t)tile * TN + n] = v;
+            if (S > 1) {   // raw sums of this K slice: [slice][matrix][M][columns of this launch's tiles]
+                if (MODE == RM_SWIGLU)
+                    p.kpart[(((size_t)slice * 2 + n / (TN / 2)) * M + m) * ((size_t)p.n_tiles * (TN / 2)) +
+                            (size_t)(tile - p.tile0) * (TN / 2) + n % (TN / 2)] = v;
+                else
+                    p.kpart[((size_t)slice * M + m) * ((size_t)p.n_tiles * TN) + (size_t)(tile - p.tile0) * TN + n] = v;
                 continue;
             }
             const float sc = rs[hf * 64 + ml];
@@ -1881,6 +1886,43 @@ __global__ __launch_bounds__(TN * 2, 2) void rows_big_kernel(RowsP2 p)
                 }
             }
         }
+    }
+}
+
+// Second half of a K-split QKV launch of the large tiles (weight rows in natural order): one wave per (row, 64
+// columns) adds the slices of its column and of the column's rotary partner in a fixed order, scales both by the row's
+// RMS factor, rotates and writes the query row / the cache rows.
+template <bool F16>
+__global__ __launch_bounds__(64) void rows_finish_qkv_kernel(RowsP2 p)
+{
+    const int m = blockIdx.y, lane = threadIdx.x, half = p.hd >> 1;
+    const size_t nt = (size_t)gridDim.x * 64;
+    const int col = blockIdx.x * 64 + lane, row = p.fin_tile0 * 64 + col;
+    const bool rotary = row < p.dq + p.dkv;   // uniform over the wave (dq, dkv are multiples of 128)
+    float v = 0.f, other = 0.f;
+    for (int sl = 0; sl < p.ksplit; sl++) {
+        const float* src = p.kpart + ((size_t)sl * p.M + m) * nt;
+        v += src[col];
+        if (rotary) other += src[col ^ half];
+    }
+    if (p.ssq) {
+        float sq = 0.f;
+        for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)m * p.n_ssq + i];
+        const float sc = 1.0f / sqrtf(wave_sum(sq) / (float)p.K + p.eps);
+        v *= sc; other *= sc;
+    }
+    const int pos = p.pos_dev[0] + p.pos_off + m;
+    if (rotary) {
+        const bool is_q = row < p.dq;
+        const int jj = is_q ? row : row - p.dq;
+        const int head = jj / p.hd, e = jj % p.hd, i = e % half;
+        const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+        const float ov = e < half ? v * cs[0] - other * cs[1] : v * cs[0] + other * cs[1];
+        if (is_q) p.y[(size_t)m * p.ldy + (size_t)head * p.hd + e] = ov;
+        else kv_put(p.kc, ((size_t)head * p.max_seq + pos) * p.hd + e, ov, p.kt);
+    } else {
+        const int e = row - p.dq - p.dkv;
+        kv_put(p.vc, ((size_t)(e / p.hd) * p.max_seq + pos) * p.hd + (e % p.hd), v, p.kt);
     }
 }
 
@@ -1991,7 +2033,10 @@ static hipError_t launch_big(const RowsP2& p, hipStream_t s)
     hipLaunchKernelGGL((rows_big_kernel<MODE, F16, TN>), dim3(p.n_tiles * ((p.M + MB_TM - 1) / MB_TM) * S), dim3(TN * 2), lds, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
-    hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(p.n_tiles * (TN / 64), p.M), dim3(64), 0, s, p);
+    if (MODE == RM_QKV)   // natural row order: its own finishing kernel
+        hipLaunchKernelGGL((rows_finish_qkv_kernel<F16>), dim3(p.n_tiles * (TN / 64), p.M), dim3(64), 0, s, p);
+    else
+        hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(p.n_tiles * (MODE == RM_SWIGLU ? TN / 128 : TN / 64), p.M), dim3(64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -2036,6 +2081,43 @@ hipError_t rows_big(const Dims& D, const RowsFused& f, hipStream_t s)
         if (ks > nc) ks = nc;
         if ((size_t)ks * per_slice > f.kpart_floats) ks = (int)(f.kpart_floats / per_slice);
         if (ks > 1) { p.ksplit = ks; p.kpart = f.kpart; }
+    }
+    // A QKV launch with blocks for at most half of the slots (prompts of up to 256 rows at the 7B shape) is cut along K
+    // as well; its finishing kernel rotates and writes the cache rows.
+    if (f.kpart && f.mode == RM_QKV && force_ks != 1) {
+        const int slots = tn == 256 ? 256 : 512, nc = f.K / MB_CK;
+        const size_t per_slice = (size_t)f.M * n_tiles * tn;
+        int ks = force_ks > 1 ? force_ks : slots / (n_tiles * m_blocks);
+        if (ks > 4) ks = 4;
+        if (ks > nc) ks = nc;
+        if ((size_t)ks * per_slice > f.kpart_floats) ks = (int)(f.kpart_floats / per_slice);
+        if (ks > 1) { p.ksplit = ks; p.kpart = f.kpart; }
+    }
+    // Gate / up with a last round that would leave most CUs idle (7B, 512 rows: 344 blocks for 256 slots): the tiles
+    // of the whole rounds run as they are, the rest (all of them when there is no whole round) are cut along K into as
+    // many slices as fill the slots once more, and the finishing kernel adds the slices and applies SwiGLU
+    // (1 + 1/2 block times instead of 2).
+    if (f.kpart && f.mode == RM_SWIGLU && force_ks != 1) {
+        const int slots = tn == 256 ? 256 : 512, units = n_tiles * m_blocks;
+        const int whole_tiles = units / slots * slots / m_blocks, tail_tiles = n_tiles - whole_tiles;
+        const int tail_units = tail_tiles * m_blocks, nc = f.K / MB_CK;
+        if (tail_tiles > 0) {
+            int ks = slots / tail_units;
+            if (ks > 4) ks = 4;
+            if (ks > nc) ks = nc;
+            const size_t per_slice = (size_t)2 * f.M * tail_tiles * (tn / 2);
+            if ((size_t)ks * per_slice > f.kpart_floats) ks = (int)(f.kpart_floats / per_slice);
+            if (ks > 1) {
+                if (whole_tiles > 0) {
+                    RowsP2 a = p;
+                    a.n_tiles = whole_tiles;
+                    const hipError_t e = f16 ? launch_big_tn<RM_SWIGLU, true>(a, tn, s) : launch_big_tn<RM_SWIGLU, false>(a, tn, s);
+                    if (e != hipSuccess) return e;
+                }
+                p.tile0 = whole_tiles; p.n_tiles = tail_tiles; p.fin_tile0 = whole_tiles * (tn / 128);
+                p.ksplit = ks; p.kpart = f.kpart;
+            }
+        }
     }
     switch (f.mode) {
         case RM_STORE: return f16 ? launch_big_tn<RM_STORE, true>(p, tn, s) : launch_big_tn<RM_STORE, false>(p, tn, s);

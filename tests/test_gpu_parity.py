@@ -17,8 +17,11 @@ GQA16 = ModelShape(3, 512, 4, 2, 688, 1024, dtype="fp16")       # fp16, head_dim
 WIDE64 = ModelShape(3, 512, 8, 1, 1408, 2048)                   # bf16, one KV head of 64: fits the 64-row prompt tiling only
 TILE128 = ModelShape(3, 384, 3, 3, 1472, 2176)                  # bf16, head_dim 128, widths 3 x 128, FFN 23 x 64, vocab 17 x 128:
                                                                  # every prompt GEMM takes the 128-row tiles (K-split included)
+TALLFFN = ModelShape(2, 256, 2, 2, 11008, 1024)                  # bf16, the 7B FFN width on a narrow model: with 385+ prompt rows the
+                                                                 # gate/up GEMM has more 256-row blocks than CUs -> its last tiles are cut along K
+TALLFFN64 = ModelShape(2, 256, 2, 2, 11072, 1024, dtype="fp16") # fp16, FFN 173 x 64: the same with 128-row tiles (two blocks per CU)
 SHAPES = {"tiny": WORKLOADS["tiny"].shape, "mini": MINI, "gqa": GQA, "gqa32": GQA32, "mini16": MINI16, "gqa16": GQA16,
-          "wide64": WIDE64, "tile128": TILE128}
+          "wide64": WIDE64, "tile128": TILE128, "tallffn": TALLFFN, "tallffn64": TALLFFN64}
 
 
 @pytest.fixture(scope="module")
@@ -45,7 +48,7 @@ def test_prefill_logits_and_first_token(ssd, name, plen):
     assert ctx.ssd_get_stats()["n_tokens"] == plen + 1
 
 
-@pytest.mark.parametrize("name", ["mini", "gqa", "mini16", "wide64", "tile128"])
+@pytest.mark.parametrize("name", ["mini", "gqa", "mini16", "wide64", "tile128", "tallffn", "tallffn64"])
 @pytest.mark.parametrize("plen", [129, 512, 513, 700])
 def test_long_prompt_blocks(ssd, name, plen):
     """Prompts of several 128-row blocks per pass and of more than one pass (SSD_PREFILL_ROWS = 512 rows), ragged: the
@@ -116,6 +119,8 @@ MASKS = {
     "gqa16": [[0, 0, 0], [0, 1, 0]],
     "wide64": [[0, 0, 0], [0, 1, 0]],
     "tile128": [[0, 0, 0], [0, 1, 0]],
+    "tallffn": [[0, 0], [0, 1]],
+    "tallffn64": [[0, 0], [0, 1]],
 }
 
 
