@@ -1598,26 +1598,41 @@ __global__ __launch_bounds__(512) void rows_wide_kernel(RowsP2 p)
     }
 }
 
-// Second half of a K-split launch: one wave per (row, 64-column tile) adds the slices in a fixed order, applies
-// the RMS scale of the row (summing the producer's partials itself) and runs the mode's epilogue.
+// Second half of a K-split launch: one wave per (FIN_ROWS rows, 64-column tile) adds the slices in a fixed order,
+// applies the RMS scale of each row (summing the producer's partials itself) and runs the mode's epilogue.  The
+// loads of the wave's rows are independent and issued together.
+constexpr int FIN_ROWS = 4;
 template <int MODE, bool F16>
 __global__ __launch_bounds__(64) void rows_finish_kernel(RowsP2 p)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
-    const int tile = blockIdx.x + p.fin_tile0, m = blockIdx.y, lane = threadIdx.x;   // kpart covers this launch's tiles only
+    const int tile = blockIdx.x + p.fin_tile0, lane = threadIdx.x;   // kpart covers this launch's tiles only
+    const int mbase = blockIdx.y * FIN_ROWS;
     const size_t nt = (size_t)gridDim.x * 64, colx = (size_t)blockIdx.x * 64 + lane;
-    float v = 0.f, v2 = 0.f;
+    float v[FIN_ROWS], v2[FIN_ROWS];
+#pragma unroll
+    for (int r = 0; r < FIN_ROWS; r++) v[r] = v2[r] = 0.f;
     for (int sl = 0; sl < p.ksplit; sl++) {
-        v += p.kpart[(((size_t)sl * NT + 0) * p.M + m) * nt + colx];
-        if (MODE == RM_SWIGLU) v2 += p.kpart[(((size_t)sl * NT + 1) * p.M + m) * nt + colx];
+#pragma unroll
+        for (int r = 0; r < FIN_ROWS; r++) {
+            const int m = min(mbase + r, p.M - 1);   // rows past M re-read the last row, never written
+            v[r] += p.kpart[(((size_t)sl * NT + 0) * p.M + m) * nt + colx];
+            if (MODE == RM_SWIGLU) v2[r] += p.kpart[(((size_t)sl * NT + 1) * p.M + m) * nt + colx];
+        }
     }
-    if (MODE != RM_RESID && p.ssq) {
-        float sq = 0.f;
-        for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)m * p.n_ssq + i];
-        const float sc = 1.0f / sqrtf(wave_sum(sq) / (float)p.K + p.eps);
-        v *= sc; v2 *= sc;
+#pragma unroll
+    for (int r = 0; r < FIN_ROWS; r++) {
+        const int m = mbase + r;
+        if (m >= p.M) break;   // uniform
+        float a = v[r], b = v2[r];
+        if (MODE != RM_RESID && p.ssq) {
+            float sq = 0.f;
+            for (int i = lane; i < p.n_ssq; i += 64) sq += p.ssq[(size_t)m * p.n_ssq + i];
+            const float sc = 1.0f / sqrtf(wave_sum(sq) / (float)p.K + p.eps);
+            a *= sc; b *= sc;
+        }
+        m6_epilogue<MODE, F16>(p, tile, m, lane, a, b);
     }
-    m6_epilogue<MODE, F16>(p, tile, m, lane, v, v2);
 }
 
 // --- large-tile variant: any number of activation rows in one launch (whole prompts, the context window) --------
@@ -1958,7 +1973,7 @@ static hipError_t launch_wide_d(const RowsP2& p, int n_tiles, hipStream_t s)
     hipLaunchKernelGGL((rows_wide_kernel<MODE, F16, DEPTH>), dim3(n_tiles, S), dim3(512), lds, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
-    hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(n_tiles, p.M), dim3(64), 0, s, p);
+    hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(n_tiles, (p.M + FIN_ROWS - 1) / FIN_ROWS), dim3(64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -2036,7 +2051,7 @@ static hipError_t launch_big(const RowsP2& p, hipStream_t s)
     if (MODE == RM_QKV)   // natural row order: its own finishing kernel
         hipLaunchKernelGGL((rows_finish_qkv_kernel<F16>), dim3(p.n_tiles * (TN / 64), p.M), dim3(64), 0, s, p);
     else
-        hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(p.n_tiles * (MODE == RM_SWIGLU ? TN / 128 : TN / 64), p.M), dim3(64), 0, s, p);
+        hipLaunchKernelGGL((rows_finish_kernel<MODE, F16>), dim3(p.n_tiles * (MODE == RM_SWIGLU ? TN / 128 : TN / 64), (p.M + FIN_ROWS - 1) / FIN_ROWS), dim3(64), 0, s, p);
     return hipGetLastError();
 }
 
