@@ -256,6 +256,23 @@ int main(int argc, char** argv)
         }
         return 0;
     }
+    if (std::getenv("KB_GEMV")) {   // QKV, gate/up and LM-head GEMVs: work split (rows per wave, steps in flight, K split) x block cap
+        for (int cfg : {0, 281, 441, 421, 221, 242}) for (int cap : {0, 512, 1024}) {
+            opts.gemv_cfg = cfg; opts.gemv_block_cap = cap;
+            char nm[96];
+            std::snprintf(nm, sizeof nm, "gemv_qkv cfg %d cap %d", cfg, cap);
+            timeit(nm, 3 * qk * 2.0, n, [&](int i) {
+                const uint16_t* w = W + (size_t)i * 3 * qk;
+                CK(gemv_qkv(D, w, w + qk, w + 2 * qk, gain, x, rope, pos, 0, q, kc, vc, 0)); });
+            std::snprintf(nm, sizeof nm, "gemv_gateup cfg %d cap %d", cfg, cap);
+            timeit(nm, 2 * gu * 2.0, n, [&](int i) {
+                const uint16_t* w = W + (size_t)i * 2 * gu;
+                CK(gemv_swiglu(D, w, w + gu, gain, x, act, 0)); });
+            std::snprintf(nm, sizeof nm, "gemv_lmhead cfg %d cap %d", cfg, cap);
+            timeit(nm, lm * 2.0, n, [&](int i) { CK(gemv_lmhead(D, W + (size_t)i * lm, gain, x, logits, 0)); });
+        }
+        return 0;
+    }
     if (std::getenv("KB_SWEEP")) {   // launch time against size: fixed cost and streaming rate of probe and GEMV
         for (int mb : {16, 32, 64, 128, 256}) {
             char nm[64];

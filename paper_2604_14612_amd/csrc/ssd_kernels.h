@@ -16,6 +16,7 @@ struct LaunchOpts {
     int gemv_resid_cfg = 0;     // residual projections: 100 R + 10 D + KS forces rows per group / steps in flight / K split
     int rows_depth = 0;         // > 0 forces the number of weight stripes a 16-row block keeps in flight
     int wide_depth = 0;         // the same for the 64-row blocks
+    int gemv_cfg = 0;           // single-row GEMVs other than the residual projections: 100 R + 10 D + KS of a work split (kernel_bench sweeps)
     int wide_ksplit = 0;        // 64-row blocks: 1 = never cut K, > 1 forces the number of K slices
     int attn_splits = 0;        // > 0 forces the attention split count (scratch must have been sized for it)
     int attn_kernel = 0;        // 0 heuristic, 1 LDS-staged kernel always, 3 the same in its plain (non-MFMA) form

@@ -16,6 +16,7 @@
 
 #include <math.h>
 
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 
@@ -273,11 +274,23 @@ template <typename WT> __device__ __forceinline__ u32x4_t gv_load(const WT* p)
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
 }
 
-// acc += w . x for one 128-bit weight vector; xs points at the matching activations in LDS
+// LDS position of element i of the staged input vector.  With 8 elements per lane (16-bit weights) a chunk of 512
+// elements is stored as two planes of 64 float4: plane 0 holds elements 8 l .. 8 l + 3 of lane l, plane 1 elements
+// 8 l + 4 .. 8 l + 7, so that each of a wave's two 128-bit reads covers 1 KB of consecutive LDS (in natural order the
+// lanes are 32 bytes apart and every read has two-way bank conflicts: measured 1.6-2 us of a 32 us launch).
+template <int VEC> __device__ __forceinline__ int gv_xpos(int i)
+{
+    if (VEC != 8) return i;
+    return (i & ~511) + ((i >> 2) & 1) * 256 + ((i & 511) >> 3) * 4 + (i & 3);
+}
+constexpr int GV_XB = 256;   // floats between a lane's two float4 (16-bit weights)
+constexpr int GV_RES_ROUNDS = 8;   // rounds of a block whose residual values are staged in LDS (later rounds read memory)
+
+// acc += w . x for one 128-bit weight vector; xs points at the lane's activations of this chunk in LDS
 template <typename WT> __device__ __forceinline__ float gv_dot(u32x4_t w, const float* xs, float acc);
 template <> __device__ __forceinline__ float gv_dot<uint16_t>(u32x4_t w, const float* xs, float acc)
 {
-    float4 a = *reinterpret_cast<const float4*>(xs), b = *reinterpret_cast<const float4*>(xs + 4);
+    float4 a = *reinterpret_cast<const float4*>(xs), b = *reinterpret_cast<const float4*>(xs + GV_XB);
     acc = fmaf(__uint_as_float(w.x << 16), a.x, acc);
     acc = fmaf(__uint_as_float(w.x & 0xffff0000u), a.y, acc);
     acc = fmaf(__uint_as_float(w.y << 16), a.z, acc);
@@ -291,7 +304,7 @@ template <> __device__ __forceinline__ float gv_dot<uint16_t>(u32x4_t w, const f
 template <> __device__ __forceinline__ float gv_dot<f16_t>(u32x4_t w, const float* xs, float acc)
 {
     const f16x8_t h = __builtin_bit_cast(f16x8_t, w);
-    float4 a = *reinterpret_cast<const float4*>(xs), b = *reinterpret_cast<const float4*>(xs + 4);
+    float4 a = *reinterpret_cast<const float4*>(xs), b = *reinterpret_cast<const float4*>(xs + GV_XB);
     acc = fmaf((float)h[0], a.x, acc); acc = fmaf((float)h[1], a.y, acc);
     acc = fmaf((float)h[2], a.z, acc); acc = fmaf((float)h[3], a.w, acc);
     acc = fmaf((float)h[4], b.x, acc); acc = fmaf((float)h[5], b.y, acc);
@@ -346,13 +359,16 @@ __device__ __forceinline__ void vstat_merge(VStat& a, const VStat& b)
     }
 }
 
-// finished sums s[0..R) of logical rows j0.. ; sc = RMS scale (1 when no norm)
+// finished sums s[0..R) of logical rows j0.. ; sc = RMS scale (1 when no norm).  What the epilogue reads besides its
+// sums comes out of LDS, staged by the kernel's prologue -- the rotary row of the position (rope_row, QKV) and the
+// residual values of the group (res, null = read them from memory) -- so that no memory load sits between the steps
+// of the weight pipeline (a load there has to be waited for together with every weight load in flight).
 template <typename WT, int EPI, int R>
-__device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float (&s)[R], float sc, VStat& vs)
+__device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float (&s)[R], float sc, VStat& vs, int pos,
+                                            const float* rope_row, const float* res)
 {
     if (EPI == EPI_QKV) {
         const int half = p.hd >> 1;
-        const int pos = p.pos_dev[0] + p.pos_off;
 #pragma unroll
         for (int t = 0; t < R; t += 2) {
             const int j = j0 + t;
@@ -361,7 +377,7 @@ __device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float 
                 const bool is_q = j < p.dq;
                 const int jj = is_q ? j : j - p.dq;
                 const int head = jj / p.hd, i = (jj % p.hd) >> 1;
-                const float* cs = p.rope + ((size_t)pos * half + i) * 2;
+                const float* cs = rope_row + i * 2;
                 const float c = cs[0], sn = cs[1];
                 const float ra = a * c - b * sn, rb = b * c + a * sn;
                 if (is_q) {
@@ -392,7 +408,7 @@ __device__ __forceinline__ void gv_epilogue(const GemvP& p, int j0, const float 
 #pragma unroll
         for (int t = 0; t < R; t++) {
             // chained: the residual was written by a kernel that may still have been running when this one started
-            const float v = (p.wait_flag ? coh_load(p.y + j0 + t) : p.y[j0 + t]) + s[t];
+            const float v = (res ? res[t] : p.wait_flag ? coh_load(p.y + j0 + t) : p.y[j0 + t]) + s[t];
             if (p.done_flag) coh_store(p.y + j0 + t, v);
             else p.y[j0 + t] = v;
             if (p.tap) p.tap[j0 + t] = v;
@@ -413,42 +429,48 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
     extern __shared__ __align__(16) float xs[];
     __shared__ float red[GV_WAVES];
     __shared__ float part[GV_WAVES][R];
+    __shared__ float rope_row[EPI == EPI_QKV ? 128 : 1];                                  // (cos, sin) pairs of the position
+    __shared__ float res_s[EPI == EPI_RESID ? GV_WAVES * GV_RES_ROUNDS * R : 1];          // [group slot][round][row]
     constexpr int VEC = Elem<WT>::VEC, CH = 64 * VEC, GPB = GV_WAVES / KS;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    // made wave-uniform for the compiler: group numbers and row pointers stay in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int grp = wave / KS, kp = wave % KS;
     const int K = p.K;
     const int n_groups = p.n_rows / R;
     const int nfull = K / CH, tail = K - nfull * CH;   // tail is a multiple of VEC
-    // Every wave of the block walks the same (round, step) sequence so that block barriers stay
-    // uniform: S steps per group, wave kp owns chunk kp + step*KS when that chunk exists.
-    const int S = nfull > 0 ? (nfull + KS - 1) / KS : 1;
-    const bool my_tail = tail > 0 && (nfull % KS) == kp && lane * VEC < tail;
+    // A row is NCH chunks of one load step, the last one partial when tail > 0 (lanes past the row's end are masked).
+    // Wave kp owns chunks kp, kp + KS, ..: S steps per group, the same for every wave of the block so that block
+    // barriers stay uniform.
+    const int NCH = nfull + (tail > 0 ? 1 : 0);
+    const int S = (NCH + KS - 1) / KS;
     const int n_gblocks = (n_groups + GPB - 1) / GPB;
     const int n_rounds = (n_gblocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
-    const size_t lane_off = (size_t)kp * CH + lane * VEC;
+    const int T = n_rounds * S;   // this wave's items (group, step), walked in order
+    const int lv_full = lane * VEC;
+    const int lv_tail = tail > 0 ? min(lane * VEC, tail - VEC) : 0;   // lanes past a partial chunk re-read its last vector
+    const bool lane_in_tail = lane * VEC < tail;
 
-    // issue side of the software pipeline: runs D steps ahead of the consume side, across groups
+    // Issue side of the software pipeline: D items ahead of the consume side, across groups.  Every issue is
+    // UNCONDITIONAL -- a slot past the last group re-reads the last group, a step past the last chunk re-reads the last
+    // chunk, and such items are never consumed.  With conditional loads the compiler cannot count what is in flight and
+    // waits for everything, the loads just issued included, before every step: one memory latency per step.
     int ri = 0, ci = 0;
-    bool ai = false;
     const WT* wi[R];
     auto set_issue_rows = [&]() {
-        const int g = ((int)blockIdx.x + ri * (int)gridDim.x) * GPB + grp;
-        ai = ri < n_rounds && g < n_groups;
-        if (ai) {
+        int g = ((int)blockIdx.x + min(ri, max(n_rounds - 1, 0)) * (int)gridDim.x) * GPB + grp;
+        g = min(g, n_groups - 1);
 #pragma unroll
-            for (int r = 0; r < R; r++) wi[r] = gv_row_ptr<WT, EPI>(p, g * R + r) + lane_off;
-        }
+        for (int r = 0; r < R; r++) wi[r] = gv_row_ptr<WT, EPI>(p, g * R + r);
     };
     set_issue_rows();
     u32x4_t buf[D][R];
     auto issue = [&](int s) {
-        if (ri < n_rounds) {
-            if (ai && kp + ci * KS < nfull) {
+        const int c = min(kp + ci * KS, NCH - 1);
+        const size_t off = (size_t)c * CH + (c == nfull ? lv_tail : lv_full);
 #pragma unroll
-                for (int r = 0; r < R; r++) buf[s][r] = gv_load(wi[r] + (size_t)ci * KS * CH);
-            }
-            if (++ci == S) { ci = 0; ++ri; set_issue_rows(); }
-        }
+        for (int r = 0; r < R; r++) buf[s][r] = gv_load(wi[r] + off);
+        if (++ci == S) { ci = 0; ++ri; set_issue_rows(); }
     };
     // the first weight loads do not depend on the activations: start them before staging the input
 #pragma unroll
@@ -486,7 +508,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
                 num.z = fmaf(w, oo[sp].z, num.z); num.w = fmaf(w, oo[sp].w, num.w);
                 den = fmaf(w, ll[sp], den);
             }
-            *reinterpret_cast<float4*>(xs + i) = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
+            *reinterpret_cast<float4*>(xs + gv_xpos<VEC>(i)) = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
         }
     } else
     for (int i = threadIdx.x * 4; i < K; i += GV_THREADS * 4) {
@@ -496,7 +518,20 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
             const float4 g = *reinterpret_cast<const float4*>(p.gain + i);
             v.x *= g.x; v.y *= g.y; v.z *= g.z; v.w *= g.w;
         }
-        *reinterpret_cast<float4*>(xs + i) = v;
+        *reinterpret_cast<float4*>(xs + gv_xpos<VEC>(i)) = v;
+    }
+    int pos = 0;
+    if (EPI == EPI_QKV) {
+        pos = p.pos_dev[0] + p.pos_off;
+        if ((int)threadIdx.x < p.hd) rope_row[threadIdx.x] = p.rope[(size_t)pos * p.hd + threadIdx.x];   // hd / 2 pairs
+    }
+    if (EPI == EPI_RESID) {
+        for (int i = threadIdx.x; i < GPB * GV_RES_ROUNDS * R; i += GV_THREADS) {
+            const int r = i % R, rnd = (i / R) % GV_RES_ROUNDS, gs = i / (R * GV_RES_ROUNDS);
+            const int g = ((int)blockIdx.x + rnd * (int)gridDim.x) * GPB + gs;
+            if (rnd < n_rounds && g < n_groups)
+                res_s[(gs * GV_RES_ROUNDS + rnd) * R + r] = p.wait_flag ? coh_load(p.y + g * R + r) : p.y[g * R + r];
+        }
     }
     float sc = 1.0f;
     if (p.gain) {
@@ -511,63 +546,65 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
         sc = 1.0f / sqrtf(t / (float)K + p.eps);
     }
 
-    const float* xp = xs + lane_off;
+    const float* xp = xs + (size_t)kp * CH + lane * (VEC == 8 ? 4 : VEC);   // the lane's first float4 of chunk kp
     VStat vs = {-INFINITY, 0.f, 0x7fffffff};
     int rc = 0, cc = 0;
     float acc[R];
 #pragma unroll
     for (int r = 0; r < R; r++) acc[r] = 0.f;
-    while (rc < n_rounds) {
+    auto consume = [&](int s) {
+        if (rc < n_rounds) {   // uniform over the block; false only for the padding items behind the last group
+            const int g = ((int)blockIdx.x + rc * (int)gridDim.x) * GPB + grp;
+            const bool act = g < n_groups;
+            const int c = kp + cc * KS;
+            if (act && (c < nfull || (c == nfull && lane_in_tail))) {
 #pragma unroll
-        for (int s = 0; s < D; s++) {
-            if (rc < n_rounds) {  // uniform over the block
-                const int g = ((int)blockIdx.x + rc * (int)gridDim.x) * GPB + grp;
-                const bool act = g < n_groups;
-                if (act && kp + cc * KS < nfull) {
+                for (int r = 0; r < R; r++) acc[r] = gv_dot<WT>(buf[s][r], xp + (size_t)cc * KS * CH, acc[r]);
+            }
+            if (++cc == S) {  // group finished
 #pragma unroll
-                    for (int r = 0; r < R; r++) acc[r] = gv_dot<WT>(buf[s][r], xp + (size_t)cc * KS * CH, acc[r]);
-                }
-                issue(s);
-                if (++cc == S) {  // group finished
-                    if (act && my_tail) {  // the one partial chunk: only lanes still inside the row take part
-                        const size_t o = (size_t)(nfull - kp) * CH;
+                for (int r = 0; r < R; r++) acc[r] = wave_sum(acc[r]);
+                const float* res = (EPI == EPI_RESID && rc < GV_RES_ROUNDS) ? res_s + (grp * GV_RES_ROUNDS + rc) * R : nullptr;
+                if (KS == 1) {
+                    if (act && lane == 0) gv_epilogue<WT, EPI, R>(p, g * R, acc, sc, vs, pos, rope_row, res);
+                } else {
+                    if (lane == 0) {
+#pragma unroll
+                        for (int r = 0; r < R; r++) part[wave][r] = acc[r];
+                    }
+                    __syncthreads();
+                    if (act && kp == 0 && lane == 0) {
+                        float sm[R];
 #pragma unroll
                         for (int r = 0; r < R; r++) {
-                            const WT* w = gv_row_ptr<WT, EPI>(p, g * R + r) + lane_off + o;
-                            acc[r] = gv_dot<WT>(gv_load(w), xp + o, acc[r]);
+                            float t = 0.f;
+#pragma unroll
+                            for (int j = 0; j < KS; j++) t += part[grp * KS + j][r];
+                            sm[r] = t;
                         }
+                        gv_epilogue<WT, EPI, R>(p, g * R, sm, sc, vs, pos, rope_row, res);
                     }
-#pragma unroll
-                    for (int r = 0; r < R; r++) acc[r] = wave_sum(acc[r]);
-                    if (KS == 1) {
-                        if (act && lane == 0) gv_epilogue<WT, EPI, R>(p, g * R, acc, sc, vs);
-                    } else {
-                        if (lane == 0) {
-#pragma unroll
-                            for (int r = 0; r < R; r++) part[wave][r] = acc[r];
-                        }
-                        __syncthreads();
-                        if (act && kp == 0 && lane == 0) {
-                            float sm[R];
-#pragma unroll
-                            for (int r = 0; r < R; r++) {
-                                float t = 0.f;
-#pragma unroll
-                                for (int j = 0; j < KS; j++) t += part[grp * KS + j][r];
-                                sm[r] = t;
-                            }
-                            gv_epilogue<WT, EPI, R>(p, g * R, sm, sc, vs);
-                        }
-                        __syncthreads();
-                    }
-#pragma unroll
-                    for (int r = 0; r < R; r++) acc[r] = 0.f;
-                    cc = 0;
-                    ++rc;
+                    __syncthreads();
                 }
+#pragma unroll
+                for (int r = 0; r < R; r++) acc[r] = 0.f;
+                cc = 0;
+                ++rc;
             }
         }
+    };
+    // steady state: every step consumes the oldest item and refills its slot; the last D items are consumed without
+    // a refill (the item count is padded to a multiple of D: padding items are re-reads that are not consumed)
+    const int Tp = (T + D - 1) / D * D;
+    for (int t = 0; t + D < Tp; t += D) {
+#pragma unroll
+        for (int s = 0; s < D; s++) {
+            consume(s);
+            issue(s);
+        }
     }
+#pragma unroll
+    for (int s = 0; s < D; s++) consume(s);
     chain_signal(p);
     if (EPI == EPI_STORE && p.vstat) {   // block partial of the soft-max statistics: lane 0 of every wave holds one
         __shared__ float vred[GV_WAVES * 3];
@@ -630,7 +667,8 @@ static hipError_t ensure_lds(const void* fn, size_t lds, std::atomic<size_t>& li
 template <typename WT, int EPI, int R, int D, int KS>
 static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s, LaunchOpts* opt, int* blocks_out)
 {
-    size_t lds = (size_t)p.K * sizeof(float);
+    constexpr int CHF = 64 * Elem<WT>::VEC;   // the staged vector is laid out in whole chunks of one load step
+    size_t lds = (size_t)ceil_div(p.K, CHF) * CHF * sizeof(float);
     static std::atomic<size_t> lds_limit{0};  // per instantiation
     {
         hipError_t e = ensure_lds((const void*)gemv_kernel<WT, EPI, R, D, KS>, lds, lds_limit);
@@ -638,10 +676,12 @@ static hipError_t launch_gemv_cfg(const GemvP& p, hipStream_t s, LaunchOpts* opt
     }
     constexpr int GPB = GV_WAVES / KS;
     int blocks = ceil_div(p.n_rows / R, GPB);
-    // three blocks fit a CU at this kernel's register use: 768 persistent blocks are all resident at once
-    // and leave no second, partial round of blocks.  The variant that folds attention partials in its
-    // prologue re-reads them per block, so it runs one block per CU.
-    int cap = p.part ? 256 : 768;
+    // up to four blocks fit a CU (registers: eight waves per SIMD; LDS: the staged vector): persistent blocks that are
+    // all resident at once leave no second, partial round of blocks.  Measured: three per CU are best for the
+    // layer's GEMVs, four for the LM head.  The variant that folds attention partials in its prologue re-reads them
+    // per block, so it runs one block per CU.
+    const int per_cu = (int)std::min<size_t>(EPI == EPI_STORE ? 4 : 3, std::max<size_t>(1, ((size_t)160 << 10) / (lds + 1024)));
+    int cap = p.part ? 256 : 256 * per_cu;
     if (opt && opt->gemv_block_cap > 0) cap = opt->gemv_block_cap;
     if (blocks > cap) {
         // equal work per block: with r rounds needed, use just enough blocks for r full rounds (gate/up at 7B:
@@ -685,13 +725,26 @@ static hipError_t launch_gemv_t(const GemvP& p, hipStream_t s, LaunchOpts* opt, 
             default: break;
         }
     }
-    if (p.n_rows >= 8192) return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s, opt, blocks_out);
+    if constexpr (EPI != EPI_RESID && sizeof(WT) == 2) {   // tuning hook (kernel_bench sweeps)
+        switch (opt ? opt->gemv_cfg : 0) {
+            case 281: return launch_gemv_cfg<WT, EPI, 2, 8, 1>(p, s, opt, blocks_out);
+            case 441: return launch_gemv_cfg<WT, EPI, 4, 4, 1>(p, s, opt, blocks_out);
+            case 421: return launch_gemv_cfg<WT, EPI, 4, 2, 1>(p, s, opt, blocks_out);
+            case 221: return launch_gemv_cfg<WT, EPI, 2, 2, 1>(p, s, opt, blocks_out);
+            case 242: return launch_gemv_cfg<WT, EPI, 2, 4, 2>(p, s, opt, blocks_out);
+            default: break;
+        }
+    }
+    // measured (work-split sweeps at the 7B shape, `KB_GEMV=1` / `KB_RESID=1 kernel_bench`): row pairs with four steps
+    // in flight everywhere; QKV and gate/up gain 0.5-0.8 us from two waves sharing a pair, the down projection 0.4 us
+    // from four, the LM head and the projection that folds the attention partials are best with a wave per pair
+    if (p.n_rows >= 8192) {
+        if constexpr (sizeof(WT) == 2 && (EPI == EPI_QKV || EPI == EPI_SWIGLU)) return launch_gemv_cfg<WT, EPI, 2, 4, 2>(p, s, opt, blocks_out);
+        return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s, opt, blocks_out);
+    }
     if constexpr (EPI == EPI_RESID && sizeof(WT) == 2) {
-        // measured (work-split sweep of the two residual projections at the 7B shape): the variant that folds
-        // attention partials gains 0.7 us from four rows and four steps in flight per wave, the down projection
-        // 0.4 us from row pairs with K cut four ways
-        if (p.part && ch <= 12) return launch_gemv_cfg<WT, EPI, 4, 4, 2>(p, s, opt, blocks_out);
-        if (ch > 12 && ch <= 40) return launch_gemv_cfg<WT, EPI, 2, 2, 4>(p, s, opt, blocks_out);
+        if (p.part && ch <= 12) return launch_gemv_cfg<WT, EPI, 2, 4, 1>(p, s, opt, blocks_out);
+        if (ch > 12 && ch <= 40) return launch_gemv_cfg<WT, EPI, 2, 4, 4>(p, s, opt, blocks_out);
     }
     if (ch <= 12) return launch_gemv_cfg<WT, EPI, 2, 2, 2>(p, s, opt, blocks_out);
     if (ch <= 40) return launch_gemv_cfg<WT, EPI, 4, 2, 4>(p, s, opt, blocks_out);
@@ -1186,7 +1239,9 @@ __device__ __forceinline__ void m2_epilogue(const RowsP2& p, int t, const float*
 constexpr int M3_CK = 512;
 constexpr int M3_PITCH = M3_CK * 2 + 16;  // bytes per LDS row (16-byte pad spreads the banks)
 
-template <int MODE, int M3_D, bool F16>  // M3_D = stripes in flight per block; F16: fp16 storage, else bf16
+// M3_D = stripes in flight per block; F16: fp16 storage, else bf16; NU = activation vectors per thread and stripe
+// (2 covers up to 8 rows, 4 up to 16)
+template <int MODE, int M3_D, bool F16, int NU>
 __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
@@ -1206,49 +1261,52 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
-        for (int j = 0; j < 2; j++) ap[t][j] = m2_row<MODE>(p, tile, 2 * wave + j, t) + lane * 8;
+        for (int j = 0; j < 2; j++) ap[t][j] = m2_row<MODE>(p, tile, 2 * wave + j, t);
     // activation vectors (16 bytes each) of one stripe: [hi|lo][M][64]; thread takes v = tid, tid+512, ...
     const int nbv = M * 128;
-    const uint16_t* bsrc[4];
-    int bdst[4];
-    int bk[4];
+    const uint16_t* bsrc[NU];
+    int bdst[NU];
+    int bk[NU];
 #pragma unroll
-    for (int u = 0; u < 4; u++) {
+    for (int u = 0; u < NU; u++) {
         const int v = min(tid + u * 512, nbv - 1);
         const int which = v / (M * 64), rem = v % (M * 64), c = rem >> 6, kk = (rem & 63) * 8;
-        bsrc[u] = (which ? p.bl : p.bh) + (size_t)c * p.ldb + kk;
+        bsrc[u] = (which ? p.bl : p.bh) + (size_t)c * p.ldb;
         bdst[u] = (which ? M : 0) * M3_PITCH + c * M3_PITCH + kk * 2;
         bk[u] = kk;
     }
-    // register ring: the loads of the next M3_D stripes are in flight while one stripe is multiplied
-    u32x4_t ra[M3_D][NT][2], rb[M3_D][4];
+    // Register ring: the loads of the next M3_D stripes are in flight while one stripe is multiplied.  Every load is
+    // UNCONDITIONAL: addresses past the end of K (or past the last activation vector) are clamped to valid ones and
+    // the values are replaced by zeros when the stripe is stored to LDS.  With loads under conditions the compiler
+    // cannot count what is in flight and waits for everything, the stripes just requested included.
+    u32x4_t ra[M3_D][NT][2], rb[M3_D][NU];
     const u32x4_t zero4 = {0u, 0u, 0u, 0u};
     auto gload = [&](int slot, int ck) {
         const int k0 = ck * M3_CK;
-        const bool ok = k0 + lane * 8 < K;
+        const int ka = min(k0 + lane * 8, K - 8);
 #pragma unroll
         for (int t = 0; t < NT; t++)
 #pragma unroll
-            for (int j = 0; j < 2; j++) ra[slot][t][j] = ok ? gv_load(ap[t][j] + k0) : zero4;
+            for (int j = 0; j < 2; j++) ra[slot][t][j] = gv_load(ap[t][j] + ka);
 #pragma unroll
-        for (int u = 0; u < 4; u++)
-            if (tid + u * 512 < nbv)
-                rb[slot][u] = k0 + bk[u] < K ? *reinterpret_cast<const u32x4_t*>(bsrc[u] + k0) : zero4;
+        for (int u = 0; u < NU; u++) rb[slot][u] = *reinterpret_cast<const u32x4_t*>(bsrc[u] + min(k0 + bk[u], K - 8));
     };
     f32x4_t acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; t++) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int bc = min(r16, M - 1);  // columns >= M read a valid row; their results are never stored
-    auto stage = [&](int slot) {
+    auto stage = [&](int slot, int ck) {
+        const int k0 = ck * M3_CK;
+        const bool ok = k0 + lane * 8 < K;
         __syncthreads();  // previous stripe fully consumed
 #pragma unroll
         for (int t = 0; t < NT; t++)
 #pragma unroll
             for (int j = 0; j < 2; j++)
-                *reinterpret_cast<u32x4_t*>(As + (t * 16 + 2 * wave + j) * M3_PITCH + lane * 16) = ra[slot][t][j];
+                *reinterpret_cast<u32x4_t*>(As + (t * 16 + 2 * wave + j) * M3_PITCH + lane * 16) = ok ? ra[slot][t][j] : zero4;
 #pragma unroll
-        for (int u = 0; u < 4; u++)
-            if (tid + u * 512 < nbv) *reinterpret_cast<u32x4_t*>(Bh + bdst[u]) = rb[slot][u];
+        for (int u = 0; u < NU; u++)
+            if (tid + u * 512 < nbv) *reinterpret_cast<u32x4_t*>(Bh + bdst[u]) = k0 + bk[u] < K ? rb[slot][u] : zero4;
         __syncthreads();
     };
     auto multiply = [&](int ck) {
@@ -1266,8 +1324,7 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
         }
     };
 #pragma unroll
-    for (int sl = 0; sl < M3_D; sl++)
-        if (sl < NC) gload(sl, sl);
+    for (int sl = 0; sl < M3_D; sl++) gload(sl, min(sl, NC - 1));
     // RMS scale of every activation row from the producer's per-tile sums of squares (read by the epilogue).
     // Measured per mode: gate/up (long-lived blocks, two stripes in flight) loses least when the partials are
     // summed after the weight stream, the short-lived blocks of QKV and the LM head when it happens up front.
@@ -1281,23 +1338,24 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
     };
     if (tid < 16) rs[tid] = 1.0f;
     if (MODE != RM_RESID && MODE != RM_SWIGLU && p.ssq) row_scales();
+    // steady state: every step stores its slot's stripe, refills the slot and multiplies; the stripe count is padded
+    // to a multiple of M3_D (a padding request re-reads the last stripe and is never stored); the last M3_D steps
+    // request nothing
+    const int NCp = (NC + M3_D - 1) / M3_D * M3_D;
     int ck0 = 0;
-    for (; ck0 + 2 * M3_D <= NC; ck0 += M3_D) {  // steady state: every step refills its slot, no conditions
+    for (; ck0 + M3_D < NCp; ck0 += M3_D) {
 #pragma unroll
         for (int sl = 0; sl < M3_D; sl++) {
-            stage(sl);
-            gload(sl, ck0 + sl + M3_D);
+            stage(sl, ck0 + sl);
+            gload(sl, min(ck0 + sl + M3_D, NC - 1));
             multiply(ck0 + sl);
         }
     }
-    for (; ck0 < NC; ck0 += M3_D) {  // drain
 #pragma unroll
-        for (int sl = 0; sl < M3_D; sl++) {
-            if (ck0 + sl < NC) {
-                stage(sl);
-                if (ck0 + sl + M3_D < NC) gload(sl, ck0 + sl + M3_D);
-                multiply(ck0 + sl);
-            }
+    for (int sl = 0; sl < M3_D; sl++) {
+        if (ck0 + sl < NC) {   // uniform
+            stage(sl, ck0 + sl);
+            multiply(ck0 + sl);
         }
     }
     if (MODE == RM_SWIGLU && p.ssq) row_scales();
@@ -1311,18 +1369,24 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
     m2_epilogue<MODE, F16>(p, tile, red, 8, 0, fin, rs);
 }
 
-template <int MODE, int DEPTH, bool F16>
-static hipError_t launch_mfma3(const RowsP2& p, int n_tiles, hipStream_t s)
+template <int MODE, int DEPTH, bool F16, int NU>
+static hipError_t launch_mfma3_nu(const RowsP2& p, int n_tiles, hipStream_t s)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     const size_t lds = (size_t)(NT * 16 + 2 * p.M) * M3_PITCH;
     static std::atomic<size_t> lds_limit{0};  // per instantiation
     {
-        hipError_t e = ensure_lds((const void*)rows_mfma3_kernel<MODE, DEPTH, F16>, lds, lds_limit);
+        hipError_t e = ensure_lds((const void*)rows_mfma3_kernel<MODE, DEPTH, F16, NU>, lds, lds_limit);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((rows_mfma3_kernel<MODE, DEPTH, F16>), dim3(n_tiles), dim3(512), lds, s, p);
+    hipLaunchKernelGGL((rows_mfma3_kernel<MODE, DEPTH, F16, NU>), dim3(n_tiles), dim3(512), lds, s, p);
     return hipGetLastError();
+}
+
+template <int MODE, int DEPTH, bool F16>
+static hipError_t launch_mfma3(const RowsP2& p, int n_tiles, hipStream_t s)
+{
+    return p.M <= 8 ? launch_mfma3_nu<MODE, DEPTH, F16, 2>(p, n_tiles, s) : launch_mfma3_nu<MODE, DEPTH, F16, 4>(p, n_tiles, s);
 }
 
 template <int MODE, bool F16>
@@ -1335,8 +1399,7 @@ static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s, const LaunchOp
     switch (depth) {
         case 1: return launch_mfma3<MODE, 1, F16>(p, n_tiles, s);
         case 2: return launch_mfma3<MODE, 2, F16>(p, n_tiles, s);
-        case 3: return launch_mfma3<MODE, 3, F16>(p, n_tiles, s);
-        default: return launch_mfma3<MODE, 4, F16>(p, n_tiles, s);
+        default: return launch_mfma3<MODE, 3, F16>(p, n_tiles, s);
     }
 }
 
