@@ -455,18 +455,27 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
     // UNCONDITIONAL -- a slot past the last group re-reads the last group, a step past the last chunk re-reads the last
     // chunk, and such items are never consumed.  With conditional loads the compiler cannot count what is in flight and
     // waits for everything, the loads just issued included, before every step: one memory latency per step.
-    int ri = 0, ci = 0;
+    // The waves of a launch start together and their rows lie a multiple of the memory channels' interleave apart:
+    // where a wave owns whole rows (KS = 1), group g walks its chunks starting at its (g mod S_kp)-th one and wraps
+    // around, so that the waves are spread over the row (and the channels) from the first step on; waves that share a
+    // row start at different chunks anyway (measured: the rotation gains 4 % on the LM head and loses 1-3 % there).
+    // S_kp = chunks this wave owns.
+    const int S_kp = kp < NCH ? (NCH - kp + KS - 1) / KS : 0;
+    int ri = 0, ci = 0, rot_i = 0;
     const WT* wi[R];
     auto set_issue_rows = [&]() {
         int g = ((int)blockIdx.x + min(ri, max(n_rounds - 1, 0)) * (int)gridDim.x) * GPB + grp;
         g = min(g, n_groups - 1);
+        rot_i = (KS == 1 && S_kp > 0) ? g % S_kp : 0;
 #pragma unroll
         for (int r = 0; r < R; r++) wi[r] = gv_row_ptr<WT, EPI>(p, g * R + r);
     };
     set_issue_rows();
     u32x4_t buf[D][R];
     auto issue = [&](int s) {
-        const int c = min(kp + ci * KS, NCH - 1);
+        int j = ci + rot_i;
+        if (j >= S_kp) j -= S_kp;
+        const int c = ci < S_kp ? kp + j * KS : NCH - 1;   // (a step past the wave's last chunk re-reads the row's last chunk)
         const size_t off = (size_t)c * CH + (c == nfull ? lv_tail : lv_full);
 #pragma unroll
         for (int r = 0; r < R; r++) buf[s][r] = gv_load(wi[r] + off);
@@ -556,10 +565,12 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
         if (rc < n_rounds) {   // uniform over the block; false only for the padding items behind the last group
             const int g = ((int)blockIdx.x + rc * (int)gridDim.x) * GPB + grp;
             const bool act = g < n_groups;
-            const int c = kp + cc * KS;
-            if (act && (c < nfull || (c == nfull && lane_in_tail))) {
+            int j = cc + ((KS == 1 && S_kp > 0) ? g % S_kp : 0);   // the issue side's chunk order
+            if (j >= S_kp) j -= S_kp;
+            const int c = kp + j * KS;
+            if (act && cc < S_kp && (c < nfull || lane_in_tail)) {
 #pragma unroll
-                for (int r = 0; r < R; r++) acc[r] = gv_dot<WT>(buf[s][r], xp + (size_t)cc * KS * CH, acc[r]);
+                for (int r = 0; r < R; r++) acc[r] = gv_dot<WT>(buf[s][r], xp + (size_t)j * KS * CH, acc[r]);
             }
             if (++cc == S) {  // group finished
 #pragma unroll
@@ -1240,7 +1251,7 @@ constexpr int M3_CK = 512;
 constexpr int M3_PITCH = M3_CK * 2 + 16;  // bytes per LDS row (16-byte pad spreads the banks)
 
 // M3_D = stripes in flight per block; F16: fp16 storage, else bf16; NU = activation vectors per thread and stripe
-// (2 covers up to 8 rows, 4 up to 16)
+// (2 covers up to 8 rows, 3 up to 12, 4 up to 16)
 template <int MODE, int M3_D, bool F16, int NU>
 __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
 {
@@ -1323,8 +1334,13 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
             }
         }
     };
+    // The blocks of a launch start together and their rows lie a multiple of the memory channels' interleave apart: walking
+    // K from 0 in every block would send all of them to the same channels at the same time.  Block `tile` starts at
+    // stripe tile % NC and wraps around.
+    const int rot = MODE == RM_STORE ? 0 : tile % NC;   // (the LM head runs several rounds of blocks: measured better without)
+    auto sidx = [&](int i) { const int c = min(i, NC - 1) + rot; return c >= NC ? c - NC : c; };
 #pragma unroll
-    for (int sl = 0; sl < M3_D; sl++) gload(sl, min(sl, NC - 1));
+    for (int sl = 0; sl < M3_D; sl++) gload(sl, sidx(sl));
     // RMS scale of every activation row from the producer's per-tile sums of squares (read by the epilogue).
     // Measured per mode: gate/up (long-lived blocks, two stripes in flight) loses least when the partials are
     // summed after the weight stream, the short-lived blocks of QKV and the LM head when it happens up front.
@@ -1346,16 +1362,16 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
     for (; ck0 + M3_D < NCp; ck0 += M3_D) {
 #pragma unroll
         for (int sl = 0; sl < M3_D; sl++) {
-            stage(sl, ck0 + sl);
-            gload(sl, min(ck0 + sl + M3_D, NC - 1));
-            multiply(ck0 + sl);
+            stage(sl, sidx(ck0 + sl));
+            gload(sl, sidx(ck0 + sl + M3_D));
+            multiply(sidx(ck0 + sl));
         }
     }
 #pragma unroll
     for (int sl = 0; sl < M3_D; sl++) {
         if (ck0 + sl < NC) {   // uniform
-            stage(sl, ck0 + sl);
-            multiply(ck0 + sl);
+            stage(sl, sidx(ck0 + sl));
+            multiply(sidx(ck0 + sl));
         }
     }
     if (MODE == RM_SWIGLU && p.ssq) row_scales();
@@ -1386,7 +1402,9 @@ static hipError_t launch_mfma3_nu(const RowsP2& p, int n_tiles, hipStream_t s)
 template <int MODE, int DEPTH, bool F16>
 static hipError_t launch_mfma3(const RowsP2& p, int n_tiles, hipStream_t s)
 {
-    return p.M <= 8 ? launch_mfma3_nu<MODE, DEPTH, F16, 2>(p, n_tiles, s) : launch_mfma3_nu<MODE, DEPTH, F16, 4>(p, n_tiles, s);
+    if (p.M <= 8) return launch_mfma3_nu<MODE, DEPTH, F16, 2>(p, n_tiles, s);
+    if (p.M <= 12) return launch_mfma3_nu<MODE, DEPTH, F16, 3>(p, n_tiles, s);
+    return launch_mfma3_nu<MODE, DEPTH, F16, 4>(p, n_tiles, s);
 }
 
 template <int MODE, bool F16>
@@ -1394,8 +1412,8 @@ static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s, const LaunchOp
 {
     const int forced = opt ? opt->rows_depth : 0;
     const int n_tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
-    // few tiles -> few blocks per CU -> each block keeps more stripes in flight
-    const int depth = forced > 0 ? forced : (n_tiles <= 512 ? 3 : (MODE == RM_SWIGLU ? 2 : 1));
+    // two stripes in flight measured best or equal for every GEMM of the 7B verify layer (`KB_ROWS=1 kernel_bench`)
+    const int depth = forced > 0 ? forced : 2;
     switch (depth) {
         case 1: return launch_mfma3<MODE, 1, F16>(p, n_tiles, s);
         case 2: return launch_mfma3<MODE, 2, F16>(p, n_tiles, s);
