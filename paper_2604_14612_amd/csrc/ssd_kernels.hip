@@ -458,7 +458,9 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvP p)
     // The waves of a launch start together and their rows lie a multiple of the memory channels' interleave apart:
     // where a wave owns whole rows (KS = 1), group g walks its chunks starting at its (g mod S_kp)-th one and wraps
     // around, so that the waves are spread over the row (and the channels) from the first step on; waves that share a
-    // row start at different chunks anyway (measured: the rotation gains 4 % on the LM head and loses 1-3 % there).
+    // row start at different chunks anyway (measured: the rotation gains 4 % on the 7B LM head, 10 % on the 70B one, and
+    // loses 1-3 % where waves share rows; a start at (block / 8) mod S_kp, which is what helps the 16-row kernel, loses
+    // up to 15 % here).
     // S_kp = chunks this wave owns.
     const int S_kp = kp < NCH ? (NCH - kp + KS - 1) / KS : 0;
     int ri = 0, ci = 0, rot_i = 0;
@@ -1334,10 +1336,13 @@ __global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
             }
         }
     };
-    // The blocks of a launch start together and their rows lie a multiple of the memory channels' interleave apart: walking
-    // K from 0 in every block would send all of them to the same channels at the same time.  Block `tile` starts at
-    // stripe tile % NC and wraps around.
-    const int rot = MODE == RM_STORE ? 0 : tile % NC;   // (the LM head runs several rounds of blocks: measured better without)
+    // The blocks of a launch start together and would all ask the memory channels for the same stripe at the same time:
+    // block `tile` starts its walk over K at stripe (tile / 8) % NC and wraps around (workgroups go to the eight XCDs
+    // round-robin by id, so blocks that follow each other on one XCD start one stripe apart).  Measured against a walk
+    // from 0 in every block: 7B QKV 28.0 -> 25.1 us, gate/up 39.4 -> 36.3, down 24.6 -> 22.6; 70B gate/up 170 -> 147,
+    // output projection 35 -> 29, LM head 108 -> 90 (a start at tile % NC instead is 20 % SLOWER than a walk from 0 at
+    // K = 8192).
+    const int rot = (tile / 8) % NC;
     auto sidx = [&](int i) { const int c = min(i, NC - 1) + rot; return c >= NC ? c - NC : c; };
 #pragma unroll
     for (int sl = 0; sl < M3_D; sl++) gload(sl, sidx(sl));
