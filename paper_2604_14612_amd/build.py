@@ -6,6 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssd.so")
 KERNEL_BENCH = os.path.join(HERE, "kernel_bench")
+STREAM_PROBE = os.path.join(HERE, "stream_probe")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -49,6 +50,11 @@ def build(verbose: bool = False) -> str:
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("kernel_bench build failed:\n" + r.stderr)
+    # stand-alone streaming-rate probe (access shapes of the weight-streaming kernels)
+    r = subprocess.run([HIPCC] + DEVICE_FLAGS + ["-o", STREAM_PROBE, os.path.join(CSRC, "stream_probe.hip")],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("stream_probe build failed:\n" + r.stderr)
     return LIB
 
 
