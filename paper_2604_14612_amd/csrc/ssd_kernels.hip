@@ -782,6 +782,7 @@ hipError_t gemv_qkv(const Dims& D, const void* wq, const void* wk, const void* w
                     const float* rope, const int* pos_dev, int pos_off, float* qbuf, void* kc, void* vc, hipStream_t s,
                     const Chain* ch, int* blocks_out)
 {
+    if (D.hd > 128 || D.hd % 2) return hipErrorInvalidValue;   // the kernel stages one rotary row of hd floats in a 128-float LDS array
     GemvP p = {};
     set_chain(p, ch);
     p.w0 = wq; p.w1 = wk; p.w2 = wv; p.in = x; p.gain = gain; p.eps = D.eps; p.K = D.d;
