@@ -1256,7 +1256,7 @@ constexpr int M3_PITCH = M3_CK * 2 + 16;  // bytes per LDS row (16-byte pad spre
 // M3_D = stripes in flight per block; F16: fp16 storage, else bf16; NU = activation vectors per thread and stripe
 // (2 covers up to 8 rows, 3 up to 12, 4 up to 16)
 template <int MODE, int M3_D, bool F16, int NU>
-__global__ __launch_bounds__(512) void rows_mfma3_kernel(RowsP2 p)
+__global__ __launch_bounds__(512, (NU <= 2 ? 6 : 4)) void rows_mfma3_kernel(RowsP2 p)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     extern __shared__ __align__(16) unsigned char sm3[];
@@ -1418,8 +1418,10 @@ static hipError_t rows_fused_mode(const RowsP2& p, hipStream_t s, const LaunchOp
 {
     const int forced = opt ? opt->rows_depth : 0;
     const int n_tiles = MODE == RM_SWIGLU ? p.n[0] / 16 : (p.n[0] + p.n[1] + p.n[2]) / 16;
-    // two stripes in flight measured best or equal for every GEMM of the 7B verify layer (`KB_ROWS=1 kernel_bench`)
-    const int depth = forced > 0 ? forced : 2;
+    // measured (`KB_ROWS=1 kernel_bench`, and at the 13B / 70B / Llama-3-8B shapes): two stripes in flight are best or
+    // equal everywhere except gate/up, whose ring for two stripes of two matrices does not fit the registers of three
+    // blocks per CU (the kernel is compiled for six waves per SIMD)
+    const int depth = forced > 0 ? forced : (MODE == RM_SWIGLU ? 1 : 2);
     switch (depth) {
         case 1: return launch_mfma3<MODE, 1, F16>(p, n_tiles, s);
         case 2: return launch_mfma3<MODE, 2, F16>(p, n_tiles, s);
