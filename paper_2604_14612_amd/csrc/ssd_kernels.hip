@@ -1256,7 +1256,7 @@ constexpr int M3_PITCH = M3_CK * 2 + 16;  // bytes per LDS row (16-byte pad spre
 // M3_D = stripes in flight per block; F16: fp16 storage, else bf16; NU = activation vectors per thread and stripe
 // (2 covers up to 8 rows, 3 up to 12, 4 up to 16)
 template <int MODE, int M3_D, bool F16, int NU>
-__global__ __launch_bounds__(512, (NU <= 2 ? 6 : 4)) void rows_mfma3_kernel(RowsP2 p)
+__global__ __launch_bounds__(512, (NU <= 2 ? 6 : NU == 3 ? 5 : 4)) void rows_mfma3_kernel(RowsP2 p)
 {
     constexpr int NT = MODE == RM_SWIGLU ? 2 : 1;
     extern __shared__ __align__(16) unsigned char sm3[];
